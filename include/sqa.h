@@ -1,0 +1,187 @@
+/*
+ * sqa -- SqueezeAttention hot path for AMD MI355X (gfx950), C ABI.
+ *
+ * The calls follow the paper's Algorithm 1:
+ *   prefill:  sqa_layer_importance   (steps 1-4: cosine similarity of the hidden
+ *                                     state before/after self-attention, Sec. 3)
+ *             sqa_allocate_budgets   (steps 5-11: cluster layers into 3 groups,
+ *                                     move budget from G3 to the others; host)
+ *             sqa_prefill_scores     (H2O's accumulated attention over the prompt,
+ *                                     Sec. 5.1 "Heavy-Hitter")
+ *             sqa_prefill_compress   (steps 12 + 16-17: the sequence-wise policy
+ *                                     C_seq applied with the layer's own budget)
+ *   decode:   sqa_decode_step        (steps 14-21 with Eq. 2-3: append, evict if
+ *                                     over budget, attention, H2O accumulation)
+ *
+ * Conventions
+ *   - "DEVICE" pointers are HIP device memory owned by the caller and borrowed
+ *     until the work enqueued on `stream` has finished; "HOST" pointers are
+ *     ordinary host memory read or written before the call returns.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *   - The library allocates no device memory and keeps no global state; scratch
+ *     space comes in through `workspace` (DEVICE, 256-byte aligned), whose
+ *     minimum size the matching *_workspace_bytes call returns.
+ *   - Arguments are validated on the host before any HIP call is made; on an
+ *     error nothing is enqueued and no output is touched.  Kernels are
+ *     enqueued asynchronously; nothing synchronises the stream except
+ *     sqa_read_device_status.
+ *   - All tensors are dense, row-major, last index fastest.
+ */
+#ifndef SQA_H_
+#define SQA_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  SQA_OK = 0,
+  SQA_ERR_NULL = 1,      /* a required pointer is NULL                              */
+  SQA_ERR_SHAPE = 2,     /* non-positive size, Hq % Hkv != 0, unsupported D or group */
+  SQA_ERR_DTYPE = 3,     /* unknown sqa_dtype                                        */
+  SQA_ERR_POLICY = 4,    /* unknown sqa_policy or negative n_sink                    */
+  SQA_ERR_BUDGET = 5,    /* p outside (0,1], total < n_layers, budget too small      */
+  SQA_ERR_CAPACITY = 6,  /* cache capacity / workspace / on-chip memory too small    */
+  SQA_ERR_HIP = 7,       /* the HIP runtime reported an error                        */
+  SQA_ERR_STATE = 8      /* device-side: a cache was longer than its budget on entry */
+} sqa_status;
+
+typedef enum { SQA_F32 = 0, SQA_BF16 = 1 } sqa_dtype;
+typedef enum { SQA_SLIDING = 0, SQA_STREAMING = 1, SQA_H2O = 2 } sqa_policy;
+
+enum { SQA_MAX_LAYERS = 128 };
+
+/*
+ * One layer's compact KV cache ("K^(i)" of Algorithm 1 after C_seq).  All
+ * pointers are DEVICE memory.  A unit is one (sequence b, KV head h); unit
+ * index u = b*Hkv + h.  Slot order inside a unit is NOT position order (softmax
+ * attention does not depend on it); `pos` says which token sits in each slot.
+ *
+ * Slot layout of a unit with budget b, hh protected/heavy slots and rec = b-hh
+ * recent slots (hh = 0 sliding, n_sink streaming, floor(b/2) H2O):
+ *   while len < b : slots [0,len) hold the tokens in ascending position;
+ *   once len == b : slots [0,hh) hold the non-recent tokens (sinks / heavy
+ *                   hitters, any order), slots [hh,b) are a ring holding the rec
+ *                   most recent tokens, the oldest at slot hh + ring_head[u].
+ * sqa_prefill_compress writes this layout (ascending position, ring_head 0);
+ * sqa_decode_step keeps it.
+ */
+typedef struct sqa_layer_cache {
+  void* K;             /* [B][Hkv][capacity][D], element type = the call's dtype   */
+  void* V;             /* [B][Hkv][capacity][D]                                    */
+  float* score_acc;    /* [B][Hkv][capacity] accumulated attention (H2O; else may be NULL) */
+  int32_t* pos;        /* [B][Hkv][capacity] token position per slot = kept_idx    */
+  int32_t* lens;       /* [B][Hkv] number of valid slots                           */
+  int32_t* ring_head;  /* [B][Hkv] offset of the oldest recent token in the ring   */
+  int32_t capacity;    /* slots per unit; >= min(budget, longest length reached)   */
+  int32_t budget;      /* b^(i): most tokens this layer keeps                      */
+} sqa_layer_cache;
+
+const char* sqa_status_str(sqa_status s);
+
+/* ---- Algorithm 1 steps 1-4; Sec. 3 cosine-similarity equation -------------
+ * cos_out[l] = (1/n_tokens) * sum_j  A_j.B_j / (max(|A_j|,1e-8) * max(|B_j|,1e-8))
+ * with A_j, B_j the rows of h_in[l], h_out[l] (all tokens of the batch, b*p rows).
+ *   h_in, h_out : DEVICE [n_layers][n_tokens][hidden], dtype dt; hidden % 8 == 0
+ *   cos_out     : DEVICE float [n_layers]
+ *   workspace   : DEVICE, >= sqa_layer_importance_workspace_bytes(...)
+ * Products accumulate in fp32, the token mean in fp64, fixed order (results are
+ * run-to-run identical). */
+size_t sqa_layer_importance_workspace_bytes(int n_layers, int64_t n_tokens, int hidden);
+sqa_status sqa_layer_importance(const void* h_in, const void* h_out, sqa_dtype dt,
+                                int n_layers, int64_t n_tokens, int hidden,
+                                float* cos_out, void* workspace, size_t ws_bytes, void* stream);
+
+/* ---- Algorithm 1 steps 5-11; Sec. 4.2.2; Appendix A.2 ---------------------
+ * Host only.  Clusters the n_layers cosines into (up to) 3 groups by the exact
+ * optimum of 1-D k-means (contiguous split of the sorted values, cuts only
+ * between distinct values, ties -> smallest cuts); G3 = the group with the
+ * largest cosines.  G3 layers get floor(total_budget*p/n_layers); the rest of
+ * total_budget is split evenly over the other layers, the remainder going +1
+ * to those with the lowest layer index, so the budgets sum to total_budget.
+ * One distinct cosine value -> uniform budgets.
+ *   cos        : HOST float [n_layers]
+ *   budget_out : HOST int32 [n_layers]
+ *   group_out  : HOST int8 [n_layers] or NULL; 0 = G1 (lowest cos), 1 = G2, 2 = G3
+ * SQA_ERR_BUDGET if p is outside (0,1], total_budget < n_layers or a budget
+ * would be < 1. */
+sqa_status sqa_allocate_budgets(const float* cos, int n_layers, int64_t total_budget, double p,
+                                int32_t* budget_out, int8_t* group_out);
+
+/* ---- H2O accumulated attention of the prompt (Sec. 5.1 "Heavy-Hitter") ----
+ * scores[b][hkv][j] = sum over the g = Hq/Hkv query heads of the KV head and
+ * over prompt queries i >= j of softmax_j'<=i(Q_i.K_j'/sqrt(D))[j].
+ *   Q : DEVICE [B][Hq][P][D], K : DEVICE [B][Hkv][P][D], dtype dt
+ *   scores_out : DEVICE float [B][Hkv][P]
+ *   workspace  : DEVICE, >= sqa_prefill_scores_workspace_bytes(...) */
+size_t sqa_prefill_scores_workspace_bytes(int B, int Hq, int Hkv, int P, int D);
+sqa_status sqa_prefill_scores(const void* Q, const void* K, sqa_dtype dt,
+                              int B, int Hq, int Hkv, int P, int D,
+                              float* scores_out, void* workspace, size_t ws_bytes, void* stream);
+
+/* ---- Algorithm 1 steps 12 + 16-17: compress the prompt's KV to the budget --
+ * Per unit keeps min(P, layer->budget) tokens chosen by the policy
+ * (Sec. 2.2 / Sec. 5.1):
+ *   SQA_SLIDING   the most recent tokens;
+ *   SQA_STREAMING positions < n_sink plus the most recent (budget - n_sink);
+ *   SQA_H2O       the (budget - floor(budget/2)) most recent plus, among the
+ *                 older ones, the floor(budget/2) with the largest attn_scores,
+ *                 equal scores -> lowest position first;
+ * and gathers their K, V rows (ascending position) into the layer cache,
+ * filling pos, score_acc (H2O), lens and ring_head.
+ *   K, V        : DEVICE [B][Hkv][P][D], dtype kv_dt; must not overlap the cache
+ *   attn_scores : DEVICE float [B][Hkv][P], values >= 0, required for SQA_H2O
+ *   layer       : HOST struct with DEVICE pointers; budget and capacity preset,
+ *                 capacity >= min(P, budget)
+ * SQA_ERR_BUDGET if budget < 1 (sliding), < n_sink+1 (streaming), < 2 (H2O). */
+sqa_status sqa_prefill_compress(const void* K, const void* V, sqa_dtype kv_dt, const float* attn_scores,
+                                int B, int Hkv, int P, int D, sqa_policy policy, int n_sink,
+                                const sqa_layer_cache* layer, void* stream);
+
+/* ---- Algorithm 1 steps 14-21 with Eq. 2-3: one decode step ----------------
+ * For each of n_layers layers and each unit, in this order:
+ *   1. append the new token's k, v (position new_pos, accumulated score 0);
+ *   2. if the unit now holds budget+1 tokens, evict one by the policy (the
+ *      token leaving the recent window, or for H2O the worse of that token and
+ *      the lowest-scoring heavy hitter; equal scores evict the higher position);
+ *   3. out[h] = softmax(q[h].K^T/sqrt(D)) V for the g query heads of the unit;
+ *   4. H2O: score_acc[slot] += sum over those heads of the probability.
+ * The cache (K, V, score_acc, pos, lens, ring_head) is updated in place; pos is
+ * the kept-index result.  new_pos must exceed every position already cached.
+ *   q            : DEVICE [n_layers][B][Hq][D], dtype dt
+ *   k_new, v_new : DEVICE [n_layers][B][Hkv][D]
+ *   out          : DEVICE [n_layers][B][Hq][D], dtype dt
+ *   layers       : HOST array [n_layers] (read for validation and launch shape)
+ *   layers_dev   : DEVICE copy of the same array, or NULL (then the call uploads
+ *                  it into the workspace first)
+ *   n_layers     : 1 when layers run one after another inside a model; all
+ *                  layers at once when their inputs are known up front
+ *   workspace    : DEVICE, >= sqa_decode_workspace_bytes(n_layers); its first
+ *                  int32 is a device-side status word (see sqa_read_device_status)
+ * A unit that on entry is longer than its budget, or has no free slot, is left
+ * untouched, its out rows are zeroed and the status word is set to
+ * SQA_ERR_STATE / SQA_ERR_CAPACITY. */
+size_t sqa_decode_workspace_bytes(int n_layers);
+sqa_status sqa_decode_step(const void* q, const void* k_new, const void* v_new, sqa_dtype dt,
+                           int B, int Hq, int Hkv, int D, int32_t new_pos,
+                           sqa_policy policy, int n_sink,
+                           const sqa_layer_cache* layers, const sqa_layer_cache* layers_dev, int n_layers,
+                           void* out, void* workspace, size_t ws_bytes, void* stream);
+
+/* Zeroes the status word (enqueued on stream). */
+sqa_status sqa_clear_device_status(void* workspace, void* stream);
+/* Waits for `stream`, then copies the status word to *status_out (HOST). */
+sqa_status sqa_read_device_status(const void* workspace, void* stream, int32_t* status_out);
+
+/* ---- kept indices in ascending order (a view for callers and tests) -------
+ * out[b][hkv][i] = i-th smallest position held by the unit, -1 for i >= len.
+ *   out : DEVICE int32 [B][Hkv][layer->capacity] */
+sqa_status sqa_kept_idx_sorted(const sqa_layer_cache* layer, int B, int Hkv, int32_t* out, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SQA_H_ */

@@ -1,0 +1,207 @@
+"""Thin ctypes binding over libsqa.so (the C ABI of include/sqa.h).
+
+Argument marshalling only: every step of the path runs in the HIP library.
+PyTorch supplies device memory and the current stream.  There is no fallback:
+if the library is missing, importing this module raises.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import List, Optional, Sequence, Tuple
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libsqa.so")
+
+if not os.path.exists(LIB_PATH):
+    raise ImportError(
+        "libsqa.so is not built: run `python -m paper_2404_04793_amd.build` "
+        "(there is no CPU or PyTorch fallback for the HIP path)")
+_lib = C.CDLL(LIB_PATH)
+
+SQA_OK = 0
+ERR = {1: "NULL", 2: "SHAPE", 3: "DTYPE", 4: "POLICY", 5: "BUDGET", 6: "CAPACITY", 7: "HIP", 8: "STATE"}
+SQA_F32, SQA_BF16 = 0, 1
+POLICY = {"sliding": 0, "streaming": 1, "h2o": 2}
+SQA_MAX_LAYERS = 128
+
+
+class SqaError(RuntimeError):
+    def __init__(self, code: int, where: str):
+        self.code = code
+        _lib.sqa_status_str.restype = C.c_char_p
+        msg = _lib.sqa_status_str(C.c_int(code)).decode()
+        super().__init__("%s: SQA_ERR_%s (%s)" % (where, ERR.get(code, str(code)), msg))
+
+
+class LayerCacheStruct(C.Structure):
+    """Mirror of sqa_layer_cache."""
+    _fields_ = [("K", C.c_void_p), ("V", C.c_void_p), ("score_acc", C.c_void_p), ("pos", C.c_void_p),
+                ("lens", C.c_void_p), ("ring_head", C.c_void_p), ("capacity", C.c_int32), ("budget", C.c_int32)]
+
+
+_vp, _i, _i64, _sz, _f64 = C.c_void_p, C.c_int, C.c_int64, C.c_size_t, C.c_double
+_LCp = C.POINTER(LayerCacheStruct)
+
+_lib.sqa_layer_importance_workspace_bytes.restype = _sz
+_lib.sqa_layer_importance_workspace_bytes.argtypes = [_i, _i64, _i]
+_lib.sqa_layer_importance.restype = _i
+_lib.sqa_layer_importance.argtypes = [_vp, _vp, _i, _i, _i64, _i, _vp, _vp, _sz, _vp]
+_lib.sqa_allocate_budgets.restype = _i
+_lib.sqa_allocate_budgets.argtypes = [C.POINTER(C.c_float), _i, _i64, _f64, C.POINTER(C.c_int32), C.POINTER(C.c_int8)]
+_lib.sqa_prefill_scores_workspace_bytes.restype = _sz
+_lib.sqa_prefill_scores_workspace_bytes.argtypes = [_i, _i, _i, _i, _i]
+_lib.sqa_prefill_scores.restype = _i
+_lib.sqa_prefill_scores.argtypes = [_vp, _vp, _i, _i, _i, _i, _i, _i, _vp, _vp, _sz, _vp]
+_lib.sqa_prefill_compress.restype = _i
+_lib.sqa_prefill_compress.argtypes = [_vp, _vp, _i, _vp, _i, _i, _i, _i, _i, _i, _LCp, _vp]
+_lib.sqa_decode_workspace_bytes.restype = _sz
+_lib.sqa_decode_workspace_bytes.argtypes = [_i]
+_lib.sqa_decode_step.restype = _i
+_lib.sqa_decode_step.argtypes = [_vp, _vp, _vp, _i, _i, _i, _i, _i, C.c_int32, _i, _i, _LCp, _vp, _i,
+                                 _vp, _vp, _sz, _vp]
+_lib.sqa_clear_device_status.restype = _i
+_lib.sqa_clear_device_status.argtypes = [_vp, _vp]
+_lib.sqa_read_device_status.restype = _i
+_lib.sqa_read_device_status.argtypes = [_vp, _vp, C.POINTER(C.c_int32)]
+_lib.sqa_kept_idx_sorted.restype = _i
+_lib.sqa_kept_idx_sorted.argtypes = [_LCp, _i, _i, _vp, _vp]
+
+
+def _dt(t: torch.Tensor) -> int:
+    if t.dtype == torch.float32:
+        return SQA_F32
+    if t.dtype == torch.bfloat16:
+        return SQA_BF16
+    return -1
+
+
+def _ptr(t: Optional[torch.Tensor]):
+    return None if t is None else t.data_ptr()
+
+
+def _stream():
+    return torch.cuda.current_stream().cuda_stream
+
+
+def _check(code: int, where: str):
+    if code != SQA_OK:
+        raise SqaError(code, where)
+
+
+# --------------------------------------------------------------------------
+
+def layer_importance(h_in: torch.Tensor, h_out: torch.Tensor, cos_out: Optional[torch.Tensor] = None,
+                     workspace: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """h_in, h_out [L, T, hidden] (contiguous, device) -> cos [L] fp32 (device)."""
+    L, T, d = h_in.shape
+    if cos_out is None:
+        cos_out = torch.empty(L, dtype=torch.float32, device=h_in.device)
+    need = _lib.sqa_layer_importance_workspace_bytes(L, T, d)
+    if workspace is None:
+        workspace = torch.empty(max(need, 8), dtype=torch.uint8, device=h_in.device)
+    _check(_lib.sqa_layer_importance(_ptr(h_in), _ptr(h_out), _dt(h_in), L, T, d, _ptr(cos_out),
+                                     _ptr(workspace), workspace.numel(), _stream()), "sqa_layer_importance")
+    return cos_out
+
+
+def allocate_budgets(cos: Sequence[float], total_budget: int, p: float) -> Tuple[List[int], List[int]]:
+    """cos: host floats (rounded to fp32 here) -> (budget[L], group[L])."""
+    L = len(cos)
+    c = (C.c_float * L)(*[float(x) for x in cos])
+    b = (C.c_int32 * L)()
+    g = (C.c_int8 * L)()
+    _check(_lib.sqa_allocate_budgets(c, L, int(total_budget), float(p), b, g), "sqa_allocate_budgets")
+    return list(b), list(g)
+
+
+def prefill_scores(Q: torch.Tensor, K: torch.Tensor, scores_out: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """Q [B, Hq, P, D], K [B, Hkv, P, D] -> scores [B, Hkv, P] fp32."""
+    B, Hq, P, D = Q.shape
+    Hkv = K.shape[1]
+    if scores_out is None:
+        scores_out = torch.empty(B, Hkv, P, dtype=torch.float32, device=Q.device)
+    need = _lib.sqa_prefill_scores_workspace_bytes(B, Hq, Hkv, P, D)
+    ws = torch.empty(max(need, 8), dtype=torch.uint8, device=Q.device)
+    _check(_lib.sqa_prefill_scores(_ptr(Q), _ptr(K), _dt(Q), B, Hq, Hkv, P, D, _ptr(scores_out), _ptr(ws),
+                                   ws.numel(), _stream()), "sqa_prefill_scores")
+    return scores_out
+
+
+class LayerCaches:
+    """Device memory of the compact caches of a range of layers, plus the
+    sqa_layer_cache table on the host and its copy on the device."""
+
+    def __init__(self, budgets: Sequence[int], capacities: Sequence[int], B: int, Hkv: int, D: int,
+                 dtype: torch.dtype, device, with_scores: bool = True):
+        self.L, self.B, self.Hkv, self.D, self.dtype = len(budgets), B, Hkv, D, dtype
+        self.budgets, self.capacities = list(budgets), list(capacities)
+        self.K, self.V, self.score, self.pos, self.lens, self.head = [], [], [], [], [], []
+        self.table = (LayerCacheStruct * self.L)()
+        for i, (b, cap) in enumerate(zip(budgets, capacities)):
+            self.K.append(torch.zeros(B, Hkv, cap, D, dtype=dtype, device=device))
+            self.V.append(torch.zeros(B, Hkv, cap, D, dtype=dtype, device=device))
+            self.score.append(torch.zeros(B, Hkv, cap, dtype=torch.float32, device=device) if with_scores else None)
+            self.pos.append(torch.full((B, Hkv, cap), -1, dtype=torch.int32, device=device))
+            self.lens.append(torch.zeros(B, Hkv, dtype=torch.int32, device=device))
+            self.head.append(torch.zeros(B, Hkv, dtype=torch.int32, device=device))
+            t = self.table[i]
+            t.K, t.V = self.K[i].data_ptr(), self.V[i].data_ptr()
+            t.score_acc = self.score[i].data_ptr() if with_scores else None
+            t.pos, t.lens, t.ring_head = self.pos[i].data_ptr(), self.lens[i].data_ptr(), self.head[i].data_ptr()
+            t.capacity, t.budget = int(cap), int(b)
+        raw = bytes(memoryview(self.table))
+        self.table_dev = torch.frombuffer(bytearray(raw), dtype=torch.uint8).to(device)
+
+    def struct_ptr(self, layer: int = 0):
+        return C.cast(C.byref(self.table, layer * C.sizeof(LayerCacheStruct)), _LCp)
+
+    def dev_ptr(self, layer: int = 0):
+        return self.table_dev.data_ptr() + layer * C.sizeof(LayerCacheStruct)
+
+
+def prefill_compress(K: torch.Tensor, V: torch.Tensor, attn_scores: Optional[torch.Tensor], policy: str,
+                     n_sink: int, caches: LayerCaches, layer: int) -> None:
+    """K, V [B, Hkv, P, D] of one layer -> caches' layer `layer`."""
+    B, Hkv, P, D = K.shape
+    _check(_lib.sqa_prefill_compress(_ptr(K), _ptr(V), _dt(K), _ptr(attn_scores), B, Hkv, P, D, POLICY[policy],
+                                     n_sink, caches.struct_ptr(layer), _stream()), "sqa_prefill_compress")
+
+
+def decode_workspace(n_layers: int, device) -> torch.Tensor:
+    ws = torch.zeros(_lib.sqa_decode_workspace_bytes(n_layers), dtype=torch.uint8, device=device)
+    return ws
+
+
+def decode_step(q: torch.Tensor, k_new: torch.Tensor, v_new: torch.Tensor, new_pos: int, policy: str,
+                n_sink: int, caches: LayerCaches, out: torch.Tensor, workspace: torch.Tensor,
+                layer0: int = 0, n_layers: Optional[int] = None, use_dev_table: bool = True) -> torch.Tensor:
+    """q [n_layers, B, Hq, D], k_new / v_new [n_layers, B, Hkv, D] -> out like q."""
+    n_layers = caches.L - layer0 if n_layers is None else n_layers
+    B, Hq, D = q.shape[-3], q.shape[-2], q.shape[-1]
+    Hkv = k_new.shape[-2]
+    _check(_lib.sqa_decode_step(_ptr(q), _ptr(k_new), _ptr(v_new), _dt(q), B, Hq, Hkv, D, int(new_pos),
+                                POLICY[policy], n_sink, caches.struct_ptr(layer0),
+                                caches.dev_ptr(layer0) if use_dev_table else None, n_layers, _ptr(out),
+                                _ptr(workspace), workspace.numel(), _stream()), "sqa_decode_step")
+    return out
+
+
+def clear_device_status(workspace: torch.Tensor) -> None:
+    _check(_lib.sqa_clear_device_status(_ptr(workspace), _stream()), "sqa_clear_device_status")
+
+
+def read_device_status(workspace: torch.Tensor) -> int:
+    v = C.c_int32(0)
+    _check(_lib.sqa_read_device_status(_ptr(workspace), _stream(), C.byref(v)), "sqa_read_device_status")
+    return v.value
+
+
+def kept_idx_sorted(caches: LayerCaches, layer: int) -> torch.Tensor:
+    """-> int32 [B, Hkv, capacity]: kept positions ascending, -1 padded."""
+    out = torch.empty(caches.B, caches.Hkv, caches.capacities[layer], dtype=torch.int32, device=caches.K[layer].device)
+    _check(_lib.sqa_kept_idx_sorted(caches.struct_ptr(layer), caches.B, caches.Hkv, _ptr(out), _stream()),
+           "sqa_kept_idx_sorted")
+    return out

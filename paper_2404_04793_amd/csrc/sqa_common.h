@@ -1,0 +1,48 @@
+// Internal helpers shared by the HIP translation units of libsqa (gfx950 only).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include "sqa.h"
+
+#define SQA_WAVE 64
+
+namespace sqa {
+
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2_t;
+
+struct bf16_t { uint16_t bits; };          // storage tag for SQA_BF16
+
+template <typename T> struct elem;
+template <> struct elem<float>  { static constexpr int per16 = 4; };
+template <> struct elem<bf16_t> { static constexpr int per16 = 8; };
+
+__device__ __forceinline__ float bf16_lo(uint32_t w) { return __uint_as_float(w << 16); }
+__device__ __forceinline__ float bf16_hi(uint32_t w) { return __uint_as_float(w & 0xffff0000u); }
+
+// fp32 -> bf16, round to nearest even (inputs are finite here; NaN kept quiet)
+__device__ __forceinline__ uint32_t f32_to_bf16_bits(float f) {
+  uint32_t u = __float_as_uint(f);
+  if ((u & 0x7fffffffu) > 0x7f800000u) return (u >> 16) | 0x40u;
+  u += 0x7fffu + ((u >> 16) & 1u);
+  return u >> 16;
+}
+
+// c + a.lo*b.lo + a.hi*b.hi on two packed bf16 pairs (v_dot2_f32_bf16)
+__device__ __forceinline__ float dot2_bf16(uint32_t a, uint32_t b, float c) {
+  return __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, a), __builtin_bit_cast(bf16x2_t, b), c, false);
+}
+
+__device__ __forceinline__ uint4 ld16(const void* p) { return *reinterpret_cast<const uint4*>(p); }
+__device__ __forceinline__ void st16(void* p, uint4 v) { *reinterpret_cast<uint4*>(p) = v; }
+
+template <typename T> __device__ __forceinline__ T wave_sum(T v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, SQA_WAVE);
+  return v;
+}
+
+inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+#define SQA_HIP_CHECK(expr) do { if ((expr) != hipSuccess) { (void)hipGetLastError(); return SQA_ERR_HIP; } } while (0)
+
+}  // namespace sqa

@@ -1,0 +1,249 @@
+// Prefill compression (Algorithm 1 steps 12 + 16-17 applied to the prompt) and
+// the sorted kept-index view.  One workgroup per (sequence, KV head) unit:
+//   select  sliding / streaming: index arithmetic on the position;
+//           H2O: the floor(b/2) largest accumulated scores among the non-recent
+//           tokens by an LDS radix select (4 passes of 8 bits over the fp32 bit
+//           patterns, which order like the values because scores are >= 0);
+//           tokens equal to the threshold are taken in ascending position by an
+//           index-ordered prefix count -- never by arrival order;
+//   compact an order-preserving prefix sum turns keep flags into slot numbers;
+//   gather  the kept K and V rows are copied once (16 bytes per lane).
+// HBM traffic per unit: P scores (H2O) + read and write of the kept rows.
+#include "sqa_common.h"
+
+namespace sqa {
+
+constexpr int kCmpThreads = 256;
+constexpr int kCmpWaves = kCmpThreads / SQA_WAVE;
+constexpr int kKeysInLdsMax = 16384;     // scores staged in LDS up to this many candidates
+
+__device__ __forceinline__ uint32_t score_key(float s) {
+  const uint32_t b = __float_as_uint(s);
+  return (b & 0x80000000u) ? 0u : b;     // scores are >= 0; -0.0 and negatives order as 0
+}
+
+// exclusive prefix count of `flag` over the 256 threads (position order), and the total
+__device__ __forceinline__ int block_excl_count(bool flag, int* s_wave_tot, int& total) {
+  const int lane = threadIdx.x & (SQA_WAVE - 1), wave = threadIdx.x / SQA_WAVE;
+  const unsigned long long bal = __ballot(flag);
+  const int within = __popcll(bal & ((1ull << lane) - 1ull));
+  __syncthreads();                        // previous users of s_wave_tot are done
+  if (lane == 0) s_wave_tot[wave] = __popcll(bal);
+  __syncthreads();
+  int before = 0, tot = 0;
+#pragma unroll
+  for (int w = 0; w < kCmpWaves; ++w) { const int t = s_wave_tot[w]; before += w < wave ? t : 0; tot += t; }
+  total = tot;
+  return before + within;
+}
+
+template <typename T, int D>
+__global__ __launch_bounds__(kCmpThreads) void prefill_compress_kernel(
+    const T* __restrict__ K, const T* __restrict__ V, const float* __restrict__ scores,
+    int P, sqa_layer_cache L, int policy, int n_sink, int keys_in_lds) {
+  constexpr int ROWB = D * (int)sizeof(T);
+  constexpr int LPR = ROWB / 16;
+  extern __shared__ uint32_t s_mem[];
+  __shared__ int s_hist[256];
+  __shared__ int s_wave_tot[kCmpWaves];
+  __shared__ uint32_t s_sel[2];           // threshold key, how many equal keys to take
+
+  const int tid = threadIdx.x;
+  const int u = blockIdx.x;
+  const int b = L.budget, cap = L.capacity;
+  const int n_keep = P < b ? P : b;
+  int* s_idx = reinterpret_cast<int*>(s_mem);              // [n_keep] kept positions, ascending
+  uint32_t* s_keys = s_mem + n_keep;                       // [M] when staged
+  const float* sc = scores ? scores + (int64_t)u * P : nullptr;
+
+  // range rules
+  int lo_keep = 0;        // positions < lo_keep are always kept (sinks)
+  int hi_from = 0;        // positions >= hi_from are always kept (recent window / everything)
+  int hh = 0;             // how many of [lo_keep, hi_from) to take by score
+  if (P > b) {
+    if (policy == SQA_SLIDING) { hi_from = P - b; }
+    else if (policy == SQA_STREAMING) { lo_keep = n_sink < b ? n_sink : b; hi_from = P - (b - lo_keep); }
+    else { hh = b / 2; hi_from = P - (b - hh); }
+  }
+  const int M = hi_from;  // H2O candidates are positions [0, M)
+
+  uint32_t thr = 0xffffffffu, take_eq = 0;
+  if (hh > 0) {
+    const uint32_t* keys;
+    if (keys_in_lds) {
+      for (int i = tid; i < M; i += kCmpThreads) s_keys[i] = score_key(sc[i]);
+      keys = s_keys;
+    } else {
+      keys = nullptr;
+    }
+    uint32_t prefix = 0, mask = 0;
+    int k = hh;
+    for (int pass = 3; pass >= 0; --pass) {
+      s_hist[tid] = 0;
+      __syncthreads();
+      const int sh = pass * 8;
+      for (int i = tid; i < M; i += kCmpThreads) {
+        const uint32_t key = keys ? keys[i] : score_key(sc[i]);
+        if ((key & mask) == prefix) atomicAdd(&s_hist[(key >> sh) & 255u], 1);
+      }
+      __syncthreads();
+      if (tid == 0) {
+        int cum = 0, v = 255;
+        for (; v > 0; --v) { if (cum + s_hist[v] >= k) break; cum += s_hist[v]; }
+        s_sel[0] = (uint32_t)v; s_sel[1] = (uint32_t)(k - cum);
+      }
+      __syncthreads();
+      prefix |= s_sel[0] << sh; mask |= 255u << sh; k = (int)s_sel[1];
+      __syncthreads();
+    }
+    thr = prefix; take_eq = (uint32_t)k;
+  }
+
+  // keep flags -> slots, in position order, 256 positions at a time
+  int eq_seen = 0, kept_seen = 0;
+  for (int base = 0; base < P; base += kCmpThreads) {
+    const int i = base + tid;
+    const bool in = i < P;
+    bool keep = in && (i < lo_keep || i >= hi_from);
+    if (hh > 0) {
+      const bool cand = in && i < M;
+      const uint32_t key = cand ? score_key(sc[i]) : 0u;
+      const bool eq = cand && key == thr;
+      int eq_tot;
+      const int eq_rank = eq_seen + block_excl_count(eq, s_wave_tot, eq_tot);
+      eq_seen += eq_tot;
+      keep = keep || (cand && (key > thr || (eq && (uint32_t)eq_rank < take_eq)));
+    }
+    int kept_tot;
+    const int slot = kept_seen + block_excl_count(keep, s_wave_tot, kept_tot);
+    kept_seen += kept_tot;
+    if (keep) s_idx[slot] = i;
+  }
+  __syncthreads();
+
+  // gather rows, scores, positions
+  const T* Ku = K + (int64_t)u * P * D;
+  const T* Vu = V + (int64_t)u * P * D;
+  char* Kc = reinterpret_cast<char*>(L.K) + (int64_t)u * cap * ROWB;
+  char* Vc = reinterpret_cast<char*>(L.V) + (int64_t)u * cap * ROWB;
+  const int grp = tid / LPR, c = tid % LPR;
+  constexpr int GROUPS = kCmpThreads / LPR;
+  for (int j = grp; j < n_keep; j += 2 * GROUPS) {
+    const int j2 = j + GROUPS;
+    const int src = s_idx[j];
+    const int src2 = j2 < n_keep ? s_idx[j2] : src;
+    const uint4 k1 = ld16(reinterpret_cast<const char*>(Ku) + (int64_t)src * ROWB + c * 16);
+    const uint4 v1 = ld16(reinterpret_cast<const char*>(Vu) + (int64_t)src * ROWB + c * 16);
+    const uint4 k2 = ld16(reinterpret_cast<const char*>(Ku) + (int64_t)src2 * ROWB + c * 16);
+    const uint4 v2 = ld16(reinterpret_cast<const char*>(Vu) + (int64_t)src2 * ROWB + c * 16);
+    st16(Kc + (int64_t)j * ROWB + c * 16, k1);
+    st16(Vc + (int64_t)j * ROWB + c * 16, v1);
+    if (j2 < n_keep) {
+      st16(Kc + (int64_t)j2 * ROWB + c * 16, k2);
+      st16(Vc + (int64_t)j2 * ROWB + c * 16, v2);
+    }
+  }
+  int32_t* posu = L.pos + (int64_t)u * cap;
+  for (int j = tid; j < n_keep; j += kCmpThreads) {
+    const int src = s_idx[j];
+    posu[j] = src;
+    if (L.score_acc) L.score_acc[(int64_t)u * cap + j] = sc ? sc[src] : 0.f;
+  }
+  if (tid == 0) { L.lens[u] = n_keep; L.ring_head[u] = 0; }
+}
+
+// out[rank of pos[i]] = pos[i]; -1 beyond len.  Rank by counting (a test view, O(n^2)).
+__global__ __launch_bounds__(kCmpThreads) void kept_idx_sorted_kernel(sqa_layer_cache L, int32_t* __restrict__ out) {
+  extern __shared__ uint32_t s_mem[];
+  int* s_pos = reinterpret_cast<int*>(s_mem);
+  const int u = blockIdx.x, cap = L.capacity;
+  int len = L.lens[u];
+  len = len < 0 ? 0 : (len > cap ? cap : len);
+  const int32_t* posu = L.pos + (int64_t)u * cap;
+  int32_t* o = out + (int64_t)u * cap;
+  for (int i = threadIdx.x; i < len; i += kCmpThreads) s_pos[i] = posu[i];
+  for (int i = len + threadIdx.x; i < cap; i += kCmpThreads) o[i] = -1;
+  __syncthreads();
+  for (int i = threadIdx.x; i < len; i += kCmpThreads) {
+    const int p = s_pos[i];
+    int rank = 0;
+    for (int j = 0; j < len; ++j) rank += (s_pos[j] < p) || (s_pos[j] == p && j < i);
+    o[rank] = p;
+  }
+}
+
+typedef void (*compress_fn)(const void*, const void*, const float*, int, sqa_layer_cache, int, int, int);
+
+template <typename T, int D>
+static void launch_compress(const void* K, const void* V, const float* scores, int P, const sqa_layer_cache& L,
+                            int policy, int n_sink, int keys_in_lds, unsigned blocks, size_t lds, hipStream_t st) {
+  auto fn = prefill_compress_kernel<T, D>;
+  if (lds > 48 * 1024)
+    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(fn), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+  fn<<<blocks, kCmpThreads, lds, st>>>(static_cast<const T*>(K), static_cast<const T*>(V), scores, P, L, policy,
+                                       n_sink, keys_in_lds);
+}
+
+}  // namespace sqa
+
+extern "C" sqa_status sqa_prefill_compress(const void* K, const void* V, sqa_dtype kv_dt, const float* attn_scores,
+                                           int B, int Hkv, int P, int D, sqa_policy policy, int n_sink,
+                                           const sqa_layer_cache* layer, void* stream) {
+  using namespace sqa;
+  if (!K || !V || !layer) return SQA_ERR_NULL;
+  if (kv_dt != SQA_F32 && kv_dt != SQA_BF16) return SQA_ERR_DTYPE;
+  if (policy != SQA_SLIDING && policy != SQA_STREAMING && policy != SQA_H2O) return SQA_ERR_POLICY;
+  if (n_sink < 0) return SQA_ERR_POLICY;
+  if (B < 1 || Hkv < 1 || P < 1 || (D != 64 && D != 128) || (int64_t)B * Hkv > INT32_MAX) return SQA_ERR_SHAPE;
+  if (policy == SQA_H2O && !attn_scores) return SQA_ERR_NULL;
+  const sqa_layer_cache& L = *layer;
+  if (!L.K || !L.V || !L.pos || !L.lens || !L.ring_head) return SQA_ERR_NULL;
+  if (policy == SQA_H2O && !L.score_acc) return SQA_ERR_NULL;
+  if (!aligned16(K) || !aligned16(V) || !aligned16(L.K) || !aligned16(L.V)) return SQA_ERR_SHAPE;
+  const int min_budget = policy == SQA_H2O ? 2 : (policy == SQA_STREAMING ? n_sink + 1 : 1);
+  if (L.budget < min_budget) return SQA_ERR_BUDGET;
+  const int n_keep = P < L.budget ? P : L.budget;
+  if (L.capacity < n_keep) return SQA_ERR_CAPACITY;
+  // the prompt tensors must not overlap the cache they are gathered into
+  const size_t eb = kv_dt == SQA_F32 ? 4 : 2;
+  const size_t in_bytes = (size_t)B * Hkv * P * D * eb, c_bytes = (size_t)B * Hkv * L.capacity * D * eb;
+  auto overlaps = [](const void* a, size_t na, const void* b, size_t nb) {
+    const uintptr_t x = reinterpret_cast<uintptr_t>(a), y = reinterpret_cast<uintptr_t>(b);
+    return x < y + nb && y < x + na;
+  };
+  if (overlaps(K, in_bytes, L.K, c_bytes) || overlaps(K, in_bytes, L.V, c_bytes) ||
+      overlaps(V, in_bytes, L.K, c_bytes) || overlaps(V, in_bytes, L.V, c_bytes)) return SQA_ERR_SHAPE;
+
+  const bool h2o_select = policy == SQA_H2O && P > L.budget;
+  const int M = h2o_select ? P - (L.budget - L.budget / 2) : 0;
+  const int keys_in_lds = h2o_select && M <= kKeysInLdsMax;
+  const size_t lds = ((size_t)n_keep + (keys_in_lds ? (size_t)M : 0)) * sizeof(uint32_t);
+  if (lds > 128 * 1024) return SQA_ERR_CAPACITY;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  const unsigned blocks = (unsigned)(B * Hkv);
+  const float* sc = policy == SQA_H2O ? attn_scores : nullptr;
+  if (kv_dt == SQA_F32) {
+    if (D == 64) launch_compress<float, 64>(K, V, sc, P, L, policy, n_sink, keys_in_lds, blocks, lds, st);
+    else launch_compress<float, 128>(K, V, sc, P, L, policy, n_sink, keys_in_lds, blocks, lds, st);
+  } else {
+    if (D == 64) launch_compress<bf16_t, 64>(K, V, sc, P, L, policy, n_sink, keys_in_lds, blocks, lds, st);
+    else launch_compress<bf16_t, 128>(K, V, sc, P, L, policy, n_sink, keys_in_lds, blocks, lds, st);
+  }
+  SQA_HIP_CHECK(hipGetLastError());
+  return SQA_OK;
+}
+
+extern "C" sqa_status sqa_kept_idx_sorted(const sqa_layer_cache* layer, int B, int Hkv, int32_t* out, void* stream) {
+  using namespace sqa;
+  if (!layer || !out || !layer->pos || !layer->lens) return SQA_ERR_NULL;
+  if (B < 1 || Hkv < 1 || (int64_t)B * Hkv > INT32_MAX) return SQA_ERR_SHAPE;
+  if (layer->capacity < 1) return SQA_ERR_CAPACITY;
+  const size_t lds = (size_t)layer->capacity * sizeof(int32_t);
+  if (lds > 128 * 1024) return SQA_ERR_CAPACITY;
+  if (lds > 48 * 1024)
+    SQA_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void*>(kept_idx_sorted_kernel),
+                                      hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+  kept_idx_sorted_kernel<<<(unsigned)(B * Hkv), kCmpThreads, lds, static_cast<hipStream_t>(stream)>>>(*layer, out);
+  SQA_HIP_CHECK(hipGetLastError());
+  return SQA_OK;
+}

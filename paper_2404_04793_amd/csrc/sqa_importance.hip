@@ -1,0 +1,131 @@
+// Layer-importance probe: Algorithm 1 steps 1-4 with the cosine-similarity
+// equation of Sec. 3.  A pure streaming reduction (each hidden-state element is
+// read once), so the only roofline is HBM bandwidth.
+//
+// Mapping: grid = (blocks per layer, layers); a workgroup has 4 waves; a wave
+// owns whole token rows (row = wave id, stepping by the number of waves of the
+// layer) and its 64 lanes read the row in 16-byte pieces, 1 KiB per wave load.
+// The three dot products accumulate in fp32 per lane, are summed over the wave,
+// and lane 0 adds the row's cosine to a per-wave fp64 sum.  Partial sums go to
+// the workspace and a second tiny kernel adds them in a fixed order: no atomics,
+// results are bit-identical from run to run.
+#include "sqa_common.h"
+
+namespace sqa {
+
+constexpr int kImpThreads = 256;
+constexpr int kImpWaves = kImpThreads / SQA_WAVE;
+constexpr int kImpMaxBlocks = 1024;   // partial sums per layer
+
+template <typename T> struct Dots;
+template <> struct Dots<float> {
+  static __device__ __forceinline__ void acc(const uint4& a, const uint4& b, float& ab, float& aa, float& bb) {
+    const float a0 = __uint_as_float(a.x), a1 = __uint_as_float(a.y), a2 = __uint_as_float(a.z), a3 = __uint_as_float(a.w);
+    const float b0 = __uint_as_float(b.x), b1 = __uint_as_float(b.y), b2 = __uint_as_float(b.z), b3 = __uint_as_float(b.w);
+    ab = fmaf(a0, b0, ab); ab = fmaf(a1, b1, ab); ab = fmaf(a2, b2, ab); ab = fmaf(a3, b3, ab);
+    aa = fmaf(a0, a0, aa); aa = fmaf(a1, a1, aa); aa = fmaf(a2, a2, aa); aa = fmaf(a3, a3, aa);
+    bb = fmaf(b0, b0, bb); bb = fmaf(b1, b1, bb); bb = fmaf(b2, b2, bb); bb = fmaf(b3, b3, bb);
+  }
+};
+template <> struct Dots<bf16_t> {
+  static __device__ __forceinline__ void acc(const uint4& a, const uint4& b, float& ab, float& aa, float& bb) {
+    ab = dot2_bf16(a.x, b.x, ab); ab = dot2_bf16(a.y, b.y, ab); ab = dot2_bf16(a.z, b.z, ab); ab = dot2_bf16(a.w, b.w, ab);
+    aa = dot2_bf16(a.x, a.x, aa); aa = dot2_bf16(a.y, a.y, aa); aa = dot2_bf16(a.z, a.z, aa); aa = dot2_bf16(a.w, a.w, aa);
+    bb = dot2_bf16(b.x, b.x, bb); bb = dot2_bf16(b.y, b.y, bb); bb = dot2_bf16(b.z, b.z, bb); bb = dot2_bf16(b.w, b.w, bb);
+  }
+};
+
+template <typename T>
+__global__ __launch_bounds__(kImpThreads) void importance_partial_kernel(
+    const T* __restrict__ h_in, const T* __restrict__ h_out, int64_t n_tokens, int hidden,
+    double* __restrict__ partial /*[layers][gridDim.x]*/) {
+  constexpr int E = elem<T>::per16;
+  const int lane = threadIdx.x & (SQA_WAVE - 1);
+  const int wave = threadIdx.x / SQA_WAVE;
+  const int layer = blockIdx.y;
+  const int64_t row_elems = hidden;
+  const char* A = reinterpret_cast<const char*>(h_in + (int64_t)layer * n_tokens * row_elems);
+  const char* Bp = reinterpret_cast<const char*>(h_out + (int64_t)layer * n_tokens * row_elems);
+  const int chunks = hidden / E;                 // 16-byte pieces per row
+  const int64_t row_bytes = row_elems * (int64_t)sizeof(T);
+  const int64_t stride = (int64_t)gridDim.x * kImpWaves;
+
+  double wave_cos = 0.0;
+  for (int64_t row = (int64_t)blockIdx.x * kImpWaves + wave; row < n_tokens; row += stride) {
+    const char* a = A + row * row_bytes;
+    const char* b = Bp + row * row_bytes;
+    float ab = 0.f, aa = 0.f, bb = 0.f;
+    int c = lane;
+    for (; c + 3 * SQA_WAVE < chunks; c += 4 * SQA_WAVE) {      // 8 loads in flight per lane
+      const uint4 a0 = ld16(a + (int64_t)c * 16), b0 = ld16(b + (int64_t)c * 16);
+      const uint4 a1 = ld16(a + (int64_t)(c + SQA_WAVE) * 16), b1 = ld16(b + (int64_t)(c + SQA_WAVE) * 16);
+      const uint4 a2 = ld16(a + (int64_t)(c + 2 * SQA_WAVE) * 16), b2 = ld16(b + (int64_t)(c + 2 * SQA_WAVE) * 16);
+      const uint4 a3 = ld16(a + (int64_t)(c + 3 * SQA_WAVE) * 16), b3 = ld16(b + (int64_t)(c + 3 * SQA_WAVE) * 16);
+      Dots<T>::acc(a0, b0, ab, aa, bb); Dots<T>::acc(a1, b1, ab, aa, bb);
+      Dots<T>::acc(a2, b2, ab, aa, bb); Dots<T>::acc(a3, b3, ab, aa, bb);
+    }
+    for (; c < chunks; c += SQA_WAVE) {
+      const uint4 a0 = ld16(a + (int64_t)c * 16), b0 = ld16(b + (int64_t)c * 16);
+      Dots<T>::acc(a0, b0, ab, aa, bb);
+    }
+    ab = wave_sum(ab); aa = wave_sum(aa); bb = wave_sum(bb);
+    const double na = fmax(sqrt((double)aa), 1e-8), nb = fmax(sqrt((double)bb), 1e-8);
+    wave_cos += (double)ab / (na * nb);
+  }
+  __shared__ double s_part[kImpWaves];
+  if (lane == 0) s_part[wave] = wave_cos;
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    double s = 0.0;
+    for (int w = 0; w < kImpWaves; ++w) s += s_part[w];
+    partial[(int64_t)layer * gridDim.x + blockIdx.x] = s;
+  }
+}
+
+__global__ __launch_bounds__(SQA_WAVE) void importance_final_kernel(
+    const double* __restrict__ partial, int n_part, int64_t n_tokens, float* __restrict__ cos_out) {
+  const int layer = blockIdx.x;
+  const int lane = threadIdx.x;
+  double s = 0.0;
+  for (int i = lane; i < n_part; i += SQA_WAVE) s += partial[(int64_t)layer * n_part + i];
+  s = wave_sum(s);
+  if (lane == 0) cos_out[layer] = (float)(s / (double)n_tokens);
+}
+
+static int imp_blocks(int64_t n_tokens) {
+  int64_t b = (n_tokens + kImpWaves - 1) / kImpWaves;
+  return (int)(b < kImpMaxBlocks ? b : kImpMaxBlocks);
+}
+
+}  // namespace sqa
+
+extern "C" size_t sqa_layer_importance_workspace_bytes(int n_layers, int64_t n_tokens, int hidden) {
+  (void)hidden;
+  if (n_layers < 1 || n_tokens < 1) return 0;
+  return (size_t)n_layers * sqa::imp_blocks(n_tokens) * sizeof(double);
+}
+
+extern "C" sqa_status sqa_layer_importance(const void* h_in, const void* h_out, sqa_dtype dt,
+                                           int n_layers, int64_t n_tokens, int hidden,
+                                           float* cos_out, void* workspace, size_t ws_bytes, void* stream) {
+  using namespace sqa;
+  if (!h_in || !h_out || !cos_out || !workspace) return SQA_ERR_NULL;
+  if (dt != SQA_F32 && dt != SQA_BF16) return SQA_ERR_DTYPE;
+  if (n_layers < 1 || n_layers > 65535 || n_tokens < 1 || hidden < 8 || hidden % 8 != 0) return SQA_ERR_SHAPE;
+  if (!aligned16(h_in) || !aligned16(h_out) || (reinterpret_cast<uintptr_t>(workspace) & 7u)) return SQA_ERR_SHAPE;
+  if (ws_bytes < sqa_layer_importance_workspace_bytes(n_layers, n_tokens, hidden)) return SQA_ERR_CAPACITY;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  const int nblk = imp_blocks(n_tokens);
+  double* partial = static_cast<double*>(workspace);
+  dim3 grid(nblk, n_layers);
+  if (dt == SQA_F32)
+    importance_partial_kernel<float><<<grid, kImpThreads, 0, st>>>(
+        static_cast<const float*>(h_in), static_cast<const float*>(h_out), n_tokens, hidden, partial);
+  else
+    importance_partial_kernel<bf16_t><<<grid, kImpThreads, 0, st>>>(
+        static_cast<const bf16_t*>(h_in), static_cast<const bf16_t*>(h_out), n_tokens, hidden, partial);
+  SQA_HIP_CHECK(hipGetLastError());
+  importance_final_kernel<<<n_layers, SQA_WAVE, 0, st>>>(partial, nblk, n_tokens, cos_out);
+  SQA_HIP_CHECK(hipGetLastError());
+  return SQA_OK;
+}

@@ -1,0 +1,57 @@
+"""Helpers for the GPU parity tests: move one unit's cache state between the
+oracle's representation and the library's device layout, and the tolerance
+rule.  Test infrastructure only."""
+from __future__ import annotations
+
+import numpy as np
+import torch
+
+TOL = {"f32": 1e-5, "bf16": 2e-2}
+
+
+def rel_err(x, ref) -> float:
+    """max|x - ref| / max|ref| over one output vector (or a stack of them, row-wise worst)."""
+    x = np.asarray(x, dtype=np.float64).reshape(-1, np.shape(ref)[-1])
+    ref = np.asarray(ref, dtype=np.float64).reshape(x.shape)
+    num = np.abs(x - ref).max(axis=1)
+    den = np.maximum(np.abs(ref).max(axis=1), 1e-30)
+    return float((num / den).max())
+
+
+def np64(t: torch.Tensor) -> np.ndarray:
+    return t.detach().to("cpu").to(torch.float64).numpy()
+
+
+def import_state(caches, layer: int, b: int, h: int, c: dict) -> None:
+    """Write an oracle cache (ascending position) into unit (b, h) of a layer
+    in the library's canonical layout: slot i = i-th smallest position, ring head 0."""
+    n = len(c["pos"])
+    dev = caches.K[layer].device
+    dt = caches.dtype
+    caches.K[layer][b, h, :n] = torch.from_numpy(c["K"]).to(dt).to(dev)
+    caches.V[layer][b, h, :n] = torch.from_numpy(c["V"]).to(dt).to(dev)
+    caches.pos[layer][b, h, :n] = torch.from_numpy(c["pos"].astype(np.int32)).to(dev)
+    caches.pos[layer][b, h, n:] = -1
+    if caches.score[layer] is not None:
+        caches.score[layer][b, h, :n] = torch.from_numpy(c["score"]).to(torch.float32).to(dev)
+    caches.lens[layer][b, h] = n
+    caches.head[layer][b, h] = 0
+
+
+def export_state(caches, layer: int, b: int, h: int) -> dict:
+    """Unit (b, h) of a layer as an oracle-style cache sorted by position."""
+    n = int(caches.lens[layer][b, h].item())
+    pos = caches.pos[layer][b, h, :n].cpu().numpy().astype(np.int64)
+    order = np.argsort(pos, kind="stable")
+    out = {"pos": pos[order], "K": np64(caches.K[layer][b, h, :n])[order], "V": np64(caches.V[layer][b, h, :n])[order]}
+    if caches.score[layer] is not None:
+        out["score"] = np64(caches.score[layer][b, h, :n])[order]
+    else:
+        out["score"] = np.zeros(n)
+    return out
+
+
+def round_scores_f32(c: dict) -> dict:
+    d = dict(c)
+    d["score"] = c["score"].astype(np.float32).astype(np.float64)
+    return d

@@ -1,0 +1,123 @@
+"""CPU-side checks of the C-ABI library: it loads, exports every symbol that
+include/sqa.h declares, validates arguments before touching the GPU, and its
+host-side budget allocator agrees bit for bit with the oracle (Algorithm 1
+steps 5-11)."""
+import ctypes as C
+import os
+import re
+
+import numpy as np
+import pytest
+
+from oracle import sqa_oracle as O
+from paper_2404_04793_amd import binding as sqa
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def test_every_declared_symbol_is_exported():
+    hdr = open(os.path.join(ROOT, "include", "sqa.h")).read()
+    hdr = re.sub(r"/\*.*?\*/", "", hdr, flags=re.S)
+    names = set(re.findall(r"\b(sqa_[a-z_0-9]+)\s*\(", hdr))
+    assert {"sqa_layer_importance", "sqa_allocate_budgets", "sqa_prefill_compress", "sqa_decode_step"} <= names
+    lib = C.CDLL(sqa.LIB_PATH)
+    for n in sorted(names):
+        assert hasattr(lib, n), n
+
+
+def test_struct_layout_matches_header():
+    assert C.sizeof(sqa.LayerCacheStruct) == 56
+    assert sqa.LayerCacheStruct.capacity.offset == 48 and sqa.LayerCacheStruct.budget.offset == 52
+
+
+def test_paper_worked_example_through_the_library():
+    # Appendix A.2: 18 important / 14 unimportant layers, b_init 1000, p 0.3 -> 300 / 1544
+    r = np.random.default_rng(0)
+    cos = np.concatenate([0.4 + 0.05 * r.random(4), 0.7 + 0.04 * r.random(14), 0.94 + 0.02 * r.random(14)])
+    cos = cos[r.permutation(32)].astype(np.float32)
+    budget, group = sqa.allocate_budgets(cos, 32000, 0.3)
+    assert sum(budget) == 32000
+    assert {b for b, g in zip(budget, group) if g == 2} == {300}
+    assert min(b for b, g in zip(budget, group) if g != 2) == 1544
+    assert sum(1 for g in group if g == 2) == 14
+
+
+@pytest.mark.parametrize("seed", range(40))
+def test_budgets_bit_exact_vs_oracle(seed):
+    r = np.random.default_rng(seed)
+    L = int(r.integers(1, 100))
+    kind = seed % 4
+    if kind == 0:
+        cos = r.random(L)
+    elif kind == 1:
+        cos = np.round(r.random(L), 1)                 # many equal values
+    elif kind == 2:
+        cos = 0.9 + 0.05 * r.standard_normal(L); cos[: L // 5] = 0.4 + 0.1 * r.random(L // 5)
+    else:
+        cos = np.arange(L) / max(L, 1)                 # evenly spaced: ties between splits
+    cos = cos.astype(np.float32)
+    total = int(r.integers(L * 3, L * 4000 + 1))
+    p = float(r.choice([0.1, 0.25, 0.3, 0.35, 0.4, 0.5, 0.9, 1.0]))
+    try:
+        want = O.allocate_budgets(cos, total, p)
+    except ValueError:
+        with pytest.raises(sqa.SqaError) as e:
+            sqa.allocate_budgets(cos, total, p)
+        assert e.value.code == 5
+        return
+    got = sqa.allocate_budgets(cos, total, p)
+    assert got[0] == want[0] and got[1] == want[1]
+
+
+def test_budget_argument_errors():
+    for cos, total, p, code in [([0.1, 0.5, 0.9], 2, 0.3, 5), ([0.1, 0.5, 0.9], 30, 0.0, 5),
+                                ([0.1, 0.5, 0.9], 30, 1.01, 5), ([0.1, 0.5, 0.9], 3, 0.3, 5)]:
+        with pytest.raises(sqa.SqaError) as e:
+            sqa.allocate_budgets(cos, total, p)
+        assert e.value.code == code
+    lib = sqa._lib
+    out = (C.c_int32 * 3)()
+    assert lib.sqa_allocate_budgets(None, 3, 30, 0.3, out, None) == 1
+    assert lib.sqa_allocate_budgets((C.c_float * 3)(0.1, 0.2, 0.3), 0, 30, 0.3, out, None) == 2
+
+
+def test_device_entry_points_validate_before_any_gpu_call():
+    """Bogus but non-NULL, aligned pointers: every call must fail in validation."""
+    lib = sqa._lib
+    p = C.c_void_p(0x1000)
+    assert lib.sqa_layer_importance(None, p, 0, 1, 4, 64, p, p, 1 << 20, None) == 1
+    assert lib.sqa_layer_importance(p, p, 7, 1, 4, 64, p, p, 1 << 20, None) == 3
+    assert lib.sqa_layer_importance(p, p, 0, 1, 4, 60, p, p, 1 << 20, None) == 2
+    assert lib.sqa_layer_importance(p, p, 0, 1, 4, 64, p, p, 0, None) == 6
+    lc = sqa.LayerCacheStruct(0x1000, 0x2000, 0x3000, 0x4000, 0x5000, 0x6000, 8, 4)
+    args = lambda **kw: [kw.get("K", p), p, kw.get("dt", 1), kw.get("sc", p), 1, 1, kw.get("P", 16), kw.get("D", 128),
+                         kw.get("pol", 2), kw.get("ns", 4), C.byref(kw.get("lc", lc)), None]
+    assert lib.sqa_prefill_compress(*args(K=None)) == 1
+    assert lib.sqa_prefill_compress(*args(dt=5)) == 3
+    assert lib.sqa_prefill_compress(*args(pol=3)) == 4
+    assert lib.sqa_prefill_compress(*args(D=96)) == 2
+    assert lib.sqa_prefill_compress(*args(sc=None)) == 1                     # H2O needs scores
+    assert lib.sqa_prefill_compress(*args(pol=1, ns=4)) == 5                 # streaming: budget 4 < n_sink+1
+    small = sqa.LayerCacheStruct(0x1000, 0x2000, 0x3000, 0x4000, 0x5000, 0x6000, 3, 4)
+    assert lib.sqa_prefill_compress(*args(lc=small)) == 6                    # capacity 3 < min(P, budget)
+    one = sqa.LayerCacheStruct(0x1000, 0x2000, 0x3000, 0x4000, 0x5000, 0x6000, 8, 1)
+    assert lib.sqa_prefill_compress(*args(lc=one)) == 5                      # H2O: budget 1 < 2
+
+    def dec(**kw):
+        return lib.sqa_decode_step(kw.get("q", p), p, p, kw.get("dt", 1), 1, kw.get("Hq", 4), kw.get("Hkv", 4),
+                                   kw.get("D", 128), kw.get("pos", 5), kw.get("pol", 2), 4,
+                                   C.byref(kw.get("lc", lc)), None, kw.get("nl", 1), p, p, kw.get("ws", 1 << 20), None)
+    assert dec(q=None) == 1
+    assert dec(dt=9) == 3
+    assert dec(pol=-1) == 4
+    assert dec(Hq=6) == 2                      # Hq % Hkv != 0
+    assert dec(Hq=12) == 2                     # group of 3 not supported
+    assert dec(D=100) == 2
+    assert dec(nl=1000) == 2
+    assert dec(ws=8) == 6
+    assert dec(lc=one) == 5
+    assert lib.sqa_decode_workspace_bytes(0) == 0 and lib.sqa_decode_workspace_bytes(32) >= 256 + 32 * 56
+    assert lib.sqa_kept_idx_sorted(None, 1, 1, p, None) == 1
+    assert lib.sqa_prefill_scores(p, p, 1, 1, 6, 4, 16, 128, p, p, 1 << 20, None) == 2
+    lib.sqa_status_str.restype = C.c_char_p
+    assert lib.sqa_status_str(5) == b"bad budget"

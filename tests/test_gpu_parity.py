@@ -1,0 +1,313 @@
+"""GPU parity: the HIP library against the CPU oracle, element by element, on
+the same seeded inputs.  Everything here goes through the C ABI (binding.py is
+argument marshalling only).  Tolerances: 1e-5 relative for fp32 inputs, 2e-2
+for bf16 (per output vector, max|x-ref|/max|ref|); kept indices, lengths and
+budgets bit-exact."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import sqa_oracle as O
+from oracle import pipeline as OP
+from paper_2404_04793_amd import workloads as W
+from tests.harness import TOL, export_state, import_state, np64, rel_err, round_scores_f32
+
+pytestmark = pytest.mark.gpu
+
+DEV = "cuda:0"
+
+
+@pytest.fixture(scope="module")
+def sqa():
+    from paper_2404_04793_amd import binding
+    return binding
+
+
+def _cos_rel(c, ref):
+    return float(np.max(np.abs(c - ref) / np.maximum(np.abs(ref), 1e-3)))
+
+
+# ---------------------------------------------------------------- importance
+
+@pytest.mark.parametrize("dtype,L,T,d", [("f32", 4, 256, 256), ("bf16", 3, 1037, 4096), ("bf16", 2, 37, 328),
+                                          ("f32", 1, 5, 8), ("bf16", 1, 4099, 512)])
+def test_layer_importance(sqa, dtype, L, T, d):
+    wl = W.scaled(W.WORKLOADS["tiny"], L=L, hidden=d, dtype=dtype, B=1, P=T)
+    hs = [W.hidden_states(wl, l, DEV) for l in range(L)]
+    h_in = torch.stack([x[0] for x in hs]).contiguous()
+    h_out = torch.stack([x[1] for x in hs]).contiguous()
+    cos = sqa.layer_importance(h_in, h_out).cpu().numpy().astype(np.float64)
+    ref = O.layer_importance(np64(h_in), np64(h_out))
+    assert _cos_rel(cos, ref) < TOL[dtype] if dtype == "f32" else _cos_rel(cos, ref) < 1e-5
+    # run-to-run identical bytes
+    again = sqa.layer_importance(h_in, h_out).cpu().numpy()
+    assert np.array_equal(again.view(np.uint32), cos.astype(np.float32).view(np.uint32))
+
+
+def test_layer_importance_closed_forms(sqa):
+    a = torch.randn(2, 64, 128, device=DEV)
+    z = a.clone(); z[0, 3] = 0
+    assert np.allclose(sqa.layer_importance(a, a).cpu().numpy(), 1.0, atol=1e-6)
+    assert np.allclose(sqa.layer_importance(a, -a).cpu().numpy(), -1.0, atol=1e-6)
+    c = sqa.layer_importance(z, a).cpu().numpy()
+    assert abs(c[0] - 63 / 64) < 1e-6 and abs(c[1] - 1) < 1e-6          # zero row contributes 0
+
+
+def test_tiny_budgets_from_gpu_cosines(sqa):
+    wl = W.WORKLOADS["tiny"]
+    hs = [W.hidden_states(wl, l, DEV) for l in range(wl.L)]
+    h_in = torch.stack([x[0] for x in hs]); h_out = torch.stack([x[1] for x in hs])
+    cos = sqa.layer_importance(h_in, h_out).cpu().numpy()
+    ref = O.layer_importance(np64(h_in), np64(h_out)).astype(np.float32)
+    got = sqa.allocate_budgets(cos, wl.total_budget, wl.p)
+    want = O.allocate_budgets(ref, wl.total_budget, wl.p)
+    assert got[0] == want[0] == [85, 17, 17, 85] and got[1] == want[1]
+
+
+# ---------------------------------------------------------------- prefill scores
+
+@pytest.mark.parametrize("dtype,B,Hq,Hkv,P,D", [("f32", 1, 2, 2, 100, 64), ("bf16", 2, 4, 2, 193, 128),
+                                                 ("f32", 1, 4, 1, 64, 128), ("bf16", 1, 1, 1, 1, 64),
+                                                 ("f32", 1, 1, 1, 257, 64)])
+def test_prefill_scores(sqa, dtype, B, Hq, Hkv, P, D):
+    wl = W.scaled(W.WORKLOADS["tiny"], L=1, Hq=Hq, Hkv=Hkv, D=D, B=B, P=P, dtype=dtype)
+    K, _ = W.prompt_kv(wl, 0, DEV)
+    Q = W.prompt_q(wl, 0, DEV)
+    got = sqa.prefill_scores(Q, K).cpu().numpy().astype(np.float64)
+    Qn, Kn = np64(Q), np64(K)
+    g = Hq // Hkv
+    for b in range(B):
+        for h in range(Hkv):
+            ref = O.prefill_scores(Qn[b, h * g:(h + 1) * g], Kn[b, h])
+            assert rel_err(got[b, h], ref) < TOL[dtype]
+            assert abs(got[b, h].sum() - g * P) < 1e-3 * g * P
+
+
+# ---------------------------------------------------------------- prefill compress
+
+def _mk_caches(sqa, budgets, caps, B, Hkv, D, dtype, h2o=True):
+    return sqa.LayerCaches(budgets, caps, B, Hkv, D, torch.float32 if dtype == "f32" else torch.bfloat16, DEV, h2o)
+
+
+@pytest.mark.parametrize("policy", ["sliding", "streaming", "h2o"])
+@pytest.mark.parametrize("dtype,B,Hkv,P,D,b", [("f32", 1, 2, 256, 64, 51), ("bf16", 2, 3, 700, 128, 143),
+                                                ("bf16", 1, 1, 64, 128, 64), ("f32", 1, 1, 40, 128, 100),
+                                                ("bf16", 1, 2, 1031, 64, 6), ("bf16", 1, 1, 513, 128, 512)])
+def test_prefill_compress(sqa, policy, dtype, B, Hkv, P, D, b):
+    wl = W.scaled(W.WORKLOADS["tiny"], L=1, Hq=Hkv, Hkv=Hkv, D=D, B=B, P=P, dtype=dtype)
+    K, V = W.prompt_kv(wl, 0, DEV)
+    r = np.random.default_rng(P + b)
+    sc = r.random((B, Hkv, P)).astype(np.float32)
+    sc[:, :, r.integers(0, P, size=P // 3)] = 0.25          # many exact ties
+    sc[:, :, r.integers(0, P, size=5)] = 0.0
+    scores = torch.from_numpy(sc).to(DEV)
+    caches = _mk_caches(sqa, [b], [max(min(P, b), 1) + 1], B, Hkv, D, dtype)
+    sqa.prefill_compress(K, V, scores if policy == "h2o" else None, policy, 4, caches, 0)
+    kept = sqa.kept_idx_sorted(caches, 0).cpu().numpy()
+    Kn, Vn = np64(K), np64(V)
+    for bi in range(B):
+        for h in range(Hkv):
+            want = O.prefill_compress(Kn[bi, h], Vn[bi, h], sc[bi, h].astype(np.float64), b, policy, 4)
+            n = len(want["pos"])
+            assert int(caches.lens[0][bi, h]) == n and int(caches.head[0][bi, h]) == 0
+            assert kept[bi, h, :n].tolist() == want["pos"].tolist() and np.all(kept[bi, h, n:] == -1)
+            got = export_state(caches, 0, bi, h)
+            assert caches.pos[0][bi, h, :n].cpu().tolist() == want["pos"].tolist()   # ascending slots
+            assert np.array_equal(got["K"], want["K"]) and np.array_equal(got["V"], want["V"])
+            if policy == "h2o":
+                assert np.array_equal(got["score"], want["score"])
+
+
+def test_prefill_compress_large_prompt_h2o_global_keys(sqa):
+    """More candidates than the LDS staging limit: the select reads scores from memory."""
+    B, Hkv, P, D, b = 1, 1, 20000, 64, 300
+    K = torch.randn(B, Hkv, P, D, device=DEV).to(torch.bfloat16); V = K.clone()
+    sc = np.random.default_rng(1).integers(0, 50, size=(B, Hkv, P)).astype(np.float32) / 8
+    caches = _mk_caches(sqa, [b], [b], B, Hkv, D, "bf16")
+    sqa.prefill_compress(K, V, torch.from_numpy(sc).to(DEV), "h2o", 4, caches, 0)
+    keep = O.select_keep(np.arange(P), sc[0, 0].astype(np.float64), b, "h2o")
+    assert caches.pos[0][0, 0, :b].cpu().tolist() == keep.tolist()
+
+
+# ---------------------------------------------------------------- decode step, teacher forced
+
+def _unit_inputs(wl, layer, u_dirs, mask):
+    K, V = W.prompt_kv(wl, layer, DEV, u_dirs, mask)
+    Q = W.prompt_q(wl, layer, DEV, u_dirs)
+    q, k, v = W.decode_qkv(wl, layer, DEV, u_dirs, mask)
+    return K, V, Q, q, k, v
+
+
+CASES = [
+    # name, dtype, L, Hq, Hkv, D, B, P, S, policy, budgets
+    ("h2o_f32_mha", "f32", 2, 2, 2, 64, 1, 40, 12, "h2o", [9, 46]),
+    ("h2o_bf16_mha_ragged", "bf16", 2, 3, 3, 128, 2, 150, 10, "h2o", [37, 155]),
+    ("h2o_bf16_gqa2", "bf16", 1, 4, 2, 128, 1, 70, 8, "h2o", [21]),
+    ("stream_bf16_gqa4", "bf16", 2, 8, 2, 128, 2, 90, 9, "streaming", [13, 95]),
+    ("slide_bf16_gqa8", "bf16", 2, 8, 1, 128, 1, 300, 7, "sliding", [67, 303]),
+    ("slide_f32_d128", "f32", 1, 2, 2, 128, 1, 33, 6, "sliding", [5]),
+    ("stream_f32_d64_gqa2", "f32", 1, 4, 2, 64, 1, 50, 6, "streaming", [11]),
+    ("h2o_bf16_d64", "bf16", 1, 2, 2, 64, 1, 80, 6, "h2o", [2]),
+]
+
+
+@pytest.mark.parametrize("case", CASES, ids=[c[0] for c in CASES])
+def test_decode_teacher_forced(sqa, case):
+    name, dtype, L, Hq, Hkv, D, B, P, S, policy, budgets = case
+    wl = W.scaled(W.WORKLOADS["tiny"], L=L, Hq=Hq, Hkv=Hkv, D=D, B=B, P=P, S=S, dtype=dtype, policy=policy)
+    g = Hq // Hkv
+    u_dirs, mask = W.unit_dirs(wl), W.hh_mask(wl, DEV)
+    inp = [_unit_inputs(wl, l, u_dirs, mask) for l in range(L)]
+    caps = [min(b, P + S) for b in budgets]
+    caches = _mk_caches(sqa, budgets, caps, B, Hkv, D, dtype)
+    ws = sqa.decode_workspace(L, DEV)
+    # oracle trajectories (fp32-rounded score storage between steps)
+    state = {}
+    for l in range(L):
+        Kn, Vn, Qn = np64(inp[l][0]), np64(inp[l][1]), np64(inp[l][2])
+        for b in range(B):
+            for h in range(Hkv):
+                s0 = O.prefill_scores(Qn[b, h * g:(h + 1) * g], Kn[b, h]).astype(np.float32).astype(np.float64)
+                state[l, b, h] = O.prefill_compress(Kn[b, h], Vn[b, h], s0, budgets[l], policy, wl.n_sink)
+    q_all = torch.stack([inp[l][3] for l in range(L)], 1).contiguous()      # [S, L, B, Hq, D]
+    k_all = torch.stack([inp[l][4] for l in range(L)], 1).contiguous()
+    v_all = torch.stack([inp[l][5] for l in range(L)], 1).contiguous()
+    qn, kn, vn = np64(q_all), np64(k_all), np64(v_all)
+    out = torch.empty(L, B, Hq, D, dtype=wl.torch_dtype, device=DEV)
+    worst = 0.0
+    for t in range(S):
+        for key, c in state.items():
+            import_state(caches, key[0], key[1], key[2], c)
+        sqa.decode_step(q_all[t], k_all[t], v_all[t], P + t, policy, wl.n_sink, caches, out, ws)
+        assert sqa.read_device_status(ws) == 0
+        o = np64(out)
+        for (l, b, h), c in state.items():
+            want_out, c2 = O.decode_step(c, qn[t, l, b, h * g:(h + 1) * g], kn[t, l, b, h], vn[t, l, b, h],
+                                         P + t, budgets[l], policy, wl.n_sink)
+            got = export_state(caches, l, b, h)
+            assert got["pos"].tolist() == c2["pos"].tolist(), (name, t, l, b, h)
+            assert np.array_equal(got["K"], c2["K"]) and np.array_equal(got["V"], c2["V"])
+            worst = max(worst, rel_err(o[l, b, h * g:(h + 1) * g], want_out))
+            if policy == "h2o":
+                assert rel_err(got["score"][None], c2["score"][None]) < TOL[dtype], (name, t, l, b, h)
+            state[l, b, h] = round_scores_f32(c2)
+    assert worst < TOL[dtype], (name, worst)
+
+
+def test_decode_tie_breaking_and_leaver_cases(sqa):
+    """Hand-built H2O states: all-equal scores (evict the highest position among
+    the non-recent, i.e. the ring leaver), leaver better than the worst heavy
+    hitter (it moves), and exact ties inside the heavy region."""
+    D, b = 64, 8                                # hh 4, recent 4
+    r = np.random.default_rng(0)
+    for scores in ([0.5] * 8, [0.9, 0.1, 0.1, 0.7, 0.3, 0.2, 0.2, 0.2], [0.9, 0.4, 0.6, 0.7, 0.3, 0.2, 0.2, 0.2],
+                   [0.3, 0.3, 0.3, 0.3, 0.3, 0.0, 0.0, 0.0], [0.0] * 8):
+        c = {"K": r.standard_normal((8, D)), "V": r.standard_normal((8, D)),
+             "pos": np.array([0, 3, 5, 9, 20, 21, 22, 23]), "score": np.array(scores, dtype=np.float64)}
+        c["K"] = c["K"].astype(np.float32).astype(np.float64); c["V"] = c["V"].astype(np.float32).astype(np.float64)
+        caches = _mk_caches(sqa, [b], [b], 1, 1, D, "f32")
+        import_state(caches, 0, 0, 0, c)
+        q = torch.randn(1, 1, 1, D, device=DEV); k = torch.randn(1, 1, 1, D, device=DEV); v = torch.randn(1, 1, 1, D, device=DEV)
+        out = torch.empty_like(q); ws = sqa.decode_workspace(1, DEV)
+        sqa.decode_step(q, k, v, 24, "h2o", 4, caches, out, ws)
+        want_out, c2 = O.decode_step(c, np64(q)[0, 0], np64(k)[0, 0, 0], np64(v)[0, 0, 0], 24, b, "h2o")
+        got = export_state(caches, 0, 0, 0)
+        assert got["pos"].tolist() == c2["pos"].tolist(), scores
+        assert rel_err(np64(out)[0, 0], want_out) < 1e-5 and rel_err(got["score"][None], c2["score"][None]) < 1e-5
+
+
+def test_decode_free_running_tiny(sqa):
+    """configs[0] end to end on the GPU alone: probe -> budgets -> prompt scores
+    -> compress -> 16 decode steps, against the oracle run on its own in fp64."""
+    wl = W.WORKLOADS["tiny"]
+    g = wl.g
+    u_dirs, mask = W.unit_dirs(wl), W.hh_mask(wl, DEV)
+    hs = [W.hidden_states(wl, l, DEV) for l in range(wl.L)]
+    h_in = torch.stack([x[0] for x in hs]); h_out = torch.stack([x[1] for x in hs])
+    cos = sqa.layer_importance(h_in, h_out).cpu().numpy()
+    budgets, _ = sqa.allocate_budgets(cos, wl.total_budget, wl.p)
+    assert budgets == O.allocate_budgets(O.layer_importance(np64(h_in), np64(h_out)).astype(np.float32),
+                                         wl.total_budget, wl.p)[0]
+    caches = _mk_caches(sqa, budgets, budgets, wl.B, wl.Hkv, wl.D, wl.dtype)
+    inp = [_unit_inputs(wl, l, u_dirs, mask) for l in range(wl.L)]
+    for l in range(wl.L):
+        sc = sqa.prefill_scores(inp[l][2], inp[l][0])
+        sqa.prefill_compress(inp[l][0], inp[l][1], sc, wl.policy, wl.n_sink, caches, l)
+    q_all = torch.stack([inp[l][3] for l in range(wl.L)], 1).contiguous()
+    k_all = torch.stack([inp[l][4] for l in range(wl.L)], 1).contiguous()
+    v_all = torch.stack([inp[l][5] for l in range(wl.L)], 1).contiguous()
+    ws = sqa.decode_workspace(wl.L, DEV)
+    outs = []
+    kept = []
+    for t in range(wl.S):
+        out = torch.empty(wl.L, wl.B, wl.Hq, wl.D, dtype=wl.torch_dtype, device=DEV)
+        sqa.decode_step(q_all[t], k_all[t], v_all[t], wl.P + t, wl.policy, wl.n_sink, caches, out, ws)
+        outs.append(np64(out))
+        kept.append([sqa.kept_idx_sorted(caches, l).cpu().numpy() for l in range(wl.L)])
+    assert sqa.read_device_status(ws) == 0
+    qn, kn, vn = np64(q_all), np64(k_all), np64(v_all)
+    for l in range(wl.L):
+        Kn, Vn, Qn = np64(inp[l][0]), np64(inp[l][1]), np64(inp[l][2])
+        for h in range(wl.Hkv):
+            s0 = O.prefill_scores(Qn[0, h * g:(h + 1) * g], Kn[0, h])
+            o_ref, c, states, _ = OP.run_unit(Kn[0, h], Vn[0, h], s0, qn[:, l, 0, h * g:(h + 1) * g], kn[:, l, 0, h],
+                                              vn[:, l, 0, h], budgets[l], wl.policy, wl.n_sink, keep_states=True)
+            for t in range(wl.S):
+                n = len(states[t]["pos"])
+                assert kept[t][l][0, h, :n].tolist() == states[t]["pos"].tolist(), (l, h, t)
+                assert rel_err(outs[t][l, 0, h * g:(h + 1) * g], o_ref[t]) < 1e-5
+            got = export_state(caches, l, 0, h)
+            assert rel_err(got["score"][None], c["score"][None]) < 1e-5
+
+
+def test_decode_is_deterministic_and_per_layer_calls_agree(sqa):
+    """Same inputs twice -> identical bytes; one call over all layers == one call per layer
+    (with and without the device copy of the layer table)."""
+    wl = W.scaled(W.WORKLOADS["tiny"], L=3, Hq=4, Hkv=2, D=128, B=2, P=120, S=5, dtype="bf16")
+    budgets = [30, 125, 17]
+    u_dirs, mask = W.unit_dirs(wl), W.hh_mask(wl, DEV)
+    inp = [_unit_inputs(wl, l, u_dirs, mask) for l in range(wl.L)]
+    q_all = torch.stack([inp[l][3] for l in range(wl.L)], 1).contiguous()
+    k_all = torch.stack([inp[l][4] for l in range(wl.L)], 1).contiguous()
+    v_all = torch.stack([inp[l][5] for l in range(wl.L)], 1).contiguous()
+    results = []
+    for mode in ("all", "all", "per_layer", "per_layer_hosttable"):
+        caches = _mk_caches(sqa, budgets, budgets, wl.B, wl.Hkv, wl.D, wl.dtype)
+        for l in range(wl.L):
+            sqa.prefill_compress(inp[l][0], inp[l][1], sqa.prefill_scores(inp[l][2], inp[l][0]), "h2o", 4, caches, l)
+        ws = sqa.decode_workspace(wl.L, DEV)
+        outs = []
+        for t in range(wl.S):
+            out = torch.empty(wl.L, wl.B, wl.Hq, wl.D, dtype=wl.torch_dtype, device=DEV)
+            if mode == "all":
+                sqa.decode_step(q_all[t], k_all[t], v_all[t], wl.P + t, "h2o", 4, caches, out, ws)
+            else:
+                for l in range(wl.L):
+                    sqa.decode_step(q_all[t, l], k_all[t, l], v_all[t, l], wl.P + t, "h2o", 4, caches, out[l], ws,
+                                    layer0=l, n_layers=1, use_dev_table=(mode == "per_layer"))
+            outs.append(out)
+        assert sqa.read_device_status(ws) == 0
+        results.append((torch.stack(outs).view(torch.int16).cpu(), [s.clone().cpu() for s in caches.score],
+                        [p.clone().cpu() for p in caches.pos]))
+    for other in results[1:]:
+        assert torch.equal(results[0][0], other[0])
+        for a, b in zip(results[0][1], other[1]):
+            assert torch.equal(a.view(torch.int32), b.view(torch.int32))
+        for a, b in zip(results[0][2], other[2]):
+            assert torch.equal(a, b)
+
+
+def test_decode_reports_bad_state_without_touching_the_cache(sqa):
+    caches = _mk_caches(sqa, [4], [8], 1, 1, 64, "f32")
+    caches.lens[0][0, 0] = 6                      # longer than the budget on entry
+    q = torch.randn(1, 1, 1, 64, device=DEV); out = torch.ones_like(q)
+    ws = sqa.decode_workspace(1, DEV)
+    sqa.decode_step(q, q, q, 9, "sliding", 4, caches, out, ws)
+    assert sqa.read_device_status(ws) == 8        # SQA_ERR_STATE
+    assert int(caches.lens[0][0, 0]) == 6 and float(out.abs().sum()) == 0.0
+    sqa.clear_device_status(ws)
+    assert sqa.read_device_status(ws) == 0
+    caches2 = _mk_caches(sqa, [40], [3], 1, 1, 64, "f32")
+    caches2.lens[0][0, 0] = 3                     # no free slot
+    sqa.decode_step(q, q, q, 9, "sliding", 4, caches2, out, ws)
+    assert sqa.read_device_status(ws) == 6        # SQA_ERR_CAPACITY
