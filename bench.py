@@ -1,0 +1,159 @@
+#!/usr/bin/env python3
+"""Benchmark of the SqueezeAttention hot path on one MI355X.
+
+A "step" is one pass of the whole hot path over one synthetic batch that is
+already resident in HBM: layer-importance probe -> budgets (host) -> prompt
+compression of every layer -> S decode steps over all layers (append, evict,
+attend, accumulate).  value = generated tokens per second = B*S*steps / time.
+
+Prints ONE JSON line.  `roofline` is for the dominant kernel (the fused decode
+step): algorithmic bytes per launch / mean launch duration, measured with HIP
+events on the launch stream, against the 8 TB/s HBM peak.  `cpu_baseline` is
+the fp64 numpy oracle timed on this machine's host cores on a bounded sample.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+
+
+def cpu_baseline(sess, units_per_layer: int, steps: int):
+    """Time the oracle's decode step (Algorithm 1 steps 14-21) on a sample:
+    `units_per_layer` (sequence, KV head) units of every layer, `steps` steps."""
+    import numpy as np
+    import torch
+    from oracle import sqa_oracle as O
+    try:
+        from threadpoolctl import threadpool_limits
+    except Exception:  # pragma: no cover
+        threadpool_limits = None
+    wl = sess.wl
+    g = wl.g
+    f64 = lambda t: t.detach().cpu().to(torch.float64).numpy()
+    units = [(i // wl.Hkv % wl.B, i % wl.Hkv) for i in range(units_per_layer)]
+    ctx = threadpool_limits(limits=1) if threadpool_limits else None
+    t_total = 0.0
+    try:
+        for l in range(wl.L):
+            b_l = sess.budgets[l]
+            for (b, h) in units:
+                Kp, Vp = f64(sess.Kp[l][b, h]), f64(sess.Vp[l][b, h])
+                # untimed set-up with a stand-in score vector: which prompt tokens
+                # are kept does not change what a decode step costs
+                s0 = np.linspace(0.0, 1.0, wl.P)
+                c = O.prefill_compress(Kp, Vp, s0, b_l, wl.policy, wl.n_sink)
+                q = f64(sess.q[:steps, l, b, h * g:(h + 1) * g])
+                k = f64(sess.k_new[:steps, l, b, h]); v = f64(sess.v_new[:steps, l, b, h])
+                t0 = time.perf_counter()
+                for t in range(steps):
+                    _, c = O.decode_step(c, q[t], k[t], v[t], wl.P + t, b_l, wl.policy, wl.n_sink)
+                t_total += time.perf_counter() - t0
+    finally:
+        if ctx is not None:
+            ctx.__exit__(None, None, None)
+    frac = units_per_layer / float(wl.B * wl.Hkv)
+    est_step_s = t_total / steps / frac                 # one decode step of the whole batch
+    return {"value": wl.B / est_step_s, "unit": "tokens/s", "cores": 1, "kind": "oracle",
+            "sample": "%d of %d units of each of %d layers, first %d decode steps, %.1f s of CPU"
+                      % (units_per_layer, wl.B * wl.Hkv, wl.L, steps, t_total)}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=5)
+    ap.add_argument("--warmup", type=int, default=1)
+    ap.add_argument("--workload", default="llama2_7b")
+    ap.add_argument("--per-layer", action="store_true", help="one decode launch per layer instead of one per step")
+    ap.add_argument("--uniform", action="store_true", help="sequence-only baseline: same budget in every layer")
+    ap.add_argument("--full-cache", action="store_true", help="no compression (budget = P + S)")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the oracle timing leg")
+    ap.add_argument("--cpu-units", type=int, default=32)
+    ap.add_argument("--cpu-steps", type=int, default=128)
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2404_04793_amd import workloads as W
+    from paper_2404_04793_amd.session import Session
+
+    wl = W.WORKLOADS[args.workload]
+    torch.cuda.set_device(0)
+    sess = Session(wl, "cuda:0", uniform_budget=args.uniform, full_cache=args.full_cache)
+
+    def one_pass(ev=None):
+        if ev:
+            ev[0].record()
+        cos = sess.probe_and_allocate()
+        if ev:
+            ev[1].record()
+        sess.compress_prompt()
+        if ev:
+            ev[2].record()
+        sess.decode(per_layer=args.per_layer)
+        if ev:
+            ev[3].record()
+        return cos
+
+    for _ in range(args.warmup):
+        one_pass()
+    torch.cuda.synchronize()
+    evs = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(args.steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        cos = one_pass(evs[i])
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+
+    from paper_2404_04793_amd import binding as sqa
+    status = sqa.read_device_status(sess.dec_ws)
+    probe_ms = sum(e[0].elapsed_time(e[1]) for e in evs) / args.steps
+    comp_ms = sum(e[1].elapsed_time(e[2]) for e in evs) / args.steps
+    dec_ms = sum(e[2].elapsed_time(e[3]) for e in evs) / args.steps
+    launches = wl.S * (wl.L if args.per_layer else 1)
+    bytes_steps = sess.decode_bytes_per_step()
+    bytes_launch = sum(bytes_steps) / float(launches)
+    launch_s = dec_ms * 1e-3 / launches
+    achieved = bytes_launch / launch_s / 1e9
+    tokens = wl.B * wl.S * args.steps
+    res = {
+        "metric": "decode tokens/s + achieved HBM GB/s (attn+evict), 7B shape, 1 GPU",
+        "value": tokens / dt, "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": dt * 1e3 / args.steps, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": wl.dtype, "data": "synthetic",
+        "config": {"workload": wl.name, "layers": wl.L, "q_heads": wl.Hq, "kv_heads": wl.Hkv, "head_dim": wl.D,
+                   "batch": wl.B, "prompt": wl.P, "decode_steps": wl.S, "policy": wl.policy,
+                   "budget_pct": wl.budget_pct, "p": wl.p,
+                   "mode": "full_cache" if args.full_cache else ("uniform" if args.uniform else "squeeze"),
+                   "launch": "per_layer" if args.per_layer else "all_layers"},
+        "roofline": {"bound": "hbm", "kernel": "decode_unit_kernel", "achieved": achieved, "peak": HBM_PEAK_GBS,
+                     "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": None,
+                     "bytes_per_launch": bytes_launch, "launch_us": launch_s * 1e6},
+        "phases_ms": {"probe_and_budgets": probe_ms, "prefill_compress": comp_ms, "decode": dec_ms},
+        "decode_only_tokens_per_s": wl.B * wl.S / (dec_ms * 1e-3),
+        "probe_GBps": sess.probe_bytes() / (probe_ms * 1e-3) / 1e9,
+        "compress_GBps": sess.compress_bytes() / (comp_ms * 1e-3) / 1e9,
+        "budgets": {"low": min(sess.budgets), "high": max(sess.budgets),
+                    "n_G3": sum(1 for g in sess.groups if g == 2), "sum": sum(sess.budgets)},
+        "resident_kv_GB": sess.resident_kv_bytes() / 1e9,
+        "device_status": status,
+    }
+    if not args.no_cpu:
+        res["cpu_baseline"] = cpu_baseline(sess, args.cpu_units, min(args.cpu_steps, wl.S))
+    print(json.dumps(res))
+
+
+if __name__ == "__main__":
+    main()

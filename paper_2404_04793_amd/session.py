@@ -1,0 +1,137 @@
+"""One synthetic generation job on one GPU, driven through the binding:
+inputs resident in HBM, then Algorithm 1 end to end -- probe, budgets, prompt
+compression, S decode steps.  Used by bench.py and the full-size parity tests;
+holds no arithmetic of the method (that is all in libsqa)."""
+from __future__ import annotations
+
+from typing import Dict, List, Optional
+
+import torch
+
+from . import binding as sqa
+from . import workloads as W
+
+
+class Session:
+    def __init__(self, wl: W.Workload, device="cuda:0", keep_prompt_q: bool = False, uniform_budget: bool = False,
+                 full_cache: bool = False):
+        self.wl, self.dev = wl, device
+        self.uniform_budget, self.full_cache = uniform_budget, full_cache
+        self.u, self.mask = W.unit_dirs(wl), W.hh_mask(wl, device)
+        L = wl.L
+        # hidden states before / after self-attention, all layers: [L, T, hidden]
+        T = wl.B * wl.P
+        self.h_in = torch.empty(L, T, wl.hidden, dtype=wl.torch_dtype, device=device)
+        self.h_out = torch.empty_like(self.h_in)
+        for l in range(L):
+            a, b = W.hidden_states(wl, l, device)
+            self.h_in[l], self.h_out[l] = a, b
+        # prompt K, V (kept resident: every pass compresses them again) and H2O prompt scores
+        self.Kp, self.Vp, self.scores, self.Qp = [], [], [], []
+        for l in range(L):
+            K, V = W.prompt_kv(wl, l, device, self.u, self.mask)
+            self.Kp.append(K); self.Vp.append(V)
+            if wl.policy == "h2o":
+                Q = W.prompt_q(wl, l, device, self.u)
+                self.scores.append(sqa.prefill_scores(Q, K))
+                if keep_prompt_q:
+                    self.Qp.append(Q)
+                del Q
+            else:
+                self.scores.append(None)
+        # decode inputs for all steps: [S, L, B, H, D]
+        self.q = torch.empty(wl.S, L, wl.B, wl.Hq, wl.D, dtype=wl.torch_dtype, device=device)
+        self.k_new = torch.empty(wl.S, L, wl.B, wl.Hkv, wl.D, dtype=wl.torch_dtype, device=device)
+        self.v_new = torch.empty_like(self.k_new)
+        for l in range(L):
+            q, k, v = W.decode_qkv(wl, l, device, self.u, self.mask)
+            self.q[:, l], self.k_new[:, l], self.v_new[:, l] = q, k, v
+        self.out = torch.empty(wl.S, L, wl.B, wl.Hq, wl.D, dtype=wl.torch_dtype, device=device)
+        self.cos_dev = torch.empty(L, dtype=torch.float32, device=device)
+        self.cos_host = torch.empty(L, dtype=torch.float32, pin_memory=True)
+        n = sqa._lib.sqa_layer_importance_workspace_bytes(L, T, wl.hidden)
+        self.imp_ws = torch.empty(max(n, 8), dtype=torch.uint8, device=device)
+        self.dec_ws = sqa.decode_workspace(L, device)
+        self.caches: Optional[sqa.LayerCaches] = None
+        self.budgets: Optional[List[int]] = None
+        self.groups: Optional[List[int]] = None
+        torch.cuda.synchronize()
+
+    # -- Algorithm 1 steps 1-11 ------------------------------------------------
+    def probe_and_allocate(self):
+        wl = self.wl
+        sqa.layer_importance(self.h_in, self.h_out, self.cos_dev, self.imp_ws)
+        self.cos_host.copy_(self.cos_dev, non_blocking=False)
+        cos = self.cos_host.tolist()
+        if self.full_cache:
+            budgets, groups = [wl.P + wl.S] * wl.L, [1] * wl.L
+        elif self.uniform_budget:
+            budgets, groups = sqa.allocate_budgets(cos, wl.total_budget, 1.0)
+        else:
+            budgets, groups = sqa.allocate_budgets(cos, wl.total_budget, wl.p)
+        if self.caches is None or budgets != self.budgets:
+            caps = [min(b, wl.P + wl.S) for b in budgets]
+            self.caches = sqa.LayerCaches(budgets, caps, wl.B, wl.Hkv, wl.D, wl.torch_dtype, self.dev,
+                                          wl.policy == "h2o")
+        self.budgets, self.groups = budgets, groups
+        return cos
+
+    # -- steps 12 + 16-17 on the prompt ---------------------------------------
+    def compress_prompt(self):
+        wl = self.wl
+        for l in range(wl.L):
+            sqa.prefill_compress(self.Kp[l], self.Vp[l], self.scores[l], wl.policy, wl.n_sink, self.caches, l)
+
+    # -- steps 14-21 -----------------------------------------------------------
+    def decode(self, steps: Optional[int] = None, per_layer: bool = False, start: int = 0):
+        wl = self.wl
+        S = wl.S if steps is None else steps
+        for t in range(start, start + S):
+            if per_layer:
+                for l in range(wl.L):
+                    sqa.decode_step(self.q[t, l], self.k_new[t, l], self.v_new[t, l], wl.P + t, wl.policy, wl.n_sink,
+                                    self.caches, self.out[t, l], self.dec_ws, layer0=l, n_layers=1)
+            else:
+                sqa.decode_step(self.q[t], self.k_new[t], self.v_new[t], wl.P + t, wl.policy, wl.n_sink,
+                                self.caches, self.out[t], self.dec_ws)
+
+    def run_pass(self):
+        """The whole hot path once over this batch."""
+        self.probe_and_allocate()
+        self.compress_prompt()
+        self.decode()
+
+    # -- accounting (bytes the method must move; Sec. 2.1 KV size model) --------
+    def decode_bytes_per_step(self) -> List[int]:
+        """Algorithmic HBM bytes of each decode step: kept K and V rows read once,
+        8 bytes of score per kept token under H2O, the appended rows, q in and out."""
+        wl = self.wl
+        e, row = wl.elem_bytes, wl.D * wl.elem_bytes
+        units = wl.B * wl.Hkv
+        out = []
+        for t in range(wl.S):
+            tot = 0
+            for b in self.budgets:
+                n = min(wl.P + t + 1, b)
+                tot += units * (n * 2 * row + (8 * n if wl.policy == "h2o" else 0) + 2 * row)
+            tot += wl.L * wl.B * wl.Hq * wl.D * e * 2
+            out.append(tot)
+        return out
+
+    def probe_bytes(self) -> int:
+        wl = self.wl
+        return 2 * wl.L * wl.B * wl.P * wl.hidden * wl.elem_bytes
+
+    def compress_bytes(self) -> int:
+        wl = self.wl
+        row = wl.D * wl.elem_bytes
+        tot = 0
+        for b in self.budgets:
+            n = min(wl.P, b)
+            tot += wl.B * wl.Hkv * ((4 * wl.P if wl.policy == "h2o" else 0) + 2 * 2 * n * row)
+        return tot
+
+    def resident_kv_bytes(self) -> int:
+        wl = self.wl
+        per_slot = 2 * wl.D * wl.elem_bytes + (8 if wl.policy == "h2o" else 4)
+        return sum(wl.B * wl.Hkv * c * per_slot for c in self.caches.capacities)
