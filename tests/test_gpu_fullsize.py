@@ -1,0 +1,132 @@
+"""Full-size parity in the launch configuration bench.py times (one decode
+launch over all layers of the workload), on sampled outputs the oracle can
+compute one by one, teacher-forced per step: the oracle's state before step t
+(scores rounded once to the fp32 the accumulator stores) is imported into the
+sampled units, the GPU runs the step for the WHOLE batch, and the sampled
+units are compared.  Plus properties that hold for every unit at any size."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import sqa_oracle as O
+from paper_2404_04793_amd import workloads as W
+from tests.harness import TOL, export_state, import_state, np64, rel_err, round_scores_f32
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+
+def _run_fullsize(wl, sample_layers, units, check_steps, cos_layers):
+    from paper_2404_04793_amd import binding as sqa
+    from paper_2404_04793_amd.session import Session
+    sess = Session(wl, DEV, keep_prompt_q=True)
+    g, tol = wl.g, TOL[wl.dtype]
+
+    # ---- probe + budgets --------------------------------------------------
+    cos = np.array(sess.probe_and_allocate(), dtype=np.float32)
+    for l in cos_layers:
+        ref = O.layer_importance(np64(sess.h_in[l:l + 1]), np64(sess.h_out[l:l + 1]))[0]
+        assert abs(float(cos[l]) - ref) / max(abs(ref), 1e-3) < 1e-5, (l, cos[l], ref)
+    want_b, want_g = O.allocate_budgets(cos, wl.total_budget, wl.p)
+    assert sess.budgets == want_b and sess.groups == want_g and sum(want_b) == wl.total_budget
+    budgets = sess.budgets
+
+    # ---- prompt scores + compression on sampled units -----------------------
+    sample = [(l, b, h) for l in sample_layers for (b, h) in units]
+    state = {}
+    for (l, b, h) in sample:
+        Kn, Vn = np64(sess.Kp[l][b, h]), np64(sess.Vp[l][b, h])
+        if wl.policy == "h2o":
+            s_ref = O.prefill_scores(np64(sess.Qp[l][b, h * g:(h + 1) * g]), Kn)
+            assert rel_err(np64(sess.scores[l][b, h])[None], s_ref[None]) < tol
+            s32 = s_ref.astype(np.float32)
+            sess.scores[l][b, h] = torch.from_numpy(s32).to(DEV)      # both sides select on these
+            s0 = s32.astype(np.float64)
+        else:
+            s0 = np.zeros(wl.P)
+        state[l, b, h] = O.prefill_compress(Kn, Vn, s0, budgets[l], wl.policy, wl.n_sink)
+    sess.compress_prompt()
+    for key, c in state.items():
+        got = export_state(sess.caches, *key)
+        assert got["pos"].tolist() == c["pos"].tolist(), key
+        assert np.array_equal(got["K"], c["K"]) and np.array_equal(got["V"], c["V"])
+        if wl.policy == "h2o":
+            assert np.array_equal(got["score"], c["score"])
+    for l in range(wl.L):
+        assert bool((sess.caches.lens[l] == min(wl.P, budgets[l])).all())
+
+    # ---- decode: GPU runs every step for the whole batch; sampled units are
+    # teacher-forced at check_steps ------------------------------------------
+    qn = {k: np64(sess.q[:, k[0], k[1], k[2] * g:(k[2] + 1) * g]) for k in sample}
+    kn = {k: np64(sess.k_new[:, k[0], k[1], k[2]]) for k in sample}
+    vn = {k: np64(sess.v_new[:, k[0], k[1], k[2]]) for k in sample}
+    worst_out = 0.0
+    for t in range(wl.S):
+        if t in check_steps:
+            for key, c in state.items():
+                import_state(sess.caches, key[0], key[1], key[2], c)
+        sess.decode(steps=1, start=t)
+        for key in sample:
+            want_out, c2 = O.decode_step(state[key], qn[key][t], kn[key][t], vn[key][t], wl.P + t, budgets[key[0]],
+                                         wl.policy, wl.n_sink)
+            state[key] = round_scores_f32(c2)
+            if t in check_steps:
+                l, b, h = key
+                got = export_state(sess.caches, l, b, h)
+                assert got["pos"].tolist() == c2["pos"].tolist(), (key, t)
+                assert np.array_equal(got["K"], c2["K"]) and np.array_equal(got["V"], c2["V"]), (key, t)
+                worst_out = max(worst_out, rel_err(np64(sess.out[t, l, b, h * g:(h + 1) * g]), want_out))
+                if wl.policy == "h2o":
+                    assert rel_err(got["score"][None], c2["score"][None]) < tol, (key, t)
+    assert worst_out < tol, worst_out
+    assert sqa.read_device_status(sess.dec_ws) == 0
+
+    # ---- properties of every unit -------------------------------------------
+    end = wl.P + wl.S
+    for l in range(wl.L):
+        n = min(end, budgets[l])
+        assert bool((sess.caches.lens[l] == n).all()), l
+        kept = sqa.kept_idx_sorted(sess.caches, l)[:, :, :n].to(torch.int64)
+        assert bool((kept[:, :, 1:] > kept[:, :, :-1]).all())           # unique, ascending
+        assert int(kept.min()) >= 0 and int(kept.max()) == end - 1
+        if n == budgets[l]:
+            if wl.policy == "sliding":
+                rec = n
+            elif wl.policy == "streaming":
+                rec = n - wl.n_sink
+                assert bool((kept[:, :, :wl.n_sink] == torch.arange(wl.n_sink, device=DEV)).all())  # sinks stay
+            else:
+                rec = n - n // 2
+            want = torch.arange(end - rec, end, device=DEV)
+            assert bool((kept[:, :, n - rec:] == want).all()), l           # the recent window
+    assert bool(torch.isfinite(sess.out.float()).all())
+    if wl.policy == "h2o":
+        for l in range(wl.L):
+            tot = sess.caches.score[l][:, :, :min(end, budgets[l])].double().sum(-1)
+            assert bool((tot <= g * end * (1 + 1e-4)).all()) and bool((tot > 0).all())
+
+
+def test_llama2_7b_full_size():
+    """configs[1] exactly as bench.py runs it."""
+    wl = W.WORKLOADS["llama2_7b"]
+    _run_fullsize(wl, sample_layers=[0, 5, 17, 31], units=[(0, 0), (7, 31)],
+                  check_steps={0, 1, 2, 100, 222, 223, 224, 225, 255}, cos_layers=[0, 16, 31])
+
+
+def test_mistral_7b_gqa_streaming_reduced_batch():
+    """configs[2] at batch 4 (prompt, heads, budgets and decode length as given)."""
+    wl = W.scaled(W.WORKLOADS["mistral_7b"], B=4, S=64)
+    _run_fullsize(wl, sample_layers=[0, 9, 20], units=[(0, 0), (3, 7)], check_steps={0, 1, 31, 63}, cos_layers=[1, 20])
+
+
+def test_llama2_70b_gqa8_sliding_reduced():
+    """configs[3] at batch 2, 40 layers, 32 decode steps (head shape, prompt and budgets as given)."""
+    wl = W.scaled(W.WORKLOADS["llama2_70b"], B=2, S=32, L=40, hidden=2048)
+    _run_fullsize(wl, sample_layers=[0, 20, 39], units=[(0, 0), (1, 7)], check_steps={0, 1, 31}, cos_layers=[0, 39])
+
+
+def test_stress_7b_reduced_batch():
+    """configs[4] at batch 16, 128 decode steps (short prompt, small budgets: 35 / 571)."""
+    wl = W.scaled(W.WORKLOADS["stress_7b"], B=16, S=128)
+    _run_fullsize(wl, sample_layers=[0, 12, 30], units=[(0, 0), (15, 31)], check_steps={0, 1, 59, 60, 61, 127},
+                  cos_layers=[0, 12])
