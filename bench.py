@@ -77,6 +77,9 @@ def main():
     ap.add_argument("--uniform", action="store_true", help="sequence-only baseline: same budget in every layer")
     ap.add_argument("--full-cache", action="store_true", help="no compression (budget = P + S)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the oracle timing leg")
+    ap.add_argument("--calib-copy", action="store_true",
+                    help="after the timed region run one plain 1 GiB -> 1 GiB elementwise copy kernel "
+                         "(reference point for scaling rocprofv3's FETCH_SIZE / WRITE_SIZE counters)")
     ap.add_argument("--cpu-units", type=int, default=32)
     ap.add_argument("--cpu-steps", type=int, default=128)
     args = ap.parse_args()
@@ -116,6 +119,13 @@ def main():
         cos = one_pass(evs[i])
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
+
+    if args.calib_copy:
+        src = torch.ones(1 << 28, dtype=torch.float32, device="cuda:0")
+        dst = torch.empty_like(src)
+        torch.mul(src, 1.0, out=dst)          # reads 2^30 bytes, writes 2^30 bytes
+        torch.cuda.synchronize()
+        del src, dst
 
     from paper_2404_04793_amd import binding as sqa
     status = sqa.read_device_status(sess.dec_ws)

@@ -218,8 +218,8 @@ __global__ __launch_bounds__(kDecThreads) void decode_unit_kernel(const DecodeAr
       const char* vp = Vb + (int64_t)sl * ROWB;
       if (sl == moved_to) { kp = Kb + (int64_t)slot_new * ROWB; vp = Vb + (int64_t)slot_new * ROWB; }
       if (sl == slot_new) { kp = knew; vp = vnew; }
-      kf[uu] = ld16(kp + c * 16);
-      vf[uu] = ld16(vp + c * 16);
+      kf[uu] = ld16_nt(kp + c * 16);
+      vf[uu] = ld16_nt(vp + c * 16);
     }
     float s[kUnroll][G];
 #pragma unroll

@@ -57,15 +57,15 @@ __global__ __launch_bounds__(kImpThreads) void importance_partial_kernel(
     float ab = 0.f, aa = 0.f, bb = 0.f;
     int c = lane;
     for (; c + 3 * SQA_WAVE < chunks; c += 4 * SQA_WAVE) {      // 8 loads in flight per lane
-      const uint4 a0 = ld16(a + (int64_t)c * 16), b0 = ld16(b + (int64_t)c * 16);
-      const uint4 a1 = ld16(a + (int64_t)(c + SQA_WAVE) * 16), b1 = ld16(b + (int64_t)(c + SQA_WAVE) * 16);
-      const uint4 a2 = ld16(a + (int64_t)(c + 2 * SQA_WAVE) * 16), b2 = ld16(b + (int64_t)(c + 2 * SQA_WAVE) * 16);
-      const uint4 a3 = ld16(a + (int64_t)(c + 3 * SQA_WAVE) * 16), b3 = ld16(b + (int64_t)(c + 3 * SQA_WAVE) * 16);
+      const uint4 a0 = ld16_nt(a + (int64_t)c * 16), b0 = ld16_nt(b + (int64_t)c * 16);
+      const uint4 a1 = ld16_nt(a + (int64_t)(c + SQA_WAVE) * 16), b1 = ld16_nt(b + (int64_t)(c + SQA_WAVE) * 16);
+      const uint4 a2 = ld16_nt(a + (int64_t)(c + 2 * SQA_WAVE) * 16), b2 = ld16_nt(b + (int64_t)(c + 2 * SQA_WAVE) * 16);
+      const uint4 a3 = ld16_nt(a + (int64_t)(c + 3 * SQA_WAVE) * 16), b3 = ld16_nt(b + (int64_t)(c + 3 * SQA_WAVE) * 16);
       Dots<T>::acc(a0, b0, ab, aa, bb); Dots<T>::acc(a1, b1, ab, aa, bb);
       Dots<T>::acc(a2, b2, ab, aa, bb); Dots<T>::acc(a3, b3, ab, aa, bb);
     }
     for (; c < chunks; c += SQA_WAVE) {
-      const uint4 a0 = ld16(a + (int64_t)c * 16), b0 = ld16(b + (int64_t)c * 16);
+      const uint4 a0 = ld16_nt(a + (int64_t)c * 16), b0 = ld16_nt(b + (int64_t)c * 16);
       Dots<T>::acc(a0, b0, ab, aa, bb);
     }
     ab = wave_sum(ab); aa = wave_sum(aa); bb = wave_sum(bb);
