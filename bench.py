@@ -76,6 +76,8 @@ def main():
     ap.add_argument("--per-layer", action="store_true", help="one decode launch per layer instead of one per step")
     ap.add_argument("--uniform", action="store_true", help="sequence-only baseline: same budget in every layer")
     ap.add_argument("--full-cache", action="store_true", help="no compression (budget = P + S)")
+    ap.add_argument("--policy", default=None, choices=["h2o", "streaming", "sliding"],
+                    help="override the workload's sequence-wise policy")
     ap.add_argument("--no-cpu", action="store_true", help="skip the oracle timing leg")
     ap.add_argument("--calib-copy", action="store_true",
                     help="after the timed region run one plain 1 GiB -> 1 GiB elementwise copy kernel "
@@ -92,6 +94,8 @@ def main():
     from paper_2404_04793_amd.session import Session
 
     wl = W.WORKLOADS[args.workload]
+    if args.policy:
+        wl = W.scaled(wl, policy=args.policy)
     torch.cuda.set_device(0)
     sess = Session(wl, "cuda:0", uniform_budget=args.uniform, full_cache=args.full_cache)
 

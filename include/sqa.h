@@ -76,6 +76,11 @@ typedef struct sqa_layer_cache {
   int32_t* pos;        /* [B][Hkv][capacity] token position per slot = kept_idx    */
   int32_t* lens;       /* [B][Hkv] number of valid slots                           */
   int32_t* ring_head;  /* [B][Hkv] offset of the oldest recent token in the ring   */
+  int32_t* evict_hint; /* [B][Hkv] H2O only (else may be NULL): the next eviction,
+                          decided at the end of the previous decode step: -1 = the
+                          token leaving the ring goes, s >= 0 = heavy slot s goes,
+                          -2 = not decided (sqa_prefill_compress writes this; write
+                          it too after editing a unit's scores, positions or budget) */
   int32_t capacity;    /* slots per unit; >= min(budget, longest length reached)   */
   int32_t budget;      /* b^(i): most tokens this layer keeps                      */
 } sqa_layer_cache;
@@ -131,7 +136,7 @@ sqa_status sqa_prefill_scores(const void* Q, const void* K, sqa_dtype dt,
  *                 older ones, the floor(budget/2) with the largest attn_scores,
  *                 equal scores -> lowest position first;
  * and gathers their K, V rows (ascending position) into the layer cache,
- * filling pos, score_acc (H2O), lens and ring_head.
+ * filling pos, score_acc (H2O), lens, ring_head and evict_hint (-2).
  *   K, V        : DEVICE [B][Hkv][P][D], dtype kv_dt; must not overlap the cache
  *   attn_scores : DEVICE float [B][Hkv][P], values >= 0, required for SQA_H2O
  *   layer       : HOST struct with DEVICE pointers; budget and capacity preset,
@@ -149,8 +154,9 @@ sqa_status sqa_prefill_compress(const void* K, const void* V, sqa_dtype kv_dt, c
  *      the lowest-scoring heavy hitter; equal scores evict the higher position);
  *   3. out[h] = softmax(q[h].K^T/sqrt(D)) V for the g query heads of the unit;
  *   4. H2O: score_acc[slot] += sum over those heads of the probability.
- * The cache (K, V, score_acc, pos, lens, ring_head) is updated in place; pos is
- * the kept-index result.  new_pos must exceed every position already cached.
+ * The cache (K, V, score_acc, pos, lens, ring_head, evict_hint) is updated in
+ * place; pos is the kept-index result.  Positions are consecutive: the prompt
+ * holds 0..P-1 and every step's new_pos is the previous one plus 1.
  *   q            : DEVICE [n_layers][B][Hq][D], dtype dt
  *   k_new, v_new : DEVICE [n_layers][B][Hkv][D]
  *   out          : DEVICE [n_layers][B][Hq][D], dtype dt
@@ -159,12 +165,21 @@ sqa_status sqa_prefill_compress(const void* K, const void* V, sqa_dtype kv_dt, c
  *                  it into the workspace first)
  *   n_layers     : 1 when layers run one after another inside a model; all
  *                  layers at once when their inputs are known up front
- *   workspace    : DEVICE, >= sqa_decode_workspace_bytes(n_layers); its first
- *                  int32 is a device-side status word (see sqa_read_device_status)
+ *   workspace    : DEVICE, 256-byte aligned, >= sqa_decode_workspace_bytes(...) for
+ *                  the same layers and shapes, zero-filled once before its first
+ *                  use (sqa_decode_workspace_init); calls that share a workspace
+ *                  must not overlap in time.  Its first int32 is a device-side
+ *                  status word (see sqa_read_device_status).
+ * Long units are cut into chunks that separate workgroups stream (split-K);
+ * the workspace holds their partial results, the step's logits (H2O) and one
+ * arrival counter per unit.  The merge order is fixed: results are identical
+ * from run to run.
  * A unit that on entry is longer than its budget, or has no free slot, is left
  * untouched, its out rows are zeroed and the status word is set to
  * SQA_ERR_STATE / SQA_ERR_CAPACITY. */
-size_t sqa_decode_workspace_bytes(int n_layers);
+size_t sqa_decode_workspace_bytes(const sqa_layer_cache* layers /*HOST*/, int n_layers, int B, int Hq, int Hkv,
+                                  int D, sqa_policy policy);
+sqa_status sqa_decode_workspace_init(void* workspace, size_t ws_bytes, void* stream);
 sqa_status sqa_decode_step(const void* q, const void* k_new, const void* v_new, sqa_dtype dt,
                            int B, int Hq, int Hkv, int D, int32_t new_pos,
                            sqa_policy policy, int n_sink,

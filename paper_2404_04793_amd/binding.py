@@ -13,7 +13,7 @@ from typing import List, Optional, Sequence, Tuple
 import torch
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "libsqa.so")
+LIB_PATH = os.environ.get("SQA_LIB", os.path.join(_HERE, "libsqa.so"))   # SQA_LIB: another build of the same ABI
 
 if not os.path.exists(LIB_PATH):
     raise ImportError(
@@ -39,7 +39,8 @@ class SqaError(RuntimeError):
 class LayerCacheStruct(C.Structure):
     """Mirror of sqa_layer_cache."""
     _fields_ = [("K", C.c_void_p), ("V", C.c_void_p), ("score_acc", C.c_void_p), ("pos", C.c_void_p),
-                ("lens", C.c_void_p), ("ring_head", C.c_void_p), ("capacity", C.c_int32), ("budget", C.c_int32)]
+                ("lens", C.c_void_p), ("ring_head", C.c_void_p), ("evict_hint", C.c_void_p),
+                ("capacity", C.c_int32), ("budget", C.c_int32)]
 
 
 _vp, _i, _i64, _sz, _f64 = C.c_void_p, C.c_int, C.c_int64, C.c_size_t, C.c_double
@@ -58,7 +59,9 @@ _lib.sqa_prefill_scores.argtypes = [_vp, _vp, _i, _i, _i, _i, _i, _i, _vp, _vp, 
 _lib.sqa_prefill_compress.restype = _i
 _lib.sqa_prefill_compress.argtypes = [_vp, _vp, _i, _vp, _i, _i, _i, _i, _i, _i, _LCp, _vp]
 _lib.sqa_decode_workspace_bytes.restype = _sz
-_lib.sqa_decode_workspace_bytes.argtypes = [_i]
+_lib.sqa_decode_workspace_bytes.argtypes = [_LCp, _i, _i, _i, _i, _i, _i]
+_lib.sqa_decode_workspace_init.restype = _i
+_lib.sqa_decode_workspace_init.argtypes = [_vp, _sz, _vp]
 _lib.sqa_decode_step.restype = _i
 _lib.sqa_decode_step.argtypes = [_vp, _vp, _vp, _i, _i, _i, _i, _i, C.c_int32, _i, _i, _LCp, _vp, _i,
                                  _vp, _vp, _sz, _vp]
@@ -138,7 +141,7 @@ class LayerCaches:
                  dtype: torch.dtype, device, with_scores: bool = True):
         self.L, self.B, self.Hkv, self.D, self.dtype = len(budgets), B, Hkv, D, dtype
         self.budgets, self.capacities = list(budgets), list(capacities)
-        self.K, self.V, self.score, self.pos, self.lens, self.head = [], [], [], [], [], []
+        self.K, self.V, self.score, self.pos, self.lens, self.head, self.hint = [], [], [], [], [], [], []
         self.table = (LayerCacheStruct * self.L)()
         for i, (b, cap) in enumerate(zip(budgets, capacities)):
             self.K.append(torch.zeros(B, Hkv, cap, D, dtype=dtype, device=device))
@@ -147,10 +150,12 @@ class LayerCaches:
             self.pos.append(torch.full((B, Hkv, cap), -1, dtype=torch.int32, device=device))
             self.lens.append(torch.zeros(B, Hkv, dtype=torch.int32, device=device))
             self.head.append(torch.zeros(B, Hkv, dtype=torch.int32, device=device))
+            self.hint.append(torch.full((B, Hkv), -2, dtype=torch.int32, device=device))
             t = self.table[i]
             t.K, t.V = self.K[i].data_ptr(), self.V[i].data_ptr()
             t.score_acc = self.score[i].data_ptr() if with_scores else None
             t.pos, t.lens, t.ring_head = self.pos[i].data_ptr(), self.lens[i].data_ptr(), self.head[i].data_ptr()
+            t.evict_hint = self.hint[i].data_ptr()
             t.capacity, t.budget = int(cap), int(b)
         raw = bytes(memoryview(self.table))
         self.table_dev = torch.frombuffer(bytearray(raw), dtype=torch.uint8).to(device)
@@ -170,8 +175,16 @@ def prefill_compress(K: torch.Tensor, V: torch.Tensor, attn_scores: Optional[tor
                                      n_sink, caches.struct_ptr(layer), _stream()), "sqa_prefill_compress")
 
 
-def decode_workspace(n_layers: int, device) -> torch.Tensor:
-    ws = torch.zeros(_lib.sqa_decode_workspace_bytes(n_layers), dtype=torch.uint8, device=device)
+def decode_workspace(caches: "LayerCaches", Hq: int, policy: str, layer0: int = 0,
+                     n_layers: Optional[int] = None) -> torch.Tensor:
+    """Scratch for sqa_decode_step over layers [layer0, layer0 + n_layers) of `caches`, zero-filled."""
+    n_layers = caches.L - layer0 if n_layers is None else n_layers
+    need = _lib.sqa_decode_workspace_bytes(caches.struct_ptr(layer0), n_layers, caches.B, Hq, caches.Hkv, caches.D,
+                                           POLICY[policy])
+    if need == 0:
+        raise SqaError(2, "sqa_decode_workspace_bytes")
+    ws = torch.empty(need, dtype=torch.uint8, device=caches.K[0].device)
+    _check(_lib.sqa_decode_workspace_init(_ptr(ws), need, _stream()), "sqa_decode_workspace_init")
     return ws
 
 

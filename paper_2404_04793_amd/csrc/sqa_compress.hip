@@ -149,7 +149,7 @@ __global__ __launch_bounds__(kCmpThreads) void prefill_compress_kernel(
     posu[j] = src;
     if (L.score_acc) L.score_acc[(int64_t)u * cap + j] = sc ? sc[src] : 0.f;
   }
-  if (tid == 0) { L.lens[u] = n_keep; L.ring_head[u] = 0; }
+  if (tid == 0) { L.lens[u] = n_keep; L.ring_head[u] = 0; if (L.evict_hint) L.evict_hint[u] = -2; }
 }
 
 // out[rank of pos[i]] = pos[i]; -1 beyond len.  Rank by counting (a test view, O(n^2)).

@@ -1,29 +1,41 @@
 // Decode step over per-layer compact KV caches: Algorithm 1 steps 14-21 with the
 // append of Eq. 2-3.  One launch covers every (layer, sequence, KV head) unit of
-// the call; a workgroup of 4 waves owns one unit and does, in this order,
-//   0. read len / ring head, decide where the new token goes and (cache full)
-//      which token is evicted -- H2O: arg-min over the heavy-hitter scores held
-//      in LDS against the token leaving the recent ring;
-//   1. stream the unit's K and V rows once (16 bytes per lane, 1 KiB per wave
-//      load), online softmax in fp32; the logits of the step stay in LDS;
-//   2. combine the 4 waves, write out[g][D];
-//   3. H2O: score_acc += softmax probabilities (summed over the g query heads)
-//      from the LDS logits, one read and one write of the score per token;
+// the call.  A unit's tokens are cut into chunks of `chunk` slots; a workgroup
+// of 4 waves owns one chunk:
+//   0. read len / ring head / the eviction decision carried over from the
+//      previous step (H2O: which heavy slot, if any, the ring leaver replaces);
+//   1. stream the chunk's K and V rows once with non-temporal 16-byte loads
+//      (1 KiB per wave load), online softmax in fp32;
+//   2. combine the 4 waves.  Unit with one chunk: write out[g][D].  Split unit:
+//      write the partial (acc, m, l) and the logits to scratch, bump the unit's
+//      arrival counter; the workgroup that arrives last merges the partials in
+//      chunk order (fixed order: results do not depend on who arrives last);
+//   3. H2O: score_acc += softmax probabilities (summed over the g query heads),
+//      one read and one write of the score per token, and in the same pass the
+//      NEXT step's eviction decision (arg-min over the updated heavy scores
+//      against the next ring leaver), stored in evict_hint;
 //   4. only now touch the cache: move the surviving ring token into the evicted
 //      heavy slot, write the new token's rows, pos, lens, ring_head.
 // During 1 the two slots that 4 will rewrite are read through a remap (new
 // token from k_new/v_new, moved token from its old ring slot), so the cache is
-// read-only until every wave has finished reading: no fence is needed and no
-// row is read twice.  HBM traffic per unit is the kept rows of K and V once,
-// plus 8 bytes of score per token under H2O: the algorithmic minimum.
-// There are no atomics; results are bit-identical from run to run.
+// read-only until every workgroup of the unit has finished reading.  HBM
+// traffic per unit is the kept rows of K and V once plus 8 bytes of score per
+// token under H2O (split units add 8 bytes of logit scratch per token and
+// head).  The only atomic is the arrival counter; it decides who merges, never
+// what is computed: results are bit-identical from run to run.
 #include "sqa_common.h"
 
 namespace sqa {
 
 constexpr int kDecThreads = 256;
 constexpr int kDecWaves = kDecThreads / SQA_WAVE;
-constexpr int kUnroll = 4;
+#ifndef SQA_DEC_UNROLL
+#define SQA_DEC_UNROLL 4
+#endif
+#ifndef SQA_DEC_PREFETCH
+#define SQA_DEC_PREFETCH 1
+#endif
+constexpr int kUnroll = SQA_DEC_UNROLL;     // rows per lane group in flight per loop trip
 
 struct DecodeArgs {
   const void* q;
@@ -32,11 +44,67 @@ struct DecodeArgs {
   void* out;
   const sqa_layer_cache* layers;   // DEVICE table
   int32_t* status;
+  int32_t* cnt;                    // scratch: arrival counter per unit (zero between launches)
+  float* part;                     // scratch: per-chunk partial (acc[D], m, l) of split units
+  float* logit;                    // scratch: logits of split units (H2O)
   int B, Hq, Hkv, n_layers;
   int new_pos, policy, n_sink;
+  int chunk;                       // tokens per work item
   float scale_log2;                // log2(e) / sqrt(D)
-  uint8_t order[SQA_MAX_LAYERS];   // layers in descending budget (long units start first)
+  uint8_t order[SQA_MAX_LAYERS];       // layers in descending budget (long units start first)
+  uint32_t blk_end[SQA_MAX_LAYERS];    // work items up to and including ordered layer i
+  uint16_t nsplit[SQA_MAX_LAYERS];     // by layer: chunks per unit
+  uint32_t unit_off[SQA_MAX_LAYERS];   // by layer: first unit number of the layer within the call
+  uint32_t part_off[SQA_MAX_LAYERS];   // by layer: first partial record
+  uint32_t logit_off[SQA_MAX_LAYERS];  // by layer: first logit (floats)
 };
+
+// block-wide reductions; every thread gets the result
+__device__ __forceinline__ float block_min(float v, float* s_red) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v = fminf(v, __shfl_xor(v, o, SQA_WAVE));
+  __syncthreads();
+  if ((threadIdx.x & (SQA_WAVE - 1)) == 0) s_red[threadIdx.x / SQA_WAVE] = v;
+  __syncthreads();
+  v = s_red[0];
+#pragma unroll
+  for (int w = 1; w < kDecWaves; ++w) v = fminf(v, s_red[w]);
+  return v;
+}
+__device__ __forceinline__ unsigned long long block_max64(unsigned long long v, unsigned long long* s_red) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) {
+    const unsigned long long other = __shfl_xor(v, o, SQA_WAVE);
+    v = other > v ? other : v;
+  }
+  __syncthreads();
+  if ((threadIdx.x & (SQA_WAVE - 1)) == 0) s_red[threadIdx.x / SQA_WAVE] = v;
+  __syncthreads();
+  v = s_red[0];
+#pragma unroll
+  for (int w = 1; w < kDecWaves; ++w) v = s_red[w] > v ? s_red[w] : v;
+  return v;
+}
+
+// H2O eviction rule for a full unit: the candidates are the hh heavy slots and
+// the token leaving the recent ring; the one with the lowest accumulated score
+// goes, equal scores -> the highest position (the ring leaver is newer than
+// every heavy hitter).  Returns -1 if the leaver is evicted, else the heavy
+// slot that is evicted (the leaver moves there).  `mn` = min over the heavy
+// scores, already reduced over the block.  pos_override: slot whose position
+// is not yet in memory (or -1).
+__device__ __forceinline__ int pick_victim(const float* sc, const int32_t* posu, int hh, float mn, float leaver_score,
+                                           int override_slot, int override_pos, unsigned long long* s_red64) {
+  if (leaver_score <= mn) return -1;             // uniform over the block
+  unsigned long long best = 0ull;                // (position + 1) << 32 | slot
+  for (int i = threadIdx.x; i < hh; i += kDecThreads)
+    if (sc[i] == mn) {
+      const int ps = i == override_slot ? override_pos : posu[i];
+      const unsigned long long key = ((unsigned long long)(uint32_t)(ps + 1) << 32) | (uint32_t)i;
+      best = key > best ? key : best;
+    }
+  return (int)(uint32_t)block_max64(best, s_red64);
+}
 
 // v_exp_f32: 2^x, 1 ulp, denormal results flush to 0 (harmless in a softmax)
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
@@ -97,6 +165,7 @@ template <> struct RowMath<bf16_t> {
   }
 };
 
+
 template <typename T, int D, int G, bool H2O>
 __global__ __launch_bounds__(kDecThreads) void decode_unit_kernel(const DecodeArgs a) {
   constexpr int ROWB = D * (int)sizeof(T);        // bytes per K or V row
@@ -104,19 +173,29 @@ __global__ __launch_bounds__(kDecThreads) void decode_unit_kernel(const DecodeAr
   constexpr int RPI = SQA_WAVE / LPR;             // rows per wave load
   constexpr int EPL = RowMath<T>::EPL;            // elements per lane
   constexpr int ROWS_IT = kDecWaves * RPI;        // rows per workgroup per load
+  constexpr int PREC = D + 2;                     // floats per partial record: acc[D], m, l
 
-  extern __shared__ float s_dyn[];                // H2O: score[cap], logit[G][cap]
+  extern __shared__ float s_logit[];              // H2O, unsplit units: [G][chunk]
   __shared__ float s_m[kDecWaves][G], s_l[kDecWaves][G];
   __shared__ float s_acc[kDecWaves][G][D];
   __shared__ float s_red[kDecWaves];
   __shared__ unsigned long long s_red64[kDecWaves];
-  __shared__ int s_ctl[4];
+  __shared__ int s_ctl[2];
+  __shared__ float s_ctlf[2];
 
   const int tid = threadIdx.x, lane = tid & (SQA_WAVE - 1), wave = tid / SQA_WAVE;
   const int r = lane / LPR, c = lane % LPR;
-  const int units_per_layer = a.B * a.Hkv;
-  const int layer = a.order[blockIdx.x / units_per_layer];
-  const int u = blockIdx.x % units_per_layer;
+
+  // ---- which work item -----------------------------------------------------
+  int lo = 0, hi = a.n_layers - 1;
+  while (lo < hi) {
+    const int mid = (lo + hi) >> 1;
+    if (blockIdx.x < a.blk_end[mid]) hi = mid; else lo = mid + 1;
+  }
+  const int layer = a.order[lo];
+  const unsigned local = blockIdx.x - (lo ? a.blk_end[lo - 1] : 0u);
+  const int nsplit = a.nsplit[layer];
+  const int u = (int)(local / (unsigned)nsplit), chunk = (int)(local % (unsigned)nsplit);
   const int bidx = u / a.Hkv, kvh = u % a.Hkv;
   const sqa_layer_cache L = a.layers[layer];
   const int cap = L.capacity, budget = L.budget;
@@ -132,63 +211,34 @@ __global__ __launch_bounds__(kDecThreads) void decode_unit_kernel(const DecodeAr
   // ---- 0. where does the new token go, who leaves -------------------------
   const bool bad_state = len > budget || len > cap || len < 0 || head < 0 || (len == budget && head >= rec);
   const bool bad_cap = !bad_state && len < budget && len >= cap;
-  if (bad_state || bad_cap) {
-    for (int i = tid; i < G * D; i += kDecThreads) reinterpret_cast<T*>(outp)[i] = T{};
-    if (tid == 0) *a.status = bad_state ? SQA_ERR_STATE : SQA_ERR_CAPACITY;
+  if (bad_state || bad_cap) {                     // same verdict in every chunk of the unit
+    if (chunk == 0) {
+      for (int i = tid; i < G * D; i += kDecThreads) reinterpret_cast<T*>(outp)[i] = T{};
+      if (tid == 0) *a.status = bad_state ? SQA_ERR_STATE : SQA_ERR_CAPACITY;
+    }
     return;
   }
   const bool full = len == budget;
   const int n = full ? budget : len + 1;          // tokens attended this step
   const int slot_new = full ? hh + head : len;
-  float* s_score = s_dyn;
-  float* s_logit = s_dyn + cap;
+  float* sc = H2O ? L.score_acc + (int64_t)u * cap : nullptr;
+  const int32_t* posu = L.pos + (int64_t)u * cap;
   int moved_to = -1;                              // heavy slot that receives the ring leaver
-  if (H2O) {
-    float* sc = L.score_acc + (int64_t)u * cap;
-    for (int i = tid; i < len; i += kDecThreads) s_score[i] = sc[i];
-    __syncthreads();
-    if (full && hh > 0) {
-      // worst heavy hitter: lowest score, equal scores -> highest position
+  if (H2O && full) {
+    const int hint = L.evict_hint[u];
+    if (hint >= -1 && hint < hh) {
+      moved_to = hint;
+    } else {                                      // no decision carried over: take it now
       float mn = INFINITY;
-      for (int i = tid; i < hh; i += kDecThreads) mn = fminf(mn, s_score[i]);
-#pragma unroll
-      for (int o = 32; o > 0; o >>= 1) mn = fminf(mn, __shfl_xor(mn, o, SQA_WAVE));
-      if (lane == 0) s_red[wave] = mn;
-      __syncthreads();
-      mn = fminf(fminf(s_red[0], s_red[1]), fminf(s_red[2], s_red[3]));
-      const int32_t* posu = L.pos + (int64_t)u * cap;
-      unsigned long long best = 0ull;             // (position+1) << 32 | slot
-      for (int i = tid; i < hh; i += kDecThreads)
-        if (s_score[i] == mn) {
-          const unsigned long long key = ((unsigned long long)(uint32_t)(posu[i] + 1) << 32) | (uint32_t)i;
-          best = key > best ? key : best;
-        }
-#pragma unroll
-      for (int o = 32; o > 0; o >>= 1) {
-        const unsigned long long other = __shfl_xor(best, o, SQA_WAVE);
-        best = other > best ? other : best;
-      }
-      if (lane == 0) s_red64[wave] = best;
-      __syncthreads();
-      if (tid == 0) {
-        unsigned long long bb = s_red64[0];
-        for (int w = 1; w < kDecWaves; ++w) bb = s_red64[w] > bb ? s_red64[w] : bb;
-        const int worst = (int)(uint32_t)bb;
-        const float leaver = s_score[slot_new];
-        int mv = -1;
-        if (leaver > mn) { mv = worst; s_score[worst] = leaver; }   // leaver survives, worst heavy hitter goes
-        s_score[slot_new] = 0.f;
-        s_ctl[0] = mv;
-      }
-      __syncthreads();
-      moved_to = s_ctl[0];
-    } else {
-      if (tid == 0) s_score[slot_new] = 0.f;
-      __syncthreads();
+      for (int i = tid; i < hh; i += kDecThreads) mn = fminf(mn, sc[i]);
+      mn = block_min(mn, s_red);
+      moved_to = pick_victim(sc, posu, hh, mn, sc[slot_new], -1, 0, s_red64);
     }
   }
 
-  // ---- 1. stream K and V once, online softmax ------------------------------
+  // ---- 1. stream the chunk's K and V once, online softmax -------------------
+  const int c0 = chunk * a.chunk;
+  const int c_end = min(c0 + a.chunk, n);
   uint4 qf[G];
 #pragma unroll
   for (int g = 0; g < G; ++g)
@@ -198,6 +248,7 @@ __global__ __launch_bounds__(kDecThreads) void decode_unit_kernel(const DecodeAr
   const char* Vb = reinterpret_cast<const char*>(L.V) + (int64_t)u * cap * ROWB;
   const char* knew = reinterpret_cast<const char*>(a.k_new) + kvoff * (int64_t)sizeof(T);
   const char* vnew = reinterpret_cast<const char*>(a.v_new) + kvoff * (int64_t)sizeof(T);
+  float* glogit = (H2O && nsplit > 1) ? a.logit + a.logit_off[layer] + (int64_t)u * G * cap : nullptr;
 
   float m[G], l[G], acc[G][EPL];
 #pragma unroll
@@ -207,7 +258,7 @@ __global__ __launch_bounds__(kDecThreads) void decode_unit_kernel(const DecodeAr
     for (int e = 0; e < EPL; ++e) acc[g][e] = 0.f;
   }
 
-  for (int base = 0; base < n; base += ROWS_IT * kUnroll) {
+  for (int base = c0; base < c_end; base += ROWS_IT * kUnroll) {
     uint4 kf[kUnroll], vf[kUnroll];
     int slot[kUnroll];
 #pragma unroll
@@ -227,9 +278,13 @@ __global__ __launch_bounds__(kDecThreads) void decode_unit_kernel(const DecodeAr
 #pragma unroll
       for (int g = 0; g < G; ++g) {
         float d = group_sum<LPR>(RowMath<T>::dot(qf[g], kf[uu])) * a.scale_log2;
-        d = slot[uu] < n ? d : -INFINITY;
+        const bool valid = slot[uu] < c_end;
+        d = valid ? d : -INFINITY;
         s[uu][g] = d;
-        if (H2O && c == 0 && slot[uu] < n) s_logit[g * cap + slot[uu]] = d;
+        if (H2O && c == 0 && valid) {
+          if (glogit) glogit[(int64_t)g * cap + slot[uu]] = d;
+          else s_logit[g * a.chunk + slot[uu]] = d;
+        }
       }
 #pragma unroll
     for (int g = 0; g < G; ++g) {
@@ -258,11 +313,11 @@ __global__ __launch_bounds__(kDecThreads) void decode_unit_kernel(const DecodeAr
 #pragma unroll
     for (int o = LPR; o < SQA_WAVE; o <<= 1) {
       const float mo = __shfl_xor(m[g], o, SQA_WAVE);
-      const float lo = __shfl_xor(l[g], o, SQA_WAVE);
+      const float lo2 = __shfl_xor(l[g], o, SQA_WAVE);
       const float mx = fmaxf(m[g], mo);
       const float ms = mx == -INFINITY ? 0.f : mx;
       const float fa = fast_exp2(m[g] - ms), fb = fast_exp2(mo - ms);
-      l[g] = l[g] * fa + lo * fb;
+      l[g] = l[g] * fa + lo2 * fb;
 #pragma unroll
       for (int e = 0; e < EPL; ++e) {
         const float ao = __shfl_xor(acc[g][e], o, SQA_WAVE);
@@ -277,44 +332,101 @@ __global__ __launch_bounds__(kDecThreads) void decode_unit_kernel(const DecodeAr
     }
   }
   __syncthreads();
-  // wave 0, row group g (when G <= RPI) or looping: final m, l and the output row
+  float* part = nsplit > 1 ? a.part + ((int64_t)a.part_off[layer] + (int64_t)u * nsplit) * G * PREC : nullptr;
+  // one lane group per query head: merge the 4 waves
   for (int g = wave * RPI + r; g < G; g += kDecWaves * RPI) {
     float mx = -INFINITY;
 #pragma unroll
     for (int w = 0; w < kDecWaves; ++w) mx = fmaxf(mx, s_m[w][g]);
+    const float ms = mx == -INFINITY ? 0.f : mx;  // an empty chunk has nothing
     float lt = 0.f, o[EPL];
 #pragma unroll
     for (int e = 0; e < EPL; ++e) o[e] = 0.f;
 #pragma unroll
     for (int w = 0; w < kDecWaves; ++w) {
-      const float f = fast_exp2(s_m[w][g] - mx);      // n >= 1, so mx is finite
+      const float f = fast_exp2(s_m[w][g] - ms);
       lt += s_l[w][g] * f;
 #pragma unroll
       for (int e = 0; e < EPL; ++e) o[e] += s_acc[w][g][c * EPL + e] * f;
     }
-    const float inv = 1.f / lt;
+    if (nsplit == 1) {
+      const float inv = 1.f / lt;                 // n >= 1: lt > 0
 #pragma unroll
-    for (int e = 0; e < EPL; ++e) o[e] *= inv;
-    RowMath<T>::store(outp + (int64_t)g * ROWB + c * 16, o);
-    if (H2O && c == 0) { s_m[0][g] = mx; s_l[0][g] = inv; }   // broadcast for step 3
+      for (int e = 0; e < EPL; ++e) o[e] *= inv;
+      RowMath<T>::store(outp + (int64_t)g * ROWB + c * 16, o);
+      if (c == 0) { s_m[0][g] = mx; s_l[0][g] = inv; }
+    } else {
+      float* rec_p = part + ((int64_t)chunk * G + g) * PREC;
+#pragma unroll
+      for (int e = 0; e < EPL; ++e) rec_p[c * EPL + e] = o[e];
+      if (c == 0) { rec_p[D] = mx; rec_p[D + 1] = lt; }
+    }
   }
 
-  // ---- 3. H2O accumulation from the LDS logits -----------------------------
+  if (nsplit > 1) {
+    // publish this chunk, find out whether it is the last one of the unit
+    __threadfence();
+    __syncthreads();
+    int32_t* cnt = a.cnt + a.unit_off[layer] + u;
+    if (tid == 0) s_ctl[0] = atomicAdd(cnt, 1);
+    __syncthreads();
+    if (s_ctl[0] != nsplit - 1) return;
+    __threadfence();
+    for (int g = wave * RPI + r; g < G; g += kDecWaves * RPI) {
+      float mx = -INFINITY;
+      for (int k = 0; k < nsplit; ++k) mx = fmaxf(mx, part[((int64_t)k * G + g) * PREC + D]);
+      float lt = 0.f, o[EPL];
+#pragma unroll
+      for (int e = 0; e < EPL; ++e) o[e] = 0.f;
+      for (int k = 0; k < nsplit; ++k) {          // fixed order
+        const float* rec_p = part + ((int64_t)k * G + g) * PREC;
+        const float f = fast_exp2(rec_p[D] - mx); // some chunk is non-empty: mx is finite
+        lt += rec_p[D + 1] * f;
+#pragma unroll
+        for (int e = 0; e < EPL; ++e) o[e] += rec_p[c * EPL + e] * f;
+      }
+      const float inv = 1.f / lt;
+#pragma unroll
+      for (int e = 0; e < EPL; ++e) o[e] *= inv;
+      RowMath<T>::store(outp + (int64_t)g * ROWB + c * 16, o);
+      if (c == 0) { s_m[0][g] = mx; s_l[0][g] = inv; }
+    }
+    if (tid == 0) *cnt = 0;                       // ready for the next launch
+  }
+
+  // ---- 3. H2O accumulation and the next step's eviction decision ------------
+  int next_hint = -1;
+  const int head_next = full ? (head + 1 == rec ? 0 : head + 1) : head;
   if (H2O) {
+    const float leaver_score = moved_to >= 0 ? sc[slot_new] : 0.f;   // read before anyone rewrites it
+    const int leaver_pos = moved_to >= 0 ? posu[slot_new] : 0;
     __syncthreads();
     float fm[G], fi[G];
 #pragma unroll
     for (int g = 0; g < G; ++g) { fm[g] = s_m[0][g]; fi[g] = s_l[0][g]; }
-    float* sc = L.score_acc + (int64_t)u * cap;
+    const bool next_full = n == budget;
+    const int leaver_next = hh + head_next;
+    float mn = INFINITY;
     for (int i = tid; i < n; i += kDecThreads) {
       float p = 0.f;
 #pragma unroll
-      for (int g = 0; g < G; ++g) p += fast_exp2(s_logit[g * cap + i] - fm[g]) * fi[g];
-      sc[i] = s_score[i] + p;
+      for (int g = 0; g < G; ++g) {
+        const float lg = glogit ? glogit[(int64_t)g * cap + i] : s_logit[g * a.chunk + i];
+        p += fast_exp2(lg - fm[g]) * fi[g];
+      }
+      const float old = i == slot_new ? 0.f : (i == moved_to ? leaver_score : sc[i]);
+      const float nv = old + p;
+      sc[i] = nv;
+      if (i < hh) mn = fminf(mn, nv);
+      if (i == leaver_next) s_ctlf[0] = nv;
     }
-  } else {
-    __syncthreads();   // every wave has finished reading the cache
+    if (next_full) {
+      mn = block_min(mn, s_red);                  // also orders the s_ctlf write
+      // positions as they will be after step 4: the moved token brings its own
+      next_hint = pick_victim(sc, posu, hh, mn, s_ctlf[0], moved_to, leaver_pos, s_red64);
+    }
   }
+  __syncthreads();                                // every wave is done reading the cache rows
 
   // ---- 4. the cache update: moved row, new token, bookkeeping ---------------
   if (wave == 0 && r == 0) {
@@ -330,11 +442,12 @@ __global__ __launch_bounds__(kDecThreads) void decode_unit_kernel(const DecodeAr
     st16(Kw + (int64_t)slot_new * ROWB + c * 16, kn);
     st16(Vw + (int64_t)slot_new * ROWB + c * 16, vn);
     if (c == 0) {
-      int32_t* posu = L.pos + (int64_t)u * cap;
-      if (moved_to >= 0) posu[moved_to] = posu[slot_new];
-      posu[slot_new] = a.new_pos;
+      int32_t* posw = L.pos + (int64_t)u * cap;
+      if (moved_to >= 0) posw[moved_to] = posw[slot_new];
+      posw[slot_new] = a.new_pos;
       L.lens[u] = n;
-      if (full) L.ring_head[u] = head + 1 == rec ? 0 : head + 1;
+      if (full) L.ring_head[u] = head_next;
+      if (H2O) L.evict_hint[u] = next_hint;
     }
   }
 }
@@ -362,16 +475,78 @@ static decode_fn pick(sqa_dtype dt, int d, int g, bool h2o) {
 
 constexpr size_t kStatusBytes = 256;
 
+// How one call is cut into work items and where its scratch lives.
+struct DecodePlan {
+  int chunk;
+  uint16_t nsplit[SQA_MAX_LAYERS];
+  uint32_t unit_off[SQA_MAX_LAYERS], part_off[SQA_MAX_LAYERS], logit_off[SQA_MAX_LAYERS];
+  uint64_t blocks;
+  size_t off_table, off_cnt, off_part, off_logit, bytes;
+};
+
+static size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
+
+// chunk: about 3 work items per workgroup slot of the chip (256 CUs x 8), between 128 and 512 slots
+static sqa_status plan_decode(const sqa_layer_cache* layers, int n_layers, int B, int Hq, int Hkv, int D, bool h2o,
+                              DecodePlan* p) {
+  const int64_t units = (int64_t)B * Hkv;
+  const int g = Hq / Hkv;
+  int64_t tokens = 0;
+  for (int i = 0; i < n_layers; ++i) {
+    if (layers[i].capacity < 1) return SQA_ERR_CAPACITY;
+    if (layers[i].budget < 1) return SQA_ERR_BUDGET;
+    tokens += units * (layers[i].budget < layers[i].capacity ? layers[i].budget : layers[i].capacity);
+  }
+  int64_t c = tokens / (256 * 8 * 3);
+  c = (c / 64) * 64;
+  p->chunk = (int)(c < 128 ? 128 : (c > 512 ? 512 : c));
+  uint64_t blocks = 0, n_units = 0, n_part = 0, n_logit = 0;
+  for (int i = 0; i < n_layers; ++i) {
+    const int nmax = layers[i].budget < layers[i].capacity ? layers[i].budget : layers[i].capacity;
+    const int ns = (nmax + p->chunk - 1) / p->chunk;
+    if (ns > 65535) return SQA_ERR_CAPACITY;
+    p->nsplit[i] = (uint16_t)ns;
+    p->unit_off[i] = (uint32_t)n_units;
+    p->part_off[i] = (uint32_t)n_part;
+    p->logit_off[i] = (uint32_t)n_logit;
+    n_units += units;
+    blocks += units * ns;
+    if (ns > 1) {
+      n_part += units * ns;
+      if (h2o) n_logit += units * g * layers[i].capacity;
+    }
+    if (n_units > 0x7fffffffull || n_part > 0x7fffffffull || n_logit > 0xffffffffull || blocks > 0x7fffffffull)
+      return SQA_ERR_CAPACITY;
+  }
+  p->blocks = blocks;
+  p->off_table = kStatusBytes;
+  p->off_cnt = align256(p->off_table + (size_t)n_layers * sizeof(sqa_layer_cache));
+  p->off_part = align256(p->off_cnt + n_units * sizeof(int32_t));
+  p->off_logit = align256(p->off_part + n_part * g * (D + 2) * sizeof(float));
+  p->bytes = align256(p->off_logit + n_logit * sizeof(float));
+  return SQA_OK;
+}
+
 }  // namespace sqa
 
-extern "C" size_t sqa_decode_workspace_bytes(int n_layers) {
-  if (n_layers < 1 || n_layers > SQA_MAX_LAYERS) return 0;
-  return sqa::kStatusBytes + (size_t)n_layers * sizeof(sqa_layer_cache);
+extern "C" size_t sqa_decode_workspace_bytes(const sqa_layer_cache* layers, int n_layers, int B, int Hq, int Hkv,
+                                             int D, sqa_policy policy) {
+  if (!layers || n_layers < 1 || n_layers > SQA_MAX_LAYERS || B < 1 || Hq < 1 || Hkv < 1 || Hq % Hkv != 0 || D < 1)
+    return 0;
+  sqa::DecodePlan p;
+  if (sqa::plan_decode(layers, n_layers, B, Hq, Hkv, D, policy == SQA_H2O, &p) != SQA_OK) return 0;
+  return p.bytes;
+}
+
+extern "C" sqa_status sqa_decode_workspace_init(void* workspace, size_t ws_bytes, void* stream) {
+  if (!workspace) return SQA_ERR_NULL;
+  SQA_HIP_CHECK(hipMemsetAsync(workspace, 0, ws_bytes, static_cast<hipStream_t>(stream)));
+  return SQA_OK;
 }
 
 extern "C" sqa_status sqa_clear_device_status(void* workspace, void* stream) {
   if (!workspace) return SQA_ERR_NULL;
-  SQA_HIP_CHECK(hipMemsetAsync(workspace, 0, sqa::kStatusBytes, static_cast<hipStream_t>(stream)));
+  SQA_HIP_CHECK(hipMemsetAsync(workspace, 0, sizeof(int32_t), static_cast<hipStream_t>(stream)));
   return SQA_OK;
 }
 
@@ -396,32 +571,38 @@ extern "C" sqa_status sqa_decode_step(const void* q, const void* k_new, const vo
   if (B < 1 || Hq < 1 || Hkv < 1 || n_layers < 1 || n_layers > SQA_MAX_LAYERS || Hq % Hkv != 0 || new_pos < 0)
     return SQA_ERR_SHAPE;
   const int g = Hq / Hkv;
-  decode_fn fn = pick(dt, D, g, policy == SQA_H2O);
+  const bool h2o = policy == SQA_H2O;
+  decode_fn fn = pick(dt, D, g, h2o);
   if (!fn) return SQA_ERR_SHAPE;
-  if ((int64_t)n_layers * B * Hkv > INT32_MAX) return SQA_ERR_SHAPE;
-  if (!aligned16(q) || !aligned16(k_new) || !aligned16(v_new) || !aligned16(out) || !aligned16(workspace))
+  if (!aligned16(q) || !aligned16(k_new) || !aligned16(v_new) || !aligned16(out) ||
+      (reinterpret_cast<uintptr_t>(workspace) & 255u))
     return SQA_ERR_SHAPE;
-  if (ws_bytes < sqa_decode_workspace_bytes(n_layers)) return SQA_ERR_CAPACITY;
-  const int min_budget = policy == SQA_H2O ? 2 : (policy == SQA_STREAMING ? n_sink + 1 : 1);
-  int max_cap = 0;
+  const int min_budget = h2o ? 2 : (policy == SQA_STREAMING ? n_sink + 1 : 1);
   for (int i = 0; i < n_layers; ++i) {
     const sqa_layer_cache& c = layers[i];
     if (!c.K || !c.V || !c.pos || !c.lens || !c.ring_head) return SQA_ERR_NULL;
-    if (policy == SQA_H2O && !c.score_acc) return SQA_ERR_NULL;
+    if (h2o && (!c.score_acc || !c.evict_hint)) return SQA_ERR_NULL;
     if (!aligned16(c.K) || !aligned16(c.V)) return SQA_ERR_SHAPE;
     if (c.budget < min_budget) return SQA_ERR_BUDGET;
     if (c.capacity < 1) return SQA_ERR_CAPACITY;
-    max_cap = c.capacity > max_cap ? c.capacity : max_cap;
   }
-  const size_t lds = policy == SQA_H2O ? (size_t)(1 + g) * max_cap * sizeof(float) : 0;
-  if (lds > 96 * 1024) return SQA_ERR_CAPACITY;
+  DecodePlan plan;
+  const sqa_status ps = plan_decode(layers, n_layers, B, Hq, Hkv, D, h2o, &plan);
+  if (ps != SQA_OK) return ps;
+  if (ws_bytes < plan.bytes) return SQA_ERR_CAPACITY;
+  const size_t lds = h2o ? (size_t)g * plan.chunk * sizeof(float) : 0;
 
   hipStream_t st = static_cast<hipStream_t>(stream);
+  char* ws = static_cast<char*>(workspace);
   DecodeArgs a;
   a.q = q; a.k_new = k_new; a.v_new = v_new; a.out = out;
-  a.status = static_cast<int32_t*>(workspace);
+  a.status = reinterpret_cast<int32_t*>(ws);
+  a.cnt = reinterpret_cast<int32_t*>(ws + plan.off_cnt);
+  a.part = reinterpret_cast<float*>(ws + plan.off_part);
+  a.logit = reinterpret_cast<float*>(ws + plan.off_logit);
   a.B = B; a.Hq = Hq; a.Hkv = Hkv; a.n_layers = n_layers;
   a.new_pos = new_pos; a.policy = (int)policy; a.n_sink = n_sink;
+  a.chunk = plan.chunk;
   a.scale_log2 = (float)(1.4426950408889634 / sqrt((double)D));
   // long units first: layers in descending budget (stable)
   for (int i = 0; i < n_layers; ++i) a.order[i] = (uint8_t)i;
@@ -431,17 +612,24 @@ extern "C" sqa_status sqa_decode_step(const void* q, const void* k_new, const vo
     while (j >= 0 && layers[a.order[j]].budget < layers[x].budget) { a.order[j + 1] = a.order[j]; --j; }
     a.order[j + 1] = x;
   }
+  uint64_t run = 0;
+  for (int i = 0; i < n_layers; ++i) {
+    const int l = a.order[i];
+    run += (uint64_t)B * Hkv * plan.nsplit[l];
+    a.blk_end[i] = (uint32_t)run;
+    a.nsplit[i] = plan.nsplit[i];
+    a.unit_off[i] = plan.unit_off[i];
+    a.part_off[i] = plan.part_off[i];
+    a.logit_off[i] = plan.logit_off[i];
+  }
   if (layers_dev) {
     a.layers = layers_dev;
   } else {
-    char* tbl = static_cast<char*>(workspace) + kStatusBytes;
+    char* tbl = ws + plan.off_table;
     SQA_HIP_CHECK(hipMemcpyAsync(tbl, layers, (size_t)n_layers * sizeof(sqa_layer_cache), hipMemcpyHostToDevice, st));
     a.layers = reinterpret_cast<const sqa_layer_cache*>(tbl);
   }
-  if (lds > 48 * 1024)
-    SQA_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void*>(fn), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
-  const unsigned blocks = (unsigned)((int64_t)n_layers * B * Hkv);
-  fn<<<blocks, kDecThreads, lds, st>>>(a);
+  fn<<<(unsigned)plan.blocks, kDecThreads, lds, st>>>(a);
   SQA_HIP_CHECK(hipGetLastError());
   return SQA_OK;
 }

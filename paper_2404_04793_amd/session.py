@@ -51,7 +51,8 @@ class Session:
         self.cos_host = torch.empty(L, dtype=torch.float32, pin_memory=True)
         n = sqa._lib.sqa_layer_importance_workspace_bytes(L, T, wl.hidden)
         self.imp_ws = torch.empty(max(n, 8), dtype=torch.uint8, device=device)
-        self.dec_ws = sqa.decode_workspace(L, device)
+        self.dec_ws = None
+        self.dec_ws_layer = None
         self.caches: Optional[sqa.LayerCaches] = None
         self.budgets: Optional[List[int]] = None
         self.groups: Optional[List[int]] = None
@@ -73,6 +74,8 @@ class Session:
             caps = [min(b, wl.P + wl.S) for b in budgets]
             self.caches = sqa.LayerCaches(budgets, caps, wl.B, wl.Hkv, wl.D, wl.torch_dtype, self.dev,
                                           wl.policy == "h2o")
+            self.dec_ws = sqa.decode_workspace(self.caches, wl.Hq, wl.policy)
+            self.dec_ws_layer = [sqa.decode_workspace(self.caches, wl.Hq, wl.policy, l, 1) for l in range(wl.L)]
         self.budgets, self.groups = budgets, groups
         return cos
 
@@ -90,7 +93,7 @@ class Session:
             if per_layer:
                 for l in range(wl.L):
                     sqa.decode_step(self.q[t, l], self.k_new[t, l], self.v_new[t, l], wl.P + t, wl.policy, wl.n_sink,
-                                    self.caches, self.out[t, l], self.dec_ws, layer0=l, n_layers=1)
+                                    self.caches, self.out[t, l], self.dec_ws_layer[l], layer0=l, n_layers=1)
             else:
                 sqa.decode_step(self.q[t], self.k_new[t], self.v_new[t], wl.P + t, wl.policy, wl.n_sink,
                                 self.caches, self.out[t], self.dec_ws)

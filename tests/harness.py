@@ -36,6 +36,7 @@ def import_state(caches, layer: int, b: int, h: int, c: dict) -> None:
         caches.score[layer][b, h, :n] = torch.from_numpy(c["score"]).to(torch.float32).to(dev)
     caches.lens[layer][b, h] = n
     caches.head[layer][b, h] = 0
+    caches.hint[layer][b, h] = -2          # scores were edited: no eviction decision carried over
 
 
 def export_state(caches, layer: int, b: int, h: int) -> dict:

@@ -26,8 +26,8 @@ def test_every_declared_symbol_is_exported():
 
 
 def test_struct_layout_matches_header():
-    assert C.sizeof(sqa.LayerCacheStruct) == 56
-    assert sqa.LayerCacheStruct.capacity.offset == 48 and sqa.LayerCacheStruct.budget.offset == 52
+    assert C.sizeof(sqa.LayerCacheStruct) == 64
+    assert sqa.LayerCacheStruct.capacity.offset == 56 and sqa.LayerCacheStruct.budget.offset == 60
 
 
 def test_paper_worked_example_through_the_library():
@@ -89,7 +89,7 @@ def test_device_entry_points_validate_before_any_gpu_call():
     assert lib.sqa_layer_importance(p, p, 7, 1, 4, 64, p, p, 1 << 20, None) == 3
     assert lib.sqa_layer_importance(p, p, 0, 1, 4, 60, p, p, 1 << 20, None) == 2
     assert lib.sqa_layer_importance(p, p, 0, 1, 4, 64, p, p, 0, None) == 6
-    lc = sqa.LayerCacheStruct(0x1000, 0x2000, 0x3000, 0x4000, 0x5000, 0x6000, 8, 4)
+    lc = sqa.LayerCacheStruct(0x1000, 0x2000, 0x3000, 0x4000, 0x5000, 0x6000, 0x7000, 8, 4)
     args = lambda **kw: [kw.get("K", p), p, kw.get("dt", 1), kw.get("sc", p), 1, 1, kw.get("P", 16), kw.get("D", 128),
                          kw.get("pol", 2), kw.get("ns", 4), C.byref(kw.get("lc", lc)), None]
     assert lib.sqa_prefill_compress(*args(K=None)) == 1
@@ -98,15 +98,15 @@ def test_device_entry_points_validate_before_any_gpu_call():
     assert lib.sqa_prefill_compress(*args(D=96)) == 2
     assert lib.sqa_prefill_compress(*args(sc=None)) == 1                     # H2O needs scores
     assert lib.sqa_prefill_compress(*args(pol=1, ns=4)) == 5                 # streaming: budget 4 < n_sink+1
-    small = sqa.LayerCacheStruct(0x1000, 0x2000, 0x3000, 0x4000, 0x5000, 0x6000, 3, 4)
+    small = sqa.LayerCacheStruct(0x1000, 0x2000, 0x3000, 0x4000, 0x5000, 0x6000, 0x7000, 3, 4)
     assert lib.sqa_prefill_compress(*args(lc=small)) == 6                    # capacity 3 < min(P, budget)
-    one = sqa.LayerCacheStruct(0x1000, 0x2000, 0x3000, 0x4000, 0x5000, 0x6000, 8, 1)
+    one = sqa.LayerCacheStruct(0x1000, 0x2000, 0x3000, 0x4000, 0x5000, 0x6000, 0x7000, 8, 1)
     assert lib.sqa_prefill_compress(*args(lc=one)) == 5                      # H2O: budget 1 < 2
 
     def dec(**kw):
         return lib.sqa_decode_step(kw.get("q", p), p, p, kw.get("dt", 1), 1, kw.get("Hq", 4), kw.get("Hkv", 4),
                                    kw.get("D", 128), kw.get("pos", 5), kw.get("pol", 2), 4,
-                                   C.byref(kw.get("lc", lc)), None, kw.get("nl", 1), p, p, kw.get("ws", 1 << 20), None)
+                                   C.byref(kw.get("lc", lc)), None, kw.get("nl", 1), p, C.c_void_p(0x10000), kw.get("ws", 1 << 20), None)
     assert dec(q=None) == 1
     assert dec(dt=9) == 3
     assert dec(pol=-1) == 4
@@ -116,7 +116,12 @@ def test_device_entry_points_validate_before_any_gpu_call():
     assert dec(nl=1000) == 2
     assert dec(ws=8) == 6
     assert dec(lc=one) == 5
-    assert lib.sqa_decode_workspace_bytes(0) == 0 and lib.sqa_decode_workspace_bytes(32) >= 256 + 32 * 56
+    assert lib.sqa_decode_workspace_bytes(C.byref(lc), 0, 1, 4, 4, 128, 2) == 0
+    assert lib.sqa_decode_workspace_bytes(C.byref(lc), 1, 1, 4, 4, 128, 2) >= 256 + 64
+    big = sqa.LayerCacheStruct(0x1000, 0x2000, 0x3000, 0x4000, 0x5000, 0x6000, 0x7000, 5000, 5000)
+    # 5000 slots -> several chunks per unit: partial records, logits and counters
+    assert lib.sqa_decode_workspace_bytes(C.byref(big), 1, 2, 4, 4, 128, 2) > 2 * 4 * 5000 * 4
+    assert lib.sqa_decode_workspace_init(None, 16, None) == 1
     assert lib.sqa_kept_idx_sorted(None, 1, 1, p, None) == 1
     assert lib.sqa_prefill_scores(p, p, 1, 1, 6, 4, 16, 128, p, p, 1 << 20, None) == 2
     lib.sqa_status_str.restype = C.c_char_p

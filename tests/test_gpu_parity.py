@@ -148,6 +148,10 @@ CASES = [
     ("slide_f32_d128", "f32", 1, 2, 2, 128, 1, 33, 6, "sliding", [5]),
     ("stream_f32_d64_gqa2", "f32", 1, 4, 2, 64, 1, 50, 6, "streaming", [11]),
     ("h2o_bf16_d64", "bf16", 1, 2, 2, 64, 1, 80, 6, "h2o", [2]),
+    # budgets above the chunk size: units are split over several workgroups
+    ("h2o_bf16_split", "bf16", 2, 2, 2, 128, 2, 600, 6, "h2o", [603, 41]),
+    ("h2o_f32_split_gqa2", "f32", 1, 4, 2, 64, 1, 420, 5, "h2o", [400]),
+    ("stream_bf16_split_gqa4", "bf16", 1, 4, 1, 128, 1, 900, 4, "streaming", [777]),
 ]
 
 
@@ -160,7 +164,7 @@ def test_decode_teacher_forced(sqa, case):
     inp = [_unit_inputs(wl, l, u_dirs, mask) for l in range(L)]
     caps = [min(b, P + S) for b in budgets]
     caches = _mk_caches(sqa, budgets, caps, B, Hkv, D, dtype)
-    ws = sqa.decode_workspace(L, DEV)
+    ws = sqa.decode_workspace(caches, Hq, policy)
     # oracle trajectories (fp32-rounded score storage between steps)
     state = {}
     for l in range(L):
@@ -208,7 +212,7 @@ def test_decode_tie_breaking_and_leaver_cases(sqa):
         caches = _mk_caches(sqa, [b], [b], 1, 1, D, "f32")
         import_state(caches, 0, 0, 0, c)
         q = torch.randn(1, 1, 1, D, device=DEV); k = torch.randn(1, 1, 1, D, device=DEV); v = torch.randn(1, 1, 1, D, device=DEV)
-        out = torch.empty_like(q); ws = sqa.decode_workspace(1, DEV)
+        out = torch.empty_like(q); ws = sqa.decode_workspace(caches, 1, "h2o")
         sqa.decode_step(q, k, v, 24, "h2o", 4, caches, out, ws)
         want_out, c2 = O.decode_step(c, np64(q)[0, 0], np64(k)[0, 0, 0], np64(v)[0, 0, 0], 24, b, "h2o")
         got = export_state(caches, 0, 0, 0)
@@ -236,7 +240,7 @@ def test_decode_free_running_tiny(sqa):
     q_all = torch.stack([inp[l][3] for l in range(wl.L)], 1).contiguous()
     k_all = torch.stack([inp[l][4] for l in range(wl.L)], 1).contiguous()
     v_all = torch.stack([inp[l][5] for l in range(wl.L)], 1).contiguous()
-    ws = sqa.decode_workspace(wl.L, DEV)
+    ws = sqa.decode_workspace(caches, wl.Hq, wl.policy)
     outs = []
     kept = []
     for t in range(wl.S):
@@ -260,11 +264,50 @@ def test_decode_free_running_tiny(sqa):
             assert rel_err(got["score"][None], c["score"][None]) < 1e-5
 
 
+def test_decode_free_running_split_units(sqa):
+    """Units longer than a chunk, running on their own for many steps: the
+    eviction decision carried from step to step and the split-unit merge must
+    reproduce the oracle's kept sets and outputs."""
+    wl = W.scaled(W.WORKLOADS["tiny"], L=2, Hq=2, Hkv=2, D=64, B=2, P=500, S=40, dtype="f32")
+    budgets = [390, 36]
+    g = wl.g
+    u_dirs, mask = W.unit_dirs(wl), W.hh_mask(wl, DEV)
+    inp = [_unit_inputs(wl, l, u_dirs, mask) for l in range(wl.L)]
+    caches = _mk_caches(sqa, budgets, budgets, wl.B, wl.Hkv, wl.D, wl.dtype)
+    for l in range(wl.L):
+        sqa.prefill_compress(inp[l][0], inp[l][1], sqa.prefill_scores(inp[l][2], inp[l][0]), "h2o", 4, caches, l)
+    q_all = torch.stack([inp[l][3] for l in range(wl.L)], 1).contiguous()
+    k_all = torch.stack([inp[l][4] for l in range(wl.L)], 1).contiguous()
+    v_all = torch.stack([inp[l][5] for l in range(wl.L)], 1).contiguous()
+    ws = sqa.decode_workspace(caches, wl.Hq, "h2o")
+    outs, kept = [], []
+    for t in range(wl.S):
+        out = torch.empty(wl.L, wl.B, wl.Hq, wl.D, dtype=wl.torch_dtype, device=DEV)
+        sqa.decode_step(q_all[t], k_all[t], v_all[t], wl.P + t, "h2o", 4, caches, out, ws)
+        outs.append(np64(out))
+        kept.append([sqa.kept_idx_sorted(caches, l).cpu().numpy() for l in range(wl.L)])
+    assert sqa.read_device_status(ws) == 0
+    qn, kn, vn = np64(q_all), np64(k_all), np64(v_all)
+    for l in range(wl.L):
+        Kn, Vn, Qn = np64(inp[l][0]), np64(inp[l][1]), np64(inp[l][2])
+        for b in range(wl.B):
+            for h in range(wl.Hkv):
+                s0 = O.prefill_scores(Qn[b, h * g:(h + 1) * g], Kn[b, h])
+                o_ref, c, states, _ = OP.run_unit(Kn[b, h], Vn[b, h], s0, qn[:, l, b, h * g:(h + 1) * g],
+                                                  kn[:, l, b, h], vn[:, l, b, h], budgets[l], "h2o", 4, keep_states=True)
+                for t in range(wl.S):
+                    n = len(states[t]["pos"])
+                    assert kept[t][l][b, h, :n].tolist() == states[t]["pos"].tolist(), (l, b, h, t)
+                    assert rel_err(outs[t][l, b, h * g:(h + 1) * g], o_ref[t]) < 1e-5
+                got = export_state(caches, l, b, h)
+                assert rel_err(got["score"][None], c["score"][None]) < 1e-5
+
+
 def test_decode_is_deterministic_and_per_layer_calls_agree(sqa):
     """Same inputs twice -> identical bytes; one call over all layers == one call per layer
     (with and without the device copy of the layer table)."""
-    wl = W.scaled(W.WORKLOADS["tiny"], L=3, Hq=4, Hkv=2, D=128, B=2, P=120, S=5, dtype="bf16")
-    budgets = [30, 125, 17]
+    wl = W.scaled(W.WORKLOADS["tiny"], L=3, Hq=4, Hkv=2, D=128, B=2, P=320, S=5, dtype="bf16")
+    budgets = [30, 323, 17]
     u_dirs, mask = W.unit_dirs(wl), W.hh_mask(wl, DEV)
     inp = [_unit_inputs(wl, l, u_dirs, mask) for l in range(wl.L)]
     q_all = torch.stack([inp[l][3] for l in range(wl.L)], 1).contiguous()
@@ -275,7 +318,8 @@ def test_decode_is_deterministic_and_per_layer_calls_agree(sqa):
         caches = _mk_caches(sqa, budgets, budgets, wl.B, wl.Hkv, wl.D, wl.dtype)
         for l in range(wl.L):
             sqa.prefill_compress(inp[l][0], inp[l][1], sqa.prefill_scores(inp[l][2], inp[l][0]), "h2o", 4, caches, l)
-        ws = sqa.decode_workspace(wl.L, DEV)
+        ws = sqa.decode_workspace(caches, wl.Hq, "h2o")
+        ws1 = [sqa.decode_workspace(caches, wl.Hq, "h2o", l, 1) for l in range(wl.L)]
         outs = []
         for t in range(wl.S):
             out = torch.empty(wl.L, wl.B, wl.Hq, wl.D, dtype=wl.torch_dtype, device=DEV)
@@ -283,10 +327,10 @@ def test_decode_is_deterministic_and_per_layer_calls_agree(sqa):
                 sqa.decode_step(q_all[t], k_all[t], v_all[t], wl.P + t, "h2o", 4, caches, out, ws)
             else:
                 for l in range(wl.L):
-                    sqa.decode_step(q_all[t, l], k_all[t, l], v_all[t, l], wl.P + t, "h2o", 4, caches, out[l], ws,
+                    sqa.decode_step(q_all[t, l], k_all[t, l], v_all[t, l], wl.P + t, "h2o", 4, caches, out[l], ws1[l],
                                     layer0=l, n_layers=1, use_dev_table=(mode == "per_layer"))
             outs.append(out)
-        assert sqa.read_device_status(ws) == 0
+        assert sqa.read_device_status(ws) == 0 and all(sqa.read_device_status(w) == 0 for w in ws1)
         results.append((torch.stack(outs).view(torch.int16).cpu(), [s.clone().cpu() for s in caches.score],
                         [p.clone().cpu() for p in caches.pos]))
     for other in results[1:]:
@@ -301,7 +345,7 @@ def test_decode_reports_bad_state_without_touching_the_cache(sqa):
     caches = _mk_caches(sqa, [4], [8], 1, 1, 64, "f32")
     caches.lens[0][0, 0] = 6                      # longer than the budget on entry
     q = torch.randn(1, 1, 1, 64, device=DEV); out = torch.ones_like(q)
-    ws = sqa.decode_workspace(1, DEV)
+    ws = sqa.decode_workspace(caches, 1, "sliding")
     sqa.decode_step(q, q, q, 9, "sliding", 4, caches, out, ws)
     assert sqa.read_device_status(ws) == 8        # SQA_ERR_STATE
     assert int(caches.lens[0][0, 0]) == 6 and float(out.abs().sum()) == 0.0
@@ -309,5 +353,6 @@ def test_decode_reports_bad_state_without_touching_the_cache(sqa):
     assert sqa.read_device_status(ws) == 0
     caches2 = _mk_caches(sqa, [40], [3], 1, 1, 64, "f32")
     caches2.lens[0][0, 0] = 3                     # no free slot
+    ws = sqa.decode_workspace(caches2, 1, "sliding")
     sqa.decode_step(q, q, q, 9, "sliding", 4, caches2, out, ws)
     assert sqa.read_device_status(ws) == 6        # SQA_ERR_CAPACITY
