@@ -27,7 +27,10 @@
 
 namespace sqa {
 
-constexpr int kDecThreads = 256;
+#ifndef SQA_DEC_THREADS
+#define SQA_DEC_THREADS 256
+#endif
+constexpr int kDecThreads = SQA_DEC_THREADS;
 constexpr int kDecWaves = kDecThreads / SQA_WAVE;
 #ifndef SQA_DEC_UNROLL
 #define SQA_DEC_UNROLL 4
@@ -49,15 +52,34 @@ struct DecodeArgs {
   float* logit;                    // scratch: logits of split units (H2O)
   int B, Hq, Hkv, n_layers;
   int new_pos, policy, n_sink;
-  int chunk;                       // tokens per work item
   float scale_log2;                // log2(e) / sqrt(D)
   uint8_t order[SQA_MAX_LAYERS];       // layers in descending budget (long units start first)
   uint32_t blk_end[SQA_MAX_LAYERS];    // work items up to and including ordered layer i
-  uint16_t nsplit[SQA_MAX_LAYERS];     // by layer: chunks per unit
-  uint32_t unit_off[SQA_MAX_LAYERS];   // by layer: first unit number of the layer within the call
-  uint32_t part_off[SQA_MAX_LAYERS];   // by layer: first partial record
-  uint32_t logit_off[SQA_MAX_LAYERS];  // by layer: first logit (floats)
+  int lds_chunk;                       // row length of the LDS logit buffer
+  // Per-layer launch plan.  All fields are 32-bit on purpose: with a 16-bit
+  // table next to a 32-bit one, hipcc 7.2 folded the two uniform indices into
+  // one scalar load whose base address was only 2-byte aligned, and scalar
+  // loads drop the low address bits of the base (the wrong entry was read).
+  struct Layer {
+    uint32_t nsplit;      // chunks per unit
+    uint32_t chunk;       // slots per chunk
+    uint32_t unit_off;    // first unit number of the layer within the call
+    uint32_t part_off;    // first partial record
+    uint32_t logit_off;   // first logit (floats)
+  } lay[SQA_MAX_LAYERS];
 };
+
+// Data that one workgroup hands to another inside a launch (partial results,
+// logits) moves through agent-scope relaxed atomics: such stores are written
+// through and such loads read the coherent copy, so the hand-over needs no
+// cache write-back or invalidate (each XCD of the chip has an L2 of its own;
+// a device-scope fence would flush it, which costs far more than the data).
+__device__ __forceinline__ void st_agent(float* p, float v) {
+  __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ float ld_agent(const float* p) {
+  return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
 
 // block-wide reductions; every thread gets the result
 __device__ __forceinline__ float block_min(float v, float* s_red) {
@@ -115,6 +137,7 @@ template <int CTRL> __device__ __forceinline__ float dpp_mov(float v) {
 
 // sum over the LPR consecutive lanes that share a row; every lane gets the sum
 template <int LPR> __device__ __forceinline__ float group_sum(float v) {
+  static_assert(sizeof(DecodeArgs) <= 4096, "kernel arguments are limited to 4 KiB");
   static_assert(LPR == 8 || LPR == 16 || LPR == 32, "lanes per row");
   v += dpp_mov<0xB1>(v);            // quad_perm [1,0,3,2]
   v += dpp_mov<0x4E>(v);            // quad_perm [2,3,0,1]
@@ -175,7 +198,7 @@ __global__ __launch_bounds__(kDecThreads) void decode_unit_kernel(const DecodeAr
   constexpr int ROWS_IT = kDecWaves * RPI;        // rows per workgroup per load
   constexpr int PREC = D + 2;                     // floats per partial record: acc[D], m, l
 
-  extern __shared__ float s_logit[];              // H2O, unsplit units: [G][chunk]
+  extern __shared__ float s_logit[];              // H2O, unsplit units: [G][lds_chunk]
   __shared__ float s_m[kDecWaves][G], s_l[kDecWaves][G];
   __shared__ float s_acc[kDecWaves][G][D];
   __shared__ float s_red[kDecWaves];
@@ -194,7 +217,7 @@ __global__ __launch_bounds__(kDecThreads) void decode_unit_kernel(const DecodeAr
   }
   const int layer = a.order[lo];
   const unsigned local = blockIdx.x - (lo ? a.blk_end[lo - 1] : 0u);
-  const int nsplit = a.nsplit[layer];
+  const int nsplit = (int)a.lay[layer].nsplit;
   const int u = (int)(local / (unsigned)nsplit), chunk = (int)(local % (unsigned)nsplit);
   const int bidx = u / a.Hkv, kvh = u % a.Hkv;
   const sqa_layer_cache L = a.layers[layer];
@@ -237,8 +260,9 @@ __global__ __launch_bounds__(kDecThreads) void decode_unit_kernel(const DecodeAr
   }
 
   // ---- 1. stream the chunk's K and V once, online softmax -------------------
-  const int c0 = chunk * a.chunk;
-  const int c_end = min(c0 + a.chunk, n);
+  const int csize = (int)a.lay[layer].chunk;
+  const int c0 = chunk * csize;
+  const int c_end = min(c0 + csize, n);
   uint4 qf[G];
 #pragma unroll
   for (int g = 0; g < G; ++g)
@@ -248,7 +272,7 @@ __global__ __launch_bounds__(kDecThreads) void decode_unit_kernel(const DecodeAr
   const char* Vb = reinterpret_cast<const char*>(L.V) + (int64_t)u * cap * ROWB;
   const char* knew = reinterpret_cast<const char*>(a.k_new) + kvoff * (int64_t)sizeof(T);
   const char* vnew = reinterpret_cast<const char*>(a.v_new) + kvoff * (int64_t)sizeof(T);
-  float* glogit = (H2O && nsplit > 1) ? a.logit + a.logit_off[layer] + (int64_t)u * G * cap : nullptr;
+  float* glogit = (H2O && nsplit > 1) ? a.logit + a.lay[layer].logit_off + (int64_t)u * G * cap : nullptr;
 
   float m[G], l[G], acc[G][EPL];
 #pragma unroll
@@ -282,8 +306,8 @@ __global__ __launch_bounds__(kDecThreads) void decode_unit_kernel(const DecodeAr
         d = valid ? d : -INFINITY;
         s[uu][g] = d;
         if (H2O && c == 0 && valid) {
-          if (glogit) glogit[(int64_t)g * cap + slot[uu]] = d;
-          else s_logit[g * a.chunk + slot[uu]] = d;
+          if (glogit) st_agent(&glogit[(int64_t)g * cap + slot[uu]], d);
+          else s_logit[g * a.lds_chunk + slot[uu]] = d;
         }
       }
 #pragma unroll
@@ -332,7 +356,7 @@ __global__ __launch_bounds__(kDecThreads) void decode_unit_kernel(const DecodeAr
     }
   }
   __syncthreads();
-  float* part = nsplit > 1 ? a.part + ((int64_t)a.part_off[layer] + (int64_t)u * nsplit) * G * PREC : nullptr;
+  float* part = nsplit > 1 ? a.part + ((int64_t)a.lay[layer].part_off + (int64_t)u * nsplit) * G * PREC : nullptr;
   // one lane group per query head: merge the 4 waves
   for (int g = wave * RPI + r; g < G; g += kDecWaves * RPI) {
     float mx = -INFINITY;
@@ -358,32 +382,32 @@ __global__ __launch_bounds__(kDecThreads) void decode_unit_kernel(const DecodeAr
     } else {
       float* rec_p = part + ((int64_t)chunk * G + g) * PREC;
 #pragma unroll
-      for (int e = 0; e < EPL; ++e) rec_p[c * EPL + e] = o[e];
-      if (c == 0) { rec_p[D] = mx; rec_p[D + 1] = lt; }
+      for (int e = 0; e < EPL; ++e) st_agent(&rec_p[c * EPL + e], o[e]);
+      if (c == 0) { st_agent(&rec_p[D], mx); st_agent(&rec_p[D + 1], lt); }
     }
   }
 
   if (nsplit > 1) {
-    // publish this chunk, find out whether it is the last one of the unit
-    __threadfence();
+    // publish this chunk, find out whether it is the last one of the unit.  The
+    // barrier waits until every thread's stores above have completed (they are
+    // write-through), so whoever later sees the counter sees them too.
     __syncthreads();
-    int32_t* cnt = a.cnt + a.unit_off[layer] + u;
-    if (tid == 0) s_ctl[0] = atomicAdd(cnt, 1);
+    int32_t* cnt = a.cnt + a.lay[layer].unit_off + u;
+    if (tid == 0) s_ctl[0] = __hip_atomic_fetch_add(cnt, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     __syncthreads();
     if (s_ctl[0] != nsplit - 1) return;
-    __threadfence();
     for (int g = wave * RPI + r; g < G; g += kDecWaves * RPI) {
       float mx = -INFINITY;
-      for (int k = 0; k < nsplit; ++k) mx = fmaxf(mx, part[((int64_t)k * G + g) * PREC + D]);
+      for (int k = 0; k < nsplit; ++k) mx = fmaxf(mx, ld_agent(&part[((int64_t)k * G + g) * PREC + D]));
       float lt = 0.f, o[EPL];
 #pragma unroll
       for (int e = 0; e < EPL; ++e) o[e] = 0.f;
       for (int k = 0; k < nsplit; ++k) {          // fixed order
         const float* rec_p = part + ((int64_t)k * G + g) * PREC;
-        const float f = fast_exp2(rec_p[D] - mx); // some chunk is non-empty: mx is finite
-        lt += rec_p[D + 1] * f;
+        const float f = fast_exp2(ld_agent(&rec_p[D]) - mx);   // some chunk is non-empty: mx is finite
+        lt += ld_agent(&rec_p[D + 1]) * f;
 #pragma unroll
-        for (int e = 0; e < EPL; ++e) o[e] += rec_p[c * EPL + e] * f;
+        for (int e = 0; e < EPL; ++e) o[e] += ld_agent(&rec_p[c * EPL + e]) * f;
       }
       const float inv = 1.f / lt;
 #pragma unroll
@@ -391,7 +415,7 @@ __global__ __launch_bounds__(kDecThreads) void decode_unit_kernel(const DecodeAr
       RowMath<T>::store(outp + (int64_t)g * ROWB + c * 16, o);
       if (c == 0) { s_m[0][g] = mx; s_l[0][g] = inv; }
     }
-    if (tid == 0) *cnt = 0;                       // ready for the next launch
+    if (tid == 0) __hip_atomic_store(cnt, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);   // ready for the next launch
   }
 
   // ---- 3. H2O accumulation and the next step's eviction decision ------------
@@ -411,7 +435,7 @@ __global__ __launch_bounds__(kDecThreads) void decode_unit_kernel(const DecodeAr
       float p = 0.f;
 #pragma unroll
       for (int g = 0; g < G; ++g) {
-        const float lg = glogit ? glogit[(int64_t)g * cap + i] : s_logit[g * a.chunk + i];
+        const float lg = glogit ? ld_agent(&glogit[(int64_t)g * cap + i]) : s_logit[g * a.lds_chunk + i];
         p += fast_exp2(lg - fm[g]) * fi[g];
       }
       const float old = i == slot_new ? 0.f : (i == moved_to ? leaver_score : sc[i]);
@@ -477,8 +501,9 @@ constexpr size_t kStatusBytes = 256;
 
 // How one call is cut into work items and where its scratch lives.
 struct DecodePlan {
-  int chunk;
+  int lds_chunk;                                   // longest unsplit unit (slots)
   uint16_t nsplit[SQA_MAX_LAYERS];
+  uint32_t chunk[SQA_MAX_LAYERS];
   uint32_t unit_off[SQA_MAX_LAYERS], part_off[SQA_MAX_LAYERS], logit_off[SQA_MAX_LAYERS];
   uint64_t blocks;
   size_t off_table, off_cnt, off_part, off_logit, bytes;
@@ -486,7 +511,14 @@ struct DecodePlan {
 
 static size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 
-// chunk: about 3 work items per workgroup slot of the chip (256 CUs x 8), between 128 and 512 slots
+// Units are split only when there are too few of them to fill the chip (the
+// hand-over between workgroups costs more than the imbalance it removes): with
+// at least kMinItems units every unit is one work item, as long as its step
+// logits fit in LDS (kMaxUnsplit slots x heads).  Otherwise the target chunk is
+// what gives about kMinItems items, at least 256 slots; each layer then uses
+// the number of equal chunks nearest to that.
+constexpr int64_t kMinItems = 256 * 8;
+constexpr int kMaxUnsplit = 8192;
 static sqa_status plan_decode(const sqa_layer_cache* layers, int n_layers, int B, int Hq, int Hkv, int D, bool h2o,
                               DecodePlan* p) {
   const int64_t units = (int64_t)B * Hkv;
@@ -497,15 +529,30 @@ static sqa_status plan_decode(const sqa_layer_cache* layers, int n_layers, int B
     if (layers[i].budget < 1) return SQA_ERR_BUDGET;
     tokens += units * (layers[i].budget < layers[i].capacity ? layers[i].budget : layers[i].capacity);
   }
-  int64_t c = tokens / (256 * 8 * 3);
-  c = (c / 64) * 64;
-  p->chunk = (int)(c < 128 ? 128 : (c > 512 ? 512 : c));
+  int64_t target;
+#ifdef SQA_DEC_FORCE_CHUNK
+  target = SQA_DEC_FORCE_CHUNK;
+#else
+  if (units * n_layers >= kMinItems) {
+    target = h2o ? kMaxUnsplit / g : (int64_t)1 << 30;
+  } else {
+    target = tokens / kMinItems;
+    target = target < 256 ? 256 : target;
+  }
+#endif
   uint64_t blocks = 0, n_units = 0, n_part = 0, n_logit = 0;
+  p->lds_chunk = 64;
   for (int i = 0; i < n_layers; ++i) {
     const int nmax = layers[i].budget < layers[i].capacity ? layers[i].budget : layers[i].capacity;
-    const int ns = (nmax + p->chunk - 1) / p->chunk;
+    int64_t ns = (nmax + target / 2) / target;                  // nearest count of equal chunks
+    ns = ns < 1 ? 1 : ns;
+    int64_t ch = ((nmax + ns - 1) / ns + 63) / 64 * 64;
+    if (h2o && ns == 1 && ch * g > kMaxUnsplit) { ns = 2; ch = ((nmax + 1) / 2 + 63) / 64 * 64; }
+    ns = (nmax + ch - 1) / ch;
     if (ns > 65535) return SQA_ERR_CAPACITY;
     p->nsplit[i] = (uint16_t)ns;
+    p->chunk[i] = (uint32_t)ch;
+    if (ns == 1 && ch > p->lds_chunk) p->lds_chunk = (int)ch;
     p->unit_off[i] = (uint32_t)n_units;
     p->part_off[i] = (uint32_t)n_part;
     p->logit_off[i] = (uint32_t)n_logit;
@@ -590,7 +637,7 @@ extern "C" sqa_status sqa_decode_step(const void* q, const void* k_new, const vo
   const sqa_status ps = plan_decode(layers, n_layers, B, Hq, Hkv, D, h2o, &plan);
   if (ps != SQA_OK) return ps;
   if (ws_bytes < plan.bytes) return SQA_ERR_CAPACITY;
-  const size_t lds = h2o ? (size_t)g * plan.chunk * sizeof(float) : 0;
+  const size_t lds = h2o ? (size_t)g * plan.lds_chunk * sizeof(float) : 0;
 
   hipStream_t st = static_cast<hipStream_t>(stream);
   char* ws = static_cast<char*>(workspace);
@@ -602,7 +649,7 @@ extern "C" sqa_status sqa_decode_step(const void* q, const void* k_new, const vo
   a.logit = reinterpret_cast<float*>(ws + plan.off_logit);
   a.B = B; a.Hq = Hq; a.Hkv = Hkv; a.n_layers = n_layers;
   a.new_pos = new_pos; a.policy = (int)policy; a.n_sink = n_sink;
-  a.chunk = plan.chunk;
+  a.lds_chunk = plan.lds_chunk;
   a.scale_log2 = (float)(1.4426950408889634 / sqrt((double)D));
   // long units first: layers in descending budget (stable)
   for (int i = 0; i < n_layers; ++i) a.order[i] = (uint8_t)i;
@@ -617,10 +664,11 @@ extern "C" sqa_status sqa_decode_step(const void* q, const void* k_new, const vo
     const int l = a.order[i];
     run += (uint64_t)B * Hkv * plan.nsplit[l];
     a.blk_end[i] = (uint32_t)run;
-    a.nsplit[i] = plan.nsplit[i];
-    a.unit_off[i] = plan.unit_off[i];
-    a.part_off[i] = plan.part_off[i];
-    a.logit_off[i] = plan.logit_off[i];
+    a.lay[i].nsplit = plan.nsplit[i];
+    a.lay[i].chunk = plan.chunk[i];
+    a.lay[i].unit_off = plan.unit_off[i];
+    a.lay[i].part_off = plan.part_off[i];
+    a.lay[i].logit_off = plan.logit_off[i];
   }
   if (layers_dev) {
     a.layers = layers_dev;
