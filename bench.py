@@ -25,6 +25,11 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0
 
+# HBM bytes per decode launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, scaled by what the same
+# counters read for a plain 1 GiB copy kernel (x2.0 / x1.0); see profiles/decode_importance_compress__<workload>.txt.
+# Counters cannot be read from inside this process, so the figure is the one of the committed profile.
+MEASURED_TRAFFIC_BYTES = {("llama2_7b", "squeeze", "h2o", "all_layers"): 825845.4 * 1024 * 2.0 + 20137.2 * 1024}
+
 
 def cpu_baseline(sess, units_per_layer: int, steps: int):
     """Time the oracle's decode step (Algorithm 1 steps 14-21) on a sample:
@@ -142,6 +147,8 @@ def main():
     launch_s = dec_ms * 1e-3 / launches
     achieved = bytes_launch / launch_s / 1e9
     tokens = wl.B * wl.S * args.steps
+    mode = "full_cache" if args.full_cache else ("uniform" if args.uniform else "squeeze")
+    launch = "per_layer" if args.per_layer else "all_layers"
     res = {
         "metric": "decode tokens/s + achieved HBM GB/s (attn+evict), 7B shape, 1 GPU",
         "value": tokens / dt, "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
@@ -150,10 +157,10 @@ def main():
         "config": {"workload": wl.name, "layers": wl.L, "q_heads": wl.Hq, "kv_heads": wl.Hkv, "head_dim": wl.D,
                    "batch": wl.B, "prompt": wl.P, "decode_steps": wl.S, "policy": wl.policy,
                    "budget_pct": wl.budget_pct, "p": wl.p,
-                   "mode": "full_cache" if args.full_cache else ("uniform" if args.uniform else "squeeze"),
-                   "launch": "per_layer" if args.per_layer else "all_layers"},
+                   "mode": mode, "launch": launch},
         "roofline": {"bound": "hbm", "kernel": "decode_unit_kernel", "achieved": achieved, "peak": HBM_PEAK_GBS,
-                     "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": None,
+                     "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
+                     "traffic": MEASURED_TRAFFIC_BYTES.get((wl.name, mode, wl.policy, launch)),
                      "bytes_per_launch": bytes_launch, "launch_us": launch_s * 1e6},
         "phases_ms": {"probe_and_budgets": probe_ms, "prefill_compress": comp_ms, "decode": dec_ms},
         "decode_only_tokens_per_s": wl.B * wl.S / (dec_ms * 1e-3),
