@@ -84,6 +84,13 @@ def main():
     ap.add_argument("--policy", default=None, choices=["h2o", "streaming", "sliding"],
                     help="override the workload's sequence-wise policy")
     ap.add_argument("--no-cpu", action="store_true", help="skip the oracle timing leg")
+    ap.add_argument("--decode-only", action="store_true",
+                    help="time only the decode steps (probe, budgets and prompt compression run untimed before "
+                         "each pass); for workloads whose whole pass does not fit one GPU's memory")
+    ap.add_argument("--probe-tokens", type=int, default=None,
+                    help="hidden-state rows per layer given to the probe (default: all B*P)")
+    ap.add_argument("--decode-steps", type=int, default=None, help="decode steps per pass (default: the workload's)")
+    ap.add_argument("--batch", type=int, default=None, help="override the workload's batch")
     ap.add_argument("--calib-copy", action="store_true",
                     help="after the timed region run one plain 1 GiB -> 1 GiB elementwise copy kernel "
                          "(reference point for scaling rocprofv3's FETCH_SIZE / WRITE_SIZE counters)")
@@ -101,8 +108,13 @@ def main():
     wl = W.WORKLOADS[args.workload]
     if args.policy:
         wl = W.scaled(wl, policy=args.policy)
+    if args.decode_steps:
+        wl = W.scaled(wl, S=args.decode_steps)
+    if args.batch:
+        wl = W.scaled(wl, B=args.batch)
     torch.cuda.set_device(0)
-    sess = Session(wl, "cuda:0", uniform_budget=args.uniform, full_cache=args.full_cache)
+    sess = Session(wl, "cuda:0", uniform_budget=args.uniform, full_cache=args.full_cache,
+                   probe_tokens=args.probe_tokens)
 
     def one_pass(ev=None):
         if ev:
@@ -118,9 +130,27 @@ def main():
             ev[3].record()
         return cos
 
+    if args.decode_only:
+        def one_pass(ev=None):                       # noqa: F811
+            cos = sess.probe_and_allocate()
+            sess.compress_prompt()
+            torch.cuda.synchronize()
+            t_a = time.perf_counter()
+            if ev:
+                ev[0].record(); ev[1].record(); ev[2].record()
+            sess.decode(per_layer=args.per_layer)
+            if ev:
+                ev[3].record()
+            torch.cuda.synchronize()
+            one_pass.timed += time.perf_counter() - t_a
+            return cos
+        one_pass.timed = 0.0
+
     for _ in range(args.warmup):
         one_pass()
     torch.cuda.synchronize()
+    if args.decode_only:
+        one_pass.timed = 0.0
     evs = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(args.steps)]
     torch.cuda.synchronize()
     t0 = time.perf_counter()
@@ -128,6 +158,8 @@ def main():
         cos = one_pass(evs[i])
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
+    if args.decode_only:
+        dt = one_pass.timed
 
     if args.calib_copy:
         src = torch.ones(1 << 28, dtype=torch.float32, device="cuda:0")
@@ -157,15 +189,17 @@ def main():
         "config": {"workload": wl.name, "layers": wl.L, "q_heads": wl.Hq, "kv_heads": wl.Hkv, "head_dim": wl.D,
                    "batch": wl.B, "prompt": wl.P, "decode_steps": wl.S, "policy": wl.policy,
                    "budget_pct": wl.budget_pct, "p": wl.p,
-                   "mode": mode, "launch": launch},
+                   "mode": mode, "launch": launch,
+                   "phases": "decode_only" if args.decode_only else "whole_pass",
+                   "probe_tokens": sess.probe_tokens},
         "roofline": {"bound": "hbm", "kernel": "decode_unit_kernel", "achieved": achieved, "peak": HBM_PEAK_GBS,
                      "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
                      "traffic": MEASURED_TRAFFIC_BYTES.get((wl.name, mode, wl.policy, launch)),
                      "bytes_per_launch": bytes_launch, "launch_us": launch_s * 1e6},
         "phases_ms": {"probe_and_budgets": probe_ms, "prefill_compress": comp_ms, "decode": dec_ms},
         "decode_only_tokens_per_s": wl.B * wl.S / (dec_ms * 1e-3),
-        "probe_GBps": sess.probe_bytes() / (probe_ms * 1e-3) / 1e9,
-        "compress_GBps": sess.compress_bytes() / (comp_ms * 1e-3) / 1e9,
+        "probe_GBps": None if args.decode_only else sess.probe_bytes() / (probe_ms * 1e-3) / 1e9,
+        "compress_GBps": None if args.decode_only else sess.compress_bytes() / (comp_ms * 1e-3) / 1e9,
         "budgets": {"low": min(sess.budgets), "high": max(sess.budgets),
                     "n_G3": sum(1 for g in sess.groups if g == 2), "sum": sum(sess.budgets)},
         "resident_kv_GB": sess.resident_kv_bytes() / 1e9,

@@ -189,8 +189,13 @@ template <> struct RowMath<bf16_t> {
 };
 
 
+#ifdef SQA_DEC_WAVES_PER_EU
+#define SQA_DEC_OCC __attribute__((amdgpu_waves_per_eu(SQA_DEC_WAVES_PER_EU, SQA_DEC_WAVES_PER_EU)))
+#else
+#define SQA_DEC_OCC
+#endif
 template <typename T, int D, int G, bool H2O>
-__global__ __launch_bounds__(kDecThreads) void decode_unit_kernel(const DecodeArgs a) {
+__global__ __launch_bounds__(kDecThreads) SQA_DEC_OCC void decode_unit_kernel(const DecodeArgs a) {
   constexpr int ROWB = D * (int)sizeof(T);        // bytes per K or V row
   constexpr int LPR = ROWB / 16;                  // lanes per row
   constexpr int RPI = SQA_WAVE / LPR;             // rows per wave load
@@ -222,14 +227,43 @@ __global__ __launch_bounds__(kDecThreads) void decode_unit_kernel(const DecodeAr
   const int bidx = u / a.Hkv, kvh = u % a.Hkv;
   const sqa_layer_cache L = a.layers[layer];
   const int cap = L.capacity, budget = L.budget;
-  const int len = L.lens[u];
-  const int head = L.ring_head[u];
   const int hh = H2O ? budget / 2 : (a.policy == SQA_STREAMING ? min(a.n_sink, budget) : 0);
   const int rec = budget - hh;
+  const int csize = (int)a.lay[layer].chunk;
+  const int c0 = chunk * csize;
 
   const int64_t qoff = (((int64_t)layer * a.B + bidx) * a.Hq + (int64_t)kvh * G) * D;
   const int64_t kvoff = (((int64_t)layer * a.B + bidx) * a.Hkv + kvh) * D;
   char* outp = reinterpret_cast<char*>(a.out) + qoff * (int64_t)sizeof(T);
+  const char* Kb = reinterpret_cast<const char*>(L.K) + (int64_t)u * cap * ROWB;
+  const char* Vb = reinterpret_cast<const char*>(L.V) + (int64_t)u * cap * ROWB;
+  const char* knew = reinterpret_cast<const char*>(a.k_new) + kvoff * (int64_t)sizeof(T);
+  const char* vnew = reinterpret_cast<const char*>(a.v_new) + kvoff * (int64_t)sizeof(T);
+  float* sc = H2O ? L.score_acc + (int64_t)u * cap : nullptr;
+  const int32_t* posu = L.pos + (int64_t)u * cap;
+
+  // Everything that does not depend on the unit's length is requested now, so
+  // that one memory round trip covers the bookkeeping words, q, the new token's
+  // rows, the first rows of the chunk (read as they lie in memory; the two
+  // slots the step rewrites are patched below) and the first scores.
+  const int len = L.lens[u];
+  const int head = L.ring_head[u];
+  const int hint = H2O ? L.evict_hint[u] : -1;
+  uint4 qf[G];
+#pragma unroll
+  for (int g = 0; g < G; ++g)
+    qf[g] = ld16(reinterpret_cast<const char*>(a.q) + (qoff + (int64_t)g * D) * (int64_t)sizeof(T) + c * 16);
+  const uint4 kn_pre = ld16(knew + c * 16), vn_pre = ld16(vnew + c * 16);
+  uint4 kf[kUnroll], vf[kUnroll];
+  int slot[kUnroll];
+#pragma unroll
+  for (int uu = 0; uu < kUnroll; ++uu) {
+    slot[uu] = c0 + uu * ROWS_IT + wave * RPI + r;
+    const int sl = min(slot[uu], cap - 1);
+    kf[uu] = ld16_nt(Kb + (int64_t)sl * ROWB + c * 16);
+    vf[uu] = ld16_nt(Vb + (int64_t)sl * ROWB + c * 16);
+  }
+  const float sc_pre = H2O ? sc[min(tid, cap - 1)] : 0.f;
 
   // ---- 0. where does the new token go, who leaves -------------------------
   const bool bad_state = len > budget || len > cap || len < 0 || head < 0 || (len == budget && head >= rec);
@@ -244,11 +278,8 @@ __global__ __launch_bounds__(kDecThreads) void decode_unit_kernel(const DecodeAr
   const bool full = len == budget;
   const int n = full ? budget : len + 1;          // tokens attended this step
   const int slot_new = full ? hh + head : len;
-  float* sc = H2O ? L.score_acc + (int64_t)u * cap : nullptr;
-  const int32_t* posu = L.pos + (int64_t)u * cap;
   int moved_to = -1;                              // heavy slot that receives the ring leaver
   if (H2O && full) {
-    const int hint = L.evict_hint[u];
     if (hint >= -1 && hint < hh) {
       moved_to = hint;
     } else {                                      // no decision carried over: take it now
@@ -258,20 +289,12 @@ __global__ __launch_bounds__(kDecThreads) void decode_unit_kernel(const DecodeAr
       moved_to = pick_victim(sc, posu, hh, mn, sc[slot_new], -1, 0, s_red64);
     }
   }
+  // the ring leaver's score and position, needed in step 3 if it moves
+  const float leaver_score = (H2O && moved_to >= 0) ? sc[slot_new] : 0.f;
+  const int leaver_pos = (H2O && moved_to >= 0) ? posu[slot_new] : 0;
 
   // ---- 1. stream the chunk's K and V once, online softmax -------------------
-  const int csize = (int)a.lay[layer].chunk;
-  const int c0 = chunk * csize;
   const int c_end = min(c0 + csize, n);
-  uint4 qf[G];
-#pragma unroll
-  for (int g = 0; g < G; ++g)
-    qf[g] = ld16(reinterpret_cast<const char*>(a.q) + (qoff + (int64_t)g * D) * (int64_t)sizeof(T) + c * 16);
-
-  const char* Kb = reinterpret_cast<const char*>(L.K) + (int64_t)u * cap * ROWB;
-  const char* Vb = reinterpret_cast<const char*>(L.V) + (int64_t)u * cap * ROWB;
-  const char* knew = reinterpret_cast<const char*>(a.k_new) + kvoff * (int64_t)sizeof(T);
-  const char* vnew = reinterpret_cast<const char*>(a.v_new) + kvoff * (int64_t)sizeof(T);
   float* glogit = (H2O && nsplit > 1) ? a.logit + a.lay[layer].logit_off + (int64_t)u * G * cap : nullptr;
 
   float m[G], l[G], acc[G][EPL];
@@ -282,19 +305,29 @@ __global__ __launch_bounds__(kDecThreads) void decode_unit_kernel(const DecodeAr
     for (int e = 0; e < EPL; ++e) acc[g][e] = 0.f;
   }
 
-  for (int base = c0; base < c_end; base += ROWS_IT * kUnroll) {
-    uint4 kf[kUnroll], vf[kUnroll];
-    int slot[kUnroll];
+  // patch the rows requested before the layout of this step was known
 #pragma unroll
-    for (int uu = 0; uu < kUnroll; ++uu) {
-      slot[uu] = base + uu * ROWS_IT + wave * RPI + r;
-      const int sl = min(slot[uu], n - 1);
-      const char* kp = Kb + (int64_t)sl * ROWB;
-      const char* vp = Vb + (int64_t)sl * ROWB;
-      if (sl == moved_to) { kp = Kb + (int64_t)slot_new * ROWB; vp = Vb + (int64_t)slot_new * ROWB; }
-      if (sl == slot_new) { kp = knew; vp = vnew; }
-      kf[uu] = ld16_nt(kp + c * 16);
-      vf[uu] = ld16_nt(vp + c * 16);
+  for (int uu = 0; uu < kUnroll; ++uu) {
+    if (slot[uu] == slot_new) { kf[uu] = kn_pre; vf[uu] = vn_pre; }
+    if (slot[uu] == moved_to) {
+      kf[uu] = ld16(Kb + (int64_t)slot_new * ROWB + c * 16);
+      vf[uu] = ld16(Vb + (int64_t)slot_new * ROWB + c * 16);
+    }
+  }
+
+  for (int base = c0; base < c_end; base += ROWS_IT * kUnroll) {
+    if (base != c0) {
+#pragma unroll
+      for (int uu = 0; uu < kUnroll; ++uu) {
+        slot[uu] = base + uu * ROWS_IT + wave * RPI + r;
+        const int sl = min(slot[uu], n - 1);
+        const char* kp = Kb + (int64_t)sl * ROWB;
+        const char* vp = Vb + (int64_t)sl * ROWB;
+        if (sl == moved_to) { kp = Kb + (int64_t)slot_new * ROWB; vp = Vb + (int64_t)slot_new * ROWB; }
+        if (sl == slot_new) { kp = knew; vp = vnew; }
+        kf[uu] = ld16_nt(kp + c * 16);
+        vf[uu] = ld16_nt(vp + c * 16);
+      }
     }
     float s[kUnroll][G];
 #pragma unroll
@@ -422,8 +455,6 @@ __global__ __launch_bounds__(kDecThreads) void decode_unit_kernel(const DecodeAr
   int next_hint = -1;
   const int head_next = full ? (head + 1 == rec ? 0 : head + 1) : head;
   if (H2O) {
-    const float leaver_score = moved_to >= 0 ? sc[slot_new] : 0.f;   // read before anyone rewrites it
-    const int leaver_pos = moved_to >= 0 ? posu[slot_new] : 0;
     __syncthreads();
     float fm[G], fi[G];
 #pragma unroll
@@ -438,7 +469,8 @@ __global__ __launch_bounds__(kDecThreads) void decode_unit_kernel(const DecodeAr
         const float lg = glogit ? ld_agent(&glogit[(int64_t)g * cap + i]) : s_logit[g * a.lds_chunk + i];
         p += fast_exp2(lg - fm[g]) * fi[g];
       }
-      const float old = i == slot_new ? 0.f : (i == moved_to ? leaver_score : sc[i]);
+      const float cur = i == tid ? sc_pre : sc[i];      // the first score of each thread was requested at the start
+      const float old = i == slot_new ? 0.f : (i == moved_to ? leaver_score : cur);
       const float nv = old + p;
       sc[i] = nv;
       if (i < hh) mn = fminf(mn, nv);
@@ -462,9 +494,8 @@ __global__ __launch_bounds__(kDecThreads) void decode_unit_kernel(const DecodeAr
       st16(Kw + (int64_t)moved_to * ROWB + c * 16, kk);
       st16(Vw + (int64_t)moved_to * ROWB + c * 16, vv);
     }
-    const uint4 kn = ld16(knew + c * 16), vn = ld16(vnew + c * 16);
-    st16(Kw + (int64_t)slot_new * ROWB + c * 16, kn);
-    st16(Vw + (int64_t)slot_new * ROWB + c * 16, vn);
+    st16(Kw + (int64_t)slot_new * ROWB + c * 16, kn_pre);
+    st16(Vw + (int64_t)slot_new * ROWB + c * 16, vn_pre);
     if (c == 0) {
       int32_t* posw = L.pos + (int64_t)u * cap;
       if (moved_to >= 0) posw[moved_to] = posw[slot_new];

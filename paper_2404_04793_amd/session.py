@@ -14,17 +14,20 @@ from . import workloads as W
 
 class Session:
     def __init__(self, wl: W.Workload, device="cuda:0", keep_prompt_q: bool = False, uniform_budget: bool = False,
-                 full_cache: bool = False):
+                 full_cache: bool = False, probe_tokens: Optional[int] = None):
+        """probe_tokens: hidden-state rows per layer given to the probe (default: all B*P prompt tokens;
+        a smaller number keeps the hidden states of the largest workloads within HBM)."""
         self.wl, self.dev = wl, device
         self.uniform_budget, self.full_cache = uniform_budget, full_cache
         self.u, self.mask = W.unit_dirs(wl), W.hh_mask(wl, device)
         L = wl.L
         # hidden states before / after self-attention, all layers: [L, T, hidden]
-        T = wl.B * wl.P
+        T = wl.B * wl.P if probe_tokens is None else int(probe_tokens)
+        self.probe_tokens = T
         self.h_in = torch.empty(L, T, wl.hidden, dtype=wl.torch_dtype, device=device)
         self.h_out = torch.empty_like(self.h_in)
         for l in range(L):
-            a, b = W.hidden_states(wl, l, device)
+            a, b = W.hidden_states(wl, l, device, n_tokens=T)
             self.h_in[l], self.h_out[l] = a, b
         # prompt K, V (kept resident: every pass compresses them again) and H2O prompt scores
         self.Kp, self.Vp, self.scores, self.Qp = [], [], [], []
@@ -123,7 +126,7 @@ class Session:
 
     def probe_bytes(self) -> int:
         wl = self.wl
-        return 2 * wl.L * wl.B * wl.P * wl.hidden * wl.elem_bytes
+        return 2 * wl.L * self.probe_tokens * wl.hidden * wl.elem_bytes
 
     def compress_bytes(self) -> int:
         wl = self.wl
