@@ -91,6 +91,7 @@ def main():
                     help="hidden-state rows per layer given to the probe (default: all B*P)")
     ap.add_argument("--decode-steps", type=int, default=None, help="decode steps per pass (default: the workload's)")
     ap.add_argument("--batch", type=int, default=None, help="override the workload's batch")
+    ap.add_argument("--budget-pct", type=int, default=None, help="override b_init as a percentage of the prompt")
     ap.add_argument("--calib-copy", action="store_true",
                     help="after the timed region run one plain 1 GiB -> 1 GiB elementwise copy kernel "
                          "(reference point for scaling rocprofv3's FETCH_SIZE / WRITE_SIZE counters)")
@@ -112,6 +113,8 @@ def main():
         wl = W.scaled(wl, S=args.decode_steps)
     if args.batch:
         wl = W.scaled(wl, B=args.batch)
+    if args.budget_pct:
+        wl = W.scaled(wl, budget_pct=args.budget_pct)
     torch.cuda.set_device(0)
     sess = Session(wl, "cuda:0", uniform_budget=args.uniform, full_cache=args.full_cache,
                    probe_tokens=args.probe_tokens)

@@ -14,8 +14,11 @@ LIB = os.path.join(HERE, "libsqa.so")
 OBJ_DIR = os.path.join(HERE, "_build")
 
 COMMON = ["-O3", "-std=c++17", "-fPIC", "-I" + os.path.join(ROOT, "include"), "-I" + CSRC]
+# -amdgpu-mfma-vgpr-form keeps MFMA accumulators in ordinary VGPRs: the decode kernel rescales them with
+# vector ALU instructions, and with the default (AGPR) form the compiler copied all 32 of them back and
+# forth every tile and needed twice the registers.
 HIP_FLAGS = ["--offload-arch=gfx950", "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
-             "-Wno-unused-command-line-argument"]
+             "-mllvm", "-amdgpu-mfma-vgpr-form", "-Wno-unused-command-line-argument"]
 HOST_FLAGS = ["-ffp-contract=off"]
 
 

@@ -32,16 +32,27 @@ __device__ __forceinline__ float dot2_bf16(uint32_t a, uint32_t b, float c) {
   return __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, a), __builtin_bit_cast(bf16x2_t, b), c, false);
 }
 
-__device__ __forceinline__ uint4 ld16(const void* p) { return *reinterpret_cast<const uint4*>(p); }
-// 16-byte load marked non-temporal (global_load_dwordx4 ... nt): data that is
-// streamed once per launch.  On MI355X a pure streaming read reaches about
-// 7.1 TB/s with nt loads against about 6.3 TB/s with plain loads.
+// 16-byte global-memory accesses.  Every pointer the kernels get is device
+// global memory, but many arrive through a struct read from memory, which the
+// compiler can only treat as generic ("flat"); flat loads also count against the
+// LDS wait counter, which would serialise them with LDS traffic.  Hence the
+// explicit global address space.
 typedef unsigned v4u_t __attribute__((ext_vector_type(4)));
-__device__ __forceinline__ uint4 ld16_nt(const void* p) {
-  const v4u_t v = __builtin_nontemporal_load(reinterpret_cast<const v4u_t*>(p));
+typedef __attribute__((address_space(1))) v4u_t g_v4u_t;
+__device__ __forceinline__ uint4 ld16(const void* p) {
+  const v4u_t v = *(const g_v4u_t*)(p);
   return make_uint4(v.x, v.y, v.z, v.w);
 }
-__device__ __forceinline__ void st16(void* p, uint4 v) { *reinterpret_cast<uint4*>(p) = v; }
+// marked non-temporal (global_load_dwordx4 ... nt): data that is streamed once
+// per launch.  On MI355X a pure streaming read reaches about 7.1 TB/s with nt
+// loads against about 6.3 TB/s with plain loads.
+__device__ __forceinline__ uint4 ld16_nt(const void* p) {
+  const v4u_t v = __builtin_nontemporal_load((const g_v4u_t*)(p));
+  return make_uint4(v.x, v.y, v.z, v.w);
+}
+__device__ __forceinline__ void st16(void* p, uint4 v) {
+  *(g_v4u_t*)(p) = v4u_t{v.x, v.y, v.z, v.w};
+}
 
 template <typename T> __device__ __forceinline__ T wave_sum(T v) {
 #pragma unroll

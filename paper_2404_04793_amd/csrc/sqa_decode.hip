@@ -189,13 +189,28 @@ template <> struct RowMath<bf16_t> {
 };
 
 
+#ifndef SQA_DEC_MF_WAVES
+#define SQA_DEC_MF_WAVES 2      // waves per SIMD the matrix-core variant is compiled for
+#endif
 #ifdef SQA_DEC_WAVES_PER_EU
 #define SQA_DEC_OCC __attribute__((amdgpu_waves_per_eu(SQA_DEC_WAVES_PER_EU, SQA_DEC_WAVES_PER_EU)))
 #else
 #define SQA_DEC_OCC
 #endif
-template <typename T, int D, int G, bool H2O>
-__global__ __launch_bounds__(kDecThreads) SQA_DEC_OCC void decode_unit_kernel(const DecodeArgs a) {
+typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
+typedef float f32x4_t __attribute__((ext_vector_type(4)));
+typedef __bf16 bf16x4_t __attribute__((ext_vector_type(4)));
+typedef short v4s_t __attribute__((ext_vector_type(4)));
+typedef short v8s_t __attribute__((ext_vector_type(8)));
+typedef __attribute__((address_space(3))) v4s_t* lds_v4s_ptr;
+constexpr int kStageRow = 256 + 16;               // LDS row pitch of a staged bf16 D=128 row (padded: no bank conflicts)
+constexpr int kStageBytesPerWave = 32 * kStageRow;   // one 32-token tile
+
+// MF = true (bf16, D = 128, grouped queries): the chunk is streamed in 32-token
+// tiles through LDS and q.K^T / P.V run on the matrix cores, see section 1M.
+template <typename T, int D, int G, bool H2O, bool MF>
+__global__ __launch_bounds__(kDecThreads, MF ? SQA_DEC_MF_WAVES : 1) SQA_DEC_OCC void decode_unit_kernel(const DecodeArgs a) {
+  static_assert(!MF || (sizeof(T) == 2 && D == 128 && G <= 16), "matrix-core path: bf16, D = 128");
   constexpr int ROWB = D * (int)sizeof(T);        // bytes per K or V row
   constexpr int LPR = ROWB / 16;                  // lanes per row
   constexpr int RPI = SQA_WAVE / LPR;             // rows per wave load
@@ -256,12 +271,14 @@ __global__ __launch_bounds__(kDecThreads) SQA_DEC_OCC void decode_unit_kernel(co
   const uint4 kn_pre = ld16(knew + c * 16), vn_pre = ld16(vnew + c * 16);
   uint4 kf[kUnroll], vf[kUnroll];
   int slot[kUnroll];
+  if constexpr (!MF) {
 #pragma unroll
-  for (int uu = 0; uu < kUnroll; ++uu) {
-    slot[uu] = c0 + uu * ROWS_IT + wave * RPI + r;
-    const int sl = min(slot[uu], cap - 1);
-    kf[uu] = ld16_nt(Kb + (int64_t)sl * ROWB + c * 16);
-    vf[uu] = ld16_nt(Vb + (int64_t)sl * ROWB + c * 16);
+    for (int uu = 0; uu < kUnroll; ++uu) {
+      slot[uu] = c0 + uu * ROWS_IT + wave * RPI + r;
+      const int sl = min(slot[uu], cap - 1);
+      kf[uu] = ld16_nt(Kb + (int64_t)sl * ROWB + c * 16);
+      vf[uu] = ld16_nt(Vb + (int64_t)sl * ROWB + c * 16);
+    }
   }
   const float sc_pre = H2O ? sc[min(tid, cap - 1)] : 0.f;
 
@@ -297,95 +314,238 @@ __global__ __launch_bounds__(kDecThreads) SQA_DEC_OCC void decode_unit_kernel(co
   const int c_end = min(c0 + csize, n);
   float* glogit = (H2O && nsplit > 1) ? a.logit + a.lay[layer].logit_off + (int64_t)u * G * cap : nullptr;
 
-  float m[G], l[G], acc[G][EPL];
+  if constexpr (MF) {
+    // ---- 1M. matrix-core streaming ------------------------------------------
+    // Lane roles (v_mfma_f32_16x16x32_bf16: A row / B column = lane%16, the 8
+    // contraction slots of a lane = 8*(lane/16)+e; C column = lane%16, rows
+    // 4*(lane/16)+i):
+    //   S^T = K.Q^T : A = 16 tokens of the tile (row = token), B = q of the g
+    //                 heads (column = head, zero beyond g); contraction slot
+    //                 (j,e) of step i <-> d = 32j + 8i + e for both operands;
+    //   O^T = V^T.P^T: per 16-token half of the tile a 16x16x16 step, A = V^T
+    //                 (row = d within a block of 16), B = P^T = the probabilities
+    //                 exactly where the S^T result left them (column = head);
+    //                 contraction slot (j,e) <-> token 4j+e of the half.
+    // So softmax statistics and the output accumulator live in the lanes of
+    // their head and nothing is moved between lanes except two max/sum steps.
+    // K and V tiles pass through a wave-private 8.5 KiB LDS buffer whose rows are
+    // padded by 16 bytes, which keeps the row-wise writes and the K fragment
+    // reads free of bank conflicts.
+    char* stage = reinterpret_cast<char*>(s_logit + (H2O ? G * a.lds_chunk : 0)) + wave * kStageBytesPerWave;
+    const int hd = lane & 15, j4 = lane >> 4;
+    bf16x8_t qfr[4];
 #pragma unroll
-  for (int g = 0; g < G; ++g) {
-    m[g] = -INFINITY; l[g] = 0.f;
-#pragma unroll
-    for (int e = 0; e < EPL; ++e) acc[g][e] = 0.f;
-  }
-
-  // patch the rows requested before the layout of this step was known
-#pragma unroll
-  for (int uu = 0; uu < kUnroll; ++uu) {
-    if (slot[uu] == slot_new) { kf[uu] = kn_pre; vf[uu] = vn_pre; }
-    if (slot[uu] == moved_to) {
-      kf[uu] = ld16(Kb + (int64_t)slot_new * ROWB + c * 16);
-      vf[uu] = ld16(Vb + (int64_t)slot_new * ROWB + c * 16);
+    for (int i = 0; i < 4; ++i) {
+      uint4 w = make_uint4(0, 0, 0, 0);
+      if (hd < G) w = ld16(reinterpret_cast<const char*>(a.q) + (qoff + (int64_t)hd * D) * 2 + 64 * j4 + 16 * i);
+      qfr[i] = __builtin_bit_cast(bf16x8_t, w);
     }
-  }
-
-  for (int base = c0; base < c_end; base += ROWS_IT * kUnroll) {
-    if (base != c0) {
+    f32x4_t oacc[8];
 #pragma unroll
-      for (int uu = 0; uu < kUnroll; ++uu) {
-        slot[uu] = base + uu * ROWS_IT + wave * RPI + r;
-        const int sl = min(slot[uu], n - 1);
-        const char* kp = Kb + (int64_t)sl * ROWB;
-        const char* vp = Vb + (int64_t)sl * ROWB;
-        if (sl == moved_to) { kp = Kb + (int64_t)slot_new * ROWB; vp = Vb + (int64_t)slot_new * ROWB; }
-        if (sl == slot_new) { kp = knew; vp = vnew; }
-        kf[uu] = ld16_nt(kp + c * 16);
-        vf[uu] = ld16_nt(vp + c * 16);
-      }
-    }
-    float s[kUnroll][G];
+    for (int db = 0; db < 8; ++db) oacc[db] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+    float m_run = -INFINITY, l_run = 0.f;
+    // LDS addresses of this lane (tile rows are kStageRow bytes apart, so every
+    // other address below is one of these plus a compile-time constant)
+    char* st_wr = stage + r * kStageRow + c * 16;                       // row-wise writes: + 4i rows
+    const char* st_k = stage + hd * kStageRow + j4 * 64;                 // K fragment: + 16tt rows, + 16i bytes
+    const char* st_v = stage + (4 * j4 + (hd >> 2)) * kStageRow + (hd & 3) * 8;   // V^T quadruple: + 16 rows, + 32db bytes
+    // Registers hold a tile only between its load and its copy into LDS, so the
+    // next tile's K (then V) is requested as soon as this tile's K (V) has been
+    // copied: a wave always has a tile in flight while it computes.
+    uint4 kreg[8], vreg[8];
+    auto request_k = [&](int base) {
 #pragma unroll
-    for (int uu = 0; uu < kUnroll; ++uu)
+      for (int i = 0; i < 8; ++i)
+        kreg[i] = ld16_nt(Kb + ((uint32_t)min(base + 4 * i + r, n - 1) * (uint32_t)ROWB + (uint32_t)(c * 16)));
+    };
+    auto request_v = [&](int base) {
 #pragma unroll
-      for (int g = 0; g < G; ++g) {
-        float d = group_sum<LPR>(RowMath<T>::dot(qf[g], kf[uu])) * a.scale_log2;
-        const bool valid = slot[uu] < c_end;
-        d = valid ? d : -INFINITY;
-        s[uu][g] = d;
-        if (H2O && c == 0 && valid) {
-          if (glogit) st_agent(&glogit[(int64_t)g * cap + slot[uu]], d);
-          else s_logit[g * a.lds_chunk + slot[uu]] = d;
+      for (int i = 0; i < 8; ++i)
+        vreg[i] = ld16_nt(Vb + ((uint32_t)min(base + 4 * i + r, n - 1) * (uint32_t)ROWB + (uint32_t)(c * 16)));
+    };
+    constexpr int TSTEP = 32 * kDecWaves;
+    if (c0 + 32 * wave < c_end) { request_k(c0 + 32 * wave); request_v(c0 + 32 * wave); }
+    for (int base = c0 + 32 * wave; base < c_end; base += TSTEP) {
+      const bool more = base + TSTEP < c_end;
+      // The two slots this step rewrites are still old in memory: their rows are
+      // patched in the staged tile (wave-uniform tests, true for one tile per unit).
+      const bool has_new = slot_new >= base && slot_new < base + 32;
+      const bool has_moved = moved_to >= base && moved_to < base + 32;
+      uint4 km = make_uint4(0, 0, 0, 0), vm = km;
+      if (has_moved) { km = ld16(Kb + (int64_t)slot_new * ROWB + c * 16); vm = ld16(Vb + (int64_t)slot_new * ROWB + c * 16); }
+#pragma unroll
+      for (int i = 0; i < 8; ++i) *reinterpret_cast<uint4*>(st_wr + 4 * i * kStageRow) = kreg[i];
+      if (has_moved && ((moved_to - base) & 3) == r)
+        *reinterpret_cast<uint4*>(st_wr + ((moved_to - base) >> 2) * 4 * kStageRow) = km;
+      if (has_new && ((slot_new - base) & 3) == r)
+        *reinterpret_cast<uint4*>(st_wr + ((slot_new - base) >> 2) * 4 * kStageRow) = kn_pre;
+      if (more) request_k(base + TSTEP);
+      f32x4_t sacc[2];
+#pragma unroll
+      for (int tt = 0; tt < 2; ++tt) {
+        sacc[tt] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          const uint4 w = *reinterpret_cast<const uint4*>(st_k + 16 * tt * kStageRow + 16 * i);
+          sacc[tt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, w), qfr[i], sacc[tt], 0, 0, 0);
         }
       }
+      float sv[8];
+      float mx = -INFINITY;
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        const int tok = base + (e < 4 ? 4 * j4 + e : 16 + 4 * j4 + (e - 4));
+        float d = (e < 4 ? sacc[0][e] : sacc[1][e - 4]) * a.scale_log2;
+        const bool valid = tok < c_end;
+        d = valid ? d : -INFINITY;
+        sv[e] = d;
+        mx = fmaxf(mx, d);
+        if (H2O && valid && hd < G) {
+          if (glogit) st_agent(&glogit[(int64_t)hd * cap + tok], d);
+          else s_logit[hd * a.lds_chunk + tok] = d;
+        }
+      }
+      mx = fmaxf(mx, __shfl_xor(mx, 16, SQA_WAVE));
+      mx = fmaxf(mx, __shfl_xor(mx, 32, SQA_WAVE));
+      const float m_new = fmaxf(m_run, mx);
+      const float ms = m_new == -INFINITY ? 0.f : m_new;
+      const float alpha = fast_exp2(m_run - ms);
+      m_run = m_new;
+      bf16x4_t pfr[2];
+      float psum = 0.f;
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        const float pe = fast_exp2(sv[e] - ms);
+        psum += pe;
+        pfr[e >> 2][e & 3] = (__bf16)pe;
+      }
+      l_run = l_run * alpha + psum;
+      if (__ballot(alpha != 1.f)) {
+#pragma unroll
+        for (int db = 0; db < 8; ++db) oacc[db] *= alpha;
+      }
+      // the K fragments are consumed: the same buffer now takes the V tile
+#pragma unroll
+      for (int i = 0; i < 8; ++i) *reinterpret_cast<uint4*>(st_wr + 4 * i * kStageRow) = vreg[i];
+      if (has_moved && ((moved_to - base) & 3) == r)
+        *reinterpret_cast<uint4*>(st_wr + ((moved_to - base) >> 2) * 4 * kStageRow) = vm;
+      if (has_new && ((slot_new - base) & 3) == r)
+        *reinterpret_cast<uint4*>(st_wr + ((slot_new - base) >> 2) * 4 * kStageRow) = vn_pre;
+      if (more) request_v(base + TSTEP);
+      // V^T fragments with the transposing LDS read (ds_read_b64_tr_b16): in a
+      // block of 16 lanes, lane 4e+a supplies the address of 4 consecutive
+      // 16-bit values and lane 4a+b receives, as element e, value b of the
+      // quadruple supplied by lane 4e+a.  With lane 4e+a pointing at
+      // V[token 4j+e][16db + 4a ..], lane m = 4a+b gets V[token 4j+e][16db + m],
+      // e = 0..3: the A fragment of a 16x16x16 step over that 16-token half.
+#pragma unroll
+      for (int tt = 0; tt < 2; ++tt)
+#pragma unroll
+        for (int db = 0; db < 8; ++db) {
+          const v4s_t vt = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4s_ptr)(st_v + 16 * tt * kStageRow + 32 * db));
+          oacc[db] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(vt, __builtin_bit_cast(v4s_t, pfr[tt]), oacc[db], 0, 0, 0);
+        }
+    }
+    l_run += __shfl_xor(l_run, 16, SQA_WAVE);
+    l_run += __shfl_xor(l_run, 32, SQA_WAVE);
+    if (hd < G) {
+      if (j4 == 0) { s_m[wave][hd] = m_run; s_l[wave][hd] = l_run; }
+#pragma unroll
+      for (int db = 0; db < 8; ++db)
+#pragma unroll
+        for (int i = 0; i < 4; ++i) s_acc[wave][hd][16 * db + 4 * j4 + i] = oacc[db][i];
+    }
+  } else {
+    float m[G], l[G], acc[G][EPL];
 #pragma unroll
     for (int g = 0; g < G; ++g) {
-      float mx = m[g];
+      m[g] = -INFINITY; l[g] = 0.f;
 #pragma unroll
-      for (int uu = 0; uu < kUnroll; ++uu) mx = fmaxf(mx, s[uu][g]);
-      const float ms = mx == -INFINITY ? 0.f : mx;
-      const float alpha = fast_exp2(m[g] - ms);
-      m[g] = mx;
-      float lsum = l[g] * alpha;
-#pragma unroll
-      for (int e = 0; e < EPL; ++e) acc[g][e] *= alpha;
-#pragma unroll
-      for (int uu = 0; uu < kUnroll; ++uu) {
-        const float p = fast_exp2(s[uu][g] - ms);
-        lsum += p;
-        RowMath<T>::axpy(p, vf[uu], acc[g]);
-      }
-      l[g] = lsum;
+      for (int e = 0; e < EPL; ++e) acc[g][e] = 0.f;
     }
-  }
 
-  // ---- 2. combine row groups of the wave, then the waves --------------------
+    // patch the rows requested before the layout of this step was known
 #pragma unroll
-  for (int g = 0; g < G; ++g) {
-#pragma unroll
-    for (int o = LPR; o < SQA_WAVE; o <<= 1) {
-      const float mo = __shfl_xor(m[g], o, SQA_WAVE);
-      const float lo2 = __shfl_xor(l[g], o, SQA_WAVE);
-      const float mx = fmaxf(m[g], mo);
-      const float ms = mx == -INFINITY ? 0.f : mx;
-      const float fa = fast_exp2(m[g] - ms), fb = fast_exp2(mo - ms);
-      l[g] = l[g] * fa + lo2 * fb;
-#pragma unroll
-      for (int e = 0; e < EPL; ++e) {
-        const float ao = __shfl_xor(acc[g][e], o, SQA_WAVE);
-        acc[g][e] = acc[g][e] * fa + ao * fb;
+    for (int uu = 0; uu < kUnroll; ++uu) {
+      if (slot[uu] == slot_new) { kf[uu] = kn_pre; vf[uu] = vn_pre; }
+      if (slot[uu] == moved_to) {
+        kf[uu] = ld16(Kb + (int64_t)slot_new * ROWB + c * 16);
+        vf[uu] = ld16(Vb + (int64_t)slot_new * ROWB + c * 16);
       }
-      m[g] = mx;
     }
-    if (r == 0) {
-      if (c == 0) { s_m[wave][g] = m[g]; s_l[wave][g] = l[g]; }
+
+    for (int base = c0; base < c_end; base += ROWS_IT * kUnroll) {
+      if (base != c0) {
 #pragma unroll
-      for (int e = 0; e < EPL; ++e) s_acc[wave][g][c * EPL + e] = acc[g][e];
+        for (int uu = 0; uu < kUnroll; ++uu) {
+          slot[uu] = base + uu * ROWS_IT + wave * RPI + r;
+          const int sl = min(slot[uu], n - 1);
+          const char* kp = Kb + (int64_t)sl * ROWB;
+          const char* vp = Vb + (int64_t)sl * ROWB;
+          if (sl == moved_to) { kp = Kb + (int64_t)slot_new * ROWB; vp = Vb + (int64_t)slot_new * ROWB; }
+          if (sl == slot_new) { kp = knew; vp = vnew; }
+          kf[uu] = ld16_nt(kp + c * 16);
+          vf[uu] = ld16_nt(vp + c * 16);
+        }
+      }
+      float s[kUnroll][G];
+#pragma unroll
+      for (int uu = 0; uu < kUnroll; ++uu)
+#pragma unroll
+        for (int g = 0; g < G; ++g) {
+          float d = group_sum<LPR>(RowMath<T>::dot(qf[g], kf[uu])) * a.scale_log2;
+          const bool valid = slot[uu] < c_end;
+          d = valid ? d : -INFINITY;
+          s[uu][g] = d;
+          if (H2O && c == 0 && valid) {
+            if (glogit) st_agent(&glogit[(int64_t)g * cap + slot[uu]], d);
+            else s_logit[g * a.lds_chunk + slot[uu]] = d;
+          }
+        }
+#pragma unroll
+      for (int g = 0; g < G; ++g) {
+        float mx = m[g];
+#pragma unroll
+        for (int uu = 0; uu < kUnroll; ++uu) mx = fmaxf(mx, s[uu][g]);
+        const float ms = mx == -INFINITY ? 0.f : mx;
+        const float alpha = fast_exp2(m[g] - ms);
+        m[g] = mx;
+        float lsum = l[g] * alpha;
+#pragma unroll
+        for (int e = 0; e < EPL; ++e) acc[g][e] *= alpha;
+#pragma unroll
+        for (int uu = 0; uu < kUnroll; ++uu) {
+          const float p = fast_exp2(s[uu][g] - ms);
+          lsum += p;
+          RowMath<T>::axpy(p, vf[uu], acc[g]);
+        }
+        l[g] = lsum;
+      }
+    }
+
+    // ---- 2. combine row groups of the wave, then the waves --------------------
+#pragma unroll
+    for (int g = 0; g < G; ++g) {
+#pragma unroll
+      for (int o = LPR; o < SQA_WAVE; o <<= 1) {
+        const float mo = __shfl_xor(m[g], o, SQA_WAVE);
+        const float lo2 = __shfl_xor(l[g], o, SQA_WAVE);
+        const float mx = fmaxf(m[g], mo);
+        const float ms = mx == -INFINITY ? 0.f : mx;
+        const float fa = fast_exp2(m[g] - ms), fb = fast_exp2(mo - ms);
+        l[g] = l[g] * fa + lo2 * fb;
+#pragma unroll
+        for (int e = 0; e < EPL; ++e) {
+          const float ao = __shfl_xor(acc[g][e], o, SQA_WAVE);
+          acc[g][e] = acc[g][e] * fa + ao * fb;
+        }
+        m[g] = mx;
+      }
+      if (r == 0) {
+        if (c == 0) { s_m[wave][g] = m[g]; s_l[wave][g] = l[g]; }
+#pragma unroll
+        for (int e = 0; e < EPL; ++e) s_acc[wave][g][c * EPL + e] = acc[g][e];
+      }
     }
   }
   __syncthreads();
@@ -462,19 +622,31 @@ __global__ __launch_bounds__(kDecThreads) SQA_DEC_OCC void decode_unit_kernel(co
     const bool next_full = n == budget;
     const int leaver_next = hh + head_next;
     float mn = INFINITY;
-    for (int i = tid; i < n; i += kDecThreads) {
-      float p = 0.f;
+    constexpr int SB = 4;                         // scores requested together: one round trip per SB tokens
+    for (int i0 = tid; i0 < n; i0 += SB * kDecThreads) {
+      float cur[SB];
 #pragma unroll
-      for (int g = 0; g < G; ++g) {
-        const float lg = glogit ? ld_agent(&glogit[(int64_t)g * cap + i]) : s_logit[g * a.lds_chunk + i];
-        p += fast_exp2(lg - fm[g]) * fi[g];
+      for (int k = 0; k < SB; ++k) {
+        const int i = i0 + k * kDecThreads;
+        cur[k] = (k == 0 && i0 == tid) ? sc_pre : sc[min(i, n - 1)];   // each thread's first score came with the start
       }
-      const float cur = i == tid ? sc_pre : sc[i];      // the first score of each thread was requested at the start
-      const float old = i == slot_new ? 0.f : (i == moved_to ? leaver_score : cur);
-      const float nv = old + p;
-      sc[i] = nv;
-      if (i < hh) mn = fminf(mn, nv);
-      if (i == leaver_next) s_ctlf[0] = nv;
+#pragma unroll
+      for (int k = 0; k < SB; ++k) {
+        const int i = i0 + k * kDecThreads;
+        if (i < n) {
+          float p = 0.f;
+#pragma unroll
+          for (int g = 0; g < G; ++g) {
+            const float lg = glogit ? ld_agent(&glogit[(int64_t)g * cap + i]) : s_logit[g * a.lds_chunk + i];
+            p += fast_exp2(lg - fm[g]) * fi[g];
+          }
+          const float old = i == slot_new ? 0.f : (i == moved_to ? leaver_score : cur[k]);
+          const float nv = old + p;
+          sc[i] = nv;
+          if (i < hh) mn = fminf(mn, nv);
+          if (i == leaver_next) s_ctlf[0] = nv;
+        }
+      }
     }
     if (next_full) {
       mn = block_min(mn, s_red);                  // also orders the s_ctlf write
@@ -509,12 +681,17 @@ __global__ __launch_bounds__(kDecThreads) SQA_DEC_OCC void decode_unit_kernel(co
 
 typedef void (*decode_fn)(const DecodeArgs);
 
+// Grouped queries of 8 heads in bf16 at D = 128 go to the matrix cores: there the vector-ALU path is
+// arithmetic bound (measured 4.2 TB/s against 5.7 TB/s on the Llama-2-70B shape); at 4 heads the
+// vector-ALU path is still the faster one (6.5 against 5.8 TB/s on the Mistral-7B shape).
+constexpr int kMfmaMinGroup = 8;
+template <typename T, int D, int G> constexpr bool use_mfma() { return sizeof(T) == 2 && D == 128 && G >= kMfmaMinGroup; }
 template <typename T, int D, bool H2O> decode_fn pick_g(int g) {
   switch (g) {
-    case 1: return decode_unit_kernel<T, D, 1, H2O>;
-    case 2: return decode_unit_kernel<T, D, 2, H2O>;
-    case 4: return decode_unit_kernel<T, D, 4, H2O>;
-    case 8: return decode_unit_kernel<T, D, 8, H2O>;
+    case 1: return decode_unit_kernel<T, D, 1, H2O, false>;
+    case 2: return decode_unit_kernel<T, D, 2, H2O, false>;
+    case 4: return decode_unit_kernel<T, D, 4, H2O, use_mfma<T, D, 4>()>;
+    case 8: return decode_unit_kernel<T, D, 8, H2O, use_mfma<T, D, 8>()>;
   }
   return nullptr;
 }
@@ -668,7 +845,11 @@ extern "C" sqa_status sqa_decode_step(const void* q, const void* k_new, const vo
   const sqa_status ps = plan_decode(layers, n_layers, B, Hq, Hkv, D, h2o, &plan);
   if (ps != SQA_OK) return ps;
   if (ws_bytes < plan.bytes) return SQA_ERR_CAPACITY;
-  const size_t lds = h2o ? (size_t)g * plan.lds_chunk * sizeof(float) : 0;
+  const bool mfma = dt == SQA_BF16 && D == 128 && g >= kMfmaMinGroup;
+  const size_t lds = (h2o ? (size_t)g * plan.lds_chunk * sizeof(float) : 0) +
+                     (mfma ? (size_t)kDecWaves * kStageBytesPerWave : 0);
+  if (lds > 64 * 1024)
+    SQA_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void*>(fn), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
 
   hipStream_t st = static_cast<hipStream_t>(stream);
   char* ws = static_cast<char*>(workspace);

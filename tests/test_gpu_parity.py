@@ -152,6 +152,11 @@ CASES = [
     ("h2o_bf16_split", "bf16", 2, 2, 2, 128, 2, 600, 6, "h2o", [603, 41]),
     ("h2o_f32_split_gqa2", "f32", 1, 4, 2, 64, 1, 420, 5, "h2o", [400]),
     ("stream_bf16_split_gqa4", "bf16", 1, 4, 1, 128, 1, 900, 4, "streaming", [777]),
+    # grouped queries in bf16 at D = 128 run on the matrix cores: with H2O logits, ragged tiles, split units
+    ("h2o_bf16_gqa8_mfma", "bf16", 2, 16, 2, 128, 2, 200, 8, "h2o", [61, 205]),
+    ("stream_bf16_gqa8_mfma_split", "bf16", 1, 8, 1, 128, 1, 900, 4, "streaming", [777]),
+    ("h2o_bf16_gqa8_mfma_split", "bf16", 1, 8, 1, 128, 1, 700, 5, "h2o", [650]),
+    ("slide_bf16_gqa8_mfma_tiny", "bf16", 1, 16, 2, 128, 1, 40, 6, "sliding", [3]),
 ]
 
 
