@@ -146,6 +146,15 @@ sqa_status sqa_prefill_compress(const void* K, const void* V, sqa_dtype kv_dt, c
                                 int B, int Hkv, int P, int D, sqa_policy policy, int n_sink,
                                 const sqa_layer_cache* layer, void* stream);
 
+/* The same for n_layers layers in one launch per 32 layers (Algorithm 1's loop over i at step 12).
+ *   K, V, attn_scores : HOST arrays [n_layers] of the DEVICE pointers sqa_prefill_compress takes
+ *                       (attn_scores may be NULL unless the policy is SQA_H2O)
+ *   layers            : HOST array [n_layers] */
+sqa_status sqa_prefill_compress_layers(const void* const* K, const void* const* V, sqa_dtype kv_dt,
+                                       const float* const* attn_scores, int B, int Hkv, int P, int D,
+                                       sqa_policy policy, int n_sink, const sqa_layer_cache* layers, int n_layers,
+                                       void* stream);
+
 /* ---- Algorithm 1 steps 14-21 with Eq. 2-3: one decode step ----------------
  * For each of n_layers layers and each unit, in this order:
  *   1. append the new token's k, v (position new_pos, accumulated score 0);

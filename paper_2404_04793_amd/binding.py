@@ -58,6 +58,9 @@ _lib.sqa_prefill_scores.restype = _i
 _lib.sqa_prefill_scores.argtypes = [_vp, _vp, _i, _i, _i, _i, _i, _i, _vp, _vp, _sz, _vp]
 _lib.sqa_prefill_compress.restype = _i
 _lib.sqa_prefill_compress.argtypes = [_vp, _vp, _i, _vp, _i, _i, _i, _i, _i, _i, _LCp, _vp]
+_lib.sqa_prefill_compress_layers.restype = _i
+_lib.sqa_prefill_compress_layers.argtypes = [C.POINTER(_vp), C.POINTER(_vp), _i, C.POINTER(_vp), _i, _i, _i, _i, _i, _i,
+                                             _LCp, _i, _vp]
 _lib.sqa_decode_workspace_bytes.restype = _sz
 _lib.sqa_decode_workspace_bytes.argtypes = [_LCp, _i, _i, _i, _i, _i, _i]
 _lib.sqa_decode_workspace_init.restype = _i
@@ -173,6 +176,19 @@ def prefill_compress(K: torch.Tensor, V: torch.Tensor, attn_scores: Optional[tor
     B, Hkv, P, D = K.shape
     _check(_lib.sqa_prefill_compress(_ptr(K), _ptr(V), _dt(K), _ptr(attn_scores), B, Hkv, P, D, POLICY[policy],
                                      n_sink, caches.struct_ptr(layer), _stream()), "sqa_prefill_compress")
+
+
+def prefill_compress_layers(K: Sequence[torch.Tensor], V: Sequence[torch.Tensor],
+                            attn_scores: Optional[Sequence[Optional[torch.Tensor]]], policy: str, n_sink: int,
+                            caches: LayerCaches, layer0: int = 0) -> None:
+    """K[i], V[i] [B, Hkv, P, D] of layer layer0 + i -> caches' layers layer0 .. layer0 + len(K) - 1."""
+    n = len(K)
+    B, Hkv, P, D = K[0].shape
+    Ks = (_vp * n)(*[t.data_ptr() for t in K])
+    Vs = (_vp * n)(*[t.data_ptr() for t in V])
+    Ss = None if attn_scores is None or attn_scores[0] is None else (_vp * n)(*[t.data_ptr() for t in attn_scores])
+    _check(_lib.sqa_prefill_compress_layers(Ks, Vs, _dt(K[0]), Ss, B, Hkv, P, D, POLICY[policy], n_sink,
+                                            caches.struct_ptr(layer0), n, _stream()), "sqa_prefill_compress_layers")
 
 
 def decode_workspace(caches: "LayerCaches", Hq: int, policy: str, layer0: int = 0,

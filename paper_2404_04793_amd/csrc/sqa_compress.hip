@@ -37,10 +37,21 @@ __device__ __forceinline__ int block_excl_count(bool flag, int* s_wave_tot, int&
   return before + within;
 }
 
+constexpr int kCmpBatch = 32;             // layers per launch (their descriptors travel as kernel arguments)
+struct CompressBatch {
+  sqa_layer_cache L[kCmpBatch];
+  const void* K[kCmpBatch];
+  const void* V[kCmpBatch];
+  const float* scores[kCmpBatch];
+};
+
 template <typename T, int D>
 __global__ __launch_bounds__(kCmpThreads) void prefill_compress_kernel(
-    const T* __restrict__ K, const T* __restrict__ V, const float* __restrict__ scores,
-    int P, sqa_layer_cache L, int policy, int n_sink, int keys_in_lds) {
+    const CompressBatch batch, int P, int policy, int n_sink, int lds_key_limit) {
+  const sqa_layer_cache L = batch.L[blockIdx.y];
+  const T* __restrict__ K = static_cast<const T*>(batch.K[blockIdx.y]);
+  const T* __restrict__ V = static_cast<const T*>(batch.V[blockIdx.y]);
+  const float* __restrict__ scores = batch.scores[blockIdx.y];
   constexpr int ROWB = D * (int)sizeof(T);
   constexpr int LPR = ROWB / 16;
   extern __shared__ uint32_t s_mem[];
@@ -66,6 +77,7 @@ __global__ __launch_bounds__(kCmpThreads) void prefill_compress_kernel(
     else { hh = b / 2; hi_from = P - (b - hh); }
   }
   const int M = hi_from;  // H2O candidates are positions [0, M)
+  const bool keys_in_lds = hh > 0 && M <= lds_key_limit;
 
   uint32_t thr = 0xffffffffu, take_eq = 0;
   if (hh > 0) {
@@ -172,31 +184,20 @@ __global__ __launch_bounds__(kCmpThreads) void kept_idx_sorted_kernel(sqa_layer_
   }
 }
 
-typedef void (*compress_fn)(const void*, const void*, const float*, int, sqa_layer_cache, int, int, int);
-
 template <typename T, int D>
-static void launch_compress(const void* K, const void* V, const float* scores, int P, const sqa_layer_cache& L,
-                            int policy, int n_sink, int keys_in_lds, unsigned blocks, size_t lds, hipStream_t st) {
+static void launch_compress(const CompressBatch& batch, int n, int P, int policy, int n_sink, int lds_key_limit,
+                            unsigned units, size_t lds, hipStream_t st) {
   auto fn = prefill_compress_kernel<T, D>;
   if (lds > 48 * 1024)
     (void)hipFuncSetAttribute(reinterpret_cast<const void*>(fn), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-  fn<<<blocks, kCmpThreads, lds, st>>>(static_cast<const T*>(K), static_cast<const T*>(V), scores, P, L, policy,
-                                       n_sink, keys_in_lds);
+  fn<<<dim3(units, n), kCmpThreads, lds, st>>>(batch, P, policy, n_sink, lds_key_limit);
 }
 
-}  // namespace sqa
-
-extern "C" sqa_status sqa_prefill_compress(const void* K, const void* V, sqa_dtype kv_dt, const float* attn_scores,
-                                           int B, int Hkv, int P, int D, sqa_policy policy, int n_sink,
-                                           const sqa_layer_cache* layer, void* stream) {
-  using namespace sqa;
-  if (!K || !V || !layer) return SQA_ERR_NULL;
-  if (kv_dt != SQA_F32 && kv_dt != SQA_BF16) return SQA_ERR_DTYPE;
-  if (policy != SQA_SLIDING && policy != SQA_STREAMING && policy != SQA_H2O) return SQA_ERR_POLICY;
-  if (n_sink < 0) return SQA_ERR_POLICY;
-  if (B < 1 || Hkv < 1 || P < 1 || (D != 64 && D != 128) || (int64_t)B * Hkv > INT32_MAX) return SQA_ERR_SHAPE;
+static sqa_status check_compress_layer(const void* K, const void* V, sqa_dtype kv_dt, const float* attn_scores,
+                                       int B, int Hkv, int P, int D, sqa_policy policy, int n_sink,
+                                       const sqa_layer_cache& L, size_t* lds_out) {
+  if (!K || !V) return SQA_ERR_NULL;
   if (policy == SQA_H2O && !attn_scores) return SQA_ERR_NULL;
-  const sqa_layer_cache& L = *layer;
   if (!L.K || !L.V || !L.pos || !L.lens || !L.ring_head) return SQA_ERR_NULL;
   if (policy == SQA_H2O && !L.score_acc) return SQA_ERR_NULL;
   if (!aligned16(K) || !aligned16(V) || !aligned16(L.K) || !aligned16(L.V)) return SQA_ERR_SHAPE;
@@ -213,24 +214,69 @@ extern "C" sqa_status sqa_prefill_compress(const void* K, const void* V, sqa_dty
   };
   if (overlaps(K, in_bytes, L.K, c_bytes) || overlaps(K, in_bytes, L.V, c_bytes) ||
       overlaps(V, in_bytes, L.K, c_bytes) || overlaps(V, in_bytes, L.V, c_bytes)) return SQA_ERR_SHAPE;
-
   const bool h2o_select = policy == SQA_H2O && P > L.budget;
   const int M = h2o_select ? P - (L.budget - L.budget / 2) : 0;
-  const int keys_in_lds = h2o_select && M <= kKeysInLdsMax;
-  const size_t lds = ((size_t)n_keep + (keys_in_lds ? (size_t)M : 0)) * sizeof(uint32_t);
-  if (lds > 128 * 1024) return SQA_ERR_CAPACITY;
-  hipStream_t st = static_cast<hipStream_t>(stream);
-  const unsigned blocks = (unsigned)(B * Hkv);
-  const float* sc = policy == SQA_H2O ? attn_scores : nullptr;
-  if (kv_dt == SQA_F32) {
-    if (D == 64) launch_compress<float, 64>(K, V, sc, P, L, policy, n_sink, keys_in_lds, blocks, lds, st);
-    else launch_compress<float, 128>(K, V, sc, P, L, policy, n_sink, keys_in_lds, blocks, lds, st);
-  } else {
-    if (D == 64) launch_compress<bf16_t, 64>(K, V, sc, P, L, policy, n_sink, keys_in_lds, blocks, lds, st);
-    else launch_compress<bf16_t, 128>(K, V, sc, P, L, policy, n_sink, keys_in_lds, blocks, lds, st);
-  }
-  SQA_HIP_CHECK(hipGetLastError());
+  *lds_out = ((size_t)n_keep + (M <= kKeysInLdsMax ? (size_t)M : 0)) * sizeof(uint32_t);
   return SQA_OK;
+}
+
+}  // namespace sqa
+
+extern "C" sqa_status sqa_prefill_compress_layers(const void* const* K, const void* const* V, sqa_dtype kv_dt,
+                                                  const float* const* attn_scores, int B, int Hkv, int P, int D,
+                                                  sqa_policy policy, int n_sink, const sqa_layer_cache* layers,
+                                                  int n_layers, void* stream) {
+  using namespace sqa;
+  if (!K || !V || !layers) return SQA_ERR_NULL;
+  if (kv_dt != SQA_F32 && kv_dt != SQA_BF16) return SQA_ERR_DTYPE;
+  if (policy != SQA_SLIDING && policy != SQA_STREAMING && policy != SQA_H2O) return SQA_ERR_POLICY;
+  if (n_sink < 0) return SQA_ERR_POLICY;
+  if (B < 1 || Hkv < 1 || P < 1 || (D != 64 && D != 128) || (int64_t)B * Hkv > INT32_MAX || n_layers < 1 ||
+      n_layers > SQA_MAX_LAYERS)
+    return SQA_ERR_SHAPE;
+  if (policy == SQA_H2O && !attn_scores) return SQA_ERR_NULL;
+  size_t lds_layer[SQA_MAX_LAYERS];
+  for (int i = 0; i < n_layers; ++i) {
+    const sqa_status st = check_compress_layer(K[i], V[i], kv_dt, attn_scores ? attn_scores[i] : nullptr, B, Hkv, P, D,
+                                               policy, n_sink, layers[i], &lds_layer[i]);
+    if (st != SQA_OK) return st;
+    if (lds_layer[i] > 128 * 1024) return SQA_ERR_CAPACITY;
+  }
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  const unsigned units = (unsigned)(B * Hkv);
+  for (int l0 = 0; l0 < n_layers; l0 += kCmpBatch) {
+    const int n = n_layers - l0 < kCmpBatch ? n_layers - l0 : kCmpBatch;
+    CompressBatch batch;
+    size_t lds = 0;
+    for (int i = 0; i < n; ++i) {
+      batch.L[i] = layers[l0 + i];
+      batch.K[i] = K[l0 + i];
+      batch.V[i] = V[l0 + i];
+      batch.scores[i] = policy == SQA_H2O ? attn_scores[l0 + i] : nullptr;
+      lds = lds_layer[l0 + i] > lds ? lds_layer[l0 + i] : lds;
+    }
+    for (int i = n; i < kCmpBatch; ++i) { batch.L[i] = layers[l0]; batch.K[i] = nullptr; batch.V[i] = nullptr; batch.scores[i] = nullptr; }
+    if (kv_dt == SQA_F32) {
+      if (D == 64) launch_compress<float, 64>(batch, n, P, policy, n_sink, kKeysInLdsMax, units, lds, st);
+      else launch_compress<float, 128>(batch, n, P, policy, n_sink, kKeysInLdsMax, units, lds, st);
+    } else {
+      if (D == 64) launch_compress<bf16_t, 64>(batch, n, P, policy, n_sink, kKeysInLdsMax, units, lds, st);
+      else launch_compress<bf16_t, 128>(batch, n, P, policy, n_sink, kKeysInLdsMax, units, lds, st);
+    }
+    SQA_HIP_CHECK(hipGetLastError());
+  }
+  return SQA_OK;
+}
+
+extern "C" sqa_status sqa_prefill_compress(const void* K, const void* V, sqa_dtype kv_dt, const float* attn_scores,
+                                           int B, int Hkv, int P, int D, sqa_policy policy, int n_sink,
+                                           const sqa_layer_cache* layer, void* stream) {
+  if (!K || !V || !layer) return SQA_ERR_NULL;
+  const void* Ks[1] = {K};
+  const void* Vs[1] = {V};
+  const float* Ss[1] = {attn_scores};
+  return sqa_prefill_compress_layers(Ks, Vs, kv_dt, attn_scores ? Ss : nullptr, B, Hkv, P, D, policy, n_sink, layer, 1,
+                                     stream);
 }
 
 extern "C" sqa_status sqa_kept_idx_sorted(const sqa_layer_cache* layer, int B, int Hkv, int32_t* out, void* stream) {

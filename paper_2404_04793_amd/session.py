@@ -85,8 +85,7 @@ class Session:
     # -- steps 12 + 16-17 on the prompt ---------------------------------------
     def compress_prompt(self):
         wl = self.wl
-        for l in range(wl.L):
-            sqa.prefill_compress(self.Kp[l], self.Vp[l], self.scores[l], wl.policy, wl.n_sink, self.caches, l)
+        sqa.prefill_compress_layers(self.Kp, self.Vp, self.scores, wl.policy, wl.n_sink, self.caches)
 
     # -- steps 14-21 -----------------------------------------------------------
     def decode(self, steps: Optional[int] = None, per_layer: bool = False, start: int = 0):

@@ -118,6 +118,27 @@ def test_prefill_compress(sqa, policy, dtype, B, Hkv, P, D, b):
                 assert np.array_equal(got["score"], want["score"])
 
 
+def test_prefill_compress_layers_matches_single_layer_calls(sqa):
+    """One launch over 35 layers with different budgets (two batches of kernel arguments) == 35 calls."""
+    B, Hkv, P, D, L = 2, 2, 300, 128, 35
+    r = np.random.default_rng(5)
+    budgets = [int(x) for x in r.integers(2, 340, size=L)]
+    Ks = [torch.randn(B, Hkv, P, D, device=DEV).to(torch.bfloat16) for _ in range(L)]
+    Vs = [torch.randn(B, Hkv, P, D, device=DEV).to(torch.bfloat16) for _ in range(L)]
+    Ss = [torch.rand(B, Hkv, P, device=DEV) for _ in range(L)]
+    caps = [min(b, P) for b in budgets]
+    a = _mk_caches(sqa, budgets, caps, B, Hkv, D, "bf16")
+    b = _mk_caches(sqa, budgets, caps, B, Hkv, D, "bf16")
+    sqa.prefill_compress_layers(Ks, Vs, Ss, "h2o", 4, a)
+    for l in range(L):
+        sqa.prefill_compress(Ks[l], Vs[l], Ss[l], "h2o", 4, b, l)
+    for l in range(L):
+        assert torch.equal(a.pos[l], b.pos[l]) and torch.equal(a.lens[l], b.lens[l])
+        assert torch.equal(a.K[l].view(torch.int16), b.K[l].view(torch.int16))
+        assert torch.equal(a.V[l].view(torch.int16), b.V[l].view(torch.int16))
+        assert torch.equal(a.score[l], b.score[l]) and bool((a.hint[l] == -2).all())
+
+
 def test_prefill_compress_large_prompt_h2o_global_keys(sqa):
     """More candidates than the LDS staging limit: the select reads scores from memory."""
     B, Hkv, P, D, b = 1, 1, 20000, 64, 300
