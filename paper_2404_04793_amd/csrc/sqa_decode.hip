@@ -82,9 +82,12 @@ __device__ __forceinline__ float ld_agent(const float* p) {
 }
 
 // block-wide reductions; every thread gets the result
-__device__ __forceinline__ float block_min(float v, float* s_red) {
+// solo: only wave 0 of the workgroup is still running (the others have left),
+// so the reduction stays inside the wave and no barrier may be used.
+__device__ __forceinline__ float block_min(float v, float* s_red, bool solo) {
 #pragma unroll
   for (int o = 32; o > 0; o >>= 1) v = fminf(v, __shfl_xor(v, o, SQA_WAVE));
+  if (solo) return v;
   __syncthreads();
   if ((threadIdx.x & (SQA_WAVE - 1)) == 0) s_red[threadIdx.x / SQA_WAVE] = v;
   __syncthreads();
@@ -93,12 +96,13 @@ __device__ __forceinline__ float block_min(float v, float* s_red) {
   for (int w = 1; w < kDecWaves; ++w) v = fminf(v, s_red[w]);
   return v;
 }
-__device__ __forceinline__ unsigned long long block_max64(unsigned long long v, unsigned long long* s_red) {
+__device__ __forceinline__ unsigned long long block_max64(unsigned long long v, unsigned long long* s_red, bool solo) {
 #pragma unroll
   for (int o = 32; o > 0; o >>= 1) {
     const unsigned long long other = __shfl_xor(v, o, SQA_WAVE);
     v = other > v ? other : v;
   }
+  if (solo) return v;
   __syncthreads();
   if ((threadIdx.x & (SQA_WAVE - 1)) == 0) s_red[threadIdx.x / SQA_WAVE] = v;
   __syncthreads();
@@ -116,16 +120,18 @@ __device__ __forceinline__ unsigned long long block_max64(unsigned long long v, 
 // scores, already reduced over the block.  pos_override: slot whose position
 // is not yet in memory (or -1).
 __device__ __forceinline__ int pick_victim(const float* sc, const int32_t* posu, int hh, float mn, float leaver_score,
-                                           int override_slot, int override_pos, unsigned long long* s_red64) {
+                                           int override_slot, int override_pos, unsigned long long* s_red64,
+                                           bool solo) {
   if (leaver_score <= mn) return -1;             // uniform over the block
   unsigned long long best = 0ull;                // (position + 1) << 32 | slot
-  for (int i = threadIdx.x; i < hh; i += kDecThreads)
+  const int nthr = solo ? SQA_WAVE : kDecThreads;
+  for (int i = threadIdx.x; i < hh; i += nthr)
     if (sc[i] == mn) {
       const int ps = i == override_slot ? override_pos : posu[i];
       const unsigned long long key = ((unsigned long long)(uint32_t)(ps + 1) << 32) | (uint32_t)i;
       best = key > best ? key : best;
     }
-  return (int)(uint32_t)block_max64(best, s_red64);
+  return (int)(uint32_t)block_max64(best, s_red64, solo);
 }
 
 // v_exp_f32: 2^x, 1 ulp, denormal results flush to 0 (harmless in a softmax)
@@ -302,8 +308,8 @@ __global__ __launch_bounds__(kDecThreads, MF ? SQA_DEC_MF_WAVES : 1) SQA_DEC_OCC
     } else {                                      // no decision carried over: take it now
       float mn = INFINITY;
       for (int i = tid; i < hh; i += kDecThreads) mn = fminf(mn, sc[i]);
-      mn = block_min(mn, s_red);
-      moved_to = pick_victim(sc, posu, hh, mn, sc[slot_new], -1, 0, s_red64);
+      mn = block_min(mn, s_red, false);
+      moved_to = pick_victim(sc, posu, hh, mn, sc[slot_new], -1, 0, s_red64, false);
     }
   }
   // the ring leaver's score and position, needed in step 3 if it moves
@@ -612,10 +618,17 @@ __global__ __launch_bounds__(kDecThreads, MF ? SQA_DEC_MF_WAVES : 1) SQA_DEC_OCC
   }
 
   // ---- 3. H2O accumulation and the next step's eviction decision ------------
+  // What is left is a short tail of dependent loads and stores.  A wave keeps
+  // its registers until its last store is acknowledged, so for an unsplit unit
+  // waves 1-3 leave here and wave 0 finishes alone: three quarters of the
+  // workgroup's registers are free for the next workgroup while the tail runs.
+  __syncthreads();                                // every wave is done reading the cache rows and writing LDS
+  const bool solo = nsplit == 1;
+  if (solo && wave != 0) return;
+  const int nthr = solo ? SQA_WAVE : kDecThreads;
   int next_hint = -1;
   const int head_next = full ? (head + 1 == rec ? 0 : head + 1) : head;
   if (H2O) {
-    __syncthreads();
     float fm[G], fi[G];
 #pragma unroll
     for (int g = 0; g < G; ++g) { fm[g] = s_m[0][g]; fi[g] = s_l[0][g]; }
@@ -623,16 +636,16 @@ __global__ __launch_bounds__(kDecThreads, MF ? SQA_DEC_MF_WAVES : 1) SQA_DEC_OCC
     const int leaver_next = hh + head_next;
     float mn = INFINITY;
     constexpr int SB = 4;                         // scores requested together: one round trip per SB tokens
-    for (int i0 = tid; i0 < n; i0 += SB * kDecThreads) {
+    for (int i0 = tid; i0 < n; i0 += SB * nthr) {
       float cur[SB];
 #pragma unroll
       for (int k = 0; k < SB; ++k) {
-        const int i = i0 + k * kDecThreads;
+        const int i = i0 + k * nthr;
         cur[k] = (k == 0 && i0 == tid) ? sc_pre : sc[min(i, n - 1)];   // each thread's first score came with the start
       }
 #pragma unroll
       for (int k = 0; k < SB; ++k) {
-        const int i = i0 + k * kDecThreads;
+        const int i = i0 + k * nthr;
         if (i < n) {
           float p = 0.f;
 #pragma unroll
@@ -649,12 +662,11 @@ __global__ __launch_bounds__(kDecThreads, MF ? SQA_DEC_MF_WAVES : 1) SQA_DEC_OCC
       }
     }
     if (next_full) {
-      mn = block_min(mn, s_red);                  // also orders the s_ctlf write
+      mn = block_min(mn, s_red, solo);            // (the barrier inside also orders the s_ctlf write)
       // positions as they will be after step 4: the moved token brings its own
-      next_hint = pick_victim(sc, posu, hh, mn, s_ctlf[0], moved_to, leaver_pos, s_red64);
+      next_hint = pick_victim(sc, posu, hh, mn, s_ctlf[0], moved_to, leaver_pos, s_red64, solo);
     }
   }
-  __syncthreads();                                // every wave is done reading the cache rows
 
   // ---- 4. the cache update: moved row, new token, bookkeeping ---------------
   if (wave == 0 && r == 0) {
