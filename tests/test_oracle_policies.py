@@ -115,6 +115,14 @@ def test_top_k_is_mergeable(policy):
     assert cur == once.tolist()
 
 
+def test_streaming_sinks_are_positions_below_n_sink():
+    """The sinks are the first n tokens of the sequence (Sec. 5.1), i.e. positions < n_sink -- not
+    whatever happens to be oldest in the cache."""
+    pos = np.array([0, 1, 4, 6, 7, 8, 9])
+    assert pos[O.select_keep(pos, np.zeros(7), 5, "streaming")].tolist() == [0, 1, 7, 8, 9]
+    assert pos[O.select_keep(pos, np.zeros(7), 5, "streaming", n_sink=1)].tolist() == [0, 6, 7, 8, 9]
+
+
 def test_streaming_small_budget_and_short_prompt():
     assert O.select_keep(np.arange(10), np.zeros(10), 5, "streaming").tolist() == [0, 1, 2, 3, 9]
     assert O.select_keep(np.arange(3), np.zeros(3), 8, "streaming").tolist() == [0, 1, 2]
