@@ -1,0 +1,72 @@
+"""Attention-level analogue of the paper's throughput and memory comparisons
+(Sec. 5.3 Fig. 4: KV memory per generated token; Sec. 5.4 Table 3: tokens/s
+against batch size for the layer-wise budgets, the sequence-only baseline and
+the full cache), on synthetic inputs of the paper's shapes.
+
+    python -m paper_2404_04793_amd.report [--workload stress_7b] [--batches 1,32,64,128,224]
+                                          [--decode-steps 64]
+
+Prints a markdown table.  Only the decode steps are timed (HIP events); every
+number comes from the HIP library through the binding.
+"""
+from __future__ import annotations
+
+import argparse
+import sys
+
+import torch
+
+from . import workloads as W
+from .session import Session
+
+
+def run_mode(wl: W.Workload, mode: str, passes: int = 2):
+    sess = Session(wl, "cuda:0", uniform_budget=(mode == "uniform"), full_cache=(mode == "full"),
+                   probe_tokens=min(wl.B * wl.P, 4096))
+    best = None
+    for _ in range(passes):
+        sess.probe_and_allocate()
+        sess.compress_prompt()
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        a.record()
+        sess.decode()
+        b.record()
+        torch.cuda.synchronize()
+        ms = a.elapsed_time(b)
+        best = ms if best is None else min(best, ms)
+    tok_s = wl.B * wl.S / (best * 1e-3)
+    gbs = sum(sess.decode_bytes_per_step()) / (best * 1e-3) / 1e9
+    kv_gb = sess.resident_kv_bytes() / 1e9
+    per_seq_mb = sess.resident_kv_bytes() / wl.B / 1e6
+    del sess
+    torch.cuda.empty_cache()
+    return tok_s, gbs, kv_gb, per_seq_mb
+
+
+def main(argv=None):
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--workload", default="stress_7b")
+    ap.add_argument("--batches", default="1,32,64,128,224")
+    ap.add_argument("--decode-steps", type=int, default=64)
+    ap.add_argument("--budget-pct", type=int, default=None)
+    args = ap.parse_args(argv)
+    base = W.WORKLOADS[args.workload]
+    if args.budget_pct:
+        base = W.scaled(base, budget_pct=args.budget_pct)
+    base = W.scaled(base, S=args.decode_steps)
+    print("| batch | mode | tokens/s | GB/s | resident KV (GB) | KV per sequence (MB) |")
+    print("|---|---|---|---|---|---|")
+    for bs in [int(x) for x in args.batches.split(",")]:
+        wl = W.scaled(base, B=bs)
+        for mode in ("squeeze", "uniform", "full"):
+            try:
+                tok_s, gbs, kv_gb, per_seq = run_mode(wl, mode)
+                print("| %d | %s | %.0f | %.0f | %.2f | %.1f |" % (bs, mode, tok_s, gbs, kv_gb, per_seq))
+            except torch.cuda.OutOfMemoryError:
+                print("| %d | %s | OOM | | | |" % (bs, mode))
+            sys.stdout.flush()
+
+
+if __name__ == "__main__":
+    main()
