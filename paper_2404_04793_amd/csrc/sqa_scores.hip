@@ -166,6 +166,180 @@ __global__ __launch_bounds__(kScThreads) void score_colsum_kernel(
   }
 }
 
+// ---------------------------------------------------------------------------
+// bf16, D = 128: the same two passes on the matrix cores.
+//   v_mfma_f32_16x16x32_bf16: A row / B column = lane%16, contraction slots of
+//   a lane = 8*(lane/16)+e; C column = lane%16, rows 4*(lane/16)+i.  For both
+//   operands slot (j,e) of step i stands for d = 32j + 8i + e, so a lane's four
+//   fragments are 64 contiguous bytes of its row.
+//   pass 1  S^T = K.Q^T: a wave keeps its 16 query rows as the B operand in
+//           registers; 64-key tiles of K are staged in LDS (row-padded, double
+//           buffered) and shared by the 4 waves of the workgroup (64 query rows).
+//           A lane sees 4 keys of one query per product and keeps a running
+//           (max, sum) of its own; the 4 lanes of a query merge once at the end.
+//   pass 2  S = Q.K^T: a wave keeps its 16 keys as the B operand; 64-row tiles
+//           of Q (and their row statistics) are staged in LDS; a lane sees 4
+//           query rows of one key per product and adds exp2(s - m_i)/l_i into a
+//           per-lane column sum over all row tiles and all g heads of the group.
+// exp2 runs at a quarter of the vector rate, so the two passes are bound by
+// the P^2/2 exponentials per head about as much as by the products.
+typedef __bf16 sc_bf16x8_t __attribute__((ext_vector_type(8)));
+typedef float sc_f32x4_t __attribute__((ext_vector_type(4)));
+constexpr int kMT = 64;                 // rows of a staged tile
+constexpr int kMPitch = 256 + 16;       // LDS bytes per staged row (padded: conflict-free fragment reads)
+constexpr int kMTileBytes = kMT * kMPitch;
+
+// request one [64 x 128] bf16 tile (rows row0.., clamped to P-1): 4 x 16 bytes per thread
+__device__ __forceinline__ void tile_request(const bf16_t* __restrict__ src, int row0, int P, uint4 (&reg)[4]) {
+  const int tid = threadIdx.x;
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const int row = min(row0 + (tid >> 4) + 16 * i, P - 1);
+    reg[i] = ld16(src + (int64_t)row * 128 + (tid & 15) * 8);
+  }
+}
+__device__ __forceinline__ void tile_store(char* lds, const uint4 (&reg)[4]) {
+  const int tid = threadIdx.x;
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+    *reinterpret_cast<uint4*>(lds + ((tid >> 4) + 16 * i) * kMPitch + (tid & 15) * 16) = reg[i];
+}
+// the four fragments of row `row` (global memory) for a lane with contraction group j
+__device__ __forceinline__ void row_fragments(const bf16_t* __restrict__ src, int row, int j, sc_bf16x8_t (&fr)[4]) {
+#pragma unroll
+  for (int i = 0; i < 4; ++i) fr[i] = __builtin_bit_cast(sc_bf16x8_t, ld16(src + (int64_t)row * 128 + 32 * j + 8 * i));
+}
+// C = A_tile[16 sub .. 16 sub + 15] . B^T for one 16 x 16 block
+__device__ __forceinline__ sc_f32x4_t block_product(const char* lds, int sub, const sc_bf16x8_t (&bfr)[4]) {
+  const int lane = threadIdx.x & 63;
+  const char* p = lds + (16 * sub + (lane & 15)) * kMPitch + (lane >> 4) * 64;
+  sc_f32x4_t c = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const uint4 w = *reinterpret_cast<const uint4*>(p + 16 * i);
+    c = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(sc_bf16x8_t, w), bfr[i], c, 0, 0, 0);
+  }
+  return c;
+}
+
+__global__ __launch_bounds__(kScThreads) void score_rowstats_mfma_kernel(
+    const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K, int Hq, int Hkv, int P, float scale_log2,
+    float2* __restrict__ stats) {
+  extern __shared__ char s_tiles[];                 // 2 x [64][kMPitch]
+  const int bh = blockIdx.y, b = bh / Hq, h = bh % Hq, kvh = h / (Hq / Hkv);
+  const bf16_t* Qh = Q + (int64_t)bh * P * 128;
+  const bf16_t* Kh = K + ((int64_t)b * Hkv + kvh) * P * 128;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int n16 = lane & 15, j4 = lane >> 4;
+  const int r0 = blockIdx.x * kMT + 16 * wave;      // this wave's 16 query rows
+  const int my_row = r0 + n16;
+  sc_bf16x8_t qfr[4];
+  row_fragments(Qh, min(my_row, P - 1), j4, qfr);
+  float m_run = -INFINITY, l_run = 0.f;
+  uint4 reg[4];
+  tile_request(Kh, 0, P, reg);
+  const int n_tiles = blockIdx.x + 1;               // key tiles 0 .. the diagonal one
+  for (int kt = 0; kt < n_tiles; ++kt) {
+    char* buf = s_tiles + (kt & 1) * kMTileBytes;
+    tile_store(buf, reg);
+    __syncthreads();                                // tile kt visible; everyone is past tile kt-1
+    if (kt + 1 < n_tiles) tile_request(Kh, (kt + 1) * kMT, P, reg);
+#pragma unroll
+    for (int sub = 0; sub < 4; ++sub) {
+      const int c0 = kt * kMT + 16 * sub;
+      if (c0 > r0 + 15) continue;                   // wave-uniform: all keys beyond all of this wave's rows
+      const sc_f32x4_t s4 = block_product(buf, sub, qfr);
+      float v[4], mx = m_run;
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        const int key = c0 + 4 * j4 + e;
+        v[e] = (key <= my_row && key < P) ? s4[e] * scale_log2 : -INFINITY;
+        mx = fmaxf(mx, v[e]);
+      }
+      const float ms = mx == -INFINITY ? 0.f : mx;
+      float sum = l_run * __builtin_amdgcn_exp2f(m_run - ms);
+#pragma unroll
+      for (int e = 0; e < 4; ++e) sum += __builtin_amdgcn_exp2f(v[e] - ms);
+      l_run = sum; m_run = mx;
+    }
+  }
+  // the 4 lanes of a query row (contraction groups) merge their statistics
+#pragma unroll
+  for (int o = 16; o < 64; o <<= 1) {
+    const float mo = __shfl_xor(m_run, o, 64), lo = __shfl_xor(l_run, o, 64);
+    const float mx = fmaxf(m_run, mo);
+    const float ms = mx == -INFINITY ? 0.f : mx;
+    l_run = l_run * __builtin_amdgcn_exp2f(m_run - ms) + lo * __builtin_amdgcn_exp2f(mo - ms);
+    m_run = mx;
+  }
+  if (j4 == 0 && my_row < P) stats[(int64_t)bh * P + my_row] = make_float2(m_run, 1.f / l_run);
+}
+
+__global__ __launch_bounds__(kScThreads) void score_colsum_mfma_kernel(
+    const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K, int Hq, int Hkv, int P, float scale_log2,
+    const float2* __restrict__ stats, float* __restrict__ scores) {
+  extern __shared__ char s_tiles[];                 // 2 x ([64][kMPitch] + 64 float2)
+  constexpr int BUF = kMTileBytes + kMT * (int)sizeof(float2);
+  const int bk = blockIdx.y, b = bk / Hkv, kvh = bk % Hkv, g = Hq / Hkv;
+  const bf16_t* Kh = K + (int64_t)bk * P * 128;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int n16 = lane & 15, j4 = lane >> 4;
+  const int k0 = blockIdx.x * kMT + 16 * wave;      // this wave's 16 keys
+  const int my_key = k0 + n16;
+  sc_bf16x8_t kfr[4];
+  row_fragments(Kh, min(my_key, P - 1), j4, kfr);
+  float colsum = 0.f;
+  const int first = blockIdx.x, n_rt = (P + kMT - 1) / kMT;
+  const int total = g * (n_rt - first);             // (head, row tile) pairs, head-major
+  uint4 reg[4];
+  float2 st_reg = make_float2(0.f, 0.f);
+  auto request = [&](int it) {
+    const int hg = it / (n_rt - first), rt = first + it % (n_rt - first);
+    const int64_t bh = (int64_t)b * Hq + (int64_t)kvh * g + hg;
+    tile_request(Q + bh * P * 128, rt * kMT, P, reg);
+    if (threadIdx.x < kMT) st_reg = stats[bh * P + min(rt * kMT + (int)threadIdx.x, P - 1)];
+  };
+  request(0);
+  for (int it = 0; it < total; ++it) {
+    char* buf = s_tiles + (it & 1) * BUF;
+    float2* st_lds = reinterpret_cast<float2*>(buf + kMTileBytes);
+    tile_store(buf, reg);
+    if (threadIdx.x < kMT) st_lds[threadIdx.x] = st_reg;
+    __syncthreads();
+    if (it + 1 < total) request(it + 1);
+    const int rt = first + it % (n_rt - first);
+#pragma unroll
+    for (int sub = 0; sub < 4; ++sub) {
+      const int i0 = rt * kMT + 16 * sub;
+      if (i0 + 15 < k0) continue;                   // wave-uniform: all rows above all of this wave's keys
+      const sc_f32x4_t s4 = block_product(buf, sub, kfr);
+      const float4 sa = *reinterpret_cast<const float4*>(&st_lds[16 * sub + 4 * j4]);       // rows 4j4, 4j4+1
+      const float4 sb = *reinterpret_cast<const float4*>(&st_lds[16 * sub + 4 * j4 + 2]);   // rows 4j4+2, 4j4+3
+      const float mrow[4] = {sa.x, sa.z, sb.x, sb.z}, irow[4] = {sa.y, sa.w, sb.y, sb.w};
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        const int row = i0 + 4 * j4 + e;
+        const float p = __builtin_amdgcn_exp2f(s4[e] * scale_log2 - mrow[e]) * irow[e];
+        colsum += (row >= my_key && row < P) ? p : 0.f;
+      }
+    }
+  }
+  colsum += __shfl_xor(colsum, 16, 64);
+  colsum += __shfl_xor(colsum, 32, 64);
+  if (j4 == 0 && my_key < P) scores[(int64_t)bk * P + my_key] = colsum;
+}
+
+static void launch_scores_mfma(const void* Q, const void* K, int B, int Hq, int Hkv, int P, float* scores,
+                               float2* stats, hipStream_t st) {
+  const float scale_log2 = (float)(1.4426950408889634 / sqrt(128.0));
+  const int tiles = (P + kMT - 1) / kMT;
+  const size_t lds1 = 2 * (size_t)kMTileBytes, lds2 = 2 * ((size_t)kMTileBytes + kMT * sizeof(float2));
+  score_rowstats_mfma_kernel<<<dim3(tiles, B * Hq), kScThreads, lds1, st>>>(
+      static_cast<const bf16_t*>(Q), static_cast<const bf16_t*>(K), Hq, Hkv, P, scale_log2, stats);
+  score_colsum_mfma_kernel<<<dim3(tiles, B * Hkv), kScThreads, lds2, st>>>(
+      static_cast<const bf16_t*>(Q), static_cast<const bf16_t*>(K), Hq, Hkv, P, scale_log2, stats, scores);
+}
+
 template <typename T, int D>
 static void launch_scores(const void* Q, const void* K, int B, int Hq, int Hkv, int P, float* scores, float2* stats,
                           hipStream_t st) {
@@ -202,7 +376,7 @@ extern "C" sqa_status sqa_prefill_scores(const void* Q, const void* K, sqa_dtype
     else launch_scores<float, 128>(Q, K, B, Hq, Hkv, P, scores_out, stats, st);
   } else {
     if (D == 64) launch_scores<bf16_t, 64>(Q, K, B, Hq, Hkv, P, scores_out, stats, st);
-    else launch_scores<bf16_t, 128>(Q, K, B, Hq, Hkv, P, scores_out, stats, st);
+    else launch_scores_mfma(Q, K, B, Hq, Hkv, P, scores_out, stats, st);
   }
   SQA_HIP_CHECK(hipGetLastError());
   return SQA_OK;

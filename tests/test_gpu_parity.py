@@ -68,7 +68,11 @@ def test_tiny_budgets_from_gpu_cosines(sqa):
 
 @pytest.mark.parametrize("dtype,B,Hq,Hkv,P,D", [("f32", 1, 2, 2, 100, 64), ("bf16", 2, 4, 2, 193, 128),
                                                  ("f32", 1, 4, 1, 64, 128), ("bf16", 1, 1, 1, 1, 64),
-                                                 ("f32", 1, 1, 1, 257, 64)])
+                                                 ("f32", 1, 1, 1, 257, 64),
+                                                 # bf16 at D = 128 runs on the matrix cores: ragged and tiny prompts
+                                                 ("bf16", 1, 1, 1, 1, 128), ("bf16", 1, 2, 2, 64, 128),
+                                                 ("bf16", 1, 4, 1, 65, 128), ("bf16", 2, 8, 2, 300, 128),
+                                                 ("bf16", 1, 1, 1, 1000, 128)])
 def test_prefill_scores(sqa, dtype, B, Hq, Hkv, P, D):
     wl = W.scaled(W.WORKLOADS["tiny"], L=1, Hq=Hq, Hkv=Hkv, D=D, B=B, P=P, dtype=dtype)
     K, _ = W.prompt_kv(wl, 0, DEV)
