@@ -333,6 +333,58 @@ def test_decode_free_running_split_units(sqa):
                 assert rel_err(got["score"][None], c["score"][None]) < 1e-5
 
 
+@pytest.mark.parametrize("policy", ["sliding", "streaming", "h2o"])
+def test_decode_from_an_empty_cache(sqa, policy):
+    """No prompt at all: the first step attends to the new token alone (out = v), then the cache
+    grows to its budget and starts evicting -- 12 steps with budget 6 against the oracle."""
+    D, b, S, Hkv, g = 64, 6, 12, 2, 2
+    r = np.random.default_rng(3)
+    caches = _mk_caches(sqa, [b], [b], 1, Hkv, D, "f32")
+    ws = sqa.decode_workspace(caches, Hkv * g, policy)
+    state = {h: O.new_cache(np.zeros((0, D)), np.zeros((0, D))) for h in range(Hkv)}
+    for t in range(S):
+        q = torch.from_numpy(r.standard_normal((1, 1, Hkv * g, D)).astype(np.float32)).to(DEV)
+        k = torch.from_numpy(r.standard_normal((1, 1, Hkv, D)).astype(np.float32)).to(DEV)
+        v = torch.from_numpy(r.standard_normal((1, 1, Hkv, D)).astype(np.float32)).to(DEV)
+        out = torch.empty_like(q)
+        sqa.decode_step(q, k, v, t, policy, 4, caches, out, ws)
+        for h in range(Hkv):
+            want, state[h] = O.decode_step(state[h], np64(q)[0, 0, h * g:(h + 1) * g], np64(k)[0, 0, h], np64(v)[0, 0, h],
+                                           t, b, policy, 4)
+            assert rel_err(np64(out)[0, 0, h * g:(h + 1) * g], want) < 1e-5, (t, h)
+            got = export_state(caches, 0, 0, h)
+            assert got["pos"].tolist() == state[h]["pos"].tolist(), (t, h)
+            if t == 0:
+                assert np.allclose(np64(out)[0, 0, h * g], np64(v)[0, 0, h], atol=1e-6)
+    assert sqa.read_device_status(ws) == 0
+
+
+def test_decode_one_very_long_unit(sqa):
+    """A single unit of 20000 tokens (H2O, bf16): split over many workgroups, logits through the
+    workspace, arg-min over 10000 heavy hitters."""
+    D, P, b = 128, 20000, 20000
+    r = np.random.default_rng(11)
+    K = torch.randn(1, 1, P, D, device=DEV).to(torch.bfloat16)
+    V = torch.randn(1, 1, P, D, device=DEV).to(torch.bfloat16)
+    sc = torch.rand(1, 1, P, device=DEV)
+    caches = _mk_caches(sqa, [b], [b], 1, 1, D, "bf16")
+    sqa.prefill_compress(K, V, sc, "h2o", 4, caches, 0)
+    ws = sqa.decode_workspace(caches, 1, "h2o")
+    c = O.new_cache(np64(K)[0, 0], np64(V)[0, 0], np64(sc)[0, 0])
+    for t in range(2):
+        q = torch.randn(1, 1, 1, D, device=DEV).to(torch.bfloat16)
+        k = torch.randn(1, 1, 1, D, device=DEV).to(torch.bfloat16)
+        v = torch.randn(1, 1, 1, D, device=DEV).to(torch.bfloat16)
+        out = torch.empty_like(q)
+        sqa.decode_step(q, k, v, P + t, "h2o", 4, caches, out, ws)
+        want, c = O.decode_step(c, np64(q)[0, 0], np64(k)[0, 0, 0], np64(v)[0, 0, 0], P + t, b, "h2o")
+        c = round_scores_f32(c)
+        got = export_state(caches, 0, 0, 0)
+        assert got["pos"].tolist() == c["pos"].tolist(), t
+        assert rel_err(np64(out)[0, 0], want) < 2e-2 and rel_err(got["score"][None], c["score"][None]) < 1e-5
+    assert sqa.read_device_status(ws) == 0
+
+
 def test_decode_is_deterministic_and_per_layer_calls_agree(sqa):
     """Same inputs twice -> identical bytes; one call over all layers == one call per layer
     (with and without the device copy of the layer table)."""
