@@ -185,7 +185,35 @@ CASES = [
 ]
 
 
-@pytest.mark.parametrize("case", CASES, ids=[c[0] for c in CASES])
+def _random_cases(n, seed=2024):
+    """Seeded random shapes: every dtype / head-dim / group size the library has a kernel for, budgets
+    below, at and above the prompt length, around multiples of the 64-row tile and of the 256-slot chunk."""
+    r = np.random.default_rng(seed)
+    out = []
+    for i in range(n):
+        dtype = ["f32", "bf16"][int(r.integers(2))]
+        D = [64, 128][int(r.integers(2))]
+        g = [1, 2, 4, 8][int(r.integers(4))]
+        Hkv = int(r.integers(1, 4))
+        B = int(r.integers(1, 3))
+        L = int(r.integers(1, 4))
+        P = int(r.choice([3, 17, 63, 64, 65, 130, 255, 256, 257, 400, 513]))
+        S = int(r.integers(2, 6))
+        policy = ["sliding", "streaming", "h2o"][int(r.integers(3))]
+        lo = {"sliding": 1, "streaming": 5, "h2o": 2}[policy]
+        budgets = []
+        for _ in range(L):
+            kind = int(r.integers(4))
+            b = [int(r.integers(lo, max(lo + 1, P))), P, P + int(r.integers(1, S + 3)), int(r.integers(lo, lo + 6))][kind]
+            budgets.append(max(lo, b))
+        out.append(("rand%02d_%s_%s_D%d_g%d" % (i, policy, dtype, D, g), dtype, L, Hkv * g, Hkv, D, B, P, S, policy, budgets))
+    return out
+
+
+RANDOM_CASES = _random_cases(28)
+
+
+@pytest.mark.parametrize("case", CASES + RANDOM_CASES, ids=[c[0] for c in CASES + RANDOM_CASES])
 def test_decode_teacher_forced(sqa, case):
     name, dtype, L, Hq, Hkv, D, B, P, S, policy, budgets = case
     wl = W.scaled(W.WORKLOADS["tiny"], L=L, Hq=Hq, Hkv=Hkv, D=D, B=B, P=P, S=S, dtype=dtype, policy=policy)
