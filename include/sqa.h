@@ -100,6 +100,20 @@ sqa_status sqa_layer_importance(const void* h_in, const void* h_out, sqa_dtype d
                                 int n_layers, int64_t n_tokens, int hidden,
                                 float* cos_out, void* workspace, size_t ws_bytes, void* stream);
 
+/* The same probe fused into the producer of the "after" tensor (Sec. 3: the
+ * hidden state after the self-attention block is the block's input plus the
+ * attention output, the residual connection):
+ *   h_out[l][j][k] = h_in[l][j][k] + attn_out[l][j][k]   (fp32 add, rounded to dt)
+ * is written and cos_out[l] is taken between h_in and the stored h_out in the
+ * same pass, so the probe adds no memory traffic to the residual add.
+ *   h_in, attn_out : DEVICE [n_layers][n_tokens][hidden], dtype dt
+ *   h_out          : DEVICE, same shape; may be the very buffer h_in or attn_out
+ *                    (in-place), otherwise must not overlap them
+ * cos_out, workspace as above (same workspace size). */
+sqa_status sqa_residual_add_importance(const void* h_in, const void* attn_out, void* h_out, sqa_dtype dt,
+                                       int n_layers, int64_t n_tokens, int hidden,
+                                       float* cos_out, void* workspace, size_t ws_bytes, void* stream);
+
 /* ---- Algorithm 1 steps 5-11; Sec. 4.2.2; Appendix A.2 ---------------------
  * Host only.  Clusters the n_layers cosines into (up to) 3 groups by the exact
  * optimum of 1-D k-means (contiguous split of the sorted values, cuts only

@@ -8,6 +8,8 @@ cpu_baseline leg of bench.py may call it.
 What each function follows:
   token_cosines / layer_importance   Sec. 3, the cosine-similarity equation;
                                      Algorithm 1 steps 1-4 (mean over prompt tokens)
+  residual_hidden                    Sec. 3: the hidden state "after" the block is
+                                     the block's input plus the attention output
   cluster_layers / allocate_budgets  Algorithm 1 steps 5-11; Sec. 4.2.2 (three
                                      groups, only G3 loses budget); Appendix A.2
                                      worked example (300 / 1544)
@@ -17,7 +19,7 @@ What each function follows:
                                      (n sink tokens + recent), H2O (accumulated score)
   prefill_compress / decode_step     Algorithm 1 steps 12-21 with Eq. 2-3 (append)
 
-Readings taken where the paper is silent (all are also listed in the design doc):
+Readings taken where the paper is silent:
   * one cosine per layer = mean over ALL tokens of the batch (b x p rows);
   * a zero-norm row contributes cosine 0 (each norm is clamped at 1e-8);
   * KMeans = the global optimum of 1-D 3-means on the sorted values (a
@@ -69,6 +71,28 @@ def layer_importance(h_in, h_out) -> np.ndarray:
         c = token_cosines(h_in[i], h_out[i])
         out[i] = math.fsum(c.tolist()) / len(c)
     return out
+
+
+def round_bf16(x32: np.ndarray) -> np.ndarray:
+    """float32 array -> the nearest bfloat16 values (ties to even), returned as
+    float32.  bfloat16 = the top 16 bits of the float32 pattern."""
+    u = np.ascontiguousarray(x32, dtype=np.float32).view(np.uint32).astype(np.uint64)
+    keep_odd = (u >> np.uint64(16)) & np.uint64(1)
+    u = (u + np.uint64(0x7FFF) + keep_odd) & np.uint64(0xFFFF0000)
+    return u.astype(np.uint32).view(np.float32).reshape(np.shape(x32))
+
+
+def residual_hidden(h_in, attn_out, dtype: str) -> np.ndarray:
+    """The hidden state after the self-attention block as the model stores it:
+    h_in + attn_out (the residual connection), added in float32 and rounded to
+    the storage type ("f32" or "bf16").  Sec. 3 takes the cosine between h_in
+    and this tensor, so the stored (rounded) values are what the probe sees."""
+    s = np.asarray(h_in, dtype=np.float32) + np.asarray(attn_out, dtype=np.float32)
+    if dtype == "bf16":
+        return round_bf16(s)
+    if dtype == "f32":
+        return s
+    raise ValueError(dtype)
 
 
 # --------------------------------------------------------------------------

@@ -50,6 +50,8 @@ _lib.sqa_layer_importance_workspace_bytes.restype = _sz
 _lib.sqa_layer_importance_workspace_bytes.argtypes = [_i, _i64, _i]
 _lib.sqa_layer_importance.restype = _i
 _lib.sqa_layer_importance.argtypes = [_vp, _vp, _i, _i, _i64, _i, _vp, _vp, _sz, _vp]
+_lib.sqa_residual_add_importance.restype = _i
+_lib.sqa_residual_add_importance.argtypes = [_vp, _vp, _vp, _i, _i, _i64, _i, _vp, _vp, _sz, _vp]
 _lib.sqa_allocate_budgets.restype = _i
 _lib.sqa_allocate_budgets.argtypes = [C.POINTER(C.c_float), _i, _i64, _f64, C.POINTER(C.c_int32), C.POINTER(C.c_int8)]
 _lib.sqa_prefill_scores_workspace_bytes.restype = _sz
@@ -110,6 +112,23 @@ def layer_importance(h_in: torch.Tensor, h_out: torch.Tensor, cos_out: Optional[
         workspace = torch.empty(max(need, 8), dtype=torch.uint8, device=h_in.device)
     _check(_lib.sqa_layer_importance(_ptr(h_in), _ptr(h_out), _dt(h_in), L, T, d, _ptr(cos_out),
                                      _ptr(workspace), workspace.numel(), _stream()), "sqa_layer_importance")
+    return cos_out
+
+
+def residual_add_importance(h_in: torch.Tensor, attn_out: torch.Tensor, h_out: torch.Tensor,
+                            cos_out: Optional[torch.Tensor] = None,
+                            workspace: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """h_out = h_in + attn_out written (h_out may be h_in or attn_out itself) and cos [L] of
+    (h_in, h_out) returned, one pass.  All [L, T, hidden], contiguous, device."""
+    L, T, d = h_in.shape
+    if cos_out is None:
+        cos_out = torch.empty(L, dtype=torch.float32, device=h_in.device)
+    need = _lib.sqa_layer_importance_workspace_bytes(L, T, d)
+    if workspace is None:
+        workspace = torch.empty(max(need, 8), dtype=torch.uint8, device=h_in.device)
+    _check(_lib.sqa_residual_add_importance(_ptr(h_in), _ptr(attn_out), _ptr(h_out), _dt(h_in), L, T, d,
+                                            _ptr(cos_out), _ptr(workspace), workspace.numel(), _stream()),
+           "sqa_residual_add_importance")
     return cos_out
 
 

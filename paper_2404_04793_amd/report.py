@@ -4,7 +4,11 @@ against batch size for the layer-wise budgets, the sequence-only baseline and
 the full cache), on synthetic inputs of the paper's shapes.
 
     python -m paper_2404_04793_amd.report [--workload stress_7b] [--batches 1,32,64,128,224]
-                                          [--decode-steps 64]
+                                          [--decode-steps 64] [--equal-memory]
+
+--equal-memory adds, per batch, the full-cache run at the largest batch whose
+KV state fits in the bytes the layer-wise run holds resident at that batch
+(the "same memory, larger batch" reading of Table 3).
 
 Prints a markdown table.  Only the decode steps are timed (HIP events); every
 number comes from the HIP library through the binding.
@@ -50,6 +54,7 @@ def main(argv=None):
     ap.add_argument("--batches", default="1,32,64,128,224")
     ap.add_argument("--decode-steps", type=int, default=64)
     ap.add_argument("--budget-pct", type=int, default=None)
+    ap.add_argument("--equal-memory", action="store_true")
     args = ap.parse_args(argv)
     base = W.WORKLOADS[args.workload]
     if args.budget_pct:
@@ -59,12 +64,23 @@ def main(argv=None):
     print("|---|---|---|---|---|---|")
     for bs in [int(x) for x in args.batches.split(",")]:
         wl = W.scaled(base, B=bs)
+        held = {}
         for mode in ("squeeze", "uniform", "full"):
             try:
                 tok_s, gbs, kv_gb, per_seq = run_mode(wl, mode)
+                held[mode] = (kv_gb, per_seq)
                 print("| %d | %s | %.0f | %.0f | %.2f | %.1f |" % (bs, mode, tok_s, gbs, kv_gb, per_seq))
             except torch.cuda.OutOfMemoryError:
                 print("| %d | %s | OOM | | | |" % (bs, mode))
+            sys.stdout.flush()
+        if args.equal_memory and "squeeze" in held and "full" in held:
+            fit = int(held["squeeze"][0] * 1e3 // held["full"][1])        # GB -> MB, per-sequence MB of the full cache
+            if fit >= 1:
+                tok_s, gbs, kv_gb, per_seq = run_mode(W.scaled(base, B=fit), "full")
+                print("| %d | full, batch that fits in the squeezed run's %.2f GB | %.0f | %.0f | %.2f | %.1f |"
+                      % (fit, held["squeeze"][0], tok_s, gbs, kv_gb, per_seq))
+            else:
+                print("| 0 | full: not even one sequence fits in %.2f GB | | | | |" % held["squeeze"][0])
             sys.stdout.flush()
 
 

@@ -14,10 +14,12 @@ from . import workloads as W
 
 class Session:
     def __init__(self, wl: W.Workload, device="cuda:0", keep_prompt_q: bool = False, uniform_budget: bool = False,
-                 full_cache: bool = False, probe_tokens: Optional[int] = None):
+                 full_cache: bool = False, probe_tokens: Optional[int] = None, fused_probe: bool = False):
         """probe_tokens: hidden-state rows per layer given to the probe (default: all B*P prompt tokens;
-        a smaller number keeps the hidden states of the largest workloads within HBM)."""
+        a smaller number keeps the hidden states of the largest workloads within HBM).
+        fused_probe: the probe runs inside the residual add that writes h_out (Sec. 3)."""
         self.wl, self.dev = wl, device
+        self.fused_probe = fused_probe
         self.uniform_budget, self.full_cache = uniform_budget, full_cache
         self.u, self.mask = W.unit_dirs(wl), W.hh_mask(wl, device)
         L = wl.L
@@ -29,6 +31,8 @@ class Session:
         for l in range(L):
             a, b = W.hidden_states(wl, l, device, n_tokens=T)
             self.h_in[l], self.h_out[l] = a, b
+        # the attention block's output, so that h_in + attn_out reproduces the generated h_out (up to rounding)
+        self.attn_out = (self.h_out.float() - self.h_in.float()).to(wl.torch_dtype) if fused_probe else None
         # prompt K, V (kept resident: every pass compresses them again) and H2O prompt scores
         self.Kp, self.Vp, self.scores, self.Qp = [], [], [], []
         for l in range(L):
@@ -64,7 +68,10 @@ class Session:
     # -- Algorithm 1 steps 1-11 ------------------------------------------------
     def probe_and_allocate(self):
         wl = self.wl
-        sqa.layer_importance(self.h_in, self.h_out, self.cos_dev, self.imp_ws)
+        if self.fused_probe:
+            sqa.residual_add_importance(self.h_in, self.attn_out, self.h_out, self.cos_dev, self.imp_ws)
+        else:
+            sqa.layer_importance(self.h_in, self.h_out, self.cos_dev, self.imp_ws)
         self.cos_host.copy_(self.cos_dev, non_blocking=False)
         cos = self.cos_host.tolist()
         if self.full_cache:
@@ -125,7 +132,7 @@ class Session:
 
     def probe_bytes(self) -> int:
         wl = self.wl
-        return 2 * wl.L * self.probe_tokens * wl.hidden * wl.elem_bytes
+        return (3 if self.fused_probe else 2) * wl.L * self.probe_tokens * wl.hidden * wl.elem_bytes
 
     def compress_bytes(self) -> int:
         wl = self.wl

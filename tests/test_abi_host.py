@@ -89,6 +89,11 @@ def test_device_entry_points_validate_before_any_gpu_call():
     assert lib.sqa_layer_importance(p, p, 7, 1, 4, 64, p, p, 1 << 20, None) == 3
     assert lib.sqa_layer_importance(p, p, 0, 1, 4, 60, p, p, 1 << 20, None) == 2
     assert lib.sqa_layer_importance(p, p, 0, 1, 4, 64, p, p, 0, None) == 6
+    assert lib.sqa_residual_add_importance(p, p, None, 0, 1, 4, 64, p, p, 1 << 20, None) == 1
+    assert lib.sqa_residual_add_importance(p, None, p, 0, 1, 4, 64, p, p, 1 << 20, None) == 1
+    assert lib.sqa_residual_add_importance(p, p, C.c_void_p(0x1008), 0, 1, 4, 64, p, p, 1 << 20, None) == 2
+    assert lib.sqa_residual_add_importance(p, p, p, 2, 1, 4, 64, p, p, 1 << 20, None) == 3
+    assert lib.sqa_residual_add_importance(p, p, p, 1, 1, 4, 64, p, p, 0, None) == 6
     lc = sqa.LayerCacheStruct(0x1000, 0x2000, 0x3000, 0x4000, 0x5000, 0x6000, 0x7000, 8, 4)
     args = lambda **kw: [kw.get("K", p), p, kw.get("dt", 1), kw.get("sc", p), 1, 1, kw.get("P", 16), kw.get("D", 128),
                          kw.get("pol", 2), kw.get("ns", 4), C.byref(kw.get("lc", lc)), None]

@@ -53,6 +53,27 @@ def test_layer_importance_closed_forms(sqa):
     assert abs(c[0] - 63 / 64) < 1e-6 and abs(c[1] - 1) < 1e-6          # zero row contributes 0
 
 
+@pytest.mark.parametrize("dtype,L,T,d,inplace", [("f32", 2, 131, 256, None), ("bf16", 3, 1037, 4096, None),
+                                                  ("bf16", 2, 37, 328, "h_in"), ("f32", 1, 67, 520, "attn_out")])
+def test_residual_add_importance(sqa, dtype, L, T, d, inplace):
+    """The probe fused into the residual add: stored h_out bit for bit, cosine as the stand-alone probe."""
+    wl = W.scaled(W.WORKLOADS["tiny"], L=L, hidden=d, dtype=dtype, B=1, P=T)
+    hs = [W.hidden_states(wl, l, DEV) for l in range(L)]
+    h_in = torch.stack([x[0] for x in hs]).contiguous()
+    attn = (torch.stack([x[1] for x in hs]).float() * 0.37).to(h_in.dtype).contiguous()   # any second tensor
+    a_host, r_host = h_in.float().cpu().numpy(), attn.float().cpu().numpy()
+    want = O.residual_hidden(a_host, r_host, dtype)
+    ref = O.layer_importance(a_host.astype(np.float64), want.astype(np.float64))
+    h_out = {None: torch.empty_like(h_in), "h_in": h_in, "attn_out": attn}[inplace]
+    cos = sqa.residual_add_importance(h_in, attn, h_out).cpu().numpy().astype(np.float64)
+    got = h_out.float().cpu().numpy()
+    assert np.array_equal(got.view(np.uint32), want.view(np.uint32))
+    assert _cos_rel(cos, ref) < 1e-5
+    if inplace is None:                      # same stored tensor through the stand-alone probe: same bytes out
+        alone = sqa.layer_importance(h_in, h_out).cpu().numpy()
+        assert np.array_equal(alone.view(np.uint32), cos.astype(np.float32).view(np.uint32))
+
+
 def test_tiny_budgets_from_gpu_cosines(sqa):
     wl = W.WORKLOADS["tiny"]
     hs = [W.hidden_states(wl, l, DEV) for l in range(wl.L)]

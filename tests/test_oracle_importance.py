@@ -85,3 +85,52 @@ def test_tiny_workload_pattern():
     cos = O.layer_importance([x[0].double().numpy() for x in h], [x[1].double().numpy() for x in h])
     want = [0.4472, 0.9578, 0.9578, 0.5547]
     assert np.allclose(cos, want, atol=5e-3)
+
+
+# -- residual_hidden: the tensor the probe compares with the block's input ------
+
+def test_round_bf16_hand_values():
+    """bfloat16 keeps 8 significant bits: 1 + 2^-8 lies half way between 1 and
+    1 + 2^-7 and goes to the even one (1); 1 + 3*2^-8 is half way between
+    1 + 2^-7 and 1 + 2^-6 and goes to 1 + 2^-6 (even); anything past the half
+    way point goes up."""
+    x = np.array([1.0, 1.0 + 2.0 ** -8, 1.0 + 2.0 ** -8 + 2.0 ** -20, 1.0 + 3 * 2.0 ** -8, -(1.0 + 2.0 ** -8),
+                  1.0 + 2.0 ** -7, 0.0, 3.0e38], dtype=np.float32)
+    want = np.array([1.0, 1.0, 1.0 + 2.0 ** -7, 1.0 + 2.0 ** -6, -1.0, 1.0 + 2.0 ** -7, 0.0, 3.0e38], dtype=np.float32)
+    got = O.round_bf16(x)
+    assert got.dtype == np.float32
+    assert np.array_equal(got[:7], want[:7])
+    assert abs(float(got[7]) - 3.0e38) <= 3.0e38 * 2.0 ** -8
+
+
+def test_round_bf16_matches_an_independent_converter():
+    torch = pytest.importorskip("torch")
+    x = (_rng(11).standard_normal(20000) * np.exp(_rng(12).uniform(-20, 20, 20000))).astype(np.float32)
+    ref = torch.from_numpy(x).to(torch.bfloat16).to(torch.float32).numpy()
+    assert np.array_equal(O.round_bf16(x), ref)
+
+
+def test_round_bf16_is_idempotent_and_nearest():
+    x = _rng(13).standard_normal(5000).astype(np.float32)
+    r = O.round_bf16(x)
+    assert np.array_equal(O.round_bf16(r), r)
+    assert np.all((r.view(np.uint32) & 0xFFFF) == 0)
+    assert np.all(np.abs(r.astype(np.float64) - x) <= np.abs(x.astype(np.float64)) * 2.0 ** -8)
+
+
+def test_residual_hidden_is_the_sum():
+    A = np.array([[1.0, 2.0, -3.0]], dtype=np.float32); R = np.array([[0.5, -2.0, 1.0]], dtype=np.float32)
+    assert np.array_equal(O.residual_hidden(A, R, "f32"), np.array([[1.5, 0.0, -2.0]], dtype=np.float32))
+    assert np.array_equal(O.residual_hidden(A, R, "bf16"), np.array([[1.5, 0.0, -2.0]], dtype=np.float32))
+    # 256 + 1 = 257 needs 9 significant bits: bfloat16 stores 256 (tie to even)
+    assert O.residual_hidden(np.float32([256.0]), np.float32([1.0]), "bf16")[0] == 256.0
+    assert O.residual_hidden(np.float32([256.0]), np.float32([1.0]), "f32")[0] == 257.0
+    with pytest.raises(ValueError):
+        O.residual_hidden(A, R, "f16")
+
+
+def test_zero_attention_output_gives_importance_one():
+    """A block that adds nothing leaves the hidden state unchanged: cosine 1."""
+    A = _rng(14).standard_normal((1, 9, 32)).astype(np.float32)
+    B = O.residual_hidden(A, np.zeros_like(A), "f32")
+    assert abs(O.layer_importance(A, B)[0] - 1.0) < 1e-12
