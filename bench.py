@@ -91,6 +91,8 @@ def main():
                     help="hidden-state rows per layer given to the probe (default: all B*P)")
     ap.add_argument("--fused-probe", action="store_true",
                     help="run the probe inside the residual add that writes h_out (reads 2, writes 1 tensor)")
+    ap.add_argument("--order", default="evict_then_attend", choices=["evict_then_attend", "attend_then_evict"],
+                    help="where the policy runs inside a decode step (default: Algorithm 1 as printed)")
     ap.add_argument("--decode-steps", type=int, default=None, help="decode steps per pass (default: the workload's)")
     ap.add_argument("--batch", type=int, default=None, help="override the workload's batch")
     ap.add_argument("--budget-pct", type=int, default=None, help="override b_init as a percentage of the prompt")
@@ -119,7 +121,7 @@ def main():
         wl = W.scaled(wl, budget_pct=args.budget_pct)
     torch.cuda.set_device(0)
     sess = Session(wl, "cuda:0", uniform_budget=args.uniform, full_cache=args.full_cache,
-                   probe_tokens=args.probe_tokens, fused_probe=args.fused_probe)
+                   probe_tokens=args.probe_tokens, fused_probe=args.fused_probe, order=args.order)
 
     def one_pass(ev=None):
         if ev:
@@ -196,7 +198,7 @@ def main():
                    "budget_pct": wl.budget_pct, "p": wl.p,
                    "mode": mode, "launch": launch,
                    "phases": "decode_only" if args.decode_only else "whole_pass",
-                   "probe_tokens": sess.probe_tokens, "fused_probe": args.fused_probe},
+                   "probe_tokens": sess.probe_tokens, "fused_probe": args.fused_probe, "order": args.order},
         "roofline": {"bound": "hbm", "kernel": "decode_unit_kernel", "achieved": achieved, "peak": HBM_PEAK_GBS,
                      "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
                      "traffic": MEASURED_TRAFFIC_BYTES.get((wl.name, mode, wl.policy, launch)),

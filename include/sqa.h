@@ -46,11 +46,17 @@ typedef enum {
   SQA_ERR_BUDGET = 5,    /* p outside (0,1], total < n_layers, budget too small      */
   SQA_ERR_CAPACITY = 6,  /* cache capacity / workspace / on-chip memory too small    */
   SQA_ERR_HIP = 7,       /* the HIP runtime reported an error                        */
-  SQA_ERR_STATE = 8      /* device-side: a cache was longer than its budget on entry */
+  SQA_ERR_STATE = 8      /* device-side: a cache was longer than its budget on entry
+                            (device-side checks also report SQA_ERR_CAPACITY: no free
+                            slot, and SQA_ERR_BUDGET: a per-sequence budget out of range) */
 } sqa_status;
 
 typedef enum { SQA_F32 = 0, SQA_BF16 = 1 } sqa_dtype;
 typedef enum { SQA_SLIDING = 0, SQA_STREAMING = 1, SQA_H2O = 2 } sqa_policy;
+/* Where the policy runs inside a decode step.  Algorithm 1 as printed compresses
+ * before the step's attention (steps 16-17, then 19); Sec. 2.2 describes policies
+ * that judge tokens by the attention they just received, i.e. after it. */
+typedef enum { SQA_EVICT_THEN_ATTEND = 0, SQA_ATTEND_THEN_EVICT = 1 } sqa_order;
 
 enum { SQA_MAX_LAYERS = 128 };
 
@@ -85,6 +91,28 @@ typedef struct sqa_layer_cache {
   int32_t budget;      /* b^(i): most tokens this layer keeps                      */
 } sqa_layer_cache;
 
+/*
+ * Per-sequence variation inside one batch, for the *_ex calls.  The paper states
+ * Algorithm 1 for a batch with one prompt length p and one budget list (Sec. 2.1
+ * notation, Algorithm 1 "Require"); these fields cover batches whose sequences
+ * differ in prompt length, position and -- when each sequence is probed and
+ * budgeted on its own -- in budgets.  Every pointer is optional (NULL = the uniform value of the
+ * plain call) and DEVICE memory, read when the kernels run.
+ */
+typedef struct sqa_batch_opts {
+  const int32_t* prompt_len;   /* [B] tokens of sequence b's prompt, 0..P; its rows beyond that are padding
+                                  (sqa_prefill_scores_ex, sqa_prefill_compress_layers_ex)               */
+  const int32_t* budget_seq;   /* [n_layers][B] budget of layer l for sequence b; each must lie between the
+                                  policy's minimum and layers[l].budget, which stays the layer's maximum and
+                                  sizes capacity and scratch (compress, decode)                          */
+  const int32_t* new_pos_seq;  /* [B] position of sequence b's new token; < 0 = the sequence takes no part in
+                                  this step: its caches and out rows are left untouched (decode)          */
+  int32_t* status;             /* one int32 that compress sets to SQA_ERR_SHAPE / SQA_ERR_BUDGET when a
+                                  prompt_len / budget_seq entry is out of range (that unit is left empty);
+                                  decode reports through its workspace status word instead               */
+  int32_t order;               /* sqa_order (decode)                                                    */
+} sqa_batch_opts;
+
 const char* sqa_status_str(sqa_status s);
 
 /* ---- Algorithm 1 steps 1-4; Sec. 3 cosine-similarity equation -------------
@@ -99,6 +127,19 @@ size_t sqa_layer_importance_workspace_bytes(int n_layers, int64_t n_tokens, int 
 sqa_status sqa_layer_importance(const void* h_in, const void* h_out, sqa_dtype dt,
                                 int n_layers, int64_t n_tokens, int hidden,
                                 float* cos_out, void* workspace, size_t ws_bytes, void* stream);
+
+/* Per-sequence cosines (Sec. 3 equation with the token mean taken over one
+ * sequence's prompt instead of the whole batch), for per-sequence budgets: the token
+ * rows of the n_seq sequences lie one after another, sequence s owning rows
+ * seq_start[s] .. seq_start[s+1]-1 of every layer.
+ *   seq_start : DEVICE int32 [n_seq+1], ascending, seq_start[0] >= 0,
+ *               seq_start[n_seq] <= n_tokens; an empty sequence gets cosine 0
+ *   cos_out   : DEVICE float [n_layers][n_seq]
+ *   workspace : DEVICE, >= n_seq * sqa_layer_importance_workspace_bytes(n_layers, n_tokens, hidden) */
+sqa_status sqa_layer_importance_seq(const void* h_in, const void* h_out, sqa_dtype dt,
+                                    int n_layers, int64_t n_tokens, int hidden,
+                                    const int32_t* seq_start, int n_seq,
+                                    float* cos_out, void* workspace, size_t ws_bytes, void* stream);
 
 /* The same probe fused into the producer of the "after" tensor (Sec. 3: the
  * hidden state after the self-attention block is the block's input plus the
@@ -140,6 +181,12 @@ size_t sqa_prefill_scores_workspace_bytes(int B, int Hq, int Hkv, int P, int D);
 sqa_status sqa_prefill_scores(const void* Q, const void* K, sqa_dtype dt,
                               int B, int Hq, int Hkv, int P, int D,
                               float* scores_out, void* workspace, size_t ws_bytes, void* stream);
+/* With opts->prompt_len: only queries i < prompt_len[b] are counted; scores of
+ * positions >= prompt_len[b] come out 0.  opts may be NULL. */
+sqa_status sqa_prefill_scores_ex(const void* Q, const void* K, sqa_dtype dt,
+                                 int B, int Hq, int Hkv, int P, int D,
+                                 float* scores_out, void* workspace, size_t ws_bytes, void* stream,
+                                 const sqa_batch_opts* opts);
 
 /* ---- Algorithm 1 steps 12 + 16-17: compress the prompt's KV to the budget --
  * Per unit keeps min(P, layer->budget) tokens chosen by the policy
@@ -168,6 +215,12 @@ sqa_status sqa_prefill_compress_layers(const void* const* K, const void* const* 
                                        const float* const* attn_scores, int B, int Hkv, int P, int D,
                                        sqa_policy policy, int n_sink, const sqa_layer_cache* layers, int n_layers,
                                        void* stream);
+/* With opts->prompt_len / opts->budget_seq: unit (b, h) of layer l compresses
+ * the first prompt_len[b] tokens to budget_seq[l][b].  opts may be NULL. */
+sqa_status sqa_prefill_compress_layers_ex(const void* const* K, const void* const* V, sqa_dtype kv_dt,
+                                          const float* const* attn_scores, int B, int Hkv, int P, int D,
+                                          sqa_policy policy, int n_sink, const sqa_layer_cache* layers, int n_layers,
+                                          void* stream, const sqa_batch_opts* opts);
 
 /* ---- Algorithm 1 steps 14-21 with Eq. 2-3: one decode step ----------------
  * For each of n_layers layers and each unit, in this order:
@@ -208,6 +261,18 @@ sqa_status sqa_decode_step(const void* q, const void* k_new, const void* v_new, 
                            sqa_policy policy, int n_sink,
                            const sqa_layer_cache* layers, const sqa_layer_cache* layers_dev, int n_layers,
                            void* out, void* workspace, size_t ws_bytes, void* stream);
+
+/* The same step with per-sequence positions and budgets and the choice of order
+ * (opts may be NULL = sqa_decode_step).  Under SQA_ATTEND_THEN_EVICT steps 2-4
+ * above run as 3, 4, 2: the unit attends all len+1 tokens, accumulates, and only
+ * then evicts (H2O: by the scores just updated); evict_hint is not used and is
+ * left at -2.  With new_pos_seq the scalar new_pos is ignored. */
+sqa_status sqa_decode_step_ex(const void* q, const void* k_new, const void* v_new, sqa_dtype dt,
+                              int B, int Hq, int Hkv, int D, int32_t new_pos,
+                              sqa_policy policy, int n_sink,
+                              const sqa_layer_cache* layers, const sqa_layer_cache* layers_dev, int n_layers,
+                              void* out, void* workspace, size_t ws_bytes, void* stream,
+                              const sqa_batch_opts* opts);
 
 /* Zeroes the status word (enqueued on stream). */
 sqa_status sqa_clear_device_status(void* workspace, void* stream);

@@ -8,7 +8,8 @@ import numpy as np
 from . import sqa_oracle as O
 
 
-def run_unit(Kp, Vp, score0, q_steps, k_steps, v_steps, b, policy, n_sink=4, keep_states=False):
+def run_unit(Kp, Vp, score0, q_steps, k_steps, v_steps, b, policy, n_sink=4, keep_states=False,
+             order="evict_then_attend"):
     """Kp, Vp [P, D]; score0 [P] or None; q_steps [S, g, D]; k_steps, v_steps
     [S, D].  Compress the prompt to budget b, then S decode steps.
     Returns (outs [S, g, D], final cache, list of per-step caches or None)."""
@@ -19,7 +20,7 @@ def run_unit(Kp, Vp, score0, q_steps, k_steps, v_steps, b, policy, n_sink=4, kee
     outs = np.empty(q_steps.shape, dtype=np.float64)
     states = [] if keep_states else None
     for t in range(S):
-        outs[t], c = O.decode_step(c, q_steps[t], k_steps[t], v_steps[t], P + t, b, policy, n_sink)
+        outs[t], c = O.decode_step(c, q_steps[t], k_steps[t], v_steps[t], P + t, b, policy, n_sink, order)
         if keep_states:
             states.append(c)
     return outs, c, states, first

@@ -29,7 +29,9 @@ Readings taken where the paper is silent:
     an independent implementation of the same rule reproduces them bit for bit;
   * b_low = floor(total * p / L) (double), the rest is split evenly over the
     other layers, remainder +1 to the lowest layer indices: sum is exact;
-  * decode order per layer: append -> evict if over budget -> attend -> accumulate;
+  * decode order per layer: append -> evict if over budget -> attend -> accumulate
+    (Algorithm 1 as printed); the other order, attend -> accumulate -> evict, is
+    available as a variant;
   * H2O: per (layer, sequence, KV head); hh = floor(b/2) best by (score desc,
     position asc) among the non-recent tokens + the b-hh most recent; with
     grouped queries the probabilities of the g query heads are summed;
@@ -272,20 +274,32 @@ def attend(q, K, V) -> Tuple[np.ndarray, np.ndarray]:
     return prob @ V, prob
 
 
-def decode_step(c, q, k_new, v_new, new_pos: int, b: int, policy: str, n_sink: int = 4):
-    """One decode step of one (layer, sequence, KV head):
-    append (Eq. 2-3) -> compress if longer than b (Alg. 1 steps 16-17) ->
-    attention of the g query heads (step 19) -> H2O accumulation.
+ORDERS = ("evict_then_attend", "attend_then_evict")
+
+
+def decode_step(c, q, k_new, v_new, new_pos: int, b: int, policy: str, n_sink: int = 4,
+                order: str = "evict_then_attend"):
+    """One decode step of one (layer, sequence, KV head).
+    order "evict_then_attend" (Algorithm 1 as printed): append (Eq. 2-3) ->
+    compress if longer than b (steps 16-17) -> attention of the g query heads
+    (step 19) -> H2O accumulation.
+    order "attend_then_evict" (the other reading of Sec. 2.2, where the policy
+    runs after the step's attention has been observed): append -> attention over
+    all b+1 tokens -> H2O accumulation -> compress if longer than b.
     Returns (out [g, D], cache)."""
+    if order not in ORDERS:
+        raise ValueError(order)
     c = {
         "K": np.vstack([c["K"], np.asarray(k_new, dtype=np.float64)[None]]),
         "V": np.vstack([c["V"], np.asarray(v_new, dtype=np.float64)[None]]),
         "pos": np.append(c["pos"], np.int64(new_pos)),
         "score": np.append(c["score"], 0.0),
     }
-    if len(c["pos"]) > b:
+    if order == "evict_then_attend" and len(c["pos"]) > b:
         c = _take(c, select_keep(c["pos"], c["score"], b, policy, n_sink))
     out, prob = attend(q, c["K"], c["V"])
     if policy == "h2o":
         c["score"] = c["score"] + prob.sum(axis=0)
+    if order == "attend_then_evict" and len(c["pos"]) > b:
+        c = _take(c, select_keep(c["pos"], c["score"], b, policy, n_sink))
     return out, c

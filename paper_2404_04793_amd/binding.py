@@ -43,8 +43,17 @@ class LayerCacheStruct(C.Structure):
                 ("capacity", C.c_int32), ("budget", C.c_int32)]
 
 
+class BatchOptsStruct(C.Structure):
+    """Mirror of sqa_batch_opts."""
+    _fields_ = [("prompt_len", C.c_void_p), ("budget_seq", C.c_void_p), ("new_pos_seq", C.c_void_p),
+                ("status", C.c_void_p), ("order", C.c_int32)]
+
+
+ORDER = {"evict_then_attend": 0, "attend_then_evict": 1}
+
 _vp, _i, _i64, _sz, _f64 = C.c_void_p, C.c_int, C.c_int64, C.c_size_t, C.c_double
 _LCp = C.POINTER(LayerCacheStruct)
+_BOp = C.POINTER(BatchOptsStruct)
 
 _lib.sqa_layer_importance_workspace_bytes.restype = _sz
 _lib.sqa_layer_importance_workspace_bytes.argtypes = [_i, _i64, _i]
@@ -52,17 +61,24 @@ _lib.sqa_layer_importance.restype = _i
 _lib.sqa_layer_importance.argtypes = [_vp, _vp, _i, _i, _i64, _i, _vp, _vp, _sz, _vp]
 _lib.sqa_residual_add_importance.restype = _i
 _lib.sqa_residual_add_importance.argtypes = [_vp, _vp, _vp, _i, _i, _i64, _i, _vp, _vp, _sz, _vp]
+_lib.sqa_layer_importance_seq.restype = _i
+_lib.sqa_layer_importance_seq.argtypes = [_vp, _vp, _i, _i, _i64, _i, _vp, _i, _vp, _vp, _sz, _vp]
 _lib.sqa_allocate_budgets.restype = _i
 _lib.sqa_allocate_budgets.argtypes = [C.POINTER(C.c_float), _i, _i64, _f64, C.POINTER(C.c_int32), C.POINTER(C.c_int8)]
 _lib.sqa_prefill_scores_workspace_bytes.restype = _sz
 _lib.sqa_prefill_scores_workspace_bytes.argtypes = [_i, _i, _i, _i, _i]
 _lib.sqa_prefill_scores.restype = _i
 _lib.sqa_prefill_scores.argtypes = [_vp, _vp, _i, _i, _i, _i, _i, _i, _vp, _vp, _sz, _vp]
+_lib.sqa_prefill_scores_ex.restype = _i
+_lib.sqa_prefill_scores_ex.argtypes = [_vp, _vp, _i, _i, _i, _i, _i, _i, _vp, _vp, _sz, _vp, _BOp]
 _lib.sqa_prefill_compress.restype = _i
 _lib.sqa_prefill_compress.argtypes = [_vp, _vp, _i, _vp, _i, _i, _i, _i, _i, _i, _LCp, _vp]
 _lib.sqa_prefill_compress_layers.restype = _i
 _lib.sqa_prefill_compress_layers.argtypes = [C.POINTER(_vp), C.POINTER(_vp), _i, C.POINTER(_vp), _i, _i, _i, _i, _i, _i,
                                              _LCp, _i, _vp]
+_lib.sqa_prefill_compress_layers_ex.restype = _i
+_lib.sqa_prefill_compress_layers_ex.argtypes = [C.POINTER(_vp), C.POINTER(_vp), _i, C.POINTER(_vp), _i, _i, _i, _i, _i,
+                                                _i, _LCp, _i, _vp, _BOp]
 _lib.sqa_decode_workspace_bytes.restype = _sz
 _lib.sqa_decode_workspace_bytes.argtypes = [_LCp, _i, _i, _i, _i, _i, _i]
 _lib.sqa_decode_workspace_init.restype = _i
@@ -70,6 +86,9 @@ _lib.sqa_decode_workspace_init.argtypes = [_vp, _sz, _vp]
 _lib.sqa_decode_step.restype = _i
 _lib.sqa_decode_step.argtypes = [_vp, _vp, _vp, _i, _i, _i, _i, _i, C.c_int32, _i, _i, _LCp, _vp, _i,
                                  _vp, _vp, _sz, _vp]
+_lib.sqa_decode_step_ex.restype = _i
+_lib.sqa_decode_step_ex.argtypes = [_vp, _vp, _vp, _i, _i, _i, _i, _i, C.c_int32, _i, _i, _LCp, _vp, _i,
+                                    _vp, _vp, _sz, _vp, _BOp]
 _lib.sqa_clear_device_status.restype = _i
 _lib.sqa_clear_device_status.argtypes = [_vp, _vp]
 _lib.sqa_read_device_status.restype = _i
@@ -92,6 +111,20 @@ def _ptr(t: Optional[torch.Tensor]):
 
 def _stream():
     return torch.cuda.current_stream().cuda_stream
+
+
+def batch_opts(prompt_len: Optional[torch.Tensor] = None, budget_seq: Optional[torch.Tensor] = None,
+               new_pos_seq: Optional[torch.Tensor] = None, status: Optional[torch.Tensor] = None,
+               order: str = "evict_then_attend") -> BatchOptsStruct:
+    """sqa_batch_opts from int32 device tensors (the caller keeps them alive until the work has run)."""
+    for t in (prompt_len, budget_seq, new_pos_seq, status):
+        if t is not None and (t.dtype != torch.int32 or not t.is_contiguous()):
+            raise TypeError("per-sequence arrays are contiguous int32 tensors")
+    return BatchOptsStruct(_ptr(prompt_len), _ptr(budget_seq), _ptr(new_pos_seq), _ptr(status), ORDER[order])
+
+
+def _opts(o: Optional[BatchOptsStruct]):
+    return None if o is None else C.byref(o)
 
 
 def _check(code: int, where: str):
@@ -132,6 +165,19 @@ def residual_add_importance(h_in: torch.Tensor, attn_out: torch.Tensor, h_out: t
     return cos_out
 
 
+def layer_importance_seq(h_in: torch.Tensor, h_out: torch.Tensor, seq_start: torch.Tensor) -> torch.Tensor:
+    """h_in, h_out [L, T, hidden]; seq_start int32 [n_seq + 1] (device) -> cos [L, n_seq] fp32."""
+    L, T, d = h_in.shape
+    n_seq = seq_start.numel() - 1
+    cos_out = torch.empty(L, n_seq, dtype=torch.float32, device=h_in.device)
+    need = n_seq * _lib.sqa_layer_importance_workspace_bytes(L, T, d)
+    workspace = torch.empty(max(need, 8), dtype=torch.uint8, device=h_in.device)
+    _check(_lib.sqa_layer_importance_seq(_ptr(h_in), _ptr(h_out), _dt(h_in), L, T, d, _ptr(seq_start), n_seq,
+                                         _ptr(cos_out), _ptr(workspace), workspace.numel(), _stream()),
+           "sqa_layer_importance_seq")
+    return cos_out
+
+
 def allocate_budgets(cos: Sequence[float], total_budget: int, p: float) -> Tuple[List[int], List[int]]:
     """cos: host floats (rounded to fp32 here) -> (budget[L], group[L])."""
     L = len(cos)
@@ -142,7 +188,8 @@ def allocate_budgets(cos: Sequence[float], total_budget: int, p: float) -> Tuple
     return list(b), list(g)
 
 
-def prefill_scores(Q: torch.Tensor, K: torch.Tensor, scores_out: Optional[torch.Tensor] = None) -> torch.Tensor:
+def prefill_scores(Q: torch.Tensor, K: torch.Tensor, scores_out: Optional[torch.Tensor] = None,
+                   opts: Optional[BatchOptsStruct] = None) -> torch.Tensor:
     """Q [B, Hq, P, D], K [B, Hkv, P, D] -> scores [B, Hkv, P] fp32."""
     B, Hq, P, D = Q.shape
     Hkv = K.shape[1]
@@ -150,8 +197,8 @@ def prefill_scores(Q: torch.Tensor, K: torch.Tensor, scores_out: Optional[torch.
         scores_out = torch.empty(B, Hkv, P, dtype=torch.float32, device=Q.device)
     need = _lib.sqa_prefill_scores_workspace_bytes(B, Hq, Hkv, P, D)
     ws = torch.empty(max(need, 8), dtype=torch.uint8, device=Q.device)
-    _check(_lib.sqa_prefill_scores(_ptr(Q), _ptr(K), _dt(Q), B, Hq, Hkv, P, D, _ptr(scores_out), _ptr(ws),
-                                   ws.numel(), _stream()), "sqa_prefill_scores")
+    _check(_lib.sqa_prefill_scores_ex(_ptr(Q), _ptr(K), _dt(Q), B, Hq, Hkv, P, D, _ptr(scores_out), _ptr(ws),
+                                      ws.numel(), _stream(), _opts(opts)), "sqa_prefill_scores")
     return scores_out
 
 
@@ -199,15 +246,16 @@ def prefill_compress(K: torch.Tensor, V: torch.Tensor, attn_scores: Optional[tor
 
 def prefill_compress_layers(K: Sequence[torch.Tensor], V: Sequence[torch.Tensor],
                             attn_scores: Optional[Sequence[Optional[torch.Tensor]]], policy: str, n_sink: int,
-                            caches: LayerCaches, layer0: int = 0) -> None:
+                            caches: LayerCaches, layer0: int = 0, opts: Optional[BatchOptsStruct] = None) -> None:
     """K[i], V[i] [B, Hkv, P, D] of layer layer0 + i -> caches' layers layer0 .. layer0 + len(K) - 1."""
     n = len(K)
     B, Hkv, P, D = K[0].shape
     Ks = (_vp * n)(*[t.data_ptr() for t in K])
     Vs = (_vp * n)(*[t.data_ptr() for t in V])
     Ss = None if attn_scores is None or attn_scores[0] is None else (_vp * n)(*[t.data_ptr() for t in attn_scores])
-    _check(_lib.sqa_prefill_compress_layers(Ks, Vs, _dt(K[0]), Ss, B, Hkv, P, D, POLICY[policy], n_sink,
-                                            caches.struct_ptr(layer0), n, _stream()), "sqa_prefill_compress_layers")
+    _check(_lib.sqa_prefill_compress_layers_ex(Ks, Vs, _dt(K[0]), Ss, B, Hkv, P, D, POLICY[policy], n_sink,
+                                               caches.struct_ptr(layer0), n, _stream(), _opts(opts)),
+           "sqa_prefill_compress_layers")
 
 
 def decode_workspace(caches: "LayerCaches", Hq: int, policy: str, layer0: int = 0,
@@ -225,15 +273,23 @@ def decode_workspace(caches: "LayerCaches", Hq: int, policy: str, layer0: int = 
 
 def decode_step(q: torch.Tensor, k_new: torch.Tensor, v_new: torch.Tensor, new_pos: int, policy: str,
                 n_sink: int, caches: LayerCaches, out: torch.Tensor, workspace: torch.Tensor,
-                layer0: int = 0, n_layers: Optional[int] = None, use_dev_table: bool = True) -> torch.Tensor:
+                layer0: int = 0, n_layers: Optional[int] = None, use_dev_table: bool = True,
+                opts: Optional[BatchOptsStruct] = None) -> torch.Tensor:
     """q [n_layers, B, Hq, D], k_new / v_new [n_layers, B, Hkv, D] -> out like q."""
     n_layers = caches.L - layer0 if n_layers is None else n_layers
     B, Hq, D = q.shape[-3], q.shape[-2], q.shape[-1]
     Hkv = k_new.shape[-2]
-    _check(_lib.sqa_decode_step(_ptr(q), _ptr(k_new), _ptr(v_new), _dt(q), B, Hq, Hkv, D, int(new_pos),
-                                POLICY[policy], n_sink, caches.struct_ptr(layer0),
-                                caches.dev_ptr(layer0) if use_dev_table else None, n_layers, _ptr(out),
-                                _ptr(workspace), workspace.numel(), _stream()), "sqa_decode_step")
+    if opts is None:
+        _check(_lib.sqa_decode_step(_ptr(q), _ptr(k_new), _ptr(v_new), _dt(q), B, Hq, Hkv, D, int(new_pos),
+                                    POLICY[policy], n_sink, caches.struct_ptr(layer0),
+                                    caches.dev_ptr(layer0) if use_dev_table else None, n_layers, _ptr(out),
+                                    _ptr(workspace), workspace.numel(), _stream()), "sqa_decode_step")
+    else:
+        _check(_lib.sqa_decode_step_ex(_ptr(q), _ptr(k_new), _ptr(v_new), _dt(q), B, Hq, Hkv, D, int(new_pos),
+                                       POLICY[policy], n_sink, caches.struct_ptr(layer0),
+                                       caches.dev_ptr(layer0) if use_dev_table else None, n_layers, _ptr(out),
+                                       _ptr(workspace), workspace.numel(), _stream(), C.byref(opts)),
+               "sqa_decode_step_ex")
     return out
 
 

@@ -43,11 +43,16 @@ struct CompressBatch {
   const void* K[kCmpBatch];
   const void* V[kCmpBatch];
   const float* scores[kCmpBatch];
+  // per-sequence variation (all NULL for a uniform batch)
+  const int32_t* prompt_len;    // [B]
+  const int32_t* budget_seq;    // [n_layers][B], row of this launch's first layer = layer0
+  int32_t* status;
+  int B, Hkv, layer0;
 };
 
 template <typename T, int D>
 __global__ __launch_bounds__(kCmpThreads) void prefill_compress_kernel(
-    const CompressBatch batch, int P, int policy, int n_sink, int lds_key_limit) {
+    const CompressBatch batch, int P /*prompt rows per unit in memory*/, int policy, int n_sink, int lds_words /*dynamic LDS of the launch, in 32-bit words*/) {
   const sqa_layer_cache L = batch.L[blockIdx.y];
   const T* __restrict__ K = static_cast<const T*>(batch.K[blockIdx.y]);
   const T* __restrict__ V = static_cast<const T*>(batch.V[blockIdx.y]);
@@ -61,11 +66,28 @@ __global__ __launch_bounds__(kCmpThreads) void prefill_compress_kernel(
 
   const int tid = threadIdx.x;
   const int u = blockIdx.x;
-  const int b = L.budget, cap = L.capacity;
+  const int bidx = u / batch.Hkv;
+  const int cap = L.capacity;
+  const int P_pad = P;                                     // row pitch of the prompt tensors
+  int b = L.budget;
+  if (batch.prompt_len || batch.budget_seq) {
+    if (batch.prompt_len) P = batch.prompt_len[bidx];
+    if (batch.budget_seq) b = batch.budget_seq[(int64_t)(batch.layer0 + blockIdx.y) * batch.B + bidx];
+    const int min_budget = policy == SQA_H2O ? 2 : (policy == SQA_STREAMING ? n_sink + 1 : 1);
+    const bool bad_len = P < 0 || P > P_pad, bad_budget = b < min_budget || b > L.budget;
+    if (bad_len || bad_budget) {                           // leave the unit empty and say why
+      if (tid == 0) {
+        L.lens[u] = 0; L.ring_head[u] = 0;
+        if (L.evict_hint) L.evict_hint[u] = -2;
+        if (batch.status) *batch.status = bad_len ? SQA_ERR_SHAPE : SQA_ERR_BUDGET;
+      }
+      return;
+    }
+  }
   const int n_keep = P < b ? P : b;
   int* s_idx = reinterpret_cast<int*>(s_mem);              // [n_keep] kept positions, ascending
   uint32_t* s_keys = s_mem + n_keep;                       // [M] when staged
-  const float* sc = scores ? scores + (int64_t)u * P : nullptr;
+  const float* sc = scores ? scores + (int64_t)u * P_pad : nullptr;
 
   // range rules
   int lo_keep = 0;        // positions < lo_keep are always kept (sinks)
@@ -77,7 +99,7 @@ __global__ __launch_bounds__(kCmpThreads) void prefill_compress_kernel(
     else { hh = b / 2; hi_from = P - (b - hh); }
   }
   const int M = hi_from;  // H2O candidates are positions [0, M)
-  const bool keys_in_lds = hh > 0 && M <= lds_key_limit;
+  const bool keys_in_lds = hh > 0 && M <= kKeysInLdsMax && n_keep + M <= lds_words;
 
   uint32_t thr = 0xffffffffu, take_eq = 0;
   if (hh > 0) {
@@ -134,8 +156,8 @@ __global__ __launch_bounds__(kCmpThreads) void prefill_compress_kernel(
   __syncthreads();
 
   // gather rows, scores, positions
-  const T* Ku = K + (int64_t)u * P * D;
-  const T* Vu = V + (int64_t)u * P * D;
+  const T* Ku = K + (int64_t)u * P_pad * D;
+  const T* Vu = V + (int64_t)u * P_pad * D;
   char* Kc = reinterpret_cast<char*>(L.K) + (int64_t)u * cap * ROWB;
   char* Vc = reinterpret_cast<char*>(L.V) + (int64_t)u * cap * ROWB;
   const int grp = tid / LPR, c = tid % LPR;
@@ -185,17 +207,17 @@ __global__ __launch_bounds__(kCmpThreads) void kept_idx_sorted_kernel(sqa_layer_
 }
 
 template <typename T, int D>
-static void launch_compress(const CompressBatch& batch, int n, int P, int policy, int n_sink, int lds_key_limit,
+static void launch_compress(const CompressBatch& batch, int n, int P, int policy, int n_sink,
                             unsigned units, size_t lds, hipStream_t st) {
   auto fn = prefill_compress_kernel<T, D>;
   if (lds > 48 * 1024)
     (void)hipFuncSetAttribute(reinterpret_cast<const void*>(fn), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-  fn<<<dim3(units, n), kCmpThreads, lds, st>>>(batch, P, policy, n_sink, lds_key_limit);
+  fn<<<dim3(units, n), kCmpThreads, lds, st>>>(batch, P, policy, n_sink, (int)(lds / sizeof(uint32_t)));
 }
 
 static sqa_status check_compress_layer(const void* K, const void* V, sqa_dtype kv_dt, const float* attn_scores,
                                        int B, int Hkv, int P, int D, sqa_policy policy, int n_sink,
-                                       const sqa_layer_cache& L, size_t* lds_out) {
+                                       const sqa_layer_cache& L, bool ragged, size_t* lds_out) {
   if (!K || !V) return SQA_ERR_NULL;
   if (policy == SQA_H2O && !attn_scores) return SQA_ERR_NULL;
   if (!L.K || !L.V || !L.pos || !L.lens || !L.ring_head) return SQA_ERR_NULL;
@@ -214,8 +236,10 @@ static sqa_status check_compress_layer(const void* K, const void* V, sqa_dtype k
   };
   if (overlaps(K, in_bytes, L.K, c_bytes) || overlaps(K, in_bytes, L.V, c_bytes) ||
       overlaps(V, in_bytes, L.K, c_bytes) || overlaps(V, in_bytes, L.V, c_bytes)) return SQA_ERR_SHAPE;
-  const bool h2o_select = policy == SQA_H2O && P > L.budget;
-  const int M = h2o_select ? P - (L.budget - L.budget / 2) : 0;
+  // H2O candidates of a unit: at most P - (b - b/2) with the layer's budget, up to P - 1 with a smaller
+  // per-sequence budget; their keys are staged in LDS when they fit
+  const bool h2o_select = policy == SQA_H2O && (ragged ? P > 2 : P > L.budget);
+  const int M = h2o_select ? (ragged ? P - 1 : P - (L.budget - L.budget / 2)) : 0;
   *lds_out = ((size_t)n_keep + (M <= kKeysInLdsMax ? (size_t)M : 0)) * sizeof(uint32_t);
   return SQA_OK;
 }
@@ -226,7 +250,16 @@ extern "C" sqa_status sqa_prefill_compress_layers(const void* const* K, const vo
                                                   const float* const* attn_scores, int B, int Hkv, int P, int D,
                                                   sqa_policy policy, int n_sink, const sqa_layer_cache* layers,
                                                   int n_layers, void* stream) {
+  return sqa_prefill_compress_layers_ex(K, V, kv_dt, attn_scores, B, Hkv, P, D, policy, n_sink, layers, n_layers, stream,
+                                        nullptr);
+}
+
+extern "C" sqa_status sqa_prefill_compress_layers_ex(const void* const* K, const void* const* V, sqa_dtype kv_dt,
+                                                     const float* const* attn_scores, int B, int Hkv, int P, int D,
+                                                     sqa_policy policy, int n_sink, const sqa_layer_cache* layers,
+                                                     int n_layers, void* stream, const sqa_batch_opts* opts) {
   using namespace sqa;
+  const bool ragged = opts && (opts->prompt_len || opts->budget_seq);
   if (!K || !V || !layers) return SQA_ERR_NULL;
   if (kv_dt != SQA_F32 && kv_dt != SQA_BF16) return SQA_ERR_DTYPE;
   if (policy != SQA_SLIDING && policy != SQA_STREAMING && policy != SQA_H2O) return SQA_ERR_POLICY;
@@ -238,7 +271,7 @@ extern "C" sqa_status sqa_prefill_compress_layers(const void* const* K, const vo
   size_t lds_layer[SQA_MAX_LAYERS];
   for (int i = 0; i < n_layers; ++i) {
     const sqa_status st = check_compress_layer(K[i], V[i], kv_dt, attn_scores ? attn_scores[i] : nullptr, B, Hkv, P, D,
-                                               policy, n_sink, layers[i], &lds_layer[i]);
+                                               policy, n_sink, layers[i], ragged, &lds_layer[i]);
     if (st != SQA_OK) return st;
     if (lds_layer[i] > 128 * 1024) return SQA_ERR_CAPACITY;
   }
@@ -247,6 +280,10 @@ extern "C" sqa_status sqa_prefill_compress_layers(const void* const* K, const vo
   for (int l0 = 0; l0 < n_layers; l0 += kCmpBatch) {
     const int n = n_layers - l0 < kCmpBatch ? n_layers - l0 : kCmpBatch;
     CompressBatch batch;
+    batch.prompt_len = opts ? opts->prompt_len : nullptr;
+    batch.budget_seq = opts ? opts->budget_seq : nullptr;
+    batch.status = opts ? opts->status : nullptr;
+    batch.B = B; batch.Hkv = Hkv; batch.layer0 = l0;
     size_t lds = 0;
     for (int i = 0; i < n; ++i) {
       batch.L[i] = layers[l0 + i];
@@ -257,11 +294,11 @@ extern "C" sqa_status sqa_prefill_compress_layers(const void* const* K, const vo
     }
     for (int i = n; i < kCmpBatch; ++i) { batch.L[i] = layers[l0]; batch.K[i] = nullptr; batch.V[i] = nullptr; batch.scores[i] = nullptr; }
     if (kv_dt == SQA_F32) {
-      if (D == 64) launch_compress<float, 64>(batch, n, P, policy, n_sink, kKeysInLdsMax, units, lds, st);
-      else launch_compress<float, 128>(batch, n, P, policy, n_sink, kKeysInLdsMax, units, lds, st);
+      if (D == 64) launch_compress<float, 64>(batch, n, P, policy, n_sink, units, lds, st);
+      else launch_compress<float, 128>(batch, n, P, policy, n_sink, units, lds, st);
     } else {
-      if (D == 64) launch_compress<bf16_t, 64>(batch, n, P, policy, n_sink, kKeysInLdsMax, units, lds, st);
-      else launch_compress<bf16_t, 128>(batch, n, P, policy, n_sink, kKeysInLdsMax, units, lds, st);
+      if (D == 64) launch_compress<bf16_t, 64>(batch, n, P, policy, n_sink, units, lds, st);
+      else launch_compress<bf16_t, 128>(batch, n, P, policy, n_sink, units, lds, st);
     }
     SQA_HIP_CHECK(hipGetLastError());
   }

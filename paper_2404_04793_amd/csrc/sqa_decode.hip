@@ -50,8 +50,11 @@ struct DecodeArgs {
   int32_t* cnt;                    // scratch: arrival counter per unit (zero between launches)
   float* part;                     // scratch: per-chunk partial (acc[D], m, l) of split units
   float* logit;                    // scratch: logits of split units (H2O)
+  const int32_t* new_pos_seq;      // DEVICE [B] or NULL: per-sequence position, < 0 = sequence sits this step out
+  const int32_t* budget_seq;       // DEVICE [n_layers][B] or NULL: per-sequence budgets
   int B, Hq, Hkv, n_layers;
   int new_pos, policy, n_sink;
+  int ae;                          // 1 = attend over all len+1 tokens first, evict afterwards
   float scale_log2;                // log2(e) / sqrt(D)
   uint8_t order[SQA_MAX_LAYERS];       // layers in descending budget (long units start first)
   uint32_t blk_end[SQA_MAX_LAYERS];    // work items up to and including ordered layer i
@@ -247,7 +250,9 @@ __global__ __launch_bounds__(kDecThreads, MF ? SQA_DEC_MF_WAVES : 1) SQA_DEC_OCC
   const int u = (int)(local / (unsigned)nsplit), chunk = (int)(local % (unsigned)nsplit);
   const int bidx = u / a.Hkv, kvh = u % a.Hkv;
   const sqa_layer_cache L = a.layers[layer];
-  const int cap = L.capacity, budget = L.budget;
+  const int cap = L.capacity;
+  const int budget = a.budget_seq ? a.budget_seq[layer * a.B + bidx] : L.budget;
+  const bool sits_out = a.new_pos_seq && a.new_pos_seq[bidx] < 0;
   const int hh = H2O ? budget / 2 : (a.policy == SQA_STREAMING ? min(a.n_sink, budget) : 0);
   const int rec = budget - hh;
   const int csize = (int)a.lay[layer].chunk;
@@ -289,36 +294,48 @@ __global__ __launch_bounds__(kDecThreads, MF ? SQA_DEC_MF_WAVES : 1) SQA_DEC_OCC
   const float sc_pre = H2O ? sc[min(tid, cap - 1)] : 0.f;
 
   // ---- 0. where does the new token go, who leaves -------------------------
-  const bool bad_state = len > budget || len > cap || len < 0 || head < 0 || (len == budget && head >= rec);
-  const bool bad_cap = !bad_state && len < budget && len >= cap;
-  if (bad_state || bad_cap) {                     // same verdict in every chunk of the unit
+  if (sits_out) return;                           // the sequence takes no part in this step (every chunk agrees)
+  const int min_budget = H2O ? 2 : (a.policy == SQA_STREAMING ? a.n_sink + 1 : 1);
+  const bool bad_budget = budget < min_budget || budget > L.budget;
+  const bool bad_state = !bad_budget && (len > budget || len > cap || len < 0 || head < 0 || (len == budget && head >= rec));
+  const bool bad_cap = !bad_budget && !bad_state && len < budget && len >= cap;
+  if (bad_budget || bad_state || bad_cap) {       // same verdict in every chunk of the unit
     if (chunk == 0) {
       for (int i = tid; i < G * D; i += kDecThreads) reinterpret_cast<T*>(outp)[i] = T{};
-      if (tid == 0) *a.status = bad_state ? SQA_ERR_STATE : SQA_ERR_CAPACITY;
+      if (tid == 0) *a.status = bad_budget ? SQA_ERR_BUDGET : (bad_state ? SQA_ERR_STATE : SQA_ERR_CAPACITY);
     }
     return;
   }
   const bool full = len == budget;
-  const int n = full ? budget : len + 1;          // tokens attended this step
-  const int slot_new = full ? hh + head : len;
+  const bool ae = a.ae != 0;
+  // Evict-then-attend: a full unit attends its budget tokens, the new token already
+  // sitting (logically) in the slot it will occupy.  Attend-then-evict: the unit
+  // attends all len+1 tokens as they lie, the new token as one more slot at
+  // index len (which exists only in this step's index space when the unit is
+  // full), and the eviction happens after the accumulation (step 3).
+  const int n = (full && !ae) ? budget : len + 1; // tokens attended this step
+  const int slot_wr = full ? hh + head : len;     // physical slot the new token is written to
+  const int slot_new = ae ? len : slot_wr;        // index of the new token while streaming
+  const int rmax = min(n, cap) - 1;               // last row that may be read from memory
   int moved_to = -1;                              // heavy slot that receives the ring leaver
-  if (H2O && full) {
+  if (H2O && full && !ae) {
     if (hint >= -1 && hint < hh) {
       moved_to = hint;
     } else {                                      // no decision carried over: take it now
       float mn = INFINITY;
       for (int i = tid; i < hh; i += kDecThreads) mn = fminf(mn, sc[i]);
       mn = block_min(mn, s_red, false);
-      moved_to = pick_victim(sc, posu, hh, mn, sc[slot_new], -1, 0, s_red64, false);
+      moved_to = pick_victim(sc, posu, hh, mn, sc[slot_wr], -1, 0, s_red64, false);
     }
   }
   // the ring leaver's score and position, needed in step 3 if it moves
-  const float leaver_score = (H2O && moved_to >= 0) ? sc[slot_new] : 0.f;
-  const int leaver_pos = (H2O && moved_to >= 0) ? posu[slot_new] : 0;
+  const float leaver_score = (H2O && moved_to >= 0) ? sc[slot_wr] : 0.f;
+  const int leaver_pos = (H2O && moved_to >= 0) ? posu[slot_wr] : 0;
 
   // ---- 1. stream the chunk's K and V once, online softmax -------------------
   const int c_end = min(c0 + csize, n);
-  float* glogit = (H2O && nsplit > 1) ? a.logit + a.lay[layer].logit_off + (int64_t)u * G * cap : nullptr;
+  const int lpitch = cap + 1;                      // logit row of one head in scratch (the new token may be slot cap)
+  float* glogit = (H2O && nsplit > 1) ? a.logit + a.lay[layer].logit_off + (int64_t)u * G * lpitch : nullptr;
 
   if constexpr (MF) {
     // ---- 1M. matrix-core streaming ------------------------------------------
@@ -362,12 +379,12 @@ __global__ __launch_bounds__(kDecThreads, MF ? SQA_DEC_MF_WAVES : 1) SQA_DEC_OCC
     auto request_k = [&](int base) {
 #pragma unroll
       for (int i = 0; i < 8; ++i)
-        kreg[i] = ld16_nt(Kb + ((uint32_t)min(base + 4 * i + r, n - 1) * (uint32_t)ROWB + (uint32_t)(c * 16)));
+        kreg[i] = ld16_nt(Kb + ((uint32_t)min(base + 4 * i + r, rmax) * (uint32_t)ROWB + (uint32_t)(c * 16)));
     };
     auto request_v = [&](int base) {
 #pragma unroll
       for (int i = 0; i < 8; ++i)
-        vreg[i] = ld16_nt(Vb + ((uint32_t)min(base + 4 * i + r, n - 1) * (uint32_t)ROWB + (uint32_t)(c * 16)));
+        vreg[i] = ld16_nt(Vb + ((uint32_t)min(base + 4 * i + r, rmax) * (uint32_t)ROWB + (uint32_t)(c * 16)));
     };
     constexpr int TSTEP = 32 * kDecWaves;
     if (c0 + 32 * wave < c_end) { request_k(c0 + 32 * wave); request_v(c0 + 32 * wave); }
@@ -378,7 +395,7 @@ __global__ __launch_bounds__(kDecThreads, MF ? SQA_DEC_MF_WAVES : 1) SQA_DEC_OCC
       const bool has_new = slot_new >= base && slot_new < base + 32;
       const bool has_moved = moved_to >= base && moved_to < base + 32;
       uint4 km = make_uint4(0, 0, 0, 0), vm = km;
-      if (has_moved) { km = ld16(Kb + (int64_t)slot_new * ROWB + c * 16); vm = ld16(Vb + (int64_t)slot_new * ROWB + c * 16); }
+      if (has_moved) { km = ld16(Kb + (int64_t)slot_wr * ROWB + c * 16); vm = ld16(Vb + (int64_t)slot_wr * ROWB + c * 16); }
 #pragma unroll
       for (int i = 0; i < 8; ++i) *reinterpret_cast<uint4*>(st_wr + 4 * i * kStageRow) = kreg[i];
       if (has_moved && ((moved_to - base) & 3) == r)
@@ -407,7 +424,7 @@ __global__ __launch_bounds__(kDecThreads, MF ? SQA_DEC_MF_WAVES : 1) SQA_DEC_OCC
         sv[e] = d;
         mx = fmaxf(mx, d);
         if (H2O && valid && hd < G) {
-          if (glogit) st_agent(&glogit[(int64_t)hd * cap + tok], d);
+          if (glogit) st_agent(&glogit[(int64_t)hd * lpitch + tok], d);
           else s_logit[hd * a.lds_chunk + tok] = d;
         }
       }
@@ -475,8 +492,8 @@ __global__ __launch_bounds__(kDecThreads, MF ? SQA_DEC_MF_WAVES : 1) SQA_DEC_OCC
     for (int uu = 0; uu < kUnroll; ++uu) {
       if (slot[uu] == slot_new) { kf[uu] = kn_pre; vf[uu] = vn_pre; }
       if (slot[uu] == moved_to) {
-        kf[uu] = ld16(Kb + (int64_t)slot_new * ROWB + c * 16);
-        vf[uu] = ld16(Vb + (int64_t)slot_new * ROWB + c * 16);
+        kf[uu] = ld16(Kb + (int64_t)slot_wr * ROWB + c * 16);
+        vf[uu] = ld16(Vb + (int64_t)slot_wr * ROWB + c * 16);
       }
     }
 
@@ -488,7 +505,7 @@ __global__ __launch_bounds__(kDecThreads, MF ? SQA_DEC_MF_WAVES : 1) SQA_DEC_OCC
           const int sl = min(slot[uu], n - 1);
           const char* kp = Kb + (int64_t)sl * ROWB;
           const char* vp = Vb + (int64_t)sl * ROWB;
-          if (sl == moved_to) { kp = Kb + (int64_t)slot_new * ROWB; vp = Vb + (int64_t)slot_new * ROWB; }
+          if (sl == moved_to) { kp = Kb + (int64_t)slot_wr * ROWB; vp = Vb + (int64_t)slot_wr * ROWB; }
           if (sl == slot_new) { kp = knew; vp = vnew; }
           kf[uu] = ld16_nt(kp + c * 16);
           vf[uu] = ld16_nt(vp + c * 16);
@@ -504,7 +521,7 @@ __global__ __launch_bounds__(kDecThreads, MF ? SQA_DEC_MF_WAVES : 1) SQA_DEC_OCC
           d = valid ? d : -INFINITY;
           s[uu][g] = d;
           if (H2O && c == 0 && valid) {
-            if (glogit) st_agent(&glogit[(int64_t)g * cap + slot[uu]], d);
+            if (glogit) st_agent(&glogit[(int64_t)g * lpitch + slot[uu]], d);
             else s_logit[g * a.lds_chunk + slot[uu]] = d;
           }
         }
@@ -626,14 +643,18 @@ __global__ __launch_bounds__(kDecThreads, MF ? SQA_DEC_MF_WAVES : 1) SQA_DEC_OCC
   const bool solo = nsplit == 1;
   if (solo && wave != 0) return;
   const int nthr = solo ? SQA_WAVE : kDecThreads;
-  int next_hint = -1;
+  int next_hint = ae ? -2 : -1;
   const int head_next = full ? (head + 1 == rec ? 0 : head + 1) : head;
+  int victim = -1;                                // attend-then-evict: heavy slot evicted in this step (-1: the leaver)
   if (H2O) {
     float fm[G], fi[G];
 #pragma unroll
     for (int g = 0; g < G; ++g) { fm[g] = s_m[0][g]; fi[g] = s_l[0][g]; }
-    const bool next_full = n == budget;
-    const int leaver_next = hh + head_next;
+    // the heavy region competes with: the NEXT ring leaver for the next step's decision (evict-then-attend),
+    // or this step's ring leaver right now (attend-then-evict)
+    const bool decide = ae ? full : n == budget;
+    const int leaver_slot = ae ? slot_wr : hh + head_next;
+    const bool virt = ae && full;                 // the new token has no slot of its own yet
     float mn = INFINITY;
     constexpr int SB = 4;                         // scores requested together: one round trip per SB tokens
     for (int i0 = tid; i0 < n; i0 += SB * nthr) {
@@ -641,7 +662,7 @@ __global__ __launch_bounds__(kDecThreads, MF ? SQA_DEC_MF_WAVES : 1) SQA_DEC_OCC
 #pragma unroll
       for (int k = 0; k < SB; ++k) {
         const int i = i0 + k * nthr;
-        cur[k] = (k == 0 && i0 == tid) ? sc_pre : sc[min(i, n - 1)];   // each thread's first score came with the start
+        cur[k] = (k == 0 && i0 == tid) ? sc_pre : sc[min(i, rmax)];   // each thread's first score came with the start
       }
 #pragma unroll
       for (int k = 0; k < SB; ++k) {
@@ -650,41 +671,53 @@ __global__ __launch_bounds__(kDecThreads, MF ? SQA_DEC_MF_WAVES : 1) SQA_DEC_OCC
           float p = 0.f;
 #pragma unroll
           for (int g = 0; g < G; ++g) {
-            const float lg = glogit ? ld_agent(&glogit[(int64_t)g * cap + i]) : s_logit[g * a.lds_chunk + i];
+            const float lg = glogit ? ld_agent(&glogit[(int64_t)g * lpitch + i]) : s_logit[g * a.lds_chunk + i];
             p += fast_exp2(lg - fm[g]) * fi[g];
           }
           const float old = i == slot_new ? 0.f : (i == moved_to ? leaver_score : cur[k]);
           const float nv = old + p;
-          sc[i] = nv;
+          if (virt && i == slot_new) s_ctlf[1] = nv;   // stored in step 4, once its slot is free
+          else sc[i] = nv;
           if (i < hh) mn = fminf(mn, nv);
-          if (i == leaver_next) s_ctlf[0] = nv;
+          if (i == leaver_slot) s_ctlf[0] = nv;
         }
       }
     }
-    if (next_full) {
-      mn = block_min(mn, s_red, solo);            // (the barrier inside also orders the s_ctlf write)
+    if (decide) {
+      mn = block_min(mn, s_red, solo);            // (the barrier inside also orders the s_ctlf writes)
       // positions as they will be after step 4: the moved token brings its own
-      next_hint = pick_victim(sc, posu, hh, mn, s_ctlf[0], moved_to, leaver_pos, s_red64, solo);
+      const int v = pick_victim(sc, posu, hh, mn, s_ctlf[0], moved_to, leaver_pos, s_red64, solo);
+      if (ae) {
+        // Apply it now.  Each score is rewritten by the thread that wrote it
+        // above (slot i belongs to thread i mod nthr), so the two writes to one
+        // address are ordered by that thread's program order.
+        victim = v;
+        if (victim >= 0 && tid == victim % nthr) sc[victim] = s_ctlf[0];
+        if (tid == slot_wr % nthr) sc[slot_wr] = s_ctlf[1];
+      } else {
+        next_hint = v;
+      }
     }
   }
+  const int dst = ae ? victim : moved_to;         // heavy slot that takes over the ring leaver's row
 
   // ---- 4. the cache update: moved row, new token, bookkeeping ---------------
   if (wave == 0 && r == 0) {
     char* Kw = const_cast<char*>(Kb);
     char* Vw = const_cast<char*>(Vb);
-    if (moved_to >= 0) {
-      const uint4 kk = ld16(Kw + (int64_t)slot_new * ROWB + c * 16);
-      const uint4 vv = ld16(Vw + (int64_t)slot_new * ROWB + c * 16);
-      st16(Kw + (int64_t)moved_to * ROWB + c * 16, kk);
-      st16(Vw + (int64_t)moved_to * ROWB + c * 16, vv);
+    if (dst >= 0) {
+      const uint4 kk = ld16(Kw + (int64_t)slot_wr * ROWB + c * 16);
+      const uint4 vv = ld16(Vw + (int64_t)slot_wr * ROWB + c * 16);
+      st16(Kw + (int64_t)dst * ROWB + c * 16, kk);
+      st16(Vw + (int64_t)dst * ROWB + c * 16, vv);
     }
-    st16(Kw + (int64_t)slot_new * ROWB + c * 16, kn_pre);
-    st16(Vw + (int64_t)slot_new * ROWB + c * 16, vn_pre);
+    st16(Kw + (int64_t)slot_wr * ROWB + c * 16, kn_pre);
+    st16(Vw + (int64_t)slot_wr * ROWB + c * 16, vn_pre);
     if (c == 0) {
       int32_t* posw = L.pos + (int64_t)u * cap;
-      if (moved_to >= 0) posw[moved_to] = posw[slot_new];
-      posw[slot_new] = a.new_pos;
-      L.lens[u] = n;
+      if (dst >= 0) posw[dst] = posw[slot_wr];
+      posw[slot_wr] = a.new_pos_seq ? a.new_pos_seq[bidx] : a.new_pos;   // (read again: not kept in a register all along)
+      L.lens[u] = full ? budget : len + 1;
       if (full) L.ring_head[u] = head_next;
       if (H2O) L.evict_hint[u] = next_hint;
     }
@@ -763,7 +796,8 @@ static sqa_status plan_decode(const sqa_layer_cache* layers, int n_layers, int B
   uint64_t blocks = 0, n_units = 0, n_part = 0, n_logit = 0;
   p->lds_chunk = 64;
   for (int i = 0; i < n_layers; ++i) {
-    const int nmax = layers[i].budget < layers[i].capacity ? layers[i].budget : layers[i].capacity;
+    // + 1: under attend-then-evict a full unit attends budget + 1 tokens
+    const int nmax = (layers[i].budget < layers[i].capacity ? layers[i].budget : layers[i].capacity) + 1;
     int64_t ns = (nmax + target / 2) / target;                  // nearest count of equal chunks
     ns = ns < 1 ? 1 : ns;
     int64_t ch = ((nmax + ns - 1) / ns + 63) / 64 * 64;
@@ -780,7 +814,7 @@ static sqa_status plan_decode(const sqa_layer_cache* layers, int n_layers, int B
     blocks += units * ns;
     if (ns > 1) {
       n_part += units * ns;
-      if (h2o) n_logit += units * g * layers[i].capacity;
+      if (h2o) n_logit += units * g * ((uint64_t)layers[i].capacity + 1);
     }
     if (n_units > 0x7fffffffull || n_part > 0x7fffffffull || n_logit > 0xffffffffull || blocks > 0x7fffffffull)
       return SQA_ERR_CAPACITY;
@@ -830,12 +864,24 @@ extern "C" sqa_status sqa_decode_step(const void* q, const void* k_new, const vo
                                       sqa_policy policy, int n_sink,
                                       const sqa_layer_cache* layers, const sqa_layer_cache* layers_dev, int n_layers,
                                       void* out, void* workspace, size_t ws_bytes, void* stream) {
+  return sqa_decode_step_ex(q, k_new, v_new, dt, B, Hq, Hkv, D, new_pos, policy, n_sink, layers, layers_dev, n_layers,
+                            out, workspace, ws_bytes, stream, nullptr);
+}
+
+extern "C" sqa_status sqa_decode_step_ex(const void* q, const void* k_new, const void* v_new, sqa_dtype dt,
+                                         int B, int Hq, int Hkv, int D, int32_t new_pos,
+                                         sqa_policy policy, int n_sink,
+                                         const sqa_layer_cache* layers, const sqa_layer_cache* layers_dev, int n_layers,
+                                         void* out, void* workspace, size_t ws_bytes, void* stream,
+                                         const sqa_batch_opts* opts) {
   using namespace sqa;
   if (!q || !k_new || !v_new || !layers || !out || !workspace) return SQA_ERR_NULL;
+  if (opts && opts->order != SQA_EVICT_THEN_ATTEND && opts->order != SQA_ATTEND_THEN_EVICT) return SQA_ERR_POLICY;
   if (dt != SQA_F32 && dt != SQA_BF16) return SQA_ERR_DTYPE;
   if (policy != SQA_SLIDING && policy != SQA_STREAMING && policy != SQA_H2O) return SQA_ERR_POLICY;
   if (n_sink < 0) return SQA_ERR_POLICY;
-  if (B < 1 || Hq < 1 || Hkv < 1 || n_layers < 1 || n_layers > SQA_MAX_LAYERS || Hq % Hkv != 0 || new_pos < 0)
+  if (B < 1 || Hq < 1 || Hkv < 1 || n_layers < 1 || n_layers > SQA_MAX_LAYERS || Hq % Hkv != 0 ||
+      (new_pos < 0 && !(opts && opts->new_pos_seq)))
     return SQA_ERR_SHAPE;
   const int g = Hq / Hkv;
   const bool h2o = policy == SQA_H2O;
@@ -873,6 +919,9 @@ extern "C" sqa_status sqa_decode_step(const void* q, const void* k_new, const vo
   a.logit = reinterpret_cast<float*>(ws + plan.off_logit);
   a.B = B; a.Hq = Hq; a.Hkv = Hkv; a.n_layers = n_layers;
   a.new_pos = new_pos; a.policy = (int)policy; a.n_sink = n_sink;
+  a.new_pos_seq = opts ? opts->new_pos_seq : nullptr;
+  a.budget_seq = opts ? opts->budget_seq : nullptr;
+  a.ae = (opts && opts->order == SQA_ATTEND_THEN_EVICT) ? 1 : 0;
   a.lds_chunk = plan.lds_chunk;
   a.scale_log2 = (float)(1.4426950408889634 / sqrt((double)D));
   // long units first: layers in descending budget (stable)

@@ -63,7 +63,8 @@ template <> struct Residual<bf16_t> {
 template <typename T, bool FUSE>
 __global__ __launch_bounds__(kImpThreads) void importance_partial_kernel(
     const T* h_in, const T* other, T* h_out_w /*may be h_in or other*/, int64_t n_tokens, int hidden,
-    double* __restrict__ partial /*[layers][gridDim.x]*/) {
+    const int32_t* __restrict__ seq_start /*[gridDim.z + 1] or NULL*/,
+    double* __restrict__ partial /*[layers][gridDim.z][gridDim.x]*/) {
   constexpr int E = elem<T>::per16;
   const int lane = threadIdx.x & (SQA_WAVE - 1);
   const int wave = threadIdx.x / SQA_WAVE;
@@ -76,8 +77,16 @@ __global__ __launch_bounds__(kImpThreads) void importance_partial_kernel(
   const int64_t row_bytes = row_elems * (int64_t)sizeof(T);
   const int64_t stride = (int64_t)gridDim.x * kImpWaves;
 
+  // rows of this (layer, sequence): all of the layer's unless the tokens are segmented
+  int64_t row_lo = 0, row_hi = n_tokens;
+  if (seq_start) {
+    row_lo = seq_start[blockIdx.z];
+    row_hi = seq_start[blockIdx.z + 1];
+    row_lo = row_lo < 0 ? 0 : row_lo;
+    row_hi = row_hi > n_tokens ? n_tokens : row_hi;
+  }
   double wave_cos = 0.0;
-  for (int64_t row = (int64_t)blockIdx.x * kImpWaves + wave; row < n_tokens; row += stride) {
+  for (int64_t row = row_lo + (int64_t)blockIdx.x * kImpWaves + wave; row < row_hi; row += stride) {
     const char* a = A + row * row_bytes;
     const char* b = Bp + row * row_bytes;
     char* w = FUSE ? Wp + row * row_bytes : nullptr;
@@ -117,18 +126,28 @@ __global__ __launch_bounds__(kImpThreads) void importance_partial_kernel(
   if (threadIdx.x == 0) {
     double s = 0.0;
     for (int w = 0; w < kImpWaves; ++w) s += s_part[w];
-    partial[(int64_t)layer * gridDim.x + blockIdx.x] = s;
+    partial[((int64_t)layer * gridDim.z + blockIdx.z) * gridDim.x + blockIdx.x] = s;
   }
 }
 
+// one wave per (layer, sequence): blockIdx.x = layer * n_seq + sequence
 __global__ __launch_bounds__(SQA_WAVE) void importance_final_kernel(
-    const double* __restrict__ partial, int n_part, int64_t n_tokens, float* __restrict__ cos_out) {
-  const int layer = blockIdx.x;
+    const double* __restrict__ partial, int n_part, int64_t n_tokens, const int32_t* __restrict__ seq_start, int n_seq,
+    float* __restrict__ cos_out) {
+  const int item = blockIdx.x;
   const int lane = threadIdx.x;
   double s = 0.0;
-  for (int i = lane; i < n_part; i += SQA_WAVE) s += partial[(int64_t)layer * n_part + i];
+  for (int i = lane; i < n_part; i += SQA_WAVE) s += partial[(int64_t)item * n_part + i];
   s = wave_sum(s);
-  if (lane == 0) cos_out[layer] = (float)(s / (double)n_tokens);
+  int64_t rows = n_tokens;
+  if (seq_start) {
+    const int q = item % n_seq;
+    int64_t lo = seq_start[q], hi = seq_start[q + 1];
+    lo = lo < 0 ? 0 : lo;
+    hi = hi > n_tokens ? n_tokens : hi;
+    rows = hi - lo;
+  }
+  if (lane == 0) cos_out[item] = rows > 0 ? (float)(s / (double)rows) : 0.f;
 }
 
 static int imp_blocks(int64_t n_tokens) {
@@ -146,34 +165,35 @@ extern "C" size_t sqa_layer_importance_workspace_bytes(int n_layers, int64_t n_t
 
 namespace sqa {
 static sqa_status launch_importance(const void* h_in, const void* other, void* h_out_w, sqa_dtype dt,
-                                    int n_layers, int64_t n_tokens, int hidden,
+                                    int n_layers, int64_t n_tokens, int hidden, const int32_t* seq_start, int n_seq,
                                     float* cos_out, void* workspace, size_t ws_bytes, void* stream) {
   const bool fuse = h_out_w != nullptr;
   if (!h_in || !other || !cos_out || !workspace) return SQA_ERR_NULL;
   if (dt != SQA_F32 && dt != SQA_BF16) return SQA_ERR_DTYPE;
   if (n_layers < 1 || n_layers > 65535 || n_tokens < 1 || hidden < 8 || hidden % 8 != 0) return SQA_ERR_SHAPE;
+  if (n_seq < 1 || n_seq > 65535 || (int64_t)n_layers * n_seq > INT32_MAX) return SQA_ERR_SHAPE;
   if (!aligned16(h_in) || !aligned16(other) || !aligned16(h_out_w) || (reinterpret_cast<uintptr_t>(workspace) & 7u))
     return SQA_ERR_SHAPE;
-  if (ws_bytes < sqa_layer_importance_workspace_bytes(n_layers, n_tokens, hidden)) return SQA_ERR_CAPACITY;
+  if (ws_bytes < (size_t)n_seq * sqa_layer_importance_workspace_bytes(n_layers, n_tokens, hidden)) return SQA_ERR_CAPACITY;
   hipStream_t st = static_cast<hipStream_t>(stream);
   const int nblk = imp_blocks(n_tokens);
   double* partial = static_cast<double*>(workspace);
-  dim3 grid(nblk, n_layers);
+  dim3 grid(nblk, n_layers, n_seq);
   if (dt == SQA_F32) {
     const float* a = static_cast<const float*>(h_in);
     const float* b = static_cast<const float*>(other);
     float* w = static_cast<float*>(h_out_w);
-    if (fuse) importance_partial_kernel<float, true><<<grid, kImpThreads, 0, st>>>(a, b, w, n_tokens, hidden, partial);
-    else importance_partial_kernel<float, false><<<grid, kImpThreads, 0, st>>>(a, b, w, n_tokens, hidden, partial);
+    if (fuse) importance_partial_kernel<float, true><<<grid, kImpThreads, 0, st>>>(a, b, w, n_tokens, hidden, seq_start, partial);
+    else importance_partial_kernel<float, false><<<grid, kImpThreads, 0, st>>>(a, b, w, n_tokens, hidden, seq_start, partial);
   } else {
     const bf16_t* a = static_cast<const bf16_t*>(h_in);
     const bf16_t* b = static_cast<const bf16_t*>(other);
     bf16_t* w = static_cast<bf16_t*>(h_out_w);
-    if (fuse) importance_partial_kernel<bf16_t, true><<<grid, kImpThreads, 0, st>>>(a, b, w, n_tokens, hidden, partial);
-    else importance_partial_kernel<bf16_t, false><<<grid, kImpThreads, 0, st>>>(a, b, w, n_tokens, hidden, partial);
+    if (fuse) importance_partial_kernel<bf16_t, true><<<grid, kImpThreads, 0, st>>>(a, b, w, n_tokens, hidden, seq_start, partial);
+    else importance_partial_kernel<bf16_t, false><<<grid, kImpThreads, 0, st>>>(a, b, w, n_tokens, hidden, seq_start, partial);
   }
   SQA_HIP_CHECK(hipGetLastError());
-  importance_final_kernel<<<n_layers, SQA_WAVE, 0, st>>>(partial, nblk, n_tokens, cos_out);
+  importance_final_kernel<<<n_layers * n_seq, SQA_WAVE, 0, st>>>(partial, nblk, n_tokens, seq_start, n_seq, cos_out);
   SQA_HIP_CHECK(hipGetLastError());
   return SQA_OK;
 }
@@ -182,12 +202,23 @@ static sqa_status launch_importance(const void* h_in, const void* other, void* h
 extern "C" sqa_status sqa_layer_importance(const void* h_in, const void* h_out, sqa_dtype dt,
                                            int n_layers, int64_t n_tokens, int hidden,
                                            float* cos_out, void* workspace, size_t ws_bytes, void* stream) {
-  return sqa::launch_importance(h_in, h_out, nullptr, dt, n_layers, n_tokens, hidden, cos_out, workspace, ws_bytes, stream);
+  return sqa::launch_importance(h_in, h_out, nullptr, dt, n_layers, n_tokens, hidden, nullptr, 1, cos_out, workspace,
+                                ws_bytes, stream);
+}
+
+extern "C" sqa_status sqa_layer_importance_seq(const void* h_in, const void* h_out, sqa_dtype dt,
+                                               int n_layers, int64_t n_tokens, int hidden,
+                                               const int32_t* seq_start, int n_seq,
+                                               float* cos_out, void* workspace, size_t ws_bytes, void* stream) {
+  if (!seq_start) return SQA_ERR_NULL;
+  return sqa::launch_importance(h_in, h_out, nullptr, dt, n_layers, n_tokens, hidden, seq_start, n_seq, cos_out,
+                                workspace, ws_bytes, stream);
 }
 
 extern "C" sqa_status sqa_residual_add_importance(const void* h_in, const void* attn_out, void* h_out, sqa_dtype dt,
                                                   int n_layers, int64_t n_tokens, int hidden,
                                                   float* cos_out, void* workspace, size_t ws_bytes, void* stream) {
   if (!h_out) return SQA_ERR_NULL;
-  return sqa::launch_importance(h_in, attn_out, h_out, dt, n_layers, n_tokens, hidden, cos_out, workspace, ws_bytes, stream);
+  return sqa::launch_importance(h_in, attn_out, h_out, dt, n_layers, n_tokens, hidden, nullptr, 1, cos_out, workspace,
+                                ws_bytes, stream);
 }

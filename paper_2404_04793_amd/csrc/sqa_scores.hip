@@ -126,11 +126,13 @@ __global__ __launch_bounds__(kScThreads) void score_rowstats_kernel(
 template <typename T, int D>
 __global__ __launch_bounds__(kScThreads) void score_colsum_kernel(
     const T* __restrict__ Q, const T* __restrict__ K, int Hq, int Hkv, int P, float scale_log2,
-    const float2* __restrict__ stats, float* __restrict__ scores /*[B*Hkv][P]*/) {
+    const float2* __restrict__ stats, const int32_t* __restrict__ prompt_len /*[B] or NULL*/,
+    float* __restrict__ scores /*[B*Hkv][P]*/) {
   __shared__ __attribute__((aligned(16))) float Qs[kDK][kLd];
   __shared__ __attribute__((aligned(16))) float Ks[kDK][kLd];
   __shared__ float s_col[16][kTile];
   const int bk = blockIdx.y, b = bk / Hkv, kvh = bk % Hkv, g = Hq / Hkv;
+  const int Pq = prompt_len ? max(0, min(prompt_len[b], P)) : P;   // queries beyond the sequence's own prompt are padding
   const T* Kh = K + (int64_t)bk * P * D;
   const int col0 = blockIdx.x * kTile;
   const int ty = threadIdx.x / 16, tx = threadIdx.x % 16;
@@ -138,7 +140,7 @@ __global__ __launch_bounds__(kScThreads) void score_colsum_kernel(
   for (int hg = 0; hg < g; ++hg) {
     const int64_t bh = (int64_t)b * Hq + (int64_t)kvh * g + hg;
     const T* Qh = Q + bh * P * D;
-    for (int row0 = col0; row0 < P; row0 += kTile) {
+    for (int row0 = col0; row0 < Pq; row0 += kTile) {
       float s[4][4];
       logit_tile<T, D>(Qh, Kh, P, row0, col0, Qs, Ks, s);
 #pragma unroll
@@ -149,7 +151,7 @@ __global__ __launch_bounds__(kScThreads) void score_colsum_kernel(
         for (int j = 0; j < 4; ++j) {
           const int col = col0 + tx * 4 + j;
           const float p = __builtin_amdgcn_exp2f(s[i][j] * scale_log2 - st.x) * st.y;
-          colsum[j] += (row < P && col <= row) ? p : 0.f;
+          colsum[j] += (row < Pq && col <= row) ? p : 0.f;
         }
       }
     }
@@ -277,13 +279,15 @@ __global__ __launch_bounds__(kScThreads) void score_rowstats_mfma_kernel(
 
 __global__ __launch_bounds__(kScThreads) void score_colsum_mfma_kernel(
     const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K, int Hq, int Hkv, int P, float scale_log2,
-    const float2* __restrict__ stats, float* __restrict__ scores) {
+    const float2* __restrict__ stats, const int32_t* __restrict__ prompt_len /*[B] or NULL*/,
+    float* __restrict__ scores) {
   extern __shared__ char s_tiles[];                 // 2 x ([64][kMPitch] + 64 float2)
   constexpr int BUF = kMTileBytes + kMT * (int)sizeof(float2);
   const int bk = blockIdx.y, b = bk / Hkv, kvh = bk % Hkv, g = Hq / Hkv;
   const bf16_t* Kh = K + (int64_t)bk * P * 128;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int n16 = lane & 15, j4 = lane >> 4;
+  const int Pq = prompt_len ? max(0, min(prompt_len[b], P)) : P;   // queries beyond the sequence's own prompt are padding
   const int k0 = blockIdx.x * kMT + 16 * wave;      // this wave's 16 keys
   const int my_key = k0 + n16;
   sc_bf16x8_t kfr[4];
@@ -320,7 +324,7 @@ __global__ __launch_bounds__(kScThreads) void score_colsum_mfma_kernel(
       for (int e = 0; e < 4; ++e) {
         const int row = i0 + 4 * j4 + e;
         const float p = __builtin_amdgcn_exp2f(s4[e] * scale_log2 - mrow[e]) * irow[e];
-        colsum += (row >= my_key && row < P) ? p : 0.f;
+        colsum += (row >= my_key && row < Pq) ? p : 0.f;
       }
     }
   }
@@ -329,26 +333,26 @@ __global__ __launch_bounds__(kScThreads) void score_colsum_mfma_kernel(
   if (j4 == 0 && my_key < P) scores[(int64_t)bk * P + my_key] = colsum;
 }
 
-static void launch_scores_mfma(const void* Q, const void* K, int B, int Hq, int Hkv, int P, float* scores,
-                               float2* stats, hipStream_t st) {
+static void launch_scores_mfma(const void* Q, const void* K, int B, int Hq, int Hkv, int P, const int32_t* prompt_len,
+                               float* scores, float2* stats, hipStream_t st) {
   const float scale_log2 = (float)(1.4426950408889634 / sqrt(128.0));
   const int tiles = (P + kMT - 1) / kMT;
   const size_t lds1 = 2 * (size_t)kMTileBytes, lds2 = 2 * ((size_t)kMTileBytes + kMT * sizeof(float2));
   score_rowstats_mfma_kernel<<<dim3(tiles, B * Hq), kScThreads, lds1, st>>>(
       static_cast<const bf16_t*>(Q), static_cast<const bf16_t*>(K), Hq, Hkv, P, scale_log2, stats);
   score_colsum_mfma_kernel<<<dim3(tiles, B * Hkv), kScThreads, lds2, st>>>(
-      static_cast<const bf16_t*>(Q), static_cast<const bf16_t*>(K), Hq, Hkv, P, scale_log2, stats, scores);
+      static_cast<const bf16_t*>(Q), static_cast<const bf16_t*>(K), Hq, Hkv, P, scale_log2, stats, prompt_len, scores);
 }
 
 template <typename T, int D>
-static void launch_scores(const void* Q, const void* K, int B, int Hq, int Hkv, int P, float* scores, float2* stats,
-                          hipStream_t st) {
+static void launch_scores(const void* Q, const void* K, int B, int Hq, int Hkv, int P, const int32_t* prompt_len,
+                          float* scores, float2* stats, hipStream_t st) {
   const float scale_log2 = (float)(1.4426950408889634 / sqrt((double)D));
   const int tiles = (P + kTile - 1) / kTile;
   score_rowstats_kernel<T, D><<<dim3(tiles, B * Hq), kScThreads, 0, st>>>(
       static_cast<const T*>(Q), static_cast<const T*>(K), Hq, Hkv, P, scale_log2, stats);
   score_colsum_kernel<T, D><<<dim3(tiles, B * Hkv), kScThreads, 0, st>>>(
-      static_cast<const T*>(Q), static_cast<const T*>(K), Hq, Hkv, P, scale_log2, stats, scores);
+      static_cast<const T*>(Q), static_cast<const T*>(K), Hq, Hkv, P, scale_log2, stats, prompt_len, scores);
 }
 
 }  // namespace sqa
@@ -362,7 +366,15 @@ extern "C" size_t sqa_prefill_scores_workspace_bytes(int B, int Hq, int Hkv, int
 extern "C" sqa_status sqa_prefill_scores(const void* Q, const void* K, sqa_dtype dt,
                                          int B, int Hq, int Hkv, int P, int D,
                                          float* scores_out, void* workspace, size_t ws_bytes, void* stream) {
+  return sqa_prefill_scores_ex(Q, K, dt, B, Hq, Hkv, P, D, scores_out, workspace, ws_bytes, stream, nullptr);
+}
+
+extern "C" sqa_status sqa_prefill_scores_ex(const void* Q, const void* K, sqa_dtype dt,
+                                            int B, int Hq, int Hkv, int P, int D,
+                                            float* scores_out, void* workspace, size_t ws_bytes, void* stream,
+                                            const sqa_batch_opts* opts) {
   using namespace sqa;
+  const int32_t* plen = opts ? opts->prompt_len : nullptr;
   if (!Q || !K || !scores_out || !workspace) return SQA_ERR_NULL;
   if (dt != SQA_F32 && dt != SQA_BF16) return SQA_ERR_DTYPE;
   if (B < 1 || Hq < 1 || Hkv < 1 || P < 1 || Hq % Hkv != 0 || (D != 64 && D != 128)) return SQA_ERR_SHAPE;
@@ -372,11 +384,11 @@ extern "C" sqa_status sqa_prefill_scores(const void* Q, const void* K, sqa_dtype
   hipStream_t st = static_cast<hipStream_t>(stream);
   float2* stats = static_cast<float2*>(workspace);
   if (dt == SQA_F32) {
-    if (D == 64) launch_scores<float, 64>(Q, K, B, Hq, Hkv, P, scores_out, stats, st);
-    else launch_scores<float, 128>(Q, K, B, Hq, Hkv, P, scores_out, stats, st);
+    if (D == 64) launch_scores<float, 64>(Q, K, B, Hq, Hkv, P, plen, scores_out, stats, st);
+    else launch_scores<float, 128>(Q, K, B, Hq, Hkv, P, plen, scores_out, stats, st);
   } else {
-    if (D == 64) launch_scores<bf16_t, 64>(Q, K, B, Hq, Hkv, P, scores_out, stats, st);
-    else launch_scores_mfma(Q, K, B, Hq, Hkv, P, scores_out, stats, st);
+    if (D == 64) launch_scores<bf16_t, 64>(Q, K, B, Hq, Hkv, P, plen, scores_out, stats, st);
+    else launch_scores_mfma(Q, K, B, Hq, Hkv, P, plen, scores_out, stats, st);
   }
   SQA_HIP_CHECK(hipGetLastError());
   return SQA_OK;

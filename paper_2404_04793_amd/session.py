@@ -14,12 +14,14 @@ from . import workloads as W
 
 class Session:
     def __init__(self, wl: W.Workload, device="cuda:0", keep_prompt_q: bool = False, uniform_budget: bool = False,
-                 full_cache: bool = False, probe_tokens: Optional[int] = None, fused_probe: bool = False):
+                 full_cache: bool = False, probe_tokens: Optional[int] = None, fused_probe: bool = False,
+                 order: str = "evict_then_attend"):
         """probe_tokens: hidden-state rows per layer given to the probe (default: all B*P prompt tokens;
         a smaller number keeps the hidden states of the largest workloads within HBM).
         fused_probe: the probe runs inside the residual add that writes h_out (Sec. 3)."""
         self.wl, self.dev = wl, device
         self.fused_probe = fused_probe
+        self.opts = None if order == "evict_then_attend" else sqa.batch_opts(order=order)
         self.uniform_budget, self.full_cache = uniform_budget, full_cache
         self.u, self.mask = W.unit_dirs(wl), W.hh_mask(wl, device)
         L = wl.L
@@ -102,10 +104,11 @@ class Session:
             if per_layer:
                 for l in range(wl.L):
                     sqa.decode_step(self.q[t, l], self.k_new[t, l], self.v_new[t, l], wl.P + t, wl.policy, wl.n_sink,
-                                    self.caches, self.out[t, l], self.dec_ws_layer[l], layer0=l, n_layers=1)
+                                    self.caches, self.out[t, l], self.dec_ws_layer[l], layer0=l, n_layers=1,
+                                    opts=self.opts)
             else:
                 sqa.decode_step(self.q[t], self.k_new[t], self.v_new[t], wl.P + t, wl.policy, wl.n_sink,
-                                self.caches, self.out[t], self.dec_ws)
+                                self.caches, self.out[t], self.dec_ws, opts=self.opts)
 
     def run_pass(self):
         """The whole hot path once over this batch."""

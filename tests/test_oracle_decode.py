@@ -140,3 +140,86 @@ def test_probabilities_match_loop_softmax():
     out, prob = O.attend(q, K, V)
     want_out, want_p = _full_attention_loops(q[0], K, V)
     assert np.allclose(out[0], want_out, atol=1e-14) and np.allclose(prob[0], want_p, atol=1e-15)
+
+
+# -- the attend-then-evict variant ---------------------------------------------------
+
+AE = "attend_then_evict"
+
+
+@pytest.mark.parametrize("policy", O.POLICIES)
+def test_orders_agree_while_nothing_is_evicted(policy):
+    r = _rng(20)
+    P, S, g, D = 7, 4, 2, 4
+    K, V, q = r.standard_normal((P + S, D)), r.standard_normal((P + S, D)), r.standard_normal((S, g, D))
+    a = O.prefill_compress(K[:P], V[:P], r.random(P), P + S, policy)
+    b = {k: v.copy() for k, v in a.items()}
+    for t in range(S):
+        oa, a = O.decode_step(a, q[t], K[P + t], V[P + t], P + t, P + S, policy)
+        ob, b = O.decode_step(b, q[t], K[P + t], V[P + t], P + t, P + S, policy, order=AE)
+        assert np.array_equal(oa, ob) and np.array_equal(a["score"], b["score"]) and a["pos"].tolist() == b["pos"].tolist()
+
+
+def test_attend_then_evict_sliding_sees_one_more_token():
+    P, S, D, b = 15, 6, 4, 5
+    r = _rng(21)
+    K, V, q = r.standard_normal((P + S, D)), r.standard_normal((P + S, D)), r.standard_normal((S, 1, D))
+    c = O.prefill_compress(K[:P], V[:P], np.zeros(P), b, "sliding")
+    for t in range(S):
+        n = P + t + 1
+        out, c = O.decode_step(c, q[t], K[P + t], V[P + t], P + t, b, "sliding", order=AE)
+        want, _ = _full_attention_loops(q[t, 0], K[n - b - 1:n], V[n - b - 1:n])     # b kept + the new one
+        assert np.allclose(out[0], want, atol=1e-13)
+        assert c["pos"].tolist() == list(range(n - b, n))
+
+
+def test_attend_then_evict_streaming_kept_sets():
+    P, S, D, b = 20, 5, 4, 9
+    r = _rng(22)
+    K, V, q = r.standard_normal((P + S, D)), r.standard_normal((P + S, D)), r.standard_normal((S, 2, D))
+    c = O.prefill_compress(K[:P], V[:P], np.zeros(P), b, "streaming")
+    for t in range(S):
+        n = P + t + 1
+        out, c = O.decode_step(c, q[t], K[P + t], V[P + t], P + t, b, "streaming", order=AE)
+        seen = [0, 1, 2, 3] + list(range(n - 6, n))
+        for h in range(2):
+            want, _ = _full_attention_loops(q[t, h], K[seen], V[seen])
+            assert np.allclose(out[h], want, atol=1e-13)
+        assert c["pos"].tolist() == [0, 1, 2, 3] + list(range(n - 5, n))
+
+
+def test_attend_then_evict_h2o_uses_the_updated_scores():
+    """The victim is the worst non-recent token by the scores AFTER this step's
+    probabilities (recomputed here with the loop softmax) were added; the mass
+    kept + evicted grows by g per step."""
+    r = _rng(23)
+    P, S, D, b, g = 18, 9, 4, 8, 2
+    K, V = r.standard_normal((P + S, D)), r.standard_normal((P + S, D))
+    s0 = r.random(P)
+    c = O.prefill_compress(K[:P], V[:P], s0, b, "h2o")
+    hh, rec = b // 2, b - b // 2
+    evicted = s0.sum() - c["score"].sum()
+    for t in range(S):
+        q = r.standard_normal((g, D))
+        ps = c["pos"].tolist() + [P + t]
+        upd = dict(zip(ps, c["score"].tolist() + [0.0]))
+        for h in range(g):
+            _, pr = _full_attention_loops(q[h], K[ps], V[ps])
+            for x, w in zip(ps, pr):
+                upd[x] += w
+        out, c = O.decode_step(c, q, K[P + t], V[P + t], P + t, b, "h2o", order=AE)
+        gone = set(ps) - set(c["pos"].tolist())
+        assert len(gone) == 1
+        victim = gone.pop()
+        cand = sorted(ps)[: len(ps) - rec]
+        assert victim == min(cand, key=lambda x: (upd[x], -x))
+        evicted += upd[victim]
+        assert abs(c["score"].sum() + evicted - (s0.sum() + g * (t + 1))) < 1e-10
+        for x, sc in zip(c["pos"].tolist(), c["score"].tolist()):
+            assert abs(sc - upd[x]) < 1e-13
+
+
+def test_unknown_order_is_rejected():
+    c = O.new_cache(np.zeros((2, 4)), np.zeros((2, 4)))
+    with pytest.raises(ValueError):
+        O.decode_step(c, np.zeros((1, 4)), np.zeros(4), np.zeros(4), 2, 4, "sliding", order="evict_first")
