@@ -30,6 +30,20 @@ def test_struct_layout_matches_header():
     assert sqa.LayerCacheStruct.capacity.offset == 56 and sqa.LayerCacheStruct.budget.offset == 60
 
 
+def test_batch_opts_layout_and_validation():
+    assert C.sizeof(sqa.BatchOptsStruct) == 40 and sqa.BatchOptsStruct.order.offset == 32
+    lib = sqa._lib
+    p = C.c_void_p(0x1000)
+    lc = sqa.LayerCacheStruct(0x1000, 0x2000, 0x3000, 0x4000, 0x5000, 0x6000, 0x7000, 8, 4)
+    bad = sqa.BatchOptsStruct(None, None, None, None, 2)
+    base = [p, p, p, 1, 1, 1, 1, 128, -1, 2, 4, C.byref(lc), None, 1, p, C.c_void_p(0x1000), 1 << 20, None]
+    assert lib.sqa_decode_step_ex(*base, C.byref(bad)) == 4                       # unknown order
+    assert lib.sqa_decode_step_ex(*base, None) == 2                                # new_pos < 0 without per-sequence positions
+    assert lib.sqa_layer_importance_seq(p, p, 1, 1, 4, 64, None, 1, p, p, 1 << 20, None) == 1
+    assert lib.sqa_layer_importance_seq(p, p, 1, 1, 4, 64, p, 0, p, p, 1 << 20, None) == 2
+    assert lib.sqa_layer_importance_seq(p, p, 1, 1, 4, 64, p, 3, p, p, 16, None) == 6    # needs n_seq times the plain workspace
+
+
 def test_paper_worked_example_through_the_library():
     # Appendix A.2: 18 important / 14 unimportant layers, b_init 1000, p 0.3 -> 300 / 1544
     r = np.random.default_rng(0)
