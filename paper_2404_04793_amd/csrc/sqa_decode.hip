@@ -23,6 +23,11 @@
 // token under H2O (split units add 8 bytes of logit scratch per token and
 // head).  The only atomic is the arrival counter; it decides who merges, never
 // what is computed: results are bit-identical from run to run.
+// Short units (at most kWpuMaxSlots slots, when the call has enough of them)
+// are not shared by the 4 waves: each wave of the workgroup owns a unit of its
+// own and runs steps 0-4 alone, without a barrier.  A 4-wave pass over 64 rows
+// leaves most lanes idle on such a unit and ends in a merge that costs as much
+// as the streaming; one wave walks it 16 rows at a time with nothing to merge.
 #include "sqa_common.h"
 
 namespace sqa {
@@ -69,7 +74,9 @@ struct DecodeArgs {
     uint32_t unit_off;    // first unit number of the layer within the call
     uint32_t part_off;    // first partial record
     uint32_t logit_off;   // first logit (floats)
+    uint32_t wpu;         // 1: one wave per unit (a workgroup covers 4 units)
   } lay[SQA_MAX_LAYERS];
+  int lds_chunk_w;                     // row length of a wave's LDS logit buffer in one-wave-per-unit layers
 };
 
 // Data that one workgroup hands to another inside a launch (partial results,
@@ -124,11 +131,11 @@ __device__ __forceinline__ unsigned long long block_max64(unsigned long long v, 
 // is not yet in memory (or -1).
 __device__ __forceinline__ int pick_victim(const float* sc, const int32_t* posu, int hh, float mn, float leaver_score,
                                            int override_slot, int override_pos, unsigned long long* s_red64,
-                                           bool solo) {
+                                           bool solo, int t /*thread index among the nthr threads at work*/) {
   if (leaver_score <= mn) return -1;             // uniform over the block
   unsigned long long best = 0ull;                // (position + 1) << 32 | slot
   const int nthr = solo ? SQA_WAVE : kDecThreads;
-  for (int i = threadIdx.x; i < hh; i += nthr)
+  for (int i = t; i < hh; i += nthr)
     if (sc[i] == mn) {
       const int ps = i == override_slot ? override_pos : posu[i];
       const unsigned long long key = ((unsigned long long)(uint32_t)(ps + 1) << 32) | (uint32_t)i;
@@ -224,7 +231,6 @@ __global__ __launch_bounds__(kDecThreads, MF ? SQA_DEC_MF_WAVES : 1) SQA_DEC_OCC
   constexpr int LPR = ROWB / 16;                  // lanes per row
   constexpr int RPI = SQA_WAVE / LPR;             // rows per wave load
   constexpr int EPL = RowMath<T>::EPL;            // elements per lane
-  constexpr int ROWS_IT = kDecWaves * RPI;        // rows per workgroup per load
   constexpr int PREC = D + 2;                     // floats per partial record: acc[D], m, l
 
   extern __shared__ float s_logit[];              // H2O, unsplit units: [G][lds_chunk]
@@ -233,9 +239,12 @@ __global__ __launch_bounds__(kDecThreads, MF ? SQA_DEC_MF_WAVES : 1) SQA_DEC_OCC
   __shared__ float s_red[kDecWaves];
   __shared__ unsigned long long s_red64[kDecWaves];
   __shared__ int s_ctl[2];
-  __shared__ float s_ctlf[2];
+  __shared__ float s_ctlf[kDecWaves][2];
 
-  const int tid = threadIdx.x, lane = tid & (SQA_WAVE - 1), wave = tid / SQA_WAVE;
+  const int tid = threadIdx.x, lane = tid & (SQA_WAVE - 1);
+  // (the wave number is the same in all lanes: say so, or everything derived from it -- the unit a wave
+  // owns, its pointers, its length -- lands in vector registers and is loaded with vector loads)
+  const int wave = __builtin_amdgcn_readfirstlane(tid / SQA_WAVE);
   const int r = lane / LPR, c = lane % LPR;
 
   // ---- which work item -----------------------------------------------------
@@ -247,7 +256,19 @@ __global__ __launch_bounds__(kDecThreads, MF ? SQA_DEC_MF_WAVES : 1) SQA_DEC_OCC
   const int layer = a.order[lo];
   const unsigned local = blockIdx.x - (lo ? a.blk_end[lo - 1] : 0u);
   const int nsplit = (int)a.lay[layer].nsplit;
-  const int u = (int)(local / (unsigned)nsplit), chunk = (int)(local % (unsigned)nsplit);
+  // one wave per unit: the workgroup's waves own 4 consecutive units and never meet at a barrier
+  const bool wpu = !MF && a.lay[layer].wpu != 0;
+  const int u = wpu ? (int)local * kDecWaves + wave : (int)(local / (unsigned)nsplit);
+  const int chunk = wpu ? 0 : (int)(local % (unsigned)nsplit);
+  if (wpu && u >= a.B * a.Hkv) return;
+  const int nw = wpu ? 1 : kDecWaves;             // waves that share the unit
+  const int wv = wpu ? 0 : wave;                  // this wave's place among them
+  const int wq = wpu ? wave : 0;                  // where the unit's final softmax statistics and scalars live in LDS
+  const int tix = wpu ? lane : tid;               // this thread's place among the unit's threads
+  const int nthr0 = wpu ? SQA_WAVE : kDecThreads;
+  const int rows_it = nw * RPI;                   // rows per load of all the unit's waves
+  const int lp = wpu ? a.lds_chunk_w : a.lds_chunk;          // LDS logit row length
+  float* s_lg = s_logit + (wpu ? wave * G * a.lds_chunk_w : 0);
   const int bidx = u / a.Hkv, kvh = u % a.Hkv;
   const sqa_layer_cache L = a.layers[layer];
   const int cap = L.capacity;
@@ -285,13 +306,13 @@ __global__ __launch_bounds__(kDecThreads, MF ? SQA_DEC_MF_WAVES : 1) SQA_DEC_OCC
   if constexpr (!MF) {
 #pragma unroll
     for (int uu = 0; uu < kUnroll; ++uu) {
-      slot[uu] = c0 + uu * ROWS_IT + wave * RPI + r;
+      slot[uu] = c0 + uu * rows_it + wv * RPI + r;
       const int sl = min(slot[uu], cap - 1);
       kf[uu] = ld16_nt(Kb + (int64_t)sl * ROWB + c * 16);
       vf[uu] = ld16_nt(Vb + (int64_t)sl * ROWB + c * 16);
     }
   }
-  const float sc_pre = H2O ? sc[min(tid, cap - 1)] : 0.f;
+  const float sc_pre = H2O ? sc[min(tix, cap - 1)] : 0.f;
 
   // ---- 0. where does the new token go, who leaves -------------------------
   if (sits_out) return;                           // the sequence takes no part in this step (every chunk agrees)
@@ -301,8 +322,8 @@ __global__ __launch_bounds__(kDecThreads, MF ? SQA_DEC_MF_WAVES : 1) SQA_DEC_OCC
   const bool bad_cap = !bad_budget && !bad_state && len < budget && len >= cap;
   if (bad_budget || bad_state || bad_cap) {       // same verdict in every chunk of the unit
     if (chunk == 0) {
-      for (int i = tid; i < G * D; i += kDecThreads) reinterpret_cast<T*>(outp)[i] = T{};
-      if (tid == 0) *a.status = bad_budget ? SQA_ERR_BUDGET : (bad_state ? SQA_ERR_STATE : SQA_ERR_CAPACITY);
+      for (int i = tix; i < G * D; i += nthr0) reinterpret_cast<T*>(outp)[i] = T{};
+      if (tix == 0) *a.status = bad_budget ? SQA_ERR_BUDGET : (bad_state ? SQA_ERR_STATE : SQA_ERR_CAPACITY);
     }
     return;
   }
@@ -323,9 +344,9 @@ __global__ __launch_bounds__(kDecThreads, MF ? SQA_DEC_MF_WAVES : 1) SQA_DEC_OCC
       moved_to = hint;
     } else {                                      // no decision carried over: take it now
       float mn = INFINITY;
-      for (int i = tid; i < hh; i += kDecThreads) mn = fminf(mn, sc[i]);
-      mn = block_min(mn, s_red, false);
-      moved_to = pick_victim(sc, posu, hh, mn, sc[slot_wr], -1, 0, s_red64, false);
+      for (int i = tix; i < hh; i += nthr0) mn = fminf(mn, sc[i]);
+      mn = block_min(mn, s_red, wpu);
+      moved_to = pick_victim(sc, posu, hh, mn, sc[slot_wr], -1, 0, s_red64, wpu, tix);
     }
   }
   // the ring leaver's score and position, needed in step 3 if it moves
@@ -425,7 +446,7 @@ __global__ __launch_bounds__(kDecThreads, MF ? SQA_DEC_MF_WAVES : 1) SQA_DEC_OCC
         mx = fmaxf(mx, d);
         if (H2O && valid && hd < G) {
           if (glogit) st_agent(&glogit[(int64_t)hd * lpitch + tok], d);
-          else s_logit[hd * a.lds_chunk + tok] = d;
+          else s_lg[hd * lp + tok] = d;
         }
       }
       mx = fmaxf(mx, __shfl_xor(mx, 16, SQA_WAVE));
@@ -497,11 +518,11 @@ __global__ __launch_bounds__(kDecThreads, MF ? SQA_DEC_MF_WAVES : 1) SQA_DEC_OCC
       }
     }
 
-    for (int base = c0; base < c_end; base += ROWS_IT * kUnroll) {
+    for (int base = c0; base < c_end; base += rows_it * kUnroll) {
       if (base != c0) {
 #pragma unroll
         for (int uu = 0; uu < kUnroll; ++uu) {
-          slot[uu] = base + uu * ROWS_IT + wave * RPI + r;
+          slot[uu] = base + uu * rows_it + wv * RPI + r;
           const int sl = min(slot[uu], n - 1);
           const char* kp = Kb + (int64_t)sl * ROWB;
           const char* vp = Vb + (int64_t)sl * ROWB;
@@ -522,7 +543,7 @@ __global__ __launch_bounds__(kDecThreads, MF ? SQA_DEC_MF_WAVES : 1) SQA_DEC_OCC
           s[uu][g] = d;
           if (H2O && c == 0 && valid) {
             if (glogit) st_agent(&glogit[(int64_t)g * lpitch + slot[uu]], d);
-            else s_logit[g * a.lds_chunk + slot[uu]] = d;
+            else s_lg[g * lp + slot[uu]] = d;
           }
         }
 #pragma unroll
@@ -571,19 +592,18 @@ __global__ __launch_bounds__(kDecThreads, MF ? SQA_DEC_MF_WAVES : 1) SQA_DEC_OCC
       }
     }
   }
-  __syncthreads();
+  if (!wpu) __syncthreads();
   float* part = nsplit > 1 ? a.part + ((int64_t)a.lay[layer].part_off + (int64_t)u * nsplit) * G * PREC : nullptr;
-  // one lane group per query head: merge the 4 waves
-  for (int g = wave * RPI + r; g < G; g += kDecWaves * RPI) {
+  // one lane group per query head: merge the unit's waves (all 4, or just this one)
+  const int w_lo = wpu ? wave : 0, w_hi = wpu ? wave + 1 : kDecWaves;
+  for (int g = wv * RPI + r; g < G; g += nw * RPI) {
     float mx = -INFINITY;
-#pragma unroll
-    for (int w = 0; w < kDecWaves; ++w) mx = fmaxf(mx, s_m[w][g]);
+    for (int w = w_lo; w < w_hi; ++w) mx = fmaxf(mx, s_m[w][g]);
     const float ms = mx == -INFINITY ? 0.f : mx;  // an empty chunk has nothing
     float lt = 0.f, o[EPL];
 #pragma unroll
     for (int e = 0; e < EPL; ++e) o[e] = 0.f;
-#pragma unroll
-    for (int w = 0; w < kDecWaves; ++w) {
+    for (int w = w_lo; w < w_hi; ++w) {
       const float f = fast_exp2(s_m[w][g] - ms);
       lt += s_l[w][g] * f;
 #pragma unroll
@@ -594,7 +614,7 @@ __global__ __launch_bounds__(kDecThreads, MF ? SQA_DEC_MF_WAVES : 1) SQA_DEC_OCC
 #pragma unroll
       for (int e = 0; e < EPL; ++e) o[e] *= inv;
       RowMath<T>::store(outp + (int64_t)g * ROWB + c * 16, o);
-      if (c == 0) { s_m[0][g] = mx; s_l[0][g] = inv; }
+      if (c == 0) { s_m[wq][g] = mx; s_l[wq][g] = inv; }
     } else {
       float* rec_p = part + ((int64_t)chunk * G + g) * PREC;
 #pragma unroll
@@ -639,17 +659,18 @@ __global__ __launch_bounds__(kDecThreads, MF ? SQA_DEC_MF_WAVES : 1) SQA_DEC_OCC
   // its registers until its last store is acknowledged, so for an unsplit unit
   // waves 1-3 leave here and wave 0 finishes alone: three quarters of the
   // workgroup's registers are free for the next workgroup while the tail runs.
-  __syncthreads();                                // every wave is done reading the cache rows and writing LDS
+  if (!wpu) __syncthreads();                      // every wave is done reading the cache rows and writing LDS
   const bool solo = nsplit == 1;
-  if (solo && wave != 0) return;
+  if (solo && !wpu && wave != 0) return;
   const int nthr = solo ? SQA_WAVE : kDecThreads;
+  const int tq = solo ? lane : tid;               // this thread's place among the nthr threads still at work
   int next_hint = ae ? -2 : -1;
   const int head_next = full ? (head + 1 == rec ? 0 : head + 1) : head;
   int victim = -1;                                // attend-then-evict: heavy slot evicted in this step (-1: the leaver)
   if (H2O) {
     float fm[G], fi[G];
 #pragma unroll
-    for (int g = 0; g < G; ++g) { fm[g] = s_m[0][g]; fi[g] = s_l[0][g]; }
+    for (int g = 0; g < G; ++g) { fm[g] = s_m[wq][g]; fi[g] = s_l[wq][g]; }
     // the heavy region competes with: the NEXT ring leaver for the next step's decision (evict-then-attend),
     // or this step's ring leaver right now (attend-then-evict)
     const bool decide = ae ? full : n == budget;
@@ -657,12 +678,12 @@ __global__ __launch_bounds__(kDecThreads, MF ? SQA_DEC_MF_WAVES : 1) SQA_DEC_OCC
     const bool virt = ae && full;                 // the new token has no slot of its own yet
     float mn = INFINITY;
     constexpr int SB = 4;                         // scores requested together: one round trip per SB tokens
-    for (int i0 = tid; i0 < n; i0 += SB * nthr) {
+    for (int i0 = tq; i0 < n; i0 += SB * nthr) {
       float cur[SB];
 #pragma unroll
       for (int k = 0; k < SB; ++k) {
         const int i = i0 + k * nthr;
-        cur[k] = (k == 0 && i0 == tid) ? sc_pre : sc[min(i, rmax)];   // each thread's first score came with the start
+        cur[k] = (k == 0 && i0 == tq) ? sc_pre : sc[min(i, rmax)];   // each thread's first score came with the start
       }
 #pragma unroll
       for (int k = 0; k < SB; ++k) {
@@ -671,29 +692,29 @@ __global__ __launch_bounds__(kDecThreads, MF ? SQA_DEC_MF_WAVES : 1) SQA_DEC_OCC
           float p = 0.f;
 #pragma unroll
           for (int g = 0; g < G; ++g) {
-            const float lg = glogit ? ld_agent(&glogit[(int64_t)g * lpitch + i]) : s_logit[g * a.lds_chunk + i];
+            const float lg = glogit ? ld_agent(&glogit[(int64_t)g * lpitch + i]) : s_lg[g * lp + i];
             p += fast_exp2(lg - fm[g]) * fi[g];
           }
           const float old = i == slot_new ? 0.f : (i == moved_to ? leaver_score : cur[k]);
           const float nv = old + p;
-          if (virt && i == slot_new) s_ctlf[1] = nv;   // stored in step 4, once its slot is free
+          if (virt && i == slot_new) s_ctlf[wq][1] = nv;   // stored in step 4, once its slot is free
           else sc[i] = nv;
           if (i < hh) mn = fminf(mn, nv);
-          if (i == leaver_slot) s_ctlf[0] = nv;
+          if (i == leaver_slot) s_ctlf[wq][0] = nv;
         }
       }
     }
     if (decide) {
       mn = block_min(mn, s_red, solo);            // (the barrier inside also orders the s_ctlf writes)
       // positions as they will be after step 4: the moved token brings its own
-      const int v = pick_victim(sc, posu, hh, mn, s_ctlf[0], moved_to, leaver_pos, s_red64, solo);
+      const int v = pick_victim(sc, posu, hh, mn, s_ctlf[wq][0], moved_to, leaver_pos, s_red64, solo, tq);
       if (ae) {
         // Apply it now.  Each score is rewritten by the thread that wrote it
         // above (slot i belongs to thread i mod nthr), so the two writes to one
         // address are ordered by that thread's program order.
         victim = v;
-        if (victim >= 0 && tid == victim % nthr) sc[victim] = s_ctlf[0];
-        if (tid == slot_wr % nthr) sc[slot_wr] = s_ctlf[1];
+        if (victim >= 0 && tq == victim % nthr) sc[victim] = s_ctlf[wq][0];
+        if (tq == slot_wr % nthr) sc[slot_wr] = s_ctlf[wq][1];
       } else {
         next_hint = v;
       }
@@ -702,7 +723,7 @@ __global__ __launch_bounds__(kDecThreads, MF ? SQA_DEC_MF_WAVES : 1) SQA_DEC_OCC
   const int dst = ae ? victim : moved_to;         // heavy slot that takes over the ring leaver's row
 
   // ---- 4. the cache update: moved row, new token, bookkeeping ---------------
-  if (wave == 0 && r == 0) {
+  if ((wpu || wave == 0) && r == 0) {
     char* Kw = const_cast<char*>(Kb);
     char* Vw = const_cast<char*>(Vb);
     if (dst >= 0) {
@@ -754,7 +775,9 @@ constexpr size_t kStatusBytes = 256;
 
 // How one call is cut into work items and where its scratch lives.
 struct DecodePlan {
-  int lds_chunk;                                   // longest unsplit unit (slots)
+  int lds_chunk;                                   // longest unsplit unit shared by 4 waves (slots)
+  int lds_chunk_w;                                 // longest one-wave unit (slots)
+  uint8_t wpu[SQA_MAX_LAYERS];                     // one wave per unit in this layer
   uint16_t nsplit[SQA_MAX_LAYERS];
   uint32_t chunk[SQA_MAX_LAYERS];
   uint32_t unit_off[SQA_MAX_LAYERS], part_off[SQA_MAX_LAYERS], logit_off[SQA_MAX_LAYERS];
@@ -772,8 +795,13 @@ static size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 // the number of equal chunks nearest to that.
 constexpr int64_t kMinItems = 256 * 8;
 constexpr int kMaxUnsplit = 8192;
+// One wave per unit: for units of at most kWpuMaxSlots slots, in calls that have at least kWpuMinUnits
+// units (one wave walks a unit 16 rows at a time, so the call needs many units to keep the chip's wave
+// slots filled).  Not for the matrix-core variant, whose tiles are 32 tokens per wave already.
+constexpr int kWpuMaxSlots = 256;
+constexpr int64_t kWpuMinUnits = 4096;
 static sqa_status plan_decode(const sqa_layer_cache* layers, int n_layers, int B, int Hq, int Hkv, int D, bool h2o,
-                              DecodePlan* p) {
+                              bool allow_wpu, DecodePlan* p) {
   const int64_t units = (int64_t)B * Hkv;
   const int g = Hq / Hkv;
   int64_t tokens = 0;
@@ -795,6 +823,10 @@ static sqa_status plan_decode(const sqa_layer_cache* layers, int n_layers, int B
 #endif
   uint64_t blocks = 0, n_units = 0, n_part = 0, n_logit = 0;
   p->lds_chunk = 64;
+  p->lds_chunk_w = 64;
+#ifdef SQA_DEC_NO_WPU
+  allow_wpu = false;
+#endif
   for (int i = 0; i < n_layers; ++i) {
     // + 1: under attend-then-evict a full unit attends budget + 1 tokens
     const int nmax = (layers[i].budget < layers[i].capacity ? layers[i].budget : layers[i].capacity) + 1;
@@ -806,12 +838,14 @@ static sqa_status plan_decode(const sqa_layer_cache* layers, int n_layers, int B
     if (ns > 65535) return SQA_ERR_CAPACITY;
     p->nsplit[i] = (uint16_t)ns;
     p->chunk[i] = (uint32_t)ch;
-    if (ns == 1 && ch > p->lds_chunk) p->lds_chunk = (int)ch;
+    p->wpu[i] = allow_wpu && ns == 1 && nmax <= kWpuMaxSlots && units * n_layers >= kWpuMinUnits;
+    if (p->wpu[i]) { if (ch > p->lds_chunk_w) p->lds_chunk_w = (int)ch; }
+    else if (ns == 1 && ch > p->lds_chunk) p->lds_chunk = (int)ch;
     p->unit_off[i] = (uint32_t)n_units;
     p->part_off[i] = (uint32_t)n_part;
     p->logit_off[i] = (uint32_t)n_logit;
     n_units += units;
-    blocks += units * ns;
+    blocks += p->wpu[i] ? (units + kDecWaves - 1) / kDecWaves : units * ns;
     if (ns > 1) {
       n_part += units * ns;
       if (h2o) n_logit += units * g * ((uint64_t)layers[i].capacity + 1);
@@ -835,7 +869,7 @@ extern "C" size_t sqa_decode_workspace_bytes(const sqa_layer_cache* layers, int 
   if (!layers || n_layers < 1 || n_layers > SQA_MAX_LAYERS || B < 1 || Hq < 1 || Hkv < 1 || Hq % Hkv != 0 || D < 1)
     return 0;
   sqa::DecodePlan p;
-  if (sqa::plan_decode(layers, n_layers, B, Hq, Hkv, D, policy == SQA_H2O, &p) != SQA_OK) return 0;
+  if (sqa::plan_decode(layers, n_layers, B, Hq, Hkv, D, policy == SQA_H2O, false, &p) != SQA_OK) return 0;
   return p.bytes;
 }
 
@@ -899,12 +933,13 @@ extern "C" sqa_status sqa_decode_step_ex(const void* q, const void* k_new, const
     if (c.budget < min_budget) return SQA_ERR_BUDGET;
     if (c.capacity < 1) return SQA_ERR_CAPACITY;
   }
+  const bool mfma = dt == SQA_BF16 && D == 128 && g >= kMfmaMinGroup;
   DecodePlan plan;
-  const sqa_status ps = plan_decode(layers, n_layers, B, Hq, Hkv, D, h2o, &plan);
+  const sqa_status ps = plan_decode(layers, n_layers, B, Hq, Hkv, D, h2o, !mfma, &plan);
   if (ps != SQA_OK) return ps;
   if (ws_bytes < plan.bytes) return SQA_ERR_CAPACITY;
-  const bool mfma = dt == SQA_BF16 && D == 128 && g >= kMfmaMinGroup;
-  const size_t lds = (h2o ? (size_t)g * plan.lds_chunk * sizeof(float) : 0) +
+  const size_t lds_shared = (size_t)g * plan.lds_chunk, lds_waves = (size_t)kDecWaves * g * plan.lds_chunk_w;
+  const size_t lds = (h2o ? (lds_shared > lds_waves ? lds_shared : lds_waves) * sizeof(float) : 0) +
                      (mfma ? (size_t)kDecWaves * kStageBytesPerWave : 0);
   if (lds > 64 * 1024)
     SQA_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void*>(fn), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
@@ -923,6 +958,7 @@ extern "C" sqa_status sqa_decode_step_ex(const void* q, const void* k_new, const
   a.budget_seq = opts ? opts->budget_seq : nullptr;
   a.ae = (opts && opts->order == SQA_ATTEND_THEN_EVICT) ? 1 : 0;
   a.lds_chunk = plan.lds_chunk;
+  a.lds_chunk_w = plan.lds_chunk_w;
   a.scale_log2 = (float)(1.4426950408889634 / sqrt((double)D));
   // long units first: layers in descending budget (stable)
   for (int i = 0; i < n_layers; ++i) a.order[i] = (uint8_t)i;
@@ -935,8 +971,9 @@ extern "C" sqa_status sqa_decode_step_ex(const void* q, const void* k_new, const
   uint64_t run = 0;
   for (int i = 0; i < n_layers; ++i) {
     const int l = a.order[i];
-    run += (uint64_t)B * Hkv * plan.nsplit[l];
+    run += plan.wpu[l] ? ((uint64_t)B * Hkv + kDecWaves - 1) / kDecWaves : (uint64_t)B * Hkv * plan.nsplit[l];
     a.blk_end[i] = (uint32_t)run;
+    a.lay[i].wpu = plan.wpu[i];
     a.lay[i].nsplit = plan.nsplit[i];
     a.lay[i].chunk = plan.chunk[i];
     a.lay[i].unit_off = plan.unit_off[i];
