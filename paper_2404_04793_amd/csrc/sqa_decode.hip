@@ -372,9 +372,14 @@ __global__ __launch_bounds__(kDecThreads, MF ? SQA_DEC_MF_WAVES : 1) SQA_DEC_OCC
     //                 contraction slot (j,e) <-> token 4j+e of the half.
     // So softmax statistics and the output accumulator live in the lanes of
     // their head and nothing is moved between lanes except two max/sum steps.
-    // K and V tiles pass through a wave-private 8.5 KiB LDS buffer whose rows are
-    // padded by 16 bytes, which keeps the row-wise writes and the K fragment
-    // reads free of bank conflicts.
+    // K and V tiles pass through a wave-private 8.5 KiB LDS buffer, one after the
+    // other.  The V tile has rows padded by 16 bytes (conflict-free for the
+    // transposing reads).  The K tile has 256-byte rows whose 16-byte pieces are
+    // XOR-swizzled with the row number: piece p of tile row R lies at piece
+    // p ^ (R & 15).  A fragment read takes 16 bytes from each of 16 different rows;
+    // with padded rows that ran at 30 cycles per wave instruction on this chip
+    // (4-way bank conflicts), swizzled it runs at 8.5, and the row-wise writes
+    // keep their 13.
     char* stage = reinterpret_cast<char*>(s_logit + (H2O ? G * a.lds_chunk : 0)) + wave * kStageBytesPerWave;
     const int hd = lane & 15, j4 = lane >> 4;
     bf16x8_t qfr[4];
@@ -390,8 +395,17 @@ __global__ __launch_bounds__(kDecThreads, MF ? SQA_DEC_MF_WAVES : 1) SQA_DEC_OCC
     float m_run = -INFINITY, l_run = 0.f;
     // LDS addresses of this lane (tile rows are kStageRow bytes apart, so every
     // other address below is one of these plus a compile-time constant)
-    char* st_wr = stage + r * kStageRow + c * 16;                       // row-wise writes: + 4i rows
-    const char* st_k = stage + hd * kStageRow + j4 * 64;                 // K fragment: + 16tt rows, + 16i bytes
+    char* st_wr = stage + r * kStageRow + c * 16;                       // V: row-wise writes: + 4i rows
+    // K, swizzled: write of row 4i+r, piece c -> + 1024i + kw[i&3]; fragment i of row 16tt+hd -> + 4096tt + kr[i]
+    int kw[4], kr[4];
+#pragma unroll
+    for (int x = 0; x < 4; ++x) {
+      kw[x] = r * 256 + (((c ^ r) * 16) ^ (64 * x));
+      kr[x] = hd * 256 + ((4 * j4) ^ (hd & 12)) * 16 + ((x ^ (hd & 3)) * 16);
+    }
+    auto k_patch = [&](int row, const uint4& val) {   // row of the tile, written by the 16 lanes whose r matches
+      if ((row & 3) == r) *reinterpret_cast<uint4*>(stage + row * 256 + ((c ^ (row & 15)) * 16)) = val;
+    };
     const char* st_v = stage + (4 * j4 + (hd >> 2)) * kStageRow + (hd & 3) * 8;   // V^T quadruple: + 16 rows, + 32db bytes
     // Registers hold a tile only between its load and its copy into LDS, so the
     // next tile's K (then V) is requested as soon as this tile's K (V) has been
@@ -418,11 +432,9 @@ __global__ __launch_bounds__(kDecThreads, MF ? SQA_DEC_MF_WAVES : 1) SQA_DEC_OCC
       uint4 km = make_uint4(0, 0, 0, 0), vm = km;
       if (has_moved) { km = ld16(Kb + (int64_t)slot_wr * ROWB + c * 16); vm = ld16(Vb + (int64_t)slot_wr * ROWB + c * 16); }
 #pragma unroll
-      for (int i = 0; i < 8; ++i) *reinterpret_cast<uint4*>(st_wr + 4 * i * kStageRow) = kreg[i];
-      if (has_moved && ((moved_to - base) & 3) == r)
-        *reinterpret_cast<uint4*>(st_wr + ((moved_to - base) >> 2) * 4 * kStageRow) = km;
-      if (has_new && ((slot_new - base) & 3) == r)
-        *reinterpret_cast<uint4*>(st_wr + ((slot_new - base) >> 2) * 4 * kStageRow) = kn_pre;
+      for (int i = 0; i < 8; ++i) *reinterpret_cast<uint4*>(stage + 1024 * i + kw[i & 3]) = kreg[i];
+      if (has_moved) k_patch(moved_to - base, km);
+      if (has_new) k_patch(slot_new - base, kn_pre);
       if (more) request_k(base + TSTEP);
       f32x4_t sacc[2];
 #pragma unroll
@@ -430,7 +442,7 @@ __global__ __launch_bounds__(kDecThreads, MF ? SQA_DEC_MF_WAVES : 1) SQA_DEC_OCC
         sacc[tt] = f32x4_t{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
-          const uint4 w = *reinterpret_cast<const uint4*>(st_k + 16 * tt * kStageRow + 16 * i);
+          const uint4 w = *reinterpret_cast<const uint4*>(stage + 4096 * tt + kr[i]);
           sacc[tt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, w), qfr[i], sacc[tt], 0, 0, 0);
         }
       }
