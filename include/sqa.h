@@ -59,6 +59,7 @@ typedef enum { SQA_SLIDING = 0, SQA_STREAMING = 1, SQA_H2O = 2 } sqa_policy;
 typedef enum { SQA_EVICT_THEN_ATTEND = 0, SQA_ATTEND_THEN_EVICT = 1 } sqa_order;
 
 enum { SQA_MAX_LAYERS = 128 };
+enum { SQA_ST_LEN = 0, SQA_ST_RING_HEAD = 1, SQA_ST_EVICT_HINT = 2, SQA_ST_WORDS = 4 };
 
 /*
  * One layer's compact KV cache ("K^(i)" of Algorithm 1 after C_seq).  All
@@ -80,13 +81,20 @@ typedef struct sqa_layer_cache {
   void* V;             /* [B][Hkv][capacity][D]                                    */
   float* score_acc;    /* [B][Hkv][capacity] accumulated attention (H2O; else may be NULL) */
   int32_t* pos;        /* [B][Hkv][capacity] token position per slot = kept_idx    */
-  int32_t* lens;       /* [B][Hkv] number of valid slots                           */
-  int32_t* ring_head;  /* [B][Hkv] offset of the oldest recent token in the ring   */
-  int32_t* evict_hint; /* [B][Hkv] H2O only (else may be NULL): the next eviction,
-                          decided at the end of the previous decode step: -1 = the
-                          token leaving the ring goes, s >= 0 = heavy slot s goes,
-                          -2 = not decided (sqa_prefill_compress writes this; write
-                          it too after editing a unit's scores, positions or budget) */
+  int32_t* unit_state; /* [B][Hkv][4], 16-byte aligned: one record per unit, read and
+                          written as one 16-byte access (a step that updated three
+                          separate words per unit paid for three small writes):
+                            [SQA_ST_LEN]        number of valid slots ("len")
+                            [SQA_ST_RING_HEAD]  offset of the oldest recent token in
+                                                the ring ("ring_head")
+                            [SQA_ST_EVICT_HINT] H2O: the next eviction, decided at the
+                                                end of the previous decode step: -1 =
+                                                the token leaving the ring goes, s >= 0
+                                                = heavy slot s goes, -2 = not decided
+                                                (sqa_prefill_compress writes this; write
+                                                it too after editing a unit's scores,
+                                                positions or budget) ("evict_hint")
+                            [3]                 reserved, written as 0              */
   int32_t capacity;    /* slots per unit; >= min(budget, longest length reached)   */
   int32_t budget;      /* b^(i): most tokens this layer keeps                      */
 } sqa_layer_cache;
@@ -197,7 +205,7 @@ sqa_status sqa_prefill_scores_ex(const void* Q, const void* K, sqa_dtype dt,
  *                 older ones, the floor(budget/2) with the largest attn_scores,
  *                 equal scores -> lowest position first;
  * and gathers their K, V rows (ascending position) into the layer cache,
- * filling pos, score_acc (H2O), lens, ring_head and evict_hint (-2).
+ * filling pos, score_acc (H2O) and unit_state (len, ring_head 0, evict_hint -2).
  *   K, V        : DEVICE [B][Hkv][P][D], dtype kv_dt; must not overlap the cache
  *   attn_scores : DEVICE float [B][Hkv][P], values >= 0, required for SQA_H2O
  *   layer       : HOST struct with DEVICE pointers; budget and capacity preset,
@@ -230,7 +238,7 @@ sqa_status sqa_prefill_compress_layers_ex(const void* const* K, const void* cons
  *      the lowest-scoring heavy hitter; equal scores evict the higher position);
  *   3. out[h] = softmax(q[h].K^T/sqrt(D)) V for the g query heads of the unit;
  *   4. H2O: score_acc[slot] += sum over those heads of the probability.
- * The cache (K, V, score_acc, pos, lens, ring_head, evict_hint) is updated in
+ * The cache (K, V, score_acc, pos, unit_state) is updated in
  * place; pos is the kept-index result.  Positions are consecutive: the prompt
  * holds 0..P-1 and every step's new_pos is the previous one plus 1.
  *   q            : DEVICE [n_layers][B][Hq][D], dtype dt

@@ -39,7 +39,7 @@ class SqaError(RuntimeError):
 class LayerCacheStruct(C.Structure):
     """Mirror of sqa_layer_cache."""
     _fields_ = [("K", C.c_void_p), ("V", C.c_void_p), ("score_acc", C.c_void_p), ("pos", C.c_void_p),
-                ("lens", C.c_void_p), ("ring_head", C.c_void_p), ("evict_hint", C.c_void_p),
+                ("unit_state", C.c_void_p),
                 ("capacity", C.c_int32), ("budget", C.c_int32)]
 
 
@@ -210,21 +210,22 @@ class LayerCaches:
                  dtype: torch.dtype, device, with_scores: bool = True):
         self.L, self.B, self.Hkv, self.D, self.dtype = len(budgets), B, Hkv, D, dtype
         self.budgets, self.capacities = list(budgets), list(capacities)
-        self.K, self.V, self.score, self.pos, self.lens, self.head, self.hint = [], [], [], [], [], [], []
+        self.K, self.V, self.score, self.pos, self.state = [], [], [], [], []
+        self.lens, self.head, self.hint = [], [], []        # views of the [B, Hkv, 4] unit_state records
         self.table = (LayerCacheStruct * self.L)()
         for i, (b, cap) in enumerate(zip(budgets, capacities)):
             self.K.append(torch.zeros(B, Hkv, cap, D, dtype=dtype, device=device))
             self.V.append(torch.zeros(B, Hkv, cap, D, dtype=dtype, device=device))
             self.score.append(torch.zeros(B, Hkv, cap, dtype=torch.float32, device=device) if with_scores else None)
             self.pos.append(torch.full((B, Hkv, cap), -1, dtype=torch.int32, device=device))
-            self.lens.append(torch.zeros(B, Hkv, dtype=torch.int32, device=device))
-            self.head.append(torch.zeros(B, Hkv, dtype=torch.int32, device=device))
-            self.hint.append(torch.full((B, Hkv), -2, dtype=torch.int32, device=device))
+            st = torch.zeros(B, Hkv, 4, dtype=torch.int32, device=device)
+            st[..., 2] = -2
+            self.state.append(st)
+            self.lens.append(st[..., 0]); self.head.append(st[..., 1]); self.hint.append(st[..., 2])
             t = self.table[i]
             t.K, t.V = self.K[i].data_ptr(), self.V[i].data_ptr()
             t.score_acc = self.score[i].data_ptr() if with_scores else None
-            t.pos, t.lens, t.ring_head = self.pos[i].data_ptr(), self.lens[i].data_ptr(), self.head[i].data_ptr()
-            t.evict_hint = self.hint[i].data_ptr()
+            t.pos, t.unit_state = self.pos[i].data_ptr(), self.state[i].data_ptr()
             t.capacity, t.budget = int(cap), int(b)
         raw = bytes(memoryview(self.table))
         self.table_dev = torch.frombuffer(bytearray(raw), dtype=torch.uint8).to(device)

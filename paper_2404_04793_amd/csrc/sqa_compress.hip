@@ -77,8 +77,7 @@ __global__ __launch_bounds__(kCmpThreads) void prefill_compress_kernel(
     const bool bad_len = P < 0 || P > P_pad, bad_budget = b < min_budget || b > L.budget;
     if (bad_len || bad_budget) {                           // leave the unit empty and say why
       if (tid == 0) {
-        L.lens[u] = 0; L.ring_head[u] = 0;
-        if (L.evict_hint) L.evict_hint[u] = -2;
+        *reinterpret_cast<int4*>(L.unit_state + (int64_t)u * SQA_ST_WORDS) = make_int4(0, 0, -2, 0);
         if (batch.status) *batch.status = bad_len ? SQA_ERR_SHAPE : SQA_ERR_BUDGET;
       }
       return;
@@ -183,7 +182,7 @@ __global__ __launch_bounds__(kCmpThreads) void prefill_compress_kernel(
     posu[j] = src;
     if (L.score_acc) L.score_acc[(int64_t)u * cap + j] = sc ? sc[src] : 0.f;
   }
-  if (tid == 0) { L.lens[u] = n_keep; L.ring_head[u] = 0; if (L.evict_hint) L.evict_hint[u] = -2; }
+  if (tid == 0) *reinterpret_cast<int4*>(L.unit_state + (int64_t)u * SQA_ST_WORDS) = make_int4(n_keep, 0, -2, 0);
 }
 
 // out[rank of pos[i]] = pos[i]; -1 beyond len.  Rank by counting (a test view, O(n^2)).
@@ -191,7 +190,7 @@ __global__ __launch_bounds__(kCmpThreads) void kept_idx_sorted_kernel(sqa_layer_
   extern __shared__ uint32_t s_mem[];
   int* s_pos = reinterpret_cast<int*>(s_mem);
   const int u = blockIdx.x, cap = L.capacity;
-  int len = L.lens[u];
+  int len = L.unit_state[(int64_t)u * SQA_ST_WORDS + SQA_ST_LEN];
   len = len < 0 ? 0 : (len > cap ? cap : len);
   const int32_t* posu = L.pos + (int64_t)u * cap;
   int32_t* o = out + (int64_t)u * cap;
@@ -220,9 +219,9 @@ static sqa_status check_compress_layer(const void* K, const void* V, sqa_dtype k
                                        const sqa_layer_cache& L, bool ragged, size_t* lds_out) {
   if (!K || !V) return SQA_ERR_NULL;
   if (policy == SQA_H2O && !attn_scores) return SQA_ERR_NULL;
-  if (!L.K || !L.V || !L.pos || !L.lens || !L.ring_head) return SQA_ERR_NULL;
+  if (!L.K || !L.V || !L.pos || !L.unit_state) return SQA_ERR_NULL;
   if (policy == SQA_H2O && !L.score_acc) return SQA_ERR_NULL;
-  if (!aligned16(K) || !aligned16(V) || !aligned16(L.K) || !aligned16(L.V)) return SQA_ERR_SHAPE;
+  if (!aligned16(K) || !aligned16(V) || !aligned16(L.K) || !aligned16(L.V) || !aligned16(L.unit_state)) return SQA_ERR_SHAPE;
   const int min_budget = policy == SQA_H2O ? 2 : (policy == SQA_STREAMING ? n_sink + 1 : 1);
   if (L.budget < min_budget) return SQA_ERR_BUDGET;
   const int n_keep = P < L.budget ? P : L.budget;
@@ -318,7 +317,7 @@ extern "C" sqa_status sqa_prefill_compress(const void* K, const void* V, sqa_dty
 
 extern "C" sqa_status sqa_kept_idx_sorted(const sqa_layer_cache* layer, int B, int Hkv, int32_t* out, void* stream) {
   using namespace sqa;
-  if (!layer || !out || !layer->pos || !layer->lens) return SQA_ERR_NULL;
+  if (!layer || !out || !layer->pos || !layer->unit_state) return SQA_ERR_NULL;
   if (B < 1 || Hkv < 1 || (int64_t)B * Hkv > INT32_MAX) return SQA_ERR_SHAPE;
   if (layer->capacity < 1) return SQA_ERR_CAPACITY;
   const size_t lds = (size_t)layer->capacity * sizeof(int32_t);

@@ -293,9 +293,10 @@ __global__ __launch_bounds__(kDecThreads, MF ? SQA_DEC_MF_WAVES : 1) SQA_DEC_OCC
   // that one memory round trip covers the bookkeeping words, q, the new token's
   // rows, the first rows of the chunk (read as they lie in memory; the two
   // slots the step rewrites are patched below) and the first scores.
-  const int len = L.lens[u];
-  const int head = L.ring_head[u];
-  const int hint = H2O ? L.evict_hint[u] : -1;
+  const int4 ust = *reinterpret_cast<const int4*>(L.unit_state + (int64_t)u * SQA_ST_WORDS);   // one 16-byte record
+  const int len = ust.x;
+  const int head = ust.y;
+  const int hint = H2O ? ust.z : -1;
   uint4 qf[G];
 #pragma unroll
   for (int g = 0; g < G; ++g)
@@ -750,9 +751,8 @@ __global__ __launch_bounds__(kDecThreads, MF ? SQA_DEC_MF_WAVES : 1) SQA_DEC_OCC
       int32_t* posw = L.pos + (int64_t)u * cap;
       if (dst >= 0) posw[dst] = posw[slot_wr];
       posw[slot_wr] = a.new_pos_seq ? a.new_pos_seq[bidx] : a.new_pos;   // (read again: not kept in a register all along)
-      L.lens[u] = full ? budget : len + 1;
-      if (full) L.ring_head[u] = head_next;
-      if (H2O) L.evict_hint[u] = next_hint;
+      *reinterpret_cast<int4*>(L.unit_state + (int64_t)u * SQA_ST_WORDS) =
+          make_int4(full ? budget : len + 1, head_next, H2O ? next_hint : -2, 0);
     }
   }
 }
@@ -939,9 +939,9 @@ extern "C" sqa_status sqa_decode_step_ex(const void* q, const void* k_new, const
   const int min_budget = h2o ? 2 : (policy == SQA_STREAMING ? n_sink + 1 : 1);
   for (int i = 0; i < n_layers; ++i) {
     const sqa_layer_cache& c = layers[i];
-    if (!c.K || !c.V || !c.pos || !c.lens || !c.ring_head) return SQA_ERR_NULL;
-    if (h2o && (!c.score_acc || !c.evict_hint)) return SQA_ERR_NULL;
-    if (!aligned16(c.K) || !aligned16(c.V)) return SQA_ERR_SHAPE;
+    if (!c.K || !c.V || !c.pos || !c.unit_state) return SQA_ERR_NULL;
+    if (h2o && !c.score_acc) return SQA_ERR_NULL;
+    if (!aligned16(c.K) || !aligned16(c.V) || !aligned16(c.unit_state)) return SQA_ERR_SHAPE;
     if (c.budget < min_budget) return SQA_ERR_BUDGET;
     if (c.capacity < 1) return SQA_ERR_CAPACITY;
   }
