@@ -79,6 +79,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=1)
     ap.add_argument("--workload", default="llama2_7b")
     ap.add_argument("--per-layer", action="store_true", help="one decode launch per layer instead of one per step")
+    ap.add_argument("--graph", action="store_true",
+                    help="replay each decode step from a HIP graph recorded once (inputs copied into fixed buffers, "
+                         "positions read from a device array); meant for --per-layer, where launches dominate")
     ap.add_argument("--uniform", action="store_true", help="sequence-only baseline: same budget in every layer")
     ap.add_argument("--full-cache", action="store_true", help="no compression (budget = P + S)")
     ap.add_argument("--policy", default=None, choices=["h2o", "streaming", "sliding"],
@@ -123,6 +126,14 @@ def main():
     sess = Session(wl, "cuda:0", uniform_budget=args.uniform, full_cache=args.full_cache,
                    probe_tokens=args.probe_tokens, fused_probe=args.fused_probe, order=args.order)
 
+    def do_decode():
+        if args.graph:
+            if getattr(sess, "graph", None) is None:
+                sess.capture_step_graph(per_layer=args.per_layer)     # during the first (warm-up) pass
+            sess.decode_graph()
+        else:
+            sess.decode(per_layer=args.per_layer)
+
     def one_pass(ev=None):
         if ev:
             ev[0].record()
@@ -132,7 +143,7 @@ def main():
         sess.compress_prompt()
         if ev:
             ev[2].record()
-        sess.decode(per_layer=args.per_layer)
+        do_decode()
         if ev:
             ev[3].record()
         return cos
@@ -145,7 +156,7 @@ def main():
             t_a = time.perf_counter()
             if ev:
                 ev[0].record(); ev[1].record(); ev[2].record()
-            sess.decode(per_layer=args.per_layer)
+            do_decode()
             if ev:
                 ev[3].record()
             torch.cuda.synchronize()
@@ -187,7 +198,7 @@ def main():
     achieved = bytes_launch / launch_s / 1e9
     tokens = wl.B * wl.S * args.steps
     mode = "full_cache" if args.full_cache else ("uniform" if args.uniform else "squeeze")
-    launch = "per_layer" if args.per_layer else "all_layers"
+    launch = ("per_layer" if args.per_layer else "all_layers") + ("_graph" if args.graph else "")
     res = {
         "metric": "decode tokens/s + achieved HBM GB/s (attn+evict), 7B shape, 1 GPU",
         "value": tokens / dt, "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,

@@ -18,7 +18,9 @@
  *     until the work enqueued on `stream` has finished; "HOST" pointers are
  *     ordinary host memory read or written before the call returns.
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
- *   - The library allocates no device memory and keeps no global state; scratch
+ *   - The library allocates no device memory and keeps no state between calls
+ *     (apart from remembering which kernels it has already allowed to use
+ *     more than 64 KiB of on-chip memory on a device); scratch
  *     space comes in through `workspace` (DEVICE, 256-byte aligned), whose
  *     minimum size the matching *_workspace_bytes call returns.
  *   - Arguments are validated on the host before any HIP call is made; on an
@@ -282,7 +284,8 @@ sqa_status sqa_decode_step_ex(const void* q, const void* k_new, const void* v_ne
                               void* out, void* workspace, size_t ws_bytes, void* stream,
                               const sqa_batch_opts* opts);
 
-/* Zeroes the status word (enqueued on stream). */
+/* Zeroes the status word (a small fill kernel enqueued on stream; like
+ * sqa_decode_workspace_init it uses no memset, so both may be recorded into a HIP graph). */
 sqa_status sqa_clear_device_status(void* workspace, void* stream);
 /* Waits for `stream`, then copies the status word to *status_out (HOST). */
 sqa_status sqa_read_device_status(const void* workspace, void* stream, int32_t* status_out);

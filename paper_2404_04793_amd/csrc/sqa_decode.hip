@@ -28,6 +28,9 @@
 // own and runs steps 0-4 alone, without a barrier.  A 4-wave pass over 64 rows
 // leaves most lanes idle on such a unit and ends in a merge that costs as much
 // as the streaming; one wave walks it 16 rows at a time with nothing to merge.
+#include <map>
+#include <mutex>
+#include <utility>
 #include "sqa_common.h"
 
 namespace sqa {
@@ -785,6 +788,22 @@ static decode_fn pick(sqa_dtype dt, int d, int g, bool h2o) {
 
 constexpr size_t kStatusBytes = 256;
 
+// A kernel needs a one-time opt-in per device before a launch may ask for more than 64 KiB of dynamic
+// LDS.  Remembered per (device, kernel) so that the steady state makes no runtime call for it.
+static hipError_t allow_dynamic_lds(const void* fn, size_t bytes) {
+  static std::mutex mu;
+  static std::map<std::pair<int, const void*>, size_t> granted;
+  int dev = 0;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  std::lock_guard<std::mutex> lock(mu);
+  size_t& g = granted[std::make_pair(dev, fn)];
+  if (g >= bytes) return hipSuccess;
+  e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
+  if (e == hipSuccess) g = bytes;
+  return e;
+}
+
 // How one call is cut into work items and where its scratch lives.
 struct DecodePlan {
   int lds_chunk;                                   // longest unsplit unit shared by 4 waves (slots)
@@ -885,16 +904,33 @@ extern "C" size_t sqa_decode_workspace_bytes(const sqa_layer_cache* layers, int 
   return p.bytes;
 }
 
+namespace sqa {
+// Zero fill by a kernel rather than hipMemsetAsync: callers may record these calls into a HIP graph, and
+// memset nodes have replayed wrongly on this platform.
+__global__ __launch_bounds__(256) void zero_fill_kernel(uint32_t* __restrict__ p, size_t n_words) {
+  for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n_words; i += (size_t)gridDim.x * 256) p[i] = 0u;
+}
+static sqa_status zero_fill(void* p, size_t bytes, hipStream_t st) {
+  const size_t n_words = bytes / 4;
+  if (n_words == 0) return SQA_OK;
+  size_t blocks = (n_words + 255) / 256;
+  if (blocks > 4096) blocks = 4096;
+  zero_fill_kernel<<<(unsigned)blocks, 256, 0, st>>>(static_cast<uint32_t*>(p), n_words);
+  SQA_HIP_CHECK(hipGetLastError());
+  return SQA_OK;
+}
+}  // namespace sqa
+
 extern "C" sqa_status sqa_decode_workspace_init(void* workspace, size_t ws_bytes, void* stream) {
   if (!workspace) return SQA_ERR_NULL;
-  SQA_HIP_CHECK(hipMemsetAsync(workspace, 0, ws_bytes, static_cast<hipStream_t>(stream)));
-  return SQA_OK;
+  if (reinterpret_cast<uintptr_t>(workspace) & 3u) return SQA_ERR_SHAPE;
+  return sqa::zero_fill(workspace, ws_bytes, static_cast<hipStream_t>(stream));   // (sizes are multiples of 256)
 }
 
 extern "C" sqa_status sqa_clear_device_status(void* workspace, void* stream) {
   if (!workspace) return SQA_ERR_NULL;
-  SQA_HIP_CHECK(hipMemsetAsync(workspace, 0, sizeof(int32_t), static_cast<hipStream_t>(stream)));
-  return SQA_OK;
+  if (reinterpret_cast<uintptr_t>(workspace) & 3u) return SQA_ERR_SHAPE;
+  return sqa::zero_fill(workspace, sizeof(int32_t), static_cast<hipStream_t>(stream));
 }
 
 extern "C" sqa_status sqa_read_device_status(const void* workspace, void* stream, int32_t* status_out) {
@@ -953,8 +989,8 @@ extern "C" sqa_status sqa_decode_step_ex(const void* q, const void* k_new, const
   const size_t lds_shared = (size_t)g * plan.lds_chunk, lds_waves = (size_t)kDecWaves * g * plan.lds_chunk_w;
   const size_t lds = (h2o ? (lds_shared > lds_waves ? lds_shared : lds_waves) * sizeof(float) : 0) +
                      (mfma ? (size_t)kDecWaves * kStageBytesPerWave : 0);
-  if (lds > 64 * 1024)
-    SQA_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void*>(fn), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+  if (lds > 160 * 1024) return SQA_ERR_CAPACITY;
+  if (lds > 64 * 1024) SQA_HIP_CHECK(allow_dynamic_lds(reinterpret_cast<const void*>(fn), lds));
 
   hipStream_t st = static_cast<hipStream_t>(stream);
   char* ws = static_cast<char*>(workspace);

@@ -110,6 +110,47 @@ class Session:
                 sqa.decode_step(self.q[t], self.k_new[t], self.v_new[t], wl.P + t, wl.policy, wl.n_sink,
                                 self.caches, self.out[t], self.dec_ws, opts=self.opts)
 
+    # -- the same steps replayed from a HIP graph ---------------------------------
+    def capture_step_graph(self, per_layer: bool = True):
+        """Records one decode step (one launch per layer, or one launch in all) into a HIP graph whose
+        inputs are fixed buffers: q/k/v of the step are copied in, the position comes from a device
+        array (sqa_batch_opts.new_pos_seq), so the recorded launches never change.  Nothing in the
+        recorded work is a memset."""
+        wl = self.wl
+        self.g_q = torch.empty_like(self.q[0]); self.g_k = torch.empty_like(self.k_new[0])
+        self.g_v = torch.empty_like(self.v_new[0]); self.g_out = torch.empty_like(self.out[0])
+        self.g_pos = torch.zeros(wl.B, dtype=torch.int32, device=self.dev)
+        order = "evict_then_attend" if self.opts is None else "attend_then_evict"
+        self.g_opts = sqa.batch_opts(new_pos_seq=self.g_pos, order=order)
+
+        def step():
+            if per_layer:
+                for l in range(wl.L):
+                    sqa.decode_step(self.g_q[l], self.g_k[l], self.g_v[l], 0, wl.policy, wl.n_sink, self.caches,
+                                    self.g_out[l], self.dec_ws_layer[l], layer0=l, n_layers=1, opts=self.g_opts)
+            else:
+                sqa.decode_step(self.g_q, self.g_k, self.g_v, 0, wl.policy, wl.n_sink, self.caches, self.g_out,
+                                self.dec_ws, opts=self.g_opts)
+
+        # one eager run first (with every sequence sitting out, so no state changes): it performs the
+        # one-time per-kernel set-up that must not happen during capture
+        self.g_pos.fill_(-1)
+        step()
+        torch.cuda.synchronize()
+        self.graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(self.graph):
+            step()
+        torch.cuda.synchronize()
+
+    def decode_graph(self, steps: Optional[int] = None, start: int = 0):
+        wl = self.wl
+        S = wl.S if steps is None else steps
+        for t in range(start, start + S):
+            self.g_q.copy_(self.q[t]); self.g_k.copy_(self.k_new[t]); self.g_v.copy_(self.v_new[t])
+            self.g_pos.fill_(wl.P + t)
+            self.graph.replay()
+            self.out[t].copy_(self.g_out)
+
     def run_pass(self):
         """The whole hot path once over this batch."""
         self.probe_and_allocate()

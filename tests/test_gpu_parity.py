@@ -419,6 +419,51 @@ def test_decode_free_running_split_units(sqa):
                 assert rel_err(got["score"][None], c["score"][None]) < 1e-5
 
 
+@pytest.mark.parametrize("policy,dtype,D,g,order", [("h2o", "bf16", 128, 1, "evict_then_attend"),
+                                                     ("h2o", "f32", 64, 2, "attend_then_evict"),
+                                                     ("streaming", "bf16", 128, 4, "evict_then_attend"),
+                                                     ("sliding", "f32", 128, 1, "attend_then_evict"),
+                                                     ("h2o", "bf16", 64, 8, "evict_then_attend")])
+def test_many_short_units_one_wave_per_unit(sqa, policy, dtype, D, g, order):
+    """4096 short units in one call: the launch plan gives each wave a unit of its own.  Free running
+    from the compressed prompt for 5 steps; a sample of units against the oracle on its own."""
+    B, Hkv, L, P, S = 32, 8, 16, 40, 5
+    Hq = Hkv * g
+    lo = {"sliding": 1, "streaming": 5, "h2o": 2}[policy]
+    r = np.random.default_rng(D + g)
+    budgets = [int(x) for x in r.choice([lo, 9, 17, 33, 40, 41, 64, 200], size=L)]
+    tdt = torch.float32 if dtype == "f32" else torch.bfloat16
+    gen = torch.Generator(device="cpu").manual_seed(7)
+    mk = lambda *shape: torch.randn(*shape, generator=gen).to(tdt).to(DEV)
+    Ks, Vs = [mk(B, Hkv, P, D) for _ in range(L)], [mk(B, Hkv, P, D) for _ in range(L)]
+    Ss = [torch.rand(B, Hkv, P, generator=gen).to(DEV) for _ in range(L)]
+    q_all, k_all, v_all = mk(S, L, B, Hq, D), mk(S, L, B, Hkv, D), mk(S, L, B, Hkv, D)
+    caches = _mk_caches(sqa, budgets, [min(b, P + S) for b in budgets], B, Hkv, D, dtype)
+    sqa.prefill_compress_layers(Ks, Vs, Ss if policy == "h2o" else None, policy, 4, caches)
+    ws = sqa.decode_workspace(caches, Hq, policy)
+    opts = None if order == "evict_then_attend" else sqa.batch_opts(order=order)
+    outs, kept = [], []
+    for t in range(S):
+        out = torch.empty(L, B, Hq, D, dtype=tdt, device=DEV)
+        sqa.decode_step(q_all[t], k_all[t], v_all[t], P + t, policy, 4, caches, out, ws, opts=opts)
+        outs.append(np64(out))
+        kept.append([sqa.kept_idx_sorted(caches, l).cpu().numpy() for l in range(L)])
+    assert sqa.read_device_status(ws) == 0
+    qn, kn, vn = np64(q_all), np64(k_all), np64(v_all)
+    units = [(l, b, h) for l in range(L) for b in range(B) for h in range(Hkv)]
+    for l, b, h in units[::89] + units[-3:]:
+        o_ref, c, states, _ = OP.run_unit(np64(Ks[l])[b, h], np64(Vs[l])[b, h], np64(Ss[l])[b, h],
+                                          qn[:, l, b, h * g:(h + 1) * g], kn[:, l, b, h], vn[:, l, b, h],
+                                          budgets[l], policy, 4, keep_states=True, order=order)
+        for t in range(S):
+            n = len(states[t]["pos"])
+            assert kept[t][l][b, h, :n].tolist() == states[t]["pos"].tolist(), (l, b, h, t)
+            assert rel_err(outs[t][l, b, h * g:(h + 1) * g], o_ref[t]) < TOL[dtype], (l, b, h, t)
+        if policy == "h2o":
+            got = export_state(caches, l, b, h)
+            assert rel_err(got["score"][None], c["score"][None]) < 1e-5
+
+
 @pytest.mark.parametrize("policy", ["sliding", "streaming", "h2o"])
 def test_decode_from_an_empty_cache(sqa, policy):
     """No prompt at all: the first step attends to the new token alone (out = v), then the cache
@@ -524,3 +569,34 @@ def test_decode_reports_bad_state_without_touching_the_cache(sqa):
     ws = sqa.decode_workspace(caches2, 1, "sliding")
     sqa.decode_step(q, q, q, 9, "sliding", 4, caches2, out, ws)
     assert sqa.read_device_status(ws) == 6        # SQA_ERR_CAPACITY
+
+
+def test_decode_steps_replayed_from_a_hip_graph(sqa):
+    """One launch per layer recorded once into a HIP graph (positions from a device array), replayed
+    for every step with eager work and synchronisations between the replays: every replay must leave
+    the same bytes as the eager run of the same step."""
+    from paper_2404_04793_amd.session import Session
+    wl = W.scaled(W.WORKLOADS["tiny"], L=4, B=2, P=96, S=10, dtype="bf16", D=128, Hq=4, Hkv=2, hidden=256)
+    runs = []
+    for use_graph in (False, True):
+        sess = Session(wl, DEV)
+        sess.probe_and_allocate()
+        sess.compress_prompt()
+        if use_graph:
+            sess.capture_step_graph(per_layer=True)
+        snaps = []
+        for t in range(wl.S):
+            if use_graph:
+                sess.decode_graph(steps=1, start=t)
+                _ = (sess.q[t].float().sum() + 1).item()          # eager work and a sync between replays
+            else:
+                sess.decode(steps=1, per_layer=True, start=t)
+            torch.cuda.synchronize()
+            snaps.append((sess.out[t].clone(), [p.clone() for p in sess.caches.pos], [s.clone() for s in sess.caches.score],
+                          [s.clone() for s in sess.caches.state]))
+        assert all(sqa.read_device_status(w) == 0 for w in sess.dec_ws_layer)
+        runs.append(snaps)
+    for t, (a, b) in enumerate(zip(*runs)):
+        assert torch.equal(a[0].view(torch.int16), b[0].view(torch.int16)), t
+        for x, y in zip(a[1] + a[2] + a[3], b[1] + b[2] + b[3]):
+            assert torch.equal(x, y), t
