@@ -159,20 +159,8 @@ class Session:
 
     # -- accounting (bytes the method must move; Sec. 2.1 KV size model) --------
     def decode_bytes_per_step(self) -> List[int]:
-        """Algorithmic HBM bytes of each decode step: kept K and V rows read once,
-        8 bytes of score per kept token under H2O, the appended rows, q in and out."""
-        wl = self.wl
-        e, row = wl.elem_bytes, wl.D * wl.elem_bytes
-        units = wl.B * wl.Hkv
-        out = []
-        for t in range(wl.S):
-            tot = 0
-            for b in self.budgets:
-                n = min(wl.P + t + 1, b)
-                tot += units * (n * 2 * row + (8 * n if wl.policy == "h2o" else 0) + 2 * row)
-            tot += wl.L * wl.B * wl.Hq * wl.D * e * 2
-            out.append(tot)
-        return out
+        """Algorithmic HBM bytes of each decode step (see workloads.decode_bytes_per_step)."""
+        return W.decode_bytes_per_step(self.wl, self.budgets)
 
     def probe_bytes(self) -> int:
         wl = self.wl

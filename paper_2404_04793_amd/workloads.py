@@ -273,3 +273,23 @@ def decode_qkv(wl: Workload, layer: int, device="cpu", u=None, mask=None, steps:
     k = k + m[:, :, None, None] * boost[None, None]
     dt = wl.torch_dtype
     return q.to(dt), k.to(dt), v.to(dt)
+
+
+# -- byte accounting (what the method must move; Sec. 2.1 KV size model) ---------------------------
+
+def decode_bytes_per_step(wl: Workload, budgets) -> list:
+    """Algorithmic HBM bytes of each of the S decode steps over all layers: every kept K and V row read
+    once (n_l = min(P + t + 1, b_l) tokens per unit after the append / eviction), 8 bytes of accumulated
+    score per kept token under H2O (one read, one write), the appended K and V rows written, q read and
+    out written."""
+    e, row = wl.elem_bytes, wl.D * wl.elem_bytes
+    units = wl.B * wl.Hkv
+    out = []
+    for t in range(wl.S):
+        tot = 0
+        for b in budgets:
+            n = min(wl.P + t + 1, b)
+            tot += units * (n * 2 * row + (8 * n if wl.policy == "h2o" else 0) + 2 * row)
+        tot += wl.L * wl.B * wl.Hq * wl.D * e * 2
+        out.append(tot)
+    return out

@@ -1,0 +1,40 @@
+"""The algorithmic byte count that the roofline figure of bench.py divides by the launch time,
+checked against a count made unit by unit, token by token."""
+from paper_2404_04793_amd import workloads as W
+
+
+def _count_by_hand(wl, budgets, t):
+    row = wl.D * wl.elem_bytes
+    total = 0
+    for b in budgets:
+        for _unit in range(wl.B * wl.Hkv):
+            kept = min(wl.P + t + 1, b)
+            for _tok in range(kept):
+                total += row + row                      # its K row and its V row, read once
+                if wl.policy == "h2o":
+                    total += 4 + 4                      # accumulated score: read, write
+            total += row + row                          # the appended token's K and V rows, written
+        total += wl.B * wl.Hq * wl.D * wl.elem_bytes    # q read
+        total += wl.B * wl.Hq * wl.D * wl.elem_bytes    # out written
+    return total
+
+
+def test_tiny_counts_match_a_token_by_token_count():
+    wl = W.WORKLOADS["tiny"]
+    budgets = [85, 17, 17, 85]
+    got = W.decode_bytes_per_step(wl, budgets)
+    assert len(got) == wl.S
+    for t in (0, 7, wl.S - 1):
+        assert got[t] == _count_by_hand(wl, budgets, t)
+    streaming = W.scaled(wl, policy="streaming")
+    assert W.decode_bytes_per_step(streaming, budgets)[3] == _count_by_hand(streaming, budgets, 3)
+
+
+def test_llama2_7b_mean_is_the_figure_of_the_profile():
+    wl = W.WORKLOADS["llama2_7b"]
+    budgets = [2271, 2271] + [143] * 28 + [2271, 2271]
+    per_step = W.decode_bytes_per_step(wl, budgets)
+    assert sum(per_step) // wl.S == 1699176928
+    # 512 bytes of K and V plus 8 bytes of score per kept token and KV head, the dominant term
+    full = 256 * (28 * 143 + 4 * 2271) * 520
+    assert 0.99 < full / per_step[-1] < 1.0
