@@ -419,15 +419,18 @@ def test_decode_free_running_split_units(sqa):
                 assert rel_err(got["score"][None], c["score"][None]) < 1e-5
 
 
-@pytest.mark.parametrize("policy,dtype,D,g,order", [("h2o", "bf16", 128, 1, "evict_then_attend"),
-                                                     ("h2o", "f32", 64, 2, "attend_then_evict"),
-                                                     ("streaming", "bf16", 128, 4, "evict_then_attend"),
-                                                     ("sliding", "f32", 128, 1, "attend_then_evict"),
-                                                     ("h2o", "bf16", 64, 8, "evict_then_attend")])
-def test_many_short_units_one_wave_per_unit(sqa, policy, dtype, D, g, order):
-    """4096 short units in one call: the launch plan gives each wave a unit of its own.  Free running
-    from the compressed prompt for 5 steps; a sample of units against the oracle on its own."""
-    B, Hkv, L, P, S = 32, 8, 16, 40, 5
+@pytest.mark.parametrize("policy,dtype,D,g,order,B,Hkv,L", [
+    ("h2o", "bf16", 128, 1, "evict_then_attend", 32, 8, 16),
+    ("h2o", "f32", 64, 2, "attend_then_evict", 32, 8, 16),
+    ("streaming", "bf16", 128, 4, "evict_then_attend", 32, 8, 16),
+    ("sliding", "f32", 128, 1, "attend_then_evict", 32, 8, 16),
+    ("h2o", "bf16", 64, 8, "evict_then_attend", 32, 8, 16),
+    ("h2o", "bf16", 64, 1, "evict_then_attend", 33, 5, 25),      # 165 units per layer: the last workgroup is partly empty
+])
+def test_many_short_units_one_wave_per_unit(sqa, policy, dtype, D, g, order, B, Hkv, L):
+    """At least 4096 short units in one call: the launch plan gives each wave a unit of its own.  Free
+    running from the compressed prompt for 5 steps; a sample of units against the oracle on its own."""
+    P, S = 40, 5
     Hq = Hkv * g
     lo = {"sliding": 1, "streaming": 5, "h2o": 2}[policy]
     r = np.random.default_rng(D + g)
