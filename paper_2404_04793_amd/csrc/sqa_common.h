@@ -2,6 +2,9 @@
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
+#include <map>
+#include <mutex>
+#include <utility>
 #include "sqa.h"
 
 #define SQA_WAVE 64
@@ -61,6 +64,23 @@ template <typename T> __device__ __forceinline__ T wave_sum(T v) {
 }
 
 inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+// A kernel needs a one-time opt-in per device before a launch may ask for more dynamic LDS than the
+// default limit.  Remembered per (device, kernel), so the steady state makes no runtime call for it and a
+// caller that records launches into a HIP graph only has to run each kernel once eagerly before.
+inline hipError_t allow_dynamic_lds(const void* fn, size_t bytes) {
+  static std::mutex mu;
+  static std::map<std::pair<int, const void*>, size_t> granted;
+  int dev = 0;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  std::lock_guard<std::mutex> lock(mu);
+  size_t& g = granted[std::make_pair(dev, fn)];
+  if (g >= bytes) return hipSuccess;
+  e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
+  if (e == hipSuccess) g = bytes;
+  return e;
+}
 
 #define SQA_HIP_CHECK(expr) do { if ((expr) != hipSuccess) { (void)hipGetLastError(); return SQA_ERR_HIP; } } while (0)
 

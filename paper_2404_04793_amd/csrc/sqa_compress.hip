@@ -206,12 +206,15 @@ __global__ __launch_bounds__(kCmpThreads) void kept_idx_sorted_kernel(sqa_layer_
 }
 
 template <typename T, int D>
-static void launch_compress(const CompressBatch& batch, int n, int P, int policy, int n_sink,
-                            unsigned units, size_t lds, hipStream_t st) {
+static hipError_t launch_compress(const CompressBatch& batch, int n, int P, int policy, int n_sink,
+                                   unsigned units, size_t lds, hipStream_t st) {
   auto fn = prefill_compress_kernel<T, D>;
-  if (lds > 48 * 1024)
-    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(fn), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+  if (lds > 48 * 1024) {
+    const hipError_t e = allow_dynamic_lds(reinterpret_cast<const void*>(fn), lds);
+    if (e != hipSuccess) return e;
+  }
   fn<<<dim3(units, n), kCmpThreads, lds, st>>>(batch, P, policy, n_sink, (int)(lds / sizeof(uint32_t)));
+  return hipGetLastError();
 }
 
 static sqa_status check_compress_layer(const void* K, const void* V, sqa_dtype kv_dt, const float* attn_scores,
@@ -292,14 +295,15 @@ extern "C" sqa_status sqa_prefill_compress_layers_ex(const void* const* K, const
       lds = lds_layer[l0 + i] > lds ? lds_layer[l0 + i] : lds;
     }
     for (int i = n; i < kCmpBatch; ++i) { batch.L[i] = layers[l0]; batch.K[i] = nullptr; batch.V[i] = nullptr; batch.scores[i] = nullptr; }
+    hipError_t e;
     if (kv_dt == SQA_F32) {
-      if (D == 64) launch_compress<float, 64>(batch, n, P, policy, n_sink, units, lds, st);
-      else launch_compress<float, 128>(batch, n, P, policy, n_sink, units, lds, st);
+      if (D == 64) e = launch_compress<float, 64>(batch, n, P, policy, n_sink, units, lds, st);
+      else e = launch_compress<float, 128>(batch, n, P, policy, n_sink, units, lds, st);
     } else {
-      if (D == 64) launch_compress<bf16_t, 64>(batch, n, P, policy, n_sink, units, lds, st);
-      else launch_compress<bf16_t, 128>(batch, n, P, policy, n_sink, units, lds, st);
+      if (D == 64) e = launch_compress<bf16_t, 64>(batch, n, P, policy, n_sink, units, lds, st);
+      else e = launch_compress<bf16_t, 128>(batch, n, P, policy, n_sink, units, lds, st);
     }
-    SQA_HIP_CHECK(hipGetLastError());
+    SQA_HIP_CHECK(e);
   }
   return SQA_OK;
 }
@@ -323,8 +327,7 @@ extern "C" sqa_status sqa_kept_idx_sorted(const sqa_layer_cache* layer, int B, i
   const size_t lds = (size_t)layer->capacity * sizeof(int32_t);
   if (lds > 128 * 1024) return SQA_ERR_CAPACITY;
   if (lds > 48 * 1024)
-    SQA_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void*>(kept_idx_sorted_kernel),
-                                      hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+    SQA_HIP_CHECK(allow_dynamic_lds(reinterpret_cast<const void*>(kept_idx_sorted_kernel), lds));
   kept_idx_sorted_kernel<<<(unsigned)(B * Hkv), kCmpThreads, lds, static_cast<hipStream_t>(stream)>>>(*layer, out);
   SQA_HIP_CHECK(hipGetLastError());
   return SQA_OK;

@@ -28,9 +28,6 @@
 // own and runs steps 0-4 alone, without a barrier.  A 4-wave pass over 64 rows
 // leaves most lanes idle on such a unit and ends in a merge that costs as much
 // as the streaming; one wave walks it 16 rows at a time with nothing to merge.
-#include <map>
-#include <mutex>
-#include <utility>
 #include "sqa_common.h"
 
 namespace sqa {
@@ -787,22 +784,6 @@ static decode_fn pick(sqa_dtype dt, int d, int g, bool h2o) {
 }
 
 constexpr size_t kStatusBytes = 256;
-
-// A kernel needs a one-time opt-in per device before a launch may ask for more than 64 KiB of dynamic
-// LDS.  Remembered per (device, kernel) so that the steady state makes no runtime call for it.
-static hipError_t allow_dynamic_lds(const void* fn, size_t bytes) {
-  static std::mutex mu;
-  static std::map<std::pair<int, const void*>, size_t> granted;
-  int dev = 0;
-  hipError_t e = hipGetDevice(&dev);
-  if (e != hipSuccess) return e;
-  std::lock_guard<std::mutex> lock(mu);
-  size_t& g = granted[std::make_pair(dev, fn)];
-  if (g >= bytes) return hipSuccess;
-  e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
-  if (e == hipSuccess) g = bytes;
-  return e;
-}
 
 // How one call is cut into work items and where its scratch lives.
 struct DecodePlan {
