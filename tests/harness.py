@@ -56,3 +56,17 @@ def round_scores_f32(c: dict) -> dict:
     d = dict(c)
     d["score"] = c["score"].astype(np.float32).astype(np.float64)
     return d
+
+
+def near_tie_swap(got_pos, want_pos, c_before, c_after_full, rec, tol):
+    """Attend-then-evict decides on scores updated in this very step, in fp32 on
+    the GPU and fp64 in the oracle: when the two worst candidates are closer
+    than the fp32 error either may go.  True if that is what happened."""
+    a, b = set(got_pos) - set(want_pos), set(want_pos) - set(got_pos)
+    if len(a) != 1 or len(b) != 1:
+        return False
+    cand = sorted(c_after_full)[: len(c_after_full) - rec]
+    x, y = a.pop(), b.pop()
+    if x not in cand or y not in cand:
+        return False
+    return abs(c_after_full[x] - c_after_full[y]) <= tol * max(abs(c_after_full[x]), abs(c_after_full[y]), 1e-30)

@@ -10,16 +10,17 @@ import torch
 
 from oracle import sqa_oracle as O
 from paper_2404_04793_amd import workloads as W
-from tests.harness import TOL, export_state, import_state, np64, rel_err, round_scores_f32
+from tests.harness import TOL, export_state, import_state, near_tie_swap, np64, rel_err, round_scores_f32
 
 pytestmark = pytest.mark.gpu
 DEV = "cuda:0"
 
 
-def _run_fullsize(wl, sample_layers, units, check_steps, cos_layers):
+def _run_fullsize(wl, sample_layers, units, check_steps, cos_layers, order="evict_then_attend"):
     from paper_2404_04793_amd import binding as sqa
     from paper_2404_04793_amd.session import Session
-    sess = Session(wl, DEV, keep_prompt_q=True)
+    sess = Session(wl, DEV, keep_prompt_q=True, order=order)
+    ae = order == "attend_then_evict"
     g, tol = wl.g, TOL[wl.dtype]
 
     # ---- probe + budgets --------------------------------------------------
@@ -67,15 +68,25 @@ def _run_fullsize(wl, sample_layers, units, check_steps, cos_layers):
                 import_state(sess.caches, key[0], key[1], key[2], c)
         sess.decode(steps=1, start=t)
         for key in sample:
-            want_out, c2 = O.decode_step(state[key], qn[key][t], kn[key][t], vn[key][t], wl.P + t, budgets[key[0]],
-                                         wl.policy, wl.n_sink)
+            before = state[key]
+            want_out, c2 = O.decode_step(before, qn[key][t], kn[key][t], vn[key][t], wl.P + t, budgets[key[0]],
+                                         wl.policy, wl.n_sink, order)
             state[key] = round_scores_f32(c2)
             if t in check_steps:
                 l, b, h = key
                 got = export_state(sess.caches, l, b, h)
+                worst_out = max(worst_out, rel_err(np64(sess.out[t, l, b, h * g:(h + 1) * g]), want_out))
+                if ae and wl.policy == "h2o" and got["pos"].tolist() != c2["pos"].tolist():
+                    # decided on scores updated in this very step (fp32 there, fp64 here): a swap of two
+                    # candidates closer than the fp32 error is legitimate
+                    _, full = O.decode_step(before, qn[key][t], kn[key][t], vn[key][t], wl.P + t, 1 << 30,
+                                            wl.policy, wl.n_sink, order)
+                    upd = dict(zip(full["pos"].tolist(), full["score"].tolist()))
+                    bl = budgets[l]
+                    assert near_tie_swap(got["pos"].tolist(), c2["pos"].tolist(), before, upd, bl - bl // 2, 10 * tol)
+                    continue
                 assert got["pos"].tolist() == c2["pos"].tolist(), (key, t)
                 assert np.array_equal(got["K"], c2["K"]) and np.array_equal(got["V"], c2["V"]), (key, t)
-                worst_out = max(worst_out, rel_err(np64(sess.out[t, l, b, h * g:(h + 1) * g]), want_out))
                 if wl.policy == "h2o":
                     assert rel_err(got["score"][None], c2["score"][None]) < tol, (key, t)
     assert worst_out < tol, worst_out
@@ -111,6 +122,14 @@ def test_llama2_7b_full_size():
     wl = W.WORKLOADS["llama2_7b"]
     _run_fullsize(wl, sample_layers=[0, 5, 17, 31], units=[(0, 0), (7, 31)],
                   check_steps={0, 1, 2, 100, 222, 223, 224, 225, 255}, cos_layers=[0, 16, 31])
+
+
+def test_llama2_7b_full_size_attend_then_evict():
+    """configs[1] in the other order of a step, 48 decode steps (the 2271-slot layers never fill, the
+    143-slot layers evict from the first step on)."""
+    wl = W.scaled(W.WORKLOADS["llama2_7b"], S=48)
+    _run_fullsize(wl, sample_layers=[0, 5, 31], units=[(0, 0), (7, 31)], check_steps={0, 1, 2, 30, 47},
+                  cos_layers=[16], order="attend_then_evict")
 
 
 def test_mistral_7b_gqa_streaming_reduced_batch():

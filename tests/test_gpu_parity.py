@@ -10,7 +10,7 @@ import torch
 from oracle import sqa_oracle as O
 from oracle import pipeline as OP
 from paper_2404_04793_amd import workloads as W
-from tests.harness import TOL, export_state, import_state, np64, rel_err, round_scores_f32
+from tests.harness import TOL, export_state, import_state, near_tie_swap, np64, rel_err, round_scores_f32
 
 pytestmark = pytest.mark.gpu
 
@@ -248,20 +248,6 @@ def test_decode_teacher_forced_attend_then_evict(sqa, case):
     _teacher_forced(sqa, case, "attend_then_evict")
 
 
-def _near_tie_swap(got_pos, want_pos, c_before, c_after_full, rec, tol):
-    """Attend-then-evict decides on scores updated in this very step, in fp32 on
-    the GPU and fp64 in the oracle: when the two worst candidates are closer
-    than the fp32 error either may go.  True if that is what happened."""
-    a, b = set(got_pos) - set(want_pos), set(want_pos) - set(got_pos)
-    if len(a) != 1 or len(b) != 1:
-        return False
-    cand = sorted(c_after_full)[: len(c_after_full) - rec]
-    x, y = a.pop(), b.pop()
-    if x not in cand or y not in cand:
-        return False
-    return abs(c_after_full[x] - c_after_full[y]) <= tol * max(abs(c_after_full[x]), abs(c_after_full[y]), 1e-30)
-
-
 def _teacher_forced(sqa, case, order):
     name, dtype, L, Hq, Hkv, D, B, P, S, policy, budgets = case
     ae = order == "attend_then_evict"
@@ -302,7 +288,7 @@ def _teacher_forced(sqa, case, order):
                 _, full = O.decode_step(c, qn[t, l, b, h * g:(h + 1) * g], kn[t, l, b, h], vn[t, l, b, h],
                                         P + t, 1 << 30, policy, wl.n_sink, order)       # nothing evicted: all updated scores
                 upd = dict(zip(full["pos"].tolist(), full["score"].tolist()))
-                assert _near_tie_swap(got["pos"].tolist(), c2["pos"].tolist(), c, upd, budgets[l] - budgets[l] // 2,
+                assert near_tie_swap(got["pos"].tolist(), c2["pos"].tolist(), c, upd, budgets[l] - budgets[l] // 2,
                                       10 * TOL[dtype]), (name, t, l, b, h)
                 state[l, b, h] = round_scores_f32(c2)
                 continue
