@@ -145,3 +145,23 @@ def test_device_entry_points_validate_before_any_gpu_call():
     assert lib.sqa_prefill_scores(p, p, 1, 1, 6, 4, 16, 128, p, p, 1 << 20, None) == 2
     lib.sqa_status_str.restype = C.c_char_p
     assert lib.sqa_status_str(5) == b"bad budget"
+
+
+def test_header_is_plain_c(tmp_path):
+    """The boundary is a C ABI: include/sqa.h must compile as strict C99, without a C++ or HIP compiler."""
+    import shutil
+    import subprocess
+    gcc = shutil.which("gcc")
+    if gcc is None:
+        pytest.skip("no gcc")
+    src = tmp_path / "use_header.c"
+    src.write_text('#include "sqa.h"\n'
+                   'int main(void) {\n'
+                   '  sqa_batch_opts o = {0}; sqa_layer_cache c = {0};\n'
+                   '  (void)o; (void)c;\n'
+                   '  return sizeof(sqa_layer_cache) == 48 && SQA_ST_WORDS == 4 ? 0 : 1;\n'
+                   '}\n')
+    r = subprocess.run([gcc, "-std=c99", "-Wall", "-Wextra", "-pedantic", "-Werror", "-I", os.path.join(ROOT, "include"),
+                        str(src), "-o", str(tmp_path / "use_header")], capture_output=True, text=True)
+    assert r.returncode == 0, r.stderr
+    assert subprocess.run([str(tmp_path / "use_header")]).returncode == 0
