@@ -799,13 +799,15 @@ struct DecodePlan {
 
 static size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 
-// Units are split only when there are too few of them to fill the chip (the
-// hand-over between workgroups costs more than the imbalance it removes): with
-// at least kMinItems units every unit is one work item, as long as its step
-// logits fit in LDS (kMaxUnsplit slots x heads).  Otherwise the target chunk is
-// what gives about kMinItems items, at least 256 slots; each layer then uses
-// the number of equal chunks nearest to that.
-constexpr int64_t kMinItems = 256 * 8;
+// Units are split only when the call would otherwise have too few work items to fill the chip or a
+// few items much longer than the rest (the hand-over between workgroups costs more than the imbalance
+// it removes): the target chunk is 1/kMinItems of the call's tokens, at least 256 slots and at most what
+// lets a unit's step logits fit in LDS (kMaxUnsplit slots x heads); each layer uses the number of equal
+// chunks nearest to that, so units shorter than 1.5 targets stay whole.
+#ifndef SQA_DEC_MIN_ITEMS
+#define SQA_DEC_MIN_ITEMS (256 * 4)
+#endif
+constexpr int64_t kMinItems = SQA_DEC_MIN_ITEMS;
 constexpr int kMaxUnsplit = 8192;
 // One wave per unit: for units of at most kWpuMaxSlots slots, in calls that have at least kWpuMinUnits
 // units (one wave walks a unit 16 rows at a time, so the call needs many units to keep the chip's wave
@@ -826,12 +828,9 @@ static sqa_status plan_decode(const sqa_layer_cache* layers, int n_layers, int B
 #ifdef SQA_DEC_FORCE_CHUNK
   target = SQA_DEC_FORCE_CHUNK;
 #else
-  if (units * n_layers >= kMinItems) {
-    target = h2o ? kMaxUnsplit / g : (int64_t)1 << 30;
-  } else {
-    target = tokens / kMinItems;
-    target = target < 256 ? 256 : target;
-  }
+  target = tokens / kMinItems;
+  target = target < 256 ? 256 : target;
+  if (h2o && target > kMaxUnsplit / g) target = kMaxUnsplit / g;
 #endif
   uint64_t blocks = 0, n_units = 0, n_part = 0, n_logit = 0;
   p->lds_chunk = 64;
