@@ -82,6 +82,9 @@ def main():
     ap.add_argument("--graph", action="store_true",
                     help="replay each decode step from a HIP graph recorded once (inputs copied into fixed buffers, "
                          "positions read from a device array); meant for --per-layer, where launches dominate")
+    ap.add_argument("--ragged", action="store_true",
+                    help="a ragged batch: prompt lengths from P down to about P/2, each sequence probed, budgeted and "
+                         "positioned on its own (per-sequence budgets and positions from device arrays)")
     ap.add_argument("--uniform", action="store_true", help="sequence-only baseline: same budget in every layer")
     ap.add_argument("--full-cache", action="store_true", help="no compression (budget = P + S)")
     ap.add_argument("--policy", default=None, choices=["h2o", "streaming", "sliding"],
@@ -123,8 +126,9 @@ def main():
     if args.budget_pct:
         wl = W.scaled(wl, budget_pct=args.budget_pct)
     torch.cuda.set_device(0)
+    plen = [wl.P - (b * wl.P) // (2 * wl.B) for b in range(wl.B)] if args.ragged else None
     sess = Session(wl, "cuda:0", uniform_budget=args.uniform, full_cache=args.full_cache,
-                   probe_tokens=args.probe_tokens, fused_probe=args.fused_probe, order=args.order)
+                   probe_tokens=args.probe_tokens, fused_probe=args.fused_probe, order=args.order, prompt_len=plen)
 
     def do_decode():
         if args.graph:
@@ -209,7 +213,8 @@ def main():
                    "budget_pct": wl.budget_pct, "p": wl.p,
                    "mode": mode, "launch": launch,
                    "phases": "decode_only" if args.decode_only else "whole_pass",
-                   "probe_tokens": sess.probe_tokens, "fused_probe": args.fused_probe, "order": args.order},
+                   "probe_tokens": sess.probe_tokens, "fused_probe": args.fused_probe, "order": args.order,
+                   "ragged_prompt_lengths": plen},
         "roofline": {"bound": "hbm", "kernel": "decode_unit_kernel", "achieved": achieved, "peak": HBM_PEAK_GBS,
                      "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
                      "traffic": MEASURED_TRAFFIC_BYTES.get((wl.name, mode, wl.policy, launch)),
@@ -219,7 +224,8 @@ def main():
         "probe_GBps": None if args.decode_only else sess.probe_bytes() / (probe_ms * 1e-3) / 1e9,
         "compress_GBps": None if args.decode_only else sess.compress_bytes() / (comp_ms * 1e-3) / 1e9,
         "budgets": {"low": min(sess.budgets), "high": max(sess.budgets),
-                    "n_G3": sum(1 for g in sess.groups if g == 2), "sum": sum(sess.budgets)},
+                    "n_G3": None if sess.groups is None else sum(1 for g in sess.groups if g == 2),
+                    "sum": sum(sess.budgets)},
         "resident_kv_GB": sess.resident_kv_bytes() / 1e9,
         "device_status": status,
     }

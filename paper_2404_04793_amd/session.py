@@ -15,13 +15,30 @@ from . import workloads as W
 class Session:
     def __init__(self, wl: W.Workload, device="cuda:0", keep_prompt_q: bool = False, uniform_budget: bool = False,
                  full_cache: bool = False, probe_tokens: Optional[int] = None, fused_probe: bool = False,
-                 order: str = "evict_then_attend"):
+                 order: str = "evict_then_attend", prompt_len: Optional[List[int]] = None):
         """probe_tokens: hidden-state rows per layer given to the probe (default: all B*P prompt tokens;
         a smaller number keeps the hidden states of the largest workloads within HBM).
-        fused_probe: the probe runs inside the residual add that writes h_out (Sec. 3)."""
+        fused_probe: the probe runs inside the residual add that writes h_out (Sec. 3).
+        prompt_len: a ragged batch -- sequence b's prompt is its first prompt_len[b] <= P tokens (the
+        tensors stay padded to P); each sequence is then probed and budgeted on its own
+        (sqa_layer_importance_seq, one sqa_allocate_budgets per sequence) and decodes at its own position."""
         self.wl, self.dev = wl, device
         self.fused_probe = fused_probe
+        self.order = order
         self.opts = None if order == "evict_then_attend" else sqa.batch_opts(order=order)
+        self.ragged = prompt_len is not None
+        if self.ragged:
+            assert len(prompt_len) == wl.B and all(1 <= x <= wl.P for x in prompt_len)
+            assert not (uniform_budget or full_cache or fused_probe or probe_tokens)
+            self.prompt_len = [int(x) for x in prompt_len]
+            self.plen_dev = torch.tensor(self.prompt_len, dtype=torch.int32, device=device)
+            starts = [0]
+            for x in self.prompt_len:
+                starts.append(starts[-1] + x)                 # the hidden-state rows of the sequences, packed
+            self.seq_start = torch.tensor(starts, dtype=torch.int32, device=device)
+            self.pos_steps = (self.plen_dev[None, :] + torch.arange(wl.S, dtype=torch.int32, device=device)[:, None]).contiguous()
+            self.status = torch.zeros(1, dtype=torch.int32, device=device)
+            self.budget_seq = None
         self.uniform_budget, self.full_cache = uniform_budget, full_cache
         self.u, self.mask = W.unit_dirs(wl), W.hh_mask(wl, device)
         L = wl.L
@@ -42,7 +59,8 @@ class Session:
             self.Kp.append(K); self.Vp.append(V)
             if wl.policy == "h2o":
                 Q = W.prompt_q(wl, l, device, self.u)
-                self.scores.append(sqa.prefill_scores(Q, K))
+                self.scores.append(sqa.prefill_scores(Q, K, opts=sqa.batch_opts(prompt_len=self.plen_dev)
+                                                      if self.ragged else None))
                 if keep_prompt_q:
                     self.Qp.append(Q)
                 del Q
@@ -70,6 +88,8 @@ class Session:
     # -- Algorithm 1 steps 1-11 ------------------------------------------------
     def probe_and_allocate(self):
         wl = self.wl
+        if self.ragged:
+            return self._probe_and_allocate_ragged()
         if self.fused_probe:
             sqa.residual_add_importance(self.h_in, self.attn_out, self.h_out, self.cos_dev, self.imp_ws)
         else:
@@ -91,24 +111,49 @@ class Session:
         self.budgets, self.groups = budgets, groups
         return cos
 
+    def _probe_and_allocate_ragged(self):
+        wl = self.wl
+        cos = sqa.layer_importance_seq(self.h_in, self.h_out, self.seq_start).cpu()       # [L, B]
+        per_seq = []
+        for b in range(wl.B):
+            total = wl.L * max(self.prompt_len[b] * wl.budget_pct // 100, 8)
+            per_seq.append(sqa.allocate_budgets(cos[:, b].tolist(), total, wl.p)[0])
+        budget_seq = [[per_seq[b][l] for b in range(wl.B)] for l in range(wl.L)]         # [L][B]
+        budgets = [max(row) for row in budget_seq]                                       # the layers' maxima
+        if self.caches is None or budget_seq != self.budget_seq:
+            caps = [min(b, wl.P + wl.S) for b in budgets]
+            self.caches = sqa.LayerCaches(budgets, caps, wl.B, wl.Hkv, wl.D, wl.torch_dtype, self.dev,
+                                          wl.policy == "h2o")
+            self.dec_ws = sqa.decode_workspace(self.caches, wl.Hq, wl.policy)
+            self.dec_ws_layer = [sqa.decode_workspace(self.caches, wl.Hq, wl.policy, l, 1) for l in range(wl.L)]
+            self.bseq_dev = torch.tensor(budget_seq, dtype=torch.int32, device=self.dev)
+            self.opts_pre = sqa.batch_opts(prompt_len=self.plen_dev, budget_seq=self.bseq_dev, status=self.status)
+            self.opts_step = [sqa.batch_opts(budget_seq=self.bseq_dev, new_pos_seq=self.pos_steps[t], order=self.order)
+                              for t in range(wl.S)]
+        self.budget_seq, self.budgets, self.groups = budget_seq, budgets, None
+        return cos.mean(dim=1).tolist()
+
     # -- steps 12 + 16-17 on the prompt ---------------------------------------
     def compress_prompt(self):
         wl = self.wl
-        sqa.prefill_compress_layers(self.Kp, self.Vp, self.scores, wl.policy, wl.n_sink, self.caches)
+        sqa.prefill_compress_layers(self.Kp, self.Vp, self.scores, wl.policy, wl.n_sink, self.caches,
+                                    opts=self.opts_pre if self.ragged else None)
 
     # -- steps 14-21 -----------------------------------------------------------
     def decode(self, steps: Optional[int] = None, per_layer: bool = False, start: int = 0):
         wl = self.wl
         S = wl.S if steps is None else steps
         for t in range(start, start + S):
+            opts = self.opts_step[t] if self.ragged else self.opts
             if per_layer:
+                assert not self.ragged        # (budget_seq rows are addressed from the call's first layer)
                 for l in range(wl.L):
                     sqa.decode_step(self.q[t, l], self.k_new[t, l], self.v_new[t, l], wl.P + t, wl.policy, wl.n_sink,
                                     self.caches, self.out[t, l], self.dec_ws_layer[l], layer0=l, n_layers=1,
-                                    opts=self.opts)
+                                    opts=opts)
             else:
                 sqa.decode_step(self.q[t], self.k_new[t], self.v_new[t], wl.P + t, wl.policy, wl.n_sink,
-                                self.caches, self.out[t], self.dec_ws, opts=self.opts)
+                                self.caches, self.out[t], self.dec_ws, opts=opts)
 
     # -- the same steps replayed from a HIP graph ---------------------------------
     def capture_step_graph(self, per_layer: bool = True):
@@ -160,19 +205,24 @@ class Session:
     # -- accounting (bytes the method must move; Sec. 2.1 KV size model) --------
     def decode_bytes_per_step(self) -> List[int]:
         """Algorithmic HBM bytes of each decode step (see workloads.decode_bytes_per_step)."""
+        if self.ragged:
+            return W.decode_bytes_per_step_ragged(self.wl, self.budget_seq, self.prompt_len)
         return W.decode_bytes_per_step(self.wl, self.budgets)
 
     def probe_bytes(self) -> int:
         wl = self.wl
-        return (3 if self.fused_probe else 2) * wl.L * self.probe_tokens * wl.hidden * wl.elem_bytes
+        rows = sum(self.prompt_len) if self.ragged else self.probe_tokens
+        return (3 if self.fused_probe else 2) * wl.L * rows * wl.hidden * wl.elem_bytes
 
     def compress_bytes(self) -> int:
         wl = self.wl
         row = wl.D * wl.elem_bytes
         tot = 0
-        for b in self.budgets:
-            n = min(wl.P, b)
-            tot += wl.B * wl.Hkv * ((4 * wl.P if wl.policy == "h2o" else 0) + 2 * 2 * n * row)
+        for l, b in enumerate(self.budgets):
+            for s in range(wl.B):
+                P = self.prompt_len[s] if self.ragged else wl.P
+                n = min(P, self.budget_seq[l][s] if self.ragged else b)
+                tot += wl.Hkv * ((4 * P if wl.policy == "h2o" else 0) + 2 * 2 * n * row)
         return tot
 
     def resident_kv_bytes(self) -> int:

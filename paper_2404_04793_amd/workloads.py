@@ -293,3 +293,19 @@ def decode_bytes_per_step(wl: Workload, budgets) -> list:
         tot += wl.L * wl.B * wl.Hq * wl.D * e * 2
         out.append(tot)
     return out
+
+
+def decode_bytes_per_step_ragged(wl: Workload, budget_seq, prompt_len) -> list:
+    """The same count for a ragged batch: budget_seq[l][b] is layer l's budget for sequence b,
+    prompt_len[b] its prompt length (its step-t token has position prompt_len[b] + t)."""
+    e, row = wl.elem_bytes, wl.D * wl.elem_bytes
+    out = []
+    for t in range(wl.S):
+        tot = 0
+        for per_seq in budget_seq:
+            for b, budget in enumerate(per_seq):
+                n = min(prompt_len[b] + t + 1, budget)
+                tot += wl.Hkv * (n * 2 * row + (8 * n if wl.policy == "h2o" else 0) + 2 * row)
+        tot += wl.L * wl.B * wl.Hq * wl.D * e * 2
+        out.append(tot)
+    return out

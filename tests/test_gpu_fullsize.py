@@ -149,3 +149,66 @@ def test_stress_7b_reduced_batch():
     wl = W.scaled(W.WORKLOADS["stress_7b"], B=16, S=128)
     _run_fullsize(wl, sample_layers=[0, 12, 30], units=[(0, 0), (15, 31)], check_steps={0, 1, 59, 60, 61, 127},
                   cos_layers=[0, 12])
+
+
+def test_llama2_7b_ragged_batch():
+    """configs[1] with prompt lengths from 2048 down to 1152: per-sequence cosines and budgets, ragged
+    scores and compression, per-sequence positions -- the path `bench.py --ragged` times."""
+    from paper_2404_04793_amd import binding as sqa
+    from paper_2404_04793_amd.session import Session
+    wl = W.scaled(W.WORKLOADS["llama2_7b"], S=24)
+    plen = [wl.P - (b * wl.P) // (2 * wl.B) for b in range(wl.B)]
+    sess = Session(wl, DEV, keep_prompt_q=True, prompt_len=plen)
+    g, tol = wl.g, TOL[wl.dtype]
+    sess.probe_and_allocate()
+    starts = np.concatenate([[0], np.cumsum(plen)])
+    cos = sqa.layer_importance_seq(sess.h_in, sess.h_out, sess.seq_start).cpu().numpy()
+    for l, b in [(0, 0), (17, 3), (31, 7)]:
+        ref = O.layer_importance(np64(sess.h_in[l:l + 1, starts[b]:starts[b + 1]]),
+                                 np64(sess.h_out[l:l + 1, starts[b]:starts[b + 1]]))[0]
+        assert abs(float(cos[l, b]) - ref) / max(abs(ref), 1e-3) < 1e-5
+    for b in range(wl.B):
+        total = wl.L * (plen[b] * wl.budget_pct // 100)
+        want = O.allocate_budgets(cos[:, b], total, wl.p)[0]
+        assert [sess.budget_seq[l][b] for l in range(wl.L)] == want and sum(want) == total
+    sample = [(l, b, h) for l in (0, 9, 31) for (b, h) in ((0, 0), (4, 13), (7, 31))]
+    state = {}
+    for (l, b, h) in sample:
+        n = plen[b]
+        Kn, Vn = np64(sess.Kp[l][b, h, :n]), np64(sess.Vp[l][b, h, :n])
+        s_ref = O.prefill_scores(np64(sess.Qp[l][b, h * g:(h + 1) * g, :n]), Kn)
+        assert rel_err(np64(sess.scores[l][b, h, :n])[None], s_ref[None]) < tol
+        assert bool((sess.scores[l][b, h, n:] == 0).all())
+        s32 = s_ref.astype(np.float32)
+        sess.scores[l][b, h, :n] = torch.from_numpy(s32).to(DEV)
+        state[l, b, h] = O.prefill_compress(Kn, Vn, s32.astype(np.float64), sess.budget_seq[l][b], wl.policy, wl.n_sink)
+    sess.compress_prompt()
+    assert int(sess.status.item()) == 0
+    for key, c in state.items():
+        got = export_state(sess.caches, *key)
+        assert got["pos"].tolist() == c["pos"].tolist(), key
+        assert np.array_equal(got["K"], c["K"]) and np.array_equal(got["score"], c["score"])
+    check = {0, 1, 23}
+    worst = 0.0
+    for t in range(wl.S):
+        if t in check:
+            for key, c in state.items():
+                import_state(sess.caches, key[0], key[1], key[2], c)
+        sess.decode(steps=1, start=t)
+        for (l, b, h) in sample:
+            want_out, c2 = O.decode_step(state[l, b, h], np64(sess.q[t, l, b, h * g:(h + 1) * g]), np64(sess.k_new[t, l, b, h]),
+                                         np64(sess.v_new[t, l, b, h]), plen[b] + t, sess.budget_seq[l][b], wl.policy, wl.n_sink)
+            state[l, b, h] = round_scores_f32(c2)
+            if t in check:
+                got = export_state(sess.caches, l, b, h)
+                assert got["pos"].tolist() == c2["pos"].tolist(), (l, b, h, t)
+                assert np.array_equal(got["K"], c2["K"]) and np.array_equal(got["V"], c2["V"])
+                assert rel_err(got["score"][None], c2["score"][None]) < tol
+                worst = max(worst, rel_err(np64(sess.out[t, l, b, h * g:(h + 1) * g]), want_out))
+    assert worst < tol and sqa.read_device_status(sess.dec_ws) == 0
+    for l in range(wl.L):                                    # every unit: its own length and newest position
+        for b in range(wl.B):
+            n = min(plen[b] + wl.S, sess.budget_seq[l][b])
+            assert bool((sess.caches.lens[l][b] == n).all())
+            kept = sqa.kept_idx_sorted(sess.caches, l)[b, :, :n]
+            assert int(kept.max()) == plen[b] + wl.S - 1 and bool((kept[:, 1:] > kept[:, :-1]).all())

@@ -38,3 +38,16 @@ def test_llama2_7b_mean_is_the_figure_of_the_profile():
     # 512 bytes of K and V plus 8 bytes of score per kept token and KV head, the dominant term
     full = 256 * (28 * 143 + 4 * 2271) * 520
     assert 0.99 < full / per_step[-1] < 1.0
+
+
+def test_ragged_count_reduces_to_the_uniform_one_and_counts_each_sequence():
+    wl = W.scaled(W.WORKLOADS["tiny"], B=3)
+    budgets = [85, 17, 17, 85]
+    same = W.decode_bytes_per_step_ragged(wl, [[b] * 3 for b in budgets], [wl.P] * 3)
+    assert same == W.decode_bytes_per_step(wl, budgets)
+    # one sequence with a shorter prompt and smaller budgets: only its own units change
+    one = W.scaled(wl, B=1)
+    a = W.decode_bytes_per_step(one, budgets)
+    b = W.decode_bytes_per_step_ragged(W.scaled(one, P=100), [[40], [9], [9], [40]], [100])
+    mixed = W.decode_bytes_per_step_ragged(wl, [[85, 40, 85], [17, 9, 17], [17, 9, 17], [85, 40, 85]], [wl.P, 100, wl.P])
+    assert [x - 2 * y for x, y in zip(mixed, a)] == b
