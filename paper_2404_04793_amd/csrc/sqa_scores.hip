@@ -224,23 +224,39 @@ __device__ __forceinline__ sc_f32x4_t block_product(const char* lds, int sub, co
   return c;
 }
 
+// Which (tile, head) a workgroup of a 1-D launch works on.  Consecutive workgroups go to the 8 XCDs of the
+// chip in turn, each with an L2 of its own; all tiles of a head re-read that head's K (or Q) rows, so a head
+// (with the `per` query heads that share its K rows) is given to one XCD (group mod 8) and an XCD walks its
+// groups one after the other, the tile with the most work first: the rows are then fetched into one L2 once
+// instead of into all eight.  Measured at the 7B shape: 0.45 -> 0.30 ms and 0.54 -> 0.35 ms per layer.
+__device__ __forceinline__ bool xcd_tile_head(int tiles, int heads, int per, bool heavy_is_last, int& tile, int& head) {
+  const int n = blockIdx.x, xcd = n & 7, slot = n >> 3;
+  const int group = (slot / (tiles * per)) * 8 + xcd, rem = slot % (tiles * per);
+  head = group * per + rem / tiles;
+  const int t = rem % tiles;
+  tile = heavy_is_last ? tiles - 1 - t : t;
+  return head < heads;
+}
+
 __global__ __launch_bounds__(kScThreads) void score_rowstats_mfma_kernel(
     const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K, int Hq, int Hkv, int P, float scale_log2,
-    float2* __restrict__ stats) {
+    int tiles, int heads, float2* __restrict__ stats) {
   extern __shared__ char s_tiles[];                 // 2 x [64][kMPitch]
-  const int bh = blockIdx.y, b = bh / Hq, h = bh % Hq, kvh = h / (Hq / Hkv);
+  int tile_x, bh;
+  if (!xcd_tile_head(tiles, heads, Hq / Hkv, true, tile_x, bh)) return;   // (query tile t reads key tiles 0..t: the last is the longest)
+  const int b = bh / Hq, h = bh % Hq, kvh = h / (Hq / Hkv);
   const bf16_t* Qh = Q + (int64_t)bh * P * 128;
   const bf16_t* Kh = K + ((int64_t)b * Hkv + kvh) * P * 128;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int n16 = lane & 15, j4 = lane >> 4;
-  const int r0 = blockIdx.x * kMT + 16 * wave;      // this wave's 16 query rows
+  const int r0 = tile_x * kMT + 16 * wave;          // this wave's 16 query rows
   const int my_row = r0 + n16;
   sc_bf16x8_t qfr[4];
   row_fragments(Qh, min(my_row, P - 1), j4, qfr);
   float m_run = -INFINITY, l_run = 0.f;
   uint4 reg[4];
   tile_request(Kh, 0, P, reg);
-  const int n_tiles = blockIdx.x + 1;               // key tiles 0 .. the diagonal one
+  const int n_tiles = tile_x + 1;                   // key tiles 0 .. the diagonal one
   for (int kt = 0; kt < n_tiles; ++kt) {
     char* buf = s_tiles + (kt & 1) * kMTileBytes;
     tile_store(buf, reg);
@@ -280,20 +296,22 @@ __global__ __launch_bounds__(kScThreads) void score_rowstats_mfma_kernel(
 __global__ __launch_bounds__(kScThreads) void score_colsum_mfma_kernel(
     const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K, int Hq, int Hkv, int P, float scale_log2,
     const float2* __restrict__ stats, const int32_t* __restrict__ prompt_len /*[B] or NULL*/,
-    float* __restrict__ scores) {
+    int tiles, int heads, float* __restrict__ scores) {
   extern __shared__ char s_tiles[];                 // 2 x ([64][kMPitch] + 64 float2)
   constexpr int BUF = kMTileBytes + kMT * (int)sizeof(float2);
-  const int bk = blockIdx.y, b = bk / Hkv, kvh = bk % Hkv, g = Hq / Hkv;
+  int tile_x, bk;
+  if (!xcd_tile_head(tiles, heads, 1, false, tile_x, bk)) return;  // (key tile t is read by query tiles t..last: the first is the longest)
+  const int b = bk / Hkv, kvh = bk % Hkv, g = Hq / Hkv;
   const bf16_t* Kh = K + (int64_t)bk * P * 128;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int n16 = lane & 15, j4 = lane >> 4;
   const int Pq = prompt_len ? max(0, min(prompt_len[b], P)) : P;   // queries beyond the sequence's own prompt are padding
-  const int k0 = blockIdx.x * kMT + 16 * wave;      // this wave's 16 keys
+  const int k0 = tile_x * kMT + 16 * wave;          // this wave's 16 keys
   const int my_key = k0 + n16;
   sc_bf16x8_t kfr[4];
   row_fragments(Kh, min(my_key, P - 1), j4, kfr);
   float colsum = 0.f;
-  const int first = blockIdx.x, n_rt = (P + kMT - 1) / kMT;
+  const int first = tile_x, n_rt = (P + kMT - 1) / kMT;
   const int total = g * (n_rt - first);             // (head, row tile) pairs, head-major
   uint4 reg[4];
   float2 st_reg = make_float2(0.f, 0.f);
@@ -338,10 +356,12 @@ static void launch_scores_mfma(const void* Q, const void* K, int B, int Hq, int 
   const float scale_log2 = (float)(1.4426950408889634 / sqrt(128.0));
   const int tiles = (P + kMT - 1) / kMT;
   const size_t lds1 = 2 * (size_t)kMTileBytes, lds2 = 2 * ((size_t)kMTileBytes + kMT * sizeof(float2));
-  score_rowstats_mfma_kernel<<<dim3(tiles, B * Hq), kScThreads, lds1, st>>>(
-      static_cast<const bf16_t*>(Q), static_cast<const bf16_t*>(K), Hq, Hkv, P, scale_log2, stats);
-  score_colsum_mfma_kernel<<<dim3(tiles, B * Hkv), kScThreads, lds2, st>>>(
-      static_cast<const bf16_t*>(Q), static_cast<const bf16_t*>(K), Hq, Hkv, P, scale_log2, stats, prompt_len, scores);
+  auto grid = [&](int heads, int per) { return (unsigned)(((heads / per + 7) / 8) * 8 * per * tiles); };
+  score_rowstats_mfma_kernel<<<grid(B * Hq, Hq / Hkv), kScThreads, lds1, st>>>(
+      static_cast<const bf16_t*>(Q), static_cast<const bf16_t*>(K), Hq, Hkv, P, scale_log2, tiles, B * Hq, stats);
+  score_colsum_mfma_kernel<<<grid(B * Hkv, 1), kScThreads, lds2, st>>>(
+      static_cast<const bf16_t*>(Q), static_cast<const bf16_t*>(K), Hq, Hkv, P, scale_log2, stats, prompt_len, tiles,
+      B * Hkv, scores);
 }
 
 template <typename T, int D>
