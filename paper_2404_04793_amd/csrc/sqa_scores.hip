@@ -262,6 +262,27 @@ __global__ __launch_bounds__(kScThreads) void score_rowstats_mfma_kernel(
     tile_store(buf, reg);
     __syncthreads();                                // tile kt visible; everyone is past tile kt-1
     if (kt + 1 < n_tiles) tile_request(Kh, (kt + 1) * kMT, P, reg);
+    if ((kt + 1) * kMT - 1 <= r0 && (kt + 1) * kMT <= P) {
+      // Every key of the tile is visible to every row of this wave (wave-uniform test; true for all tiles
+      // but the one on the diagonal): no mask, one running-max update and one rescale for the 64 keys,
+      // the scale folded into the exponent's multiply-add.
+      sc_f32x4_t s4[4];
+#pragma unroll
+      for (int sub = 0; sub < 4; ++sub) s4[sub] = block_product(buf, sub, qfr);
+      float raw = s4[0][0];
+#pragma unroll
+      for (int sub = 0; sub < 4; ++sub)
+#pragma unroll
+        for (int e = 0; e < 4; ++e) raw = fmaxf(raw, s4[sub][e]);
+      const float mx = fmaxf(m_run, raw * scale_log2);          // finite: the tile has valid keys
+      float sum = l_run * __builtin_amdgcn_exp2f(m_run - mx);
+#pragma unroll
+      for (int sub = 0; sub < 4; ++sub)
+#pragma unroll
+        for (int e = 0; e < 4; ++e) sum += __builtin_amdgcn_exp2f(fmaf(s4[sub][e], scale_log2, -mx));
+      l_run = sum; m_run = mx;
+      continue;
+    }
 #pragma unroll
     for (int sub = 0; sub < 4; ++sub) {
       const int c0 = kt * kMT + 16 * sub;
@@ -330,6 +351,21 @@ __global__ __launch_bounds__(kScThreads) void score_colsum_mfma_kernel(
     __syncthreads();
     if (it + 1 < total) request(it + 1);
     const int rt = first + it % (n_rt - first);
+    if (rt * kMT >= k0 + 15 && (rt + 1) * kMT <= Pq) {
+      // every row of the tile sees every key of this wave and is a real query (wave-uniform; all tiles
+      // but the diagonal and the last): no mask
+#pragma unroll
+      for (int sub = 0; sub < 4; ++sub) {
+        const sc_f32x4_t s4 = block_product(buf, sub, kfr);
+        const float4 sa = *reinterpret_cast<const float4*>(&st_lds[16 * sub + 4 * j4]);
+        const float4 sb = *reinterpret_cast<const float4*>(&st_lds[16 * sub + 4 * j4 + 2]);
+        colsum = fmaf(__builtin_amdgcn_exp2f(fmaf(s4[0], scale_log2, -sa.x)), sa.y, colsum);
+        colsum = fmaf(__builtin_amdgcn_exp2f(fmaf(s4[1], scale_log2, -sa.z)), sa.w, colsum);
+        colsum = fmaf(__builtin_amdgcn_exp2f(fmaf(s4[2], scale_log2, -sb.x)), sb.y, colsum);
+        colsum = fmaf(__builtin_amdgcn_exp2f(fmaf(s4[3], scale_log2, -sb.z)), sb.w, colsum);
+      }
+      continue;
+    }
 #pragma unroll
     for (int sub = 0; sub < 4; ++sub) {
       const int i0 = rt * kMT + 16 * sub;
