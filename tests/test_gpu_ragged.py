@@ -64,11 +64,12 @@ def test_prefill_scores_ragged(sqa, dtype, D, g):
             assert np.all(got[b, h, n:] == 0.0)
 
 
-@pytest.mark.parametrize("policy", ["sliding", "streaming", "h2o"])
-def test_ragged_batch_end_to_end(sqa, policy):
+@pytest.mark.parametrize("policy,g", [("sliding", 2), ("streaming", 2), ("h2o", 2), ("h2o", 8), ("sliding", 8)])
+def test_ragged_batch_end_to_end(sqa, policy, g):
     """Three sequences with different prompt lengths and budgets through scores ->
-    compress -> decode (teacher forced), one of them sitting out some steps."""
-    dtype, L, Hkv, g, D, B, P, S = "bf16", 2, 2, 2, 128, 3, 150, 7
+    compress -> decode (teacher forced), one of them sitting out some steps.  g = 8 takes the
+    matrix-core variant of the decode kernel."""
+    dtype, L, Hkv, D, B, P, S = "bf16", 2, 2, 128, 3, 150, 7
     Hq = Hkv * g
     plen = [150, 61, 9]
     lo = {"sliding": 1, "streaming": 5, "h2o": 2}[policy]
