@@ -97,6 +97,13 @@ typedef struct sqa_layer_cache {
                                                 it too after editing a unit's scores,
                                                 positions or budget) ("evict_hint")
                             [3]                 reserved, written as 0              */
+  const int64_t* unit_offset; /* NULL: every unit owns `capacity` slots, unit u the slots
+                          [u*capacity, (u+1)*capacity) of K, V, score_acc and pos (the
+                          shapes above).  Otherwise DEVICE int64 [B*Hkv + 1], ascending:
+                          units are packed, unit u owns slots [unit_offset[u],
+                          unit_offset[u+1]) -- as many as ITS budget needs, which is what
+                          saves memory when budgets differ per sequence; `capacity` is
+                          then the largest of them                                  */
   int32_t capacity;    /* slots per unit; >= min(budget, longest length reached)   */
   int32_t budget;      /* b^(i): most tokens this layer keeps                      */
 } sqa_layer_cache;
@@ -292,7 +299,8 @@ sqa_status sqa_read_device_status(const void* workspace, void* stream, int32_t* 
 
 /* ---- kept indices in ascending order (a view for callers and tests) -------
  * out[b][hkv][i] = i-th smallest position held by the unit, -1 for i >= len.
- *   out : DEVICE int32 [B][Hkv][layer->capacity] */
+ *   out : DEVICE int32 [B][Hkv][layer->capacity]; with packed units (unit_offset)
+ *         laid out like pos: unit u's entries start at out[unit_offset[u]] */
 sqa_status sqa_kept_idx_sorted(const sqa_layer_cache* layer, int B, int Hkv, int32_t* out, void* stream);
 
 #ifdef __cplusplus

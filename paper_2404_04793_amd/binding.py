@@ -39,7 +39,7 @@ class SqaError(RuntimeError):
 class LayerCacheStruct(C.Structure):
     """Mirror of sqa_layer_cache."""
     _fields_ = [("K", C.c_void_p), ("V", C.c_void_p), ("score_acc", C.c_void_p), ("pos", C.c_void_p),
-                ("unit_state", C.c_void_p),
+                ("unit_state", C.c_void_p), ("unit_offset", C.c_void_p),
                 ("capacity", C.c_int32), ("budget", C.c_int32)]
 
 
@@ -207,17 +207,35 @@ class LayerCaches:
     sqa_layer_cache table on the host and its copy on the device."""
 
     def __init__(self, budgets: Sequence[int], capacities: Sequence[int], B: int, Hkv: int, D: int,
-                 dtype: torch.dtype, device, with_scores: bool = True):
+                 dtype: torch.dtype, device, with_scores: bool = True,
+                 unit_capacities: Optional[Sequence[Sequence[int]]] = None):
+        """unit_capacities[l][b*Hkv + h] (optional): packed units -- every unit gets exactly that many
+        slots (sqa_layer_cache.unit_offset); K, V, score, pos of a layer are then flat over the slots and
+        `capacities[l]` must be the largest of them.  Use unit(l, b, h) to address a unit either way."""
         self.L, self.B, self.Hkv, self.D, self.dtype = len(budgets), B, Hkv, D, dtype
         self.budgets, self.capacities = list(budgets), list(capacities)
         self.K, self.V, self.score, self.pos, self.state = [], [], [], [], []
         self.lens, self.head, self.hint = [], [], []        # views of the [B, Hkv, 4] unit_state records
+        self.offsets: List[Optional[torch.Tensor]] = []
+        self.offsets_host: List[Optional[List[int]]] = []
         self.table = (LayerCacheStruct * self.L)()
         for i, (b, cap) in enumerate(zip(budgets, capacities)):
-            self.K.append(torch.zeros(B, Hkv, cap, D, dtype=dtype, device=device))
-            self.V.append(torch.zeros(B, Hkv, cap, D, dtype=dtype, device=device))
-            self.score.append(torch.zeros(B, Hkv, cap, dtype=torch.float32, device=device) if with_scores else None)
-            self.pos.append(torch.full((B, Hkv, cap), -1, dtype=torch.int32, device=device))
+            if unit_capacities is None:
+                shape_rows, shape_flat = (B, Hkv, cap, D), (B, Hkv, cap)
+                self.offsets.append(None); self.offsets_host.append(None)
+            else:
+                caps_u = [int(x) for x in unit_capacities[i]]
+                assert len(caps_u) == B * Hkv and max(caps_u) == cap
+                off = [0]
+                for x in caps_u:
+                    off.append(off[-1] + x)
+                shape_rows, shape_flat = (off[-1], D), (off[-1],)
+                self.offsets_host.append(off)
+                self.offsets.append(torch.tensor(off, dtype=torch.int64, device=device))
+            self.K.append(torch.zeros(*shape_rows, dtype=dtype, device=device))
+            self.V.append(torch.zeros(*shape_rows, dtype=dtype, device=device))
+            self.score.append(torch.zeros(*shape_flat, dtype=torch.float32, device=device) if with_scores else None)
+            self.pos.append(torch.full(shape_flat, -1, dtype=torch.int32, device=device))
             st = torch.zeros(B, Hkv, 4, dtype=torch.int32, device=device)
             st[..., 2] = -2
             self.state.append(st)
@@ -226,9 +244,23 @@ class LayerCaches:
             t.K, t.V = self.K[i].data_ptr(), self.V[i].data_ptr()
             t.score_acc = self.score[i].data_ptr() if with_scores else None
             t.pos, t.unit_state = self.pos[i].data_ptr(), self.state[i].data_ptr()
+            t.unit_offset = None if self.offsets[i] is None else self.offsets[i].data_ptr()
             t.capacity, t.budget = int(cap), int(b)
         raw = bytes(memoryview(self.table))
         self.table_dev = torch.frombuffer(bytearray(raw), dtype=torch.uint8).to(device)
+
+    def unit(self, layer: int, b: int, h: int):
+        """(K, V, score or None, pos) views of unit (b, h): [slots, D], [slots, D], [slots], [slots]."""
+        sc = self.score[layer]
+        if self.offsets_host[layer] is None:
+            return self.K[layer][b, h], self.V[layer][b, h], None if sc is None else sc[b, h], self.pos[layer][b, h]
+        u = b * self.Hkv + h
+        lo, hi = self.offsets_host[layer][u], self.offsets_host[layer][u + 1]
+        return self.K[layer][lo:hi], self.V[layer][lo:hi], None if sc is None else sc[lo:hi], self.pos[layer][lo:hi]
+
+    def total_slots(self, layer: int) -> int:
+        off = self.offsets_host[layer]
+        return self.B * self.Hkv * self.capacities[layer] if off is None else off[-1]
 
     def struct_ptr(self, layer: int = 0):
         return C.cast(C.byref(self.table, layer * C.sizeof(LayerCacheStruct)), _LCp)
@@ -306,7 +338,9 @@ def read_device_status(workspace: torch.Tensor) -> int:
 
 def kept_idx_sorted(caches: LayerCaches, layer: int) -> torch.Tensor:
     """-> int32 [B, Hkv, capacity]: kept positions ascending, -1 padded."""
-    out = torch.empty(caches.B, caches.Hkv, caches.capacities[layer], dtype=torch.int32, device=caches.K[layer].device)
+    shape = (caches.B, caches.Hkv, caches.capacities[layer]) if caches.offsets_host[layer] is None \
+        else (caches.total_slots(layer),)
+    out = torch.empty(*shape, dtype=torch.int32, device=caches.K[layer].device)
     _check(_lib.sqa_kept_idx_sorted(caches.struct_ptr(layer), caches.B, caches.Hkv, _ptr(out), _stream()),
            "sqa_kept_idx_sorted")
     return out

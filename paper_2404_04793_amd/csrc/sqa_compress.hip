@@ -67,7 +67,8 @@ __global__ __launch_bounds__(kCmpThreads) void prefill_compress_kernel(
   const int tid = threadIdx.x;
   const int u = blockIdx.x;
   const int bidx = u / batch.Hkv;
-  const int cap = L.capacity;
+  const int64_t uoff = L.unit_offset ? L.unit_offset[u] : (int64_t)u * L.capacity;   // the unit's first slot
+  const int cap = L.unit_offset ? (int)(L.unit_offset[u + 1] - uoff) : L.capacity;
   const int P_pad = P;                                     // row pitch of the prompt tensors
   int b = L.budget;
   if (batch.prompt_len || batch.budget_seq) {
@@ -83,7 +84,14 @@ __global__ __launch_bounds__(kCmpThreads) void prefill_compress_kernel(
       return;
     }
   }
-  const int n_keep = P < b ? P : b;
+  int n_keep = P < b ? P : b;
+  if (n_keep > cap) {                                      // packed units: this one was given too few slots
+    if (tid == 0) {
+      *reinterpret_cast<int4*>(L.unit_state + (int64_t)u * SQA_ST_WORDS) = make_int4(0, 0, -2, 0);
+      if (batch.status) *batch.status = SQA_ERR_CAPACITY;
+    }
+    return;
+  }
   int* s_idx = reinterpret_cast<int*>(s_mem);              // [n_keep] kept positions, ascending
   uint32_t* s_keys = s_mem + n_keep;                       // [M] when staged
   const float* sc = scores ? scores + (int64_t)u * P_pad : nullptr;
@@ -157,8 +165,8 @@ __global__ __launch_bounds__(kCmpThreads) void prefill_compress_kernel(
   // gather rows, scores, positions
   const T* Ku = K + (int64_t)u * P_pad * D;
   const T* Vu = V + (int64_t)u * P_pad * D;
-  char* Kc = reinterpret_cast<char*>(L.K) + (int64_t)u * cap * ROWB;
-  char* Vc = reinterpret_cast<char*>(L.V) + (int64_t)u * cap * ROWB;
+  char* Kc = reinterpret_cast<char*>(L.K) + uoff * ROWB;
+  char* Vc = reinterpret_cast<char*>(L.V) + uoff * ROWB;
   const int grp = tid / LPR, c = tid % LPR;
   constexpr int GROUPS = kCmpThreads / LPR;
   for (int j = grp; j < n_keep; j += 2 * GROUPS) {
@@ -176,11 +184,11 @@ __global__ __launch_bounds__(kCmpThreads) void prefill_compress_kernel(
       st16(Vc + (int64_t)j2 * ROWB + c * 16, v2);
     }
   }
-  int32_t* posu = L.pos + (int64_t)u * cap;
+  int32_t* posu = L.pos + uoff;
   for (int j = tid; j < n_keep; j += kCmpThreads) {
     const int src = s_idx[j];
     posu[j] = src;
-    if (L.score_acc) L.score_acc[(int64_t)u * cap + j] = sc ? sc[src] : 0.f;
+    if (L.score_acc) L.score_acc[uoff + j] = sc ? sc[src] : 0.f;
   }
   if (tid == 0) *reinterpret_cast<int4*>(L.unit_state + (int64_t)u * SQA_ST_WORDS) = make_int4(n_keep, 0, -2, 0);
 }
@@ -189,11 +197,13 @@ __global__ __launch_bounds__(kCmpThreads) void prefill_compress_kernel(
 __global__ __launch_bounds__(kCmpThreads) void kept_idx_sorted_kernel(sqa_layer_cache L, int32_t* __restrict__ out) {
   extern __shared__ uint32_t s_mem[];
   int* s_pos = reinterpret_cast<int*>(s_mem);
-  const int u = blockIdx.x, cap = L.capacity;
+  const int u = blockIdx.x;
+  const int64_t uoff = L.unit_offset ? L.unit_offset[u] : (int64_t)u * L.capacity;
+  const int cap = L.unit_offset ? (int)(L.unit_offset[u + 1] - uoff) : L.capacity;
   int len = L.unit_state[(int64_t)u * SQA_ST_WORDS + SQA_ST_LEN];
   len = len < 0 ? 0 : (len > cap ? cap : len);
-  const int32_t* posu = L.pos + (int64_t)u * cap;
-  int32_t* o = out + (int64_t)u * cap;
+  const int32_t* posu = L.pos + uoff;
+  int32_t* o = out + uoff;
   for (int i = threadIdx.x; i < len; i += kCmpThreads) s_pos[i] = posu[i];
   for (int i = len + threadIdx.x; i < cap; i += kCmpThreads) o[i] = -1;
   __syncthreads();

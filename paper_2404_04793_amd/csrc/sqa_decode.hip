@@ -271,7 +271,8 @@ __global__ __launch_bounds__(kDecThreads, MF ? SQA_DEC_MF_WAVES : 1) SQA_DEC_OCC
   float* s_lg = s_logit + (wpu ? wave * G * a.lds_chunk_w : 0);
   const int bidx = u / a.Hkv, kvh = u % a.Hkv;
   const sqa_layer_cache L = a.layers[layer];
-  const int cap = L.capacity;
+  const int64_t uoff = L.unit_offset ? L.unit_offset[u] : (int64_t)u * L.capacity;   // the unit's first slot
+  const int cap = L.unit_offset ? (int)(L.unit_offset[u + 1] - uoff) : L.capacity;
   const int budget = a.budget_seq ? a.budget_seq[layer * a.B + bidx] : L.budget;
   const bool sits_out = a.new_pos_seq && a.new_pos_seq[bidx] < 0;
   const int hh = H2O ? budget / 2 : (a.policy == SQA_STREAMING ? min(a.n_sink, budget) : 0);
@@ -282,12 +283,12 @@ __global__ __launch_bounds__(kDecThreads, MF ? SQA_DEC_MF_WAVES : 1) SQA_DEC_OCC
   const int64_t qoff = (((int64_t)layer * a.B + bidx) * a.Hq + (int64_t)kvh * G) * D;
   const int64_t kvoff = (((int64_t)layer * a.B + bidx) * a.Hkv + kvh) * D;
   char* outp = reinterpret_cast<char*>(a.out) + qoff * (int64_t)sizeof(T);
-  const char* Kb = reinterpret_cast<const char*>(L.K) + (int64_t)u * cap * ROWB;
-  const char* Vb = reinterpret_cast<const char*>(L.V) + (int64_t)u * cap * ROWB;
+  const char* Kb = reinterpret_cast<const char*>(L.K) + uoff * ROWB;
+  const char* Vb = reinterpret_cast<const char*>(L.V) + uoff * ROWB;
   const char* knew = reinterpret_cast<const char*>(a.k_new) + kvoff * (int64_t)sizeof(T);
   const char* vnew = reinterpret_cast<const char*>(a.v_new) + kvoff * (int64_t)sizeof(T);
-  float* sc = H2O ? L.score_acc + (int64_t)u * cap : nullptr;
-  const int32_t* posu = L.pos + (int64_t)u * cap;
+  float* sc = H2O ? L.score_acc + uoff : nullptr;
+  const int32_t* posu = L.pos + uoff;
 
   // Everything that does not depend on the unit's length is requested now, so
   // that one memory round trip covers the bookkeeping words, q, the new token's
@@ -357,7 +358,7 @@ __global__ __launch_bounds__(kDecThreads, MF ? SQA_DEC_MF_WAVES : 1) SQA_DEC_OCC
   // ---- 1. stream the chunk's K and V once, online softmax -------------------
   const int c_end = min(c0 + csize, n);
   const int lpitch = cap + 1;                      // logit row of one head in scratch (the new token may be slot cap)
-  float* glogit = (H2O && nsplit > 1) ? a.logit + a.lay[layer].logit_off + (int64_t)u * G * lpitch : nullptr;
+  float* glogit = (H2O && nsplit > 1) ? a.logit + a.lay[layer].logit_off + (uoff + u) * G : nullptr;   // units before this one hold uoff slots + one spare each
 
   if constexpr (MF) {
     // ---- 1M. matrix-core streaming ------------------------------------------
@@ -748,7 +749,7 @@ __global__ __launch_bounds__(kDecThreads, MF ? SQA_DEC_MF_WAVES : 1) SQA_DEC_OCC
     st16(Kw + (int64_t)slot_wr * ROWB + c * 16, kn_pre);
     st16(Vw + (int64_t)slot_wr * ROWB + c * 16, vn_pre);
     if (c == 0) {
-      int32_t* posw = L.pos + (int64_t)u * cap;
+      int32_t* posw = L.pos + uoff;
       if (dst >= 0) posw[dst] = posw[slot_wr];
       posw[slot_wr] = a.new_pos_seq ? a.new_pos_seq[bidx] : a.new_pos;   // (read again: not kept in a register all along)
       *reinterpret_cast<int4*>(L.unit_state + (int64_t)u * SQA_ST_WORDS) =

@@ -121,9 +121,11 @@ class Session:
         budget_seq = [[per_seq[b][l] for b in range(wl.B)] for l in range(wl.L)]         # [L][B]
         budgets = [max(row) for row in budget_seq]                                       # the layers' maxima
         if self.caches is None or budget_seq != self.budget_seq:
-            caps = [min(b, wl.P + wl.S) for b in budgets]
-            self.caches = sqa.LayerCaches(budgets, caps, wl.B, wl.Hkv, wl.D, wl.torch_dtype, self.dev,
-                                          wl.policy == "h2o")
+            # packed units: every (sequence, head) owns exactly the slots its own budget can fill
+            unit_caps = [[min(budget_seq[l][b], self.prompt_len[b] + wl.S) for b in range(wl.B) for _ in range(wl.Hkv)]
+                         for l in range(wl.L)]
+            self.caches = sqa.LayerCaches(budgets, [max(c) for c in unit_caps], wl.B, wl.Hkv, wl.D, wl.torch_dtype,
+                                          self.dev, wl.policy == "h2o", unit_capacities=unit_caps)
             self.dec_ws = sqa.decode_workspace(self.caches, wl.Hq, wl.policy)
             self.dec_ws_layer = [sqa.decode_workspace(self.caches, wl.Hq, wl.policy, l, 1) for l in range(wl.L)]
             self.bseq_dev = torch.tensor(budget_seq, dtype=torch.int32, device=self.dev)
@@ -228,4 +230,4 @@ class Session:
     def resident_kv_bytes(self) -> int:
         wl = self.wl
         per_slot = 2 * wl.D * wl.elem_bytes + (8 if wl.policy == "h2o" else 4)
-        return sum(wl.B * wl.Hkv * c * per_slot for c in self.caches.capacities)
+        return sum(self.caches.total_slots(l) * per_slot for l in range(wl.L))

@@ -28,12 +28,13 @@ def import_state(caches, layer: int, b: int, h: int, c: dict) -> None:
     n = len(c["pos"])
     dev = caches.K[layer].device
     dt = caches.dtype
-    caches.K[layer][b, h, :n] = torch.from_numpy(c["K"]).to(dt).to(dev)
-    caches.V[layer][b, h, :n] = torch.from_numpy(c["V"]).to(dt).to(dev)
-    caches.pos[layer][b, h, :n] = torch.from_numpy(c["pos"].astype(np.int32)).to(dev)
-    caches.pos[layer][b, h, n:] = -1
-    if caches.score[layer] is not None:
-        caches.score[layer][b, h, :n] = torch.from_numpy(c["score"]).to(torch.float32).to(dev)
+    K, V, score, pos = caches.unit(layer, b, h)
+    K[:n] = torch.from_numpy(c["K"]).to(dt).to(dev)
+    V[:n] = torch.from_numpy(c["V"]).to(dt).to(dev)
+    pos[:n] = torch.from_numpy(c["pos"].astype(np.int32)).to(dev)
+    pos[n:] = -1
+    if score is not None:
+        score[:n] = torch.from_numpy(c["score"]).to(torch.float32).to(dev)
     caches.lens[layer][b, h] = n
     caches.head[layer][b, h] = 0
     caches.hint[layer][b, h] = -2          # scores were edited: no eviction decision carried over
@@ -42,11 +43,12 @@ def import_state(caches, layer: int, b: int, h: int, c: dict) -> None:
 def export_state(caches, layer: int, b: int, h: int) -> dict:
     """Unit (b, h) of a layer as an oracle-style cache sorted by position."""
     n = int(caches.lens[layer][b, h].item())
-    pos = caches.pos[layer][b, h, :n].cpu().numpy().astype(np.int64)
+    K, V, score, pos_t = caches.unit(layer, b, h)
+    pos = pos_t[:n].cpu().numpy().astype(np.int64)
     order = np.argsort(pos, kind="stable")
-    out = {"pos": pos[order], "K": np64(caches.K[layer][b, h, :n])[order], "V": np64(caches.V[layer][b, h, :n])[order]}
-    if caches.score[layer] is not None:
-        out["score"] = np64(caches.score[layer][b, h, :n])[order]
+    out = {"pos": pos[order], "K": np64(K[:n])[order], "V": np64(V[:n])[order]}
+    if score is not None:
+        out["score"] = np64(score[:n])[order]
     else:
         out["score"] = np.zeros(n)
     return out

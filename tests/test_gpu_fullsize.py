@@ -207,8 +207,15 @@ def test_llama2_7b_ragged_batch():
                 worst = max(worst, rel_err(np64(sess.out[t, l, b, h * g:(h + 1) * g]), want_out))
     assert worst < tol and sqa.read_device_status(sess.dec_ws) == 0
     for l in range(wl.L):                                    # every unit: its own length and newest position
+        kept_all = sqa.kept_idx_sorted(sess.caches, l)       # packed like pos: unit u starts at unit_offset[u]
+        off = sess.caches.offsets_host[l]
         for b in range(wl.B):
             n = min(plen[b] + wl.S, sess.budget_seq[l][b])
             assert bool((sess.caches.lens[l][b] == n).all())
-            kept = sqa.kept_idx_sorted(sess.caches, l)[b, :, :n]
-            assert int(kept.max()) == plen[b] + wl.S - 1 and bool((kept[:, 1:] > kept[:, :-1]).all())
+            for h in range(wl.Hkv):
+                lo = off[b * wl.Hkv + h]
+                assert off[b * wl.Hkv + h + 1] - lo == n     # exact fit
+                kept = kept_all[lo:lo + n]
+                assert int(kept[-1]) == plen[b] + wl.S - 1 and bool((kept[1:] > kept[:-1]).all())
+    dense = sum(wl.B * wl.Hkv * c for c in sess.caches.capacities)
+    assert sum(sess.caches.total_slots(l) for l in range(wl.L)) < 0.85 * dense      # the memory the packing saves

@@ -64,11 +64,13 @@ def test_prefill_scores_ragged(sqa, dtype, D, g):
             assert np.all(got[b, h, n:] == 0.0)
 
 
-@pytest.mark.parametrize("policy,g", [("sliding", 2), ("streaming", 2), ("h2o", 2), ("h2o", 8), ("sliding", 8)])
-def test_ragged_batch_end_to_end(sqa, policy, g):
+@pytest.mark.parametrize("policy,g,packed", [("sliding", 2, False), ("streaming", 2, True), ("h2o", 2, False),
+                                              ("h2o", 2, True), ("h2o", 8, True), ("sliding", 8, False)])
+def test_ragged_batch_end_to_end(sqa, policy, g, packed):
     """Three sequences with different prompt lengths and budgets through scores ->
     compress -> decode (teacher forced), one of them sitting out some steps.  g = 8 takes the
-    matrix-core variant of the decode kernel."""
+    matrix-core variant of the decode kernel; packed: every unit owns exactly the slots its own
+    budget needs (unit_offset) instead of the layer's maximum."""
     dtype, L, Hkv, D, B, P, S = "bf16", 2, 2, 128, 3, 150, 7
     Hq = Hkv * g
     plen = [150, 61, 9]
@@ -77,7 +79,9 @@ def test_ragged_batch_end_to_end(sqa, policy, g):
     layer_budget = [max(r) for r in budget_seq]
     wl = W.scaled(W.WORKLOADS["tiny"], L=L, Hq=Hq, Hkv=Hkv, D=D, B=B, P=P, S=S, dtype=dtype, policy=policy)
     u_dirs, mask = W.unit_dirs(wl), W.hh_mask(wl, DEV)
-    caches = sqa.LayerCaches(layer_budget, [min(b, P + S) for b in layer_budget], B, Hkv, D, torch.bfloat16, DEV, True)
+    unit_caps = [[min(budget_seq[l][b], plen[b] + S) for b in range(B) for _ in range(Hkv)] for l in range(L)]
+    caches = sqa.LayerCaches(layer_budget, [max(c) for c in unit_caps] if packed else [min(b, P + S) for b in layer_budget],
+                             B, Hkv, D, torch.bfloat16, DEV, True, unit_capacities=unit_caps if packed else None)
     status = torch.zeros(1, dtype=torch.int32, device=DEV)
     plen_d, bseq_d = _i32(plen), _i32(budget_seq)
     opts_pre = sqa.batch_opts(prompt_len=plen_d, budget_seq=bseq_d, status=status)
@@ -137,6 +141,18 @@ def test_ragged_batch_end_to_end(sqa, policy, g):
         for b in range(B):
             pos_now[b] += 1 if active[b] else 0
     assert worst < TOL[dtype]
+    for l in range(L):                                   # the sorted view, in the layout of pos
+        kept = sqa.kept_idx_sorted(caches, l).cpu().numpy()
+        for b in range(B):
+            for h in range(Hkv):
+                want = state[l, b, h]["pos"].tolist()
+                if packed:
+                    lo = caches.offsets_host[l][b * Hkv + h]
+                    hi = caches.offsets_host[l][b * Hkv + h + 1]
+                    row = kept[lo:hi]
+                else:
+                    row = kept[b, h]
+                assert row[:len(want)].tolist() == want and np.all(row[len(want):] == -1)
 
 
 def test_out_of_range_per_sequence_values_are_reported(sqa):
@@ -159,3 +175,8 @@ def test_out_of_range_per_sequence_values_are_reported(sqa):
     sqa.decode_step(q, q, q, 40, "sliding", 4, caches, out, ws, opts=sqa.batch_opts(budget_seq=_i32([[9, 3]])))
     assert sqa.read_device_status(ws) == 5
     assert caches.lens[0][:, 0].tolist() == [0, 3] and bool((out[0, 0] == 0).all()) and not bool((out[0, 1] == 0).any())
+    # packed units: a unit that was given fewer slots than its budget keeps is reported and left empty
+    small = sqa.LayerCaches([8], [8], B, Hkv, D, torch.float32, DEV, True, unit_capacities=[[8, 5]])
+    status.zero_()
+    sqa.prefill_compress_layers([K], [V], None, "sliding", 4, small, opts=sqa.batch_opts(status=status))
+    assert int(status.item()) == 6 and small.lens[0][:, 0].tolist() == [8, 0]
