@@ -165,3 +165,39 @@ def test_header_is_plain_c(tmp_path):
                         str(src), "-o", str(tmp_path / "use_header")], capture_output=True, text=True)
     assert r.returncode == 0, r.stderr
     assert subprocess.run([str(tmp_path / "use_header")]).returncode == 0
+
+
+def test_host_entry_point_called_from_c(tmp_path):
+    """A C program linked against libsqa.so reproduces the worked example of Appendix A.2
+    (b_init 1000, p 0.3, 18 important layers of 32: 300 for the others, 1544 or 1545 for the important ones)."""
+    import shutil
+    import subprocess
+    gcc = shutil.which("gcc")
+    if gcc is None:
+        pytest.skip("no gcc")
+    libdir = os.path.dirname(sqa.LIB_PATH)
+    src = tmp_path / "budgets.c"
+    src.write_text(r'''
+#include <stdio.h>
+#include "sqa.h"
+int main(void) {
+  float cos[32]; int32_t budget[32]; int8_t group[32];
+  /* 2 special layers near 0.4, 16 around 0.7, 14 around 0.96: the 14 form G3 */
+  for (int i = 0; i < 32; ++i) cos[i] = i < 2 ? 0.40f + 0.01f * i : (i < 16 || i >= 30 ? 0.70f + 0.0005f * i : 0.95f + 0.0005f * i);
+  sqa_status st = sqa_allocate_budgets(cos, 32, 32000, 0.3, budget, group);
+  if (st != SQA_OK) { printf("status %s\n", sqa_status_str(st)); return 2; }
+  long sum = 0; int n3 = 0;
+  for (int i = 0; i < 32; ++i) { sum += budget[i]; n3 += group[i] == 2; }
+  printf("%ld %d %d %d\n", sum, n3, (int)budget[20], (int)budget[5]);
+  return sqa_allocate_budgets(cos, 32, 16, 0.3, budget, group) == SQA_ERR_BUDGET ? 0 : 3;
+}
+''')
+    exe = tmp_path / "budgets"
+    r = subprocess.run([gcc, "-std=c99", "-Wall", "-I", os.path.join(ROOT, "include"), str(src), "-o", str(exe),
+                        "-L", libdir, "-lsqa", "-Wl,-rpath," + libdir, "-Wl,-rpath,/opt/rocm/lib"],
+                       capture_output=True, text=True)
+    assert r.returncode == 0, r.stderr
+    run = subprocess.run([str(exe)], capture_output=True, text=True)
+    assert run.returncode == 0, (run.stdout, run.stderr)
+    total, n3, low, high = [int(x) for x in run.stdout.split()]
+    assert total == 32000 and n3 == 14 and low == 300 and high in (1544, 1545)   # 14 x 300 + 18 x 1544.4 = 32000
