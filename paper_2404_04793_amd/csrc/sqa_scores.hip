@@ -15,6 +15,9 @@
 
 namespace sqa {
 
+#ifndef SQA_SC_NB
+#define SQA_SC_NB 2          // 16-row blocks a wave of the matrix-core kernels keeps in registers (4: no faster)
+#endif
 constexpr int kScThreads = 256;
 constexpr int kTile = 64;        // rows and columns of a logit tile
 constexpr int kDK = 32;          // slab of the head dimension staged per step
@@ -192,215 +195,288 @@ __global__ __launch_bounds__(kScThreads) void score_colsum_kernel(
 //   a lane = 8*(lane/16)+e; C column = lane%16, rows 4*(lane/16)+i.  For both
 //   operands slot (j,e) of step i stands for d = 32j + 8i + e, so a lane's four
 //   fragments are 64 contiguous bytes of its row.
-//   pass 1  S^T = K.Q^T: a wave keeps its 16 query rows as the B operand in
-//           registers; 64-key tiles of K are staged in LDS (row-padded, double
-//           buffered) and shared by the 4 waves of the workgroup (64 query rows).
-//           A lane sees 4 keys of one query per product and keeps a running
-//           (max, sum) of its own; the 4 lanes of a query merge once at the end.
-//   pass 2  S = Q.K^T: a wave keeps its 16 keys as the B operand; 64-row tiles
-//           of Q (and their row statistics) are staged in LDS; a lane sees 4
-//           query rows of one key per product and adds exp2(s - m_i)/l_i into a
-//           per-lane column sum over all row tiles and all g heads of the group.
-// exp2 runs at a quarter of the vector rate, so the two passes are bound by
-// the P^2/2 exponentials per head about as much as by the products.
+//   pass 1  S^T = K.Q^T: a wave keeps NB blocks of 16 query rows as B operands
+//           in registers (block b of wave w = rows 16 (w + 4 b) of the
+//           workgroup's 64 NB rows, so the diagonal's work is spread evenly);
+//           64-key tiles of K go from global memory straight into LDS (direct
+//           loads, no register staging; 16-byte pieces XOR-swizzled by the row;
+//           two buffers) and are shared by the 4 waves.  Every fragment read
+//           from LDS feeds NB products.  A lane sees 4 keys of one query per
+//           product and keeps a running (reference, sum) of its own; the 4
+//           lanes of a query merge once at the end and store
+//           c_i = m_i + log2(l_i), so that pass 2 needs one value per row.
+//   pass 2  S = Q.K^T: a wave keeps NB blocks of 16 keys as B operands; 64-row
+//           tiles of Q and their c_i are staged in LDS the same way; a lane
+//           sees 4 query rows of one key per product and adds exp2(s - c_i)
+//           into a per-lane column sum over all row tiles and all g heads.
+// Per 16x16 block a lane issues 4 products (64 cycles of the matrix pipeline)
+// and at least 4 x (multiply-add, exp2, add); on this chip vector instructions
+// hide only partly behind matrix instructions of the same SIMD (measured: 16
+// products + 16 such triples take 466 cycles with 4 waves per SIMD, 268 and 297
+// on their own), so the two passes are bound by the sum of both, not by the
+// products: 31 % of the matrix pipeline's cycles are busy.
 typedef __bf16 sc_bf16x8_t __attribute__((ext_vector_type(8)));
 typedef float sc_f32x4_t __attribute__((ext_vector_type(4)));
 constexpr int kMT = 64;                 // rows of a staged tile
-constexpr int kMPitch = 256 + 16;       // LDS bytes per staged row (padded: conflict-free fragment reads)
+constexpr int kMPitch = 256;            // LDS bytes per staged row; 16-byte piece c of row R lies at piece c ^ (R % 16)
 constexpr int kMTileBytes = kMT * kMPitch;
+constexpr float kRefFar = 65536.f;       // a row's reference moves when 4 exponentials against it add up to this
 
-// request one [64 x 128] bf16 tile (rows row0.., clamped to P-1): 4 x 16 bytes per thread
-__device__ __forceinline__ void tile_request(const bf16_t* __restrict__ src, int row0, int P, uint4 (&reg)[4]) {
-  const int tid = threadIdx.x;
+typedef __attribute__((address_space(1))) const void sc_gptr_t;
+typedef __attribute__((address_space(3))) void sc_lptr_t;
+// Copy one [64 x 128] bf16 tile (rows row0.., clamped to P-1) straight into LDS, swizzled: each wave
+// instruction fills 1 KB = 4 rows, lane l the 16-byte position l%16 of row l/16 of them, so it fetches the
+// piece that belongs there (the permutation stays inside a 256-byte row: the access is still coalesced).
+__device__ __forceinline__ void tile_to_lds(const bf16_t* __restrict__ src, int row0, int P, char* lds) {
+  const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int rr = 4 * wave + (lane >> 4);            // row within a group of 16
 #pragma unroll
   for (int i = 0; i < 4; ++i) {
-    const int row = min(row0 + (tid >> 4) + 16 * i, P - 1);
-    reg[i] = ld16(src + (int64_t)row * 128 + (tid & 15) * 8);
+    const int row = min(row0 + 16 * i + rr, P - 1);
+    const bf16_t* g = src + (int64_t)row * 128 + (((lane & 15) ^ rr) * 8);
+    __builtin_amdgcn_global_load_lds((sc_gptr_t*)g, (sc_lptr_t*)(lds + (16 * i + 4 * wave) * kMPitch), 16, 0, 0);
   }
-}
-__device__ __forceinline__ void tile_store(char* lds, const uint4 (&reg)[4]) {
-  const int tid = threadIdx.x;
-#pragma unroll
-  for (int i = 0; i < 4; ++i)
-    *reinterpret_cast<uint4*>(lds + ((tid >> 4) + 16 * i) * kMPitch + (tid & 15) * 16) = reg[i];
 }
 // the four fragments of row `row` (global memory) for a lane with contraction group j
 __device__ __forceinline__ void row_fragments(const bf16_t* __restrict__ src, int row, int j, sc_bf16x8_t (&fr)[4]) {
 #pragma unroll
   for (int i = 0; i < 4; ++i) fr[i] = __builtin_bit_cast(sc_bf16x8_t, ld16(src + (int64_t)row * 128 + 32 * j + 8 * i));
 }
-// C = A_tile[16 sub .. 16 sub + 15] . B^T for one 16 x 16 block
-__device__ __forceinline__ sc_f32x4_t block_product(const char* lds, int sub, const sc_bf16x8_t (&bfr)[4]) {
+// the A fragments of rows 16 sub .. 16 sub + 15 of a staged tile
+__device__ __forceinline__ void tile_fragments(const char* lds, int sub, sc_bf16x8_t (&fr)[4]) {
   const int lane = threadIdx.x & 63;
-  const char* p = lds + (16 * sub + (lane & 15)) * kMPitch + (lane >> 4) * 64;
+  const char* p = lds + (16 * sub + (lane & 15)) * kMPitch;
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+    fr[i] = __builtin_bit_cast(sc_bf16x8_t, *reinterpret_cast<const uint4*>(p + (((4 * (lane >> 4) + i) ^ (lane & 15)) * 16)));
+}
+__device__ __forceinline__ sc_f32x4_t block_product(const sc_bf16x8_t (&afr)[4], const sc_bf16x8_t (&bfr)[4]) {
   sc_f32x4_t c = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    const uint4 w = *reinterpret_cast<const uint4*>(p + 16 * i);
-    c = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(sc_bf16x8_t, w), bfr[i], c, 0, 0, 0);
-  }
+  for (int i = 0; i < 4; ++i) c = __builtin_amdgcn_mfma_f32_16x16x32_bf16(afr[i], bfr[i], c, 0, 0, 0);
   return c;
 }
 
+template <int NB>
 __global__ __launch_bounds__(kScThreads) void score_rowstats_mfma_kernel(
     const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K, int Hq, int Hkv, int P, float scale_log2,
-    int tiles, int heads, float2* __restrict__ stats) {
+    int tiles, int heads, float* __restrict__ cstat /*[B*Hq][P]: m_i + log2(l_i) in the exp2 domain*/) {
   extern __shared__ char s_tiles[];                 // 2 x [64][kMPitch]
+  constexpr int OWN = kMT * NB;                     // query rows of a workgroup
   int tile_x, bh;
   if (!xcd_tile_head(tiles, heads, Hq / Hkv, true, tile_x, bh)) return;   // (query tile t reads key tiles 0..t: the last is the longest)
   const int b = bh / Hq, h = bh % Hq, kvh = h / (Hq / Hkv);
   const bf16_t* Qh = Q + (int64_t)bh * P * 128;
   const bf16_t* Kh = K + ((int64_t)b * Hkv + kvh) * P * 128;
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int n16 = lane & 15, j4 = lane >> 4;
-  const int r0 = tile_x * kMT + 16 * wave;          // this wave's 16 query rows
-  const int my_row = r0 + n16;
-  sc_bf16x8_t qfr[4];
-  row_fragments(Qh, min(my_row, P - 1), j4, qfr);
-  float m_run = -INFINITY, l_run = 0.f;
-  uint4 reg[4];
-  tile_request(Kh, 0, P, reg);
-  const int n_tiles = tile_x + 1;                   // key tiles 0 .. the diagonal one
+  const int r0 = tile_x * OWN + 16 * wave;          // first row of own block 0; block bb starts at r0 + 64 bb
+  sc_bf16x8_t qfr[NB][4];
+  float m_run[NB], l_run[NB];
+#pragma unroll
+  for (int bb = 0; bb < NB; ++bb) {
+    row_fragments(Qh, min(r0 + 64 * bb + n16, P - 1), j4, qfr[bb]);
+    m_run[bb] = -INFINITY; l_run[bb] = 0.f;
+  }
+  tile_to_lds(Kh, 0, P, s_tiles);
+  const int n_tiles = (min((tile_x + 1) * OWN, P) - 1) / kMT + 1;   // key tiles 0 .. the one holding the last row
   for (int kt = 0; kt < n_tiles; ++kt) {
     char* buf = s_tiles + (kt & 1) * kMTileBytes;
-    tile_store(buf, reg);
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // this wave's part of tile kt has landed
     __syncthreads();                                // tile kt visible; everyone is past tile kt-1
-    if (kt + 1 < n_tiles) tile_request(Kh, (kt + 1) * kMT, P, reg);
+    if (kt + 1 < n_tiles) tile_to_lds(Kh, (kt + 1) * kMT, P, s_tiles + ((kt + 1) & 1) * kMTileBytes);
     if ((kt + 1) * kMT - 1 <= r0 && (kt + 1) * kMT <= P) {
-      // Every key of the tile is visible to every row of this wave (wave-uniform test; true for all tiles
-      // but the one on the diagonal): no mask, one running-max update and one rescale for the 64 keys,
-      // the scale folded into the exponent's multiply-add.
-      sc_f32x4_t s4[4];
+      // Every key of the tile is visible to every row of this wave (wave-uniform test, block 0 has the
+      // lowest rows; true for all tiles but those on the diagonal): no mask.  The exponentials are taken
+      // against the row's current reference without looking for the maximum first; only when a partial
+      // sum shows that a logit lies far above the reference (or there is no reference yet: the sum is then
+      // infinite) does the wave redo the 16 keys with the reference moved.  After the first tiles that is
+      // rare, and the common case costs one comparison per block instead of a maximum per element.
 #pragma unroll
-      for (int sub = 0; sub < 4; ++sub) s4[sub] = block_product(buf, sub, qfr);
-      float raw = s4[0][0];
+      for (int sub = 0; sub < 4; ++sub) {
+        sc_bf16x8_t afr[4];
+        tile_fragments(buf, sub, afr);
+        sc_f32x4_t s4[NB];
+        float part[NB];
+        bool far = false;
 #pragma unroll
-      for (int sub = 0; sub < 4; ++sub)
+        for (int bb = 0; bb < NB; ++bb) {
+          s4[bb] = block_product(afr, qfr[bb]);
+          const float e0 = __builtin_amdgcn_exp2f(fmaf(s4[bb][0], scale_log2, -m_run[bb]));
+          const float e1 = __builtin_amdgcn_exp2f(fmaf(s4[bb][1], scale_log2, -m_run[bb]));
+          const float e2 = __builtin_amdgcn_exp2f(fmaf(s4[bb][2], scale_log2, -m_run[bb]));
+          const float e3 = __builtin_amdgcn_exp2f(fmaf(s4[bb][3], scale_log2, -m_run[bb]));
+          part[bb] = (e0 + e1) + (e2 + e3);
+          far |= !(part[bb] < kRefFar);
+        }
+        if (__builtin_amdgcn_ballot_w64(far)) {
 #pragma unroll
-        for (int e = 0; e < 4; ++e) raw = fmaxf(raw, s4[sub][e]);
-      const float mx = fmaxf(m_run, raw * scale_log2);          // finite: the tile has valid keys
-      float sum = l_run * __builtin_amdgcn_exp2f(m_run - mx);
+          for (int bb = 0; bb < NB; ++bb) {
+            const float top = fmaxf(fmaxf(s4[bb][0], s4[bb][1]), fmaxf(s4[bb][2], s4[bb][3])) * scale_log2;
+            const float mx = fmaxf(m_run[bb], top);                      // finite: the block has valid keys
+            l_run[bb] *= __builtin_amdgcn_exp2f(m_run[bb] - mx);
+            m_run[bb] = mx;
+            float sum = 0.f;
 #pragma unroll
-      for (int sub = 0; sub < 4; ++sub)
+            for (int e = 0; e < 4; ++e) sum += __builtin_amdgcn_exp2f(fmaf(s4[bb][e], scale_log2, -mx));
+            part[bb] = sum;
+          }
+        }
 #pragma unroll
-        for (int e = 0; e < 4; ++e) sum += __builtin_amdgcn_exp2f(fmaf(s4[sub][e], scale_log2, -mx));
-      l_run = sum; m_run = mx;
+        for (int bb = 0; bb < NB; ++bb) l_run[bb] += part[bb];
+      }
       continue;
     }
 #pragma unroll
     for (int sub = 0; sub < 4; ++sub) {
       const int c0 = kt * kMT + 16 * sub;
-      if (c0 > r0 + 15) continue;                   // wave-uniform: all keys beyond all of this wave's rows
-      const sc_f32x4_t s4 = block_product(buf, sub, qfr);
-      float v[4], mx = m_run;
+      if (c0 > r0 + 64 * (NB - 1) + 15 || c0 >= P) continue;   // wave-uniform: beyond all rows of this wave
+      sc_bf16x8_t afr[4];
+      tile_fragments(buf, sub, afr);
 #pragma unroll
-      for (int e = 0; e < 4; ++e) {
-        const int key = c0 + 4 * j4 + e;
-        v[e] = (key <= my_row && key < P) ? s4[e] * scale_log2 : -INFINITY;
-        mx = fmaxf(mx, v[e]);
+      for (int bb = 0; bb < NB; ++bb) {
+        const int rb = r0 + 64 * bb, my_row = rb + n16;
+        if (c0 > rb + 15) continue;                 // wave-uniform: all keys beyond all rows of the block
+        const sc_f32x4_t s4 = block_product(afr, qfr[bb]);
+        float v[4], mx = m_run[bb];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          const int key = c0 + 4 * j4 + e;
+          v[e] = (key <= my_row && key < P) ? s4[e] * scale_log2 : -INFINITY;
+          mx = fmaxf(mx, v[e]);
+        }
+        const float ms = mx == -INFINITY ? 0.f : mx;
+        float sum = l_run[bb] * __builtin_amdgcn_exp2f(m_run[bb] - ms);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) sum += __builtin_amdgcn_exp2f(v[e] - ms);
+        l_run[bb] = sum; m_run[bb] = mx;
       }
-      const float ms = mx == -INFINITY ? 0.f : mx;
-      float sum = l_run * __builtin_amdgcn_exp2f(m_run - ms);
-#pragma unroll
-      for (int e = 0; e < 4; ++e) sum += __builtin_amdgcn_exp2f(v[e] - ms);
-      l_run = sum; m_run = mx;
     }
   }
   // the 4 lanes of a query row (contraction groups) merge their statistics
 #pragma unroll
-  for (int o = 16; o < 64; o <<= 1) {
-    const float mo = __shfl_xor(m_run, o, 64), lo = __shfl_xor(l_run, o, 64);
-    const float mx = fmaxf(m_run, mo);
-    const float ms = mx == -INFINITY ? 0.f : mx;
-    l_run = l_run * __builtin_amdgcn_exp2f(m_run - ms) + lo * __builtin_amdgcn_exp2f(mo - ms);
-    m_run = mx;
+  for (int bb = 0; bb < NB; ++bb) {
+    float m = m_run[bb], l = l_run[bb];
+#pragma unroll
+    for (int o = 16; o < 64; o <<= 1) {
+      const float mo = __shfl_xor(m, o, 64), lo = __shfl_xor(l, o, 64);
+      const float mx = fmaxf(m, mo);
+      const float ms = mx == -INFINITY ? 0.f : mx;
+      l = l * __builtin_amdgcn_exp2f(m - ms) + lo * __builtin_amdgcn_exp2f(mo - ms);
+      m = mx;
+    }
+    const int my_row = r0 + 64 * bb + n16;
+    if (j4 == 0 && my_row < P) cstat[(int64_t)bh * P + my_row] = m + __builtin_amdgcn_logf(l);
   }
-  if (j4 == 0 && my_row < P) stats[(int64_t)bh * P + my_row] = make_float2(m_run, 1.f / l_run);
 }
 
+template <int NB>
 __global__ __launch_bounds__(kScThreads) void score_colsum_mfma_kernel(
     const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K, int Hq, int Hkv, int P, float scale_log2,
-    const float2* __restrict__ stats, const int32_t* __restrict__ prompt_len /*[B] or NULL*/,
+    const float* __restrict__ cstat, const int32_t* __restrict__ prompt_len /*[B] or NULL*/,
     int tiles, int heads, float* __restrict__ scores) {
-  extern __shared__ char s_tiles[];                 // 2 x ([64][kMPitch] + 64 float2)
-  constexpr int BUF = kMTileBytes + kMT * (int)sizeof(float2);
+  extern __shared__ char s_tiles[];                 // 2 x ([64][kMPitch] + 64 floats)
+  constexpr int BUF = kMTileBytes + kMT * (int)sizeof(float);
+  constexpr int OWN = kMT * NB;                     // keys of a workgroup
   int tile_x, bk;
   if (!xcd_tile_head(tiles, heads, 1, false, tile_x, bk)) return;  // (key tile t is read by query tiles t..last: the first is the longest)
   const int b = bk / Hkv, kvh = bk % Hkv, g = Hq / Hkv;
   const bf16_t* Kh = K + (int64_t)bk * P * 128;
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int n16 = lane & 15, j4 = lane >> 4;
   const int Pq = prompt_len ? max(0, min(prompt_len[b], P)) : P;   // queries beyond the sequence's own prompt are padding
-  const int k0 = tile_x * kMT + 16 * wave;          // this wave's 16 keys
-  const int my_key = k0 + n16;
-  sc_bf16x8_t kfr[4];
-  row_fragments(Kh, min(my_key, P - 1), j4, kfr);
-  float colsum = 0.f;
-  const int first = tile_x, n_rt = (P + kMT - 1) / kMT;
-  const int total = g * (n_rt - first);             // (head, row tile) pairs, head-major
-  uint4 reg[4];
-  float2 st_reg = make_float2(0.f, 0.f);
-  auto request = [&](int it) {
-    const int hg = it / (n_rt - first), rt = first + it % (n_rt - first);
-    const int64_t bh = (int64_t)b * Hq + (int64_t)kvh * g + hg;
-    tile_request(Q + bh * P * 128, rt * kMT, P, reg);
-    if (threadIdx.x < kMT) st_reg = stats[bh * P + min(rt * kMT + (int)threadIdx.x, P - 1)];
+  const int k0 = tile_x * OWN + 16 * wave;          // first key of own block 0; block bb starts at k0 + 64 bb
+  sc_bf16x8_t kfr[NB][4];
+  float colsum[NB];
+#pragma unroll
+  for (int bb = 0; bb < NB; ++bb) {
+    row_fragments(Kh, min(k0 + 64 * bb + n16, P - 1), j4, kfr[bb]);
+    colsum[bb] = 0.f;
+  }
+  const int first = tile_x * NB, n_rt = (Pq + kMT - 1) / kMT;      // row tiles first .. n_rt - 1 see these keys
+  const int per_head = max(n_rt - first, 0);
+  const int total = g * per_head;                   // (head, row tile) pairs, head-major
+  int req_h = 0, req_rt = first, req_n = 0;         // the next (head, row tile) to request, requests so far
+  auto request = [&]() {
+    const int64_t bh = (int64_t)b * Hq + (int64_t)kvh * g + req_h;
+    char* dst = s_tiles + (req_n++ & 1) * BUF;
+    tile_to_lds(Q + bh * P * 128, req_rt * kMT, P, dst);
+    if (wave == 0)                                  // the 64 c_i of the tile's rows, 4 bytes per lane
+      __builtin_amdgcn_global_load_lds((sc_gptr_t*)(cstat + bh * P + min(req_rt * kMT + lane, P - 1)),
+                                       (sc_lptr_t*)(dst + kMTileBytes), 4, 0, 0);
+    if (++req_rt == n_rt) { req_rt = first; ++req_h; }
   };
-  request(0);
+  if (total > 0) request();
+  int rt = first - 1;
   for (int it = 0; it < total; ++it) {
     char* buf = s_tiles + (it & 1) * BUF;
-    float2* st_lds = reinterpret_cast<float2*>(buf + kMTileBytes);
-    tile_store(buf, reg);
-    if (threadIdx.x < kMT) st_lds[threadIdx.x] = st_reg;
-    __syncthreads();
-    if (it + 1 < total) request(it + 1);
-    const int rt = first + it % (n_rt - first);
-    if (rt * kMT >= k0 + 15 && (rt + 1) * kMT <= Pq) {
+    const float* st_lds = reinterpret_cast<const float*>(buf + kMTileBytes);
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // this wave's part of tile `it` has landed
+    __syncthreads();                                // tile `it` visible; everyone is past tile it-1
+    if (it + 1 < total) request();
+    if (++rt == n_rt) rt = first;
+    if (rt * kMT >= k0 + 64 * (NB - 1) + 15 && (rt + 1) * kMT <= Pq) {
       // every row of the tile sees every key of this wave and is a real query (wave-uniform; all tiles
-      // but the diagonal and the last): no mask
+      // but those on the diagonal and the last): no mask
 #pragma unroll
       for (int sub = 0; sub < 4; ++sub) {
-        const sc_f32x4_t s4 = block_product(buf, sub, kfr);
-        const float4 sa = *reinterpret_cast<const float4*>(&st_lds[16 * sub + 4 * j4]);
-        const float4 sb = *reinterpret_cast<const float4*>(&st_lds[16 * sub + 4 * j4 + 2]);
-        colsum = fmaf(__builtin_amdgcn_exp2f(fmaf(s4[0], scale_log2, -sa.x)), sa.y, colsum);
-        colsum = fmaf(__builtin_amdgcn_exp2f(fmaf(s4[1], scale_log2, -sa.z)), sa.w, colsum);
-        colsum = fmaf(__builtin_amdgcn_exp2f(fmaf(s4[2], scale_log2, -sb.x)), sb.y, colsum);
-        colsum = fmaf(__builtin_amdgcn_exp2f(fmaf(s4[3], scale_log2, -sb.z)), sb.w, colsum);
+        sc_bf16x8_t afr[4];
+        tile_fragments(buf, sub, afr);
+        const float4 c4 = *reinterpret_cast<const float4*>(&st_lds[16 * sub + 4 * j4]);   // rows 4 j4 .. 4 j4 + 3
+#pragma unroll
+        for (int bb = 0; bb < NB; ++bb) {
+          const sc_f32x4_t s4 = block_product(afr, kfr[bb]);
+          colsum[bb] += __builtin_amdgcn_exp2f(fmaf(s4[0], scale_log2, -c4.x));
+          colsum[bb] += __builtin_amdgcn_exp2f(fmaf(s4[1], scale_log2, -c4.y));
+          colsum[bb] += __builtin_amdgcn_exp2f(fmaf(s4[2], scale_log2, -c4.z));
+          colsum[bb] += __builtin_amdgcn_exp2f(fmaf(s4[3], scale_log2, -c4.w));
+        }
       }
       continue;
     }
 #pragma unroll
     for (int sub = 0; sub < 4; ++sub) {
       const int i0 = rt * kMT + 16 * sub;
-      if (i0 + 15 < k0) continue;                   // wave-uniform: all rows above all of this wave's keys
-      const sc_f32x4_t s4 = block_product(buf, sub, kfr);
-      const float4 sa = *reinterpret_cast<const float4*>(&st_lds[16 * sub + 4 * j4]);       // rows 4j4, 4j4+1
-      const float4 sb = *reinterpret_cast<const float4*>(&st_lds[16 * sub + 4 * j4 + 2]);   // rows 4j4+2, 4j4+3
-      const float mrow[4] = {sa.x, sa.z, sb.x, sb.z}, irow[4] = {sa.y, sa.w, sb.y, sb.w};
+      if (i0 + 15 < k0 || i0 >= Pq) continue;       // wave-uniform: all rows above all of this wave's keys, or padding
+      sc_bf16x8_t afr[4];
+      tile_fragments(buf, sub, afr);
+      const float4 c4 = *reinterpret_cast<const float4*>(&st_lds[16 * sub + 4 * j4]);
+      const float crow[4] = {c4.x, c4.y, c4.z, c4.w};
 #pragma unroll
-      for (int e = 0; e < 4; ++e) {
-        const int row = i0 + 4 * j4 + e;
-        const float p = __builtin_amdgcn_exp2f(s4[e] * scale_log2 - mrow[e]) * irow[e];
-        colsum += (row >= my_key && row < Pq) ? p : 0.f;
+      for (int bb = 0; bb < NB; ++bb) {
+        const int kb = k0 + 64 * bb, my_key = kb + n16;
+        if (i0 + 15 < kb) continue;                 // wave-uniform: all rows above all keys of the block
+        const sc_f32x4_t s4 = block_product(afr, kfr[bb]);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          const int row = i0 + 4 * j4 + e;
+          const float p = __builtin_amdgcn_exp2f(fmaf(s4[e], scale_log2, -crow[e]));
+          colsum[bb] += (row >= my_key && row < Pq) ? p : 0.f;
+        }
       }
     }
   }
-  colsum += __shfl_xor(colsum, 16, 64);
-  colsum += __shfl_xor(colsum, 32, 64);
-  if (j4 == 0 && my_key < P) scores[(int64_t)bk * P + my_key] = colsum;
+#pragma unroll
+  for (int bb = 0; bb < NB; ++bb) {
+    float c = colsum[bb];
+    c += __shfl_xor(c, 16, 64);
+    c += __shfl_xor(c, 32, 64);
+    const int my_key = k0 + 64 * bb + n16;
+    if (j4 == 0 && my_key < P) scores[(int64_t)bk * P + my_key] = c;
+  }
 }
 
-static void launch_scores_mfma(const void* Q, const void* K, int B, int Hq, int Hkv, int P, const int32_t* prompt_len,
-                               float* scores, float2* stats, hipStream_t st) {
+template <int NB>
+static void launch_scores_mfma(const void* Q, const void* K, int B, int Hq, int Hkv, int P,
+                                     const int32_t* prompt_len, float* scores, float* cstat, hipStream_t st) {
   const float scale_log2 = (float)(1.4426950408889634 / sqrt(128.0));
-  const int tiles = (P + kMT - 1) / kMT;
-  const size_t lds1 = 2 * (size_t)kMTileBytes, lds2 = 2 * ((size_t)kMTileBytes + kMT * sizeof(float2));
+  const int tiles = (P + kMT * NB - 1) / (kMT * NB);
+  const size_t lds1 = 2 * (size_t)kMTileBytes, lds2 = 2 * ((size_t)kMTileBytes + kMT * sizeof(float));
   auto grid = [&](int heads, int per) { return (unsigned)(((heads / per + 7) / 8) * 8 * per * tiles); };
-  score_rowstats_mfma_kernel<<<grid(B * Hq, Hq / Hkv), kScThreads, lds1, st>>>(
-      static_cast<const bf16_t*>(Q), static_cast<const bf16_t*>(K), Hq, Hkv, P, scale_log2, tiles, B * Hq, stats);
-  score_colsum_mfma_kernel<<<grid(B * Hkv, 1), kScThreads, lds2, st>>>(
-      static_cast<const bf16_t*>(Q), static_cast<const bf16_t*>(K), Hq, Hkv, P, scale_log2, stats, prompt_len, tiles,
+  score_rowstats_mfma_kernel<NB><<<grid(B * Hq, Hq / Hkv), kScThreads, lds1, st>>>(
+      static_cast<const bf16_t*>(Q), static_cast<const bf16_t*>(K), Hq, Hkv, P, scale_log2, tiles, B * Hq, cstat);
+  score_colsum_mfma_kernel<NB><<<grid(B * Hkv, 1), kScThreads, lds2, st>>>(
+      static_cast<const bf16_t*>(Q), static_cast<const bf16_t*>(K), Hq, Hkv, P, scale_log2, cstat, prompt_len, tiles,
       B * Hkv, scores);
 }
 
@@ -450,7 +526,7 @@ extern "C" sqa_status sqa_prefill_scores_ex(const void* Q, const void* K, sqa_dt
     else launch_scores<float, 128>(Q, K, B, Hq, Hkv, P, plen, scores_out, stats, st);
   } else {
     if (D == 64) launch_scores<bf16_t, 64>(Q, K, B, Hq, Hkv, P, plen, scores_out, stats, st);
-    else launch_scores_mfma(Q, K, B, Hq, Hkv, P, plen, scores_out, stats, st);
+    else launch_scores_mfma<SQA_SC_NB>(Q, K, B, Hq, Hkv, P, plen, scores_out, reinterpret_cast<float*>(stats), st);
   }
   SQA_HIP_CHECK(hipGetLastError());
   return SQA_OK;

@@ -108,6 +108,43 @@ def test_prefill_scores(sqa, dtype, B, Hq, Hkv, P, D):
             assert abs(got[b, h].sum() - g * P) < 1e-3 * g * P
 
 
+def _wide_range_qk(case, P, Hq, Hkv, D):
+    """Queries and keys that share one direction u; the keys' component along u sets the logit level."""
+    r = torch.Generator().manual_seed({"steps_up": 11, "late_peak": 12, "steps_down": 13}[case])
+    u = torch.randn(D, generator=r)
+    u = u / u.norm() * D ** 0.5
+    pos = torch.arange(P)
+    if case == "steps_up":                       # + 24 units (log2) every 40 keys
+        a = (pos // 40) * 0.5
+    elif case == "steps_down":
+        a = ((P - 1 - pos) // 40) * 0.5
+    else:                                        # one key 290 units above the rest
+        a = torch.zeros(P)
+        a[200] = 6.0
+    Q = torch.randn(1, Hq, P, D, generator=r) + 3.0 * u
+    K = torch.randn(1, Hkv, P, D, generator=r) + a[None, None, :, None] * u
+    return Q.to(torch.bfloat16), K.to(torch.bfloat16)
+
+
+@pytest.mark.parametrize("case", ["steps_up", "late_peak", "steps_down"])
+def test_prefill_scores_wide_logit_range(sqa, case):
+    """Logits that move by hundreds of units along a row: a level that steps up every 40 keys keeps
+    exceeding a row's running reference, one dominant key exceeds it once by far, a falling level never
+    does.  (The matrix-core kernels take their exponentials against a reference that only moves when a
+    partial sum shows it is far too low.)"""
+    Hq, Hkv, P, D = 4, 2, 600, 128
+    Q, K = _wide_range_qk(case, P, Hq, Hkv, D)
+    Q, K = Q.to(DEV), K.to(DEV)
+    got = sqa.prefill_scores(Q, K).cpu().numpy().astype(np.float64)
+    assert np.all(np.isfinite(got))
+    Qn, Kn = np64(Q), np64(K)
+    g = Hq // Hkv
+    for h in range(Hkv):
+        ref = O.prefill_scores(Qn[0, h * g:(h + 1) * g], Kn[0, h])
+        assert rel_err(got[0, h], ref) < TOL["bf16"]
+        assert abs(got[0, h].sum() - g * P) < 1e-3 * g * P
+
+
 # ---------------------------------------------------------------- prefill compress
 
 def _mk_caches(sqa, budgets, caps, B, Hkv, D, dtype, h2o=True):
