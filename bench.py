@@ -72,6 +72,50 @@ def cpu_baseline(sess, units_per_layer: int, steps: int):
                       % (units_per_layer, wl.B * wl.Hkv, wl.L, steps, t_total)}
 
 
+def scores_only(args, wl):
+    """The prompt-score producer alone: per layer one sqa_prefill_scores call (two kernels, row statistics then
+    column sums) on generated prompt queries and keys; 2 passes x B*Hq*P(P+1)/2 logits x 2*D flops per layer."""
+    import torch
+    from paper_2404_04793_amd import binding as sqa
+    from paper_2404_04793_amd import workloads as W
+    dev = "cuda:0"
+    n_gen = min(wl.L, 4)                                  # distinct layers' inputs, cycled
+    u_dirs, mask = W.unit_dirs(wl), W.hh_mask(wl, dev)
+    QK = [(W.prompt_q(wl, l, dev, u_dirs), W.prompt_kv(wl, l, dev, u_dirs, mask)[0]) for l in range(n_gen)]
+
+    def one_pass():
+        for l in range(wl.L):
+            sqa.prefill_scores(QK[l % n_gen][0], QK[l % n_gen][1])
+
+    for _ in range(args.warmup):
+        one_pass()
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    t0 = time.perf_counter()
+    e0.record()
+    for _ in range(args.steps):
+        one_pass()
+    e1.record()
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    call_s = e0.elapsed_time(e1) * 1e-3 / (args.steps * wl.L)
+    flops = 2 * wl.B * wl.Hq * (wl.P * (wl.P + 1) // 2) * 2 * wl.D
+    peak = 2500.0 if (wl.dtype == "bf16" and wl.D == 128) else 157.3     # matrix cores (bf16, D = 128) or fp32 vector
+    out = {
+        "metric": "H2O prompt-score producer (causal softmax column sums), TFLOP/s", "value": flops / call_s / 1e12,
+        "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": dt / args.steps * 1e3, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": wl.dtype, "data": "synthetic",
+        "config": {"workload": wl.name, "layers": wl.L, "q_heads": wl.Hq, "kv_heads": wl.Hkv, "head_dim": wl.D,
+                   "batch": wl.B, "prompt": wl.P, "phases": "scores_only"},
+        "roofline": {"bound": "mfma" if peak == 2500.0 else "alu",
+                     "kernel": "score_rowstats + score_colsum (one call = both)", "achieved": flops / call_s / 1e12,
+                     "peak": peak, "unit": "TFLOP/s", "frac": flops / call_s / 1e12 / peak, "traffic": None,
+                     "flops_per_call": flops, "call_us": call_s * 1e6},
+    }
+    print(json.dumps(out))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -105,6 +149,9 @@ def main():
     ap.add_argument("--calib-copy", action="store_true",
                     help="after the timed region run one plain 1 GiB -> 1 GiB elementwise copy kernel "
                          "(reference point for scaling rocprofv3's FETCH_SIZE / WRITE_SIZE counters)")
+    ap.add_argument("--scores-only", action="store_true",
+                    help="time only the H2O prompt-score producer (sqa_prefill_scores; set-up work of the pass, "
+                         "matrix-core bound): a step = the scores of all layers of one prompt batch")
     ap.add_argument("--cpu-units", type=int, default=32)
     ap.add_argument("--cpu-steps", type=int, default=128)
     args = ap.parse_args()
@@ -126,6 +173,8 @@ def main():
     if args.budget_pct:
         wl = W.scaled(wl, budget_pct=args.budget_pct)
     torch.cuda.set_device(0)
+    if args.scores_only:
+        return scores_only(args, wl)
     plen = [wl.P - (b * wl.P) // (2 * wl.B) for b in range(wl.B)] if args.ragged else None
     sess = Session(wl, "cuda:0", uniform_budget=args.uniform, full_cache=args.full_cache,
                    probe_tokens=args.probe_tokens, fused_probe=args.fused_probe, order=args.order, prompt_len=plen)
