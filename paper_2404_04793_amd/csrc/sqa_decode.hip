@@ -205,8 +205,10 @@ template <> struct RowMath<bf16_t> {
 };
 
 
+typedef __attribute__((address_space(1))) const void dec_gptr_t;
+typedef __attribute__((address_space(3))) void dec_lptr_t;
 #ifndef SQA_DEC_MF_WAVES
-#define SQA_DEC_MF_WAVES 2      // waves per SIMD the matrix-core variant is compiled for
+#define SQA_DEC_MF_WAVES 3      // waves per SIMD the matrix-core variant is compiled for
 #endif
 #ifdef SQA_DEC_WAVES_PER_EU
 #define SQA_DEC_OCC __attribute__((amdgpu_waves_per_eu(SQA_DEC_WAVES_PER_EU, SQA_DEC_WAVES_PER_EU)))
@@ -375,13 +377,17 @@ __global__ __launch_bounds__(kDecThreads, MF ? SQA_DEC_MF_WAVES : 1) SQA_DEC_OCC
     // So softmax statistics and the output accumulator live in the lanes of
     // their head and nothing is moved between lanes except two max/sum steps.
     // K and V tiles pass through a wave-private 8.5 KiB LDS buffer, one after the
-    // other.  The V tile has rows padded by 16 bytes (conflict-free for the
-    // transposing reads).  The K tile has 256-byte rows whose 16-byte pieces are
-    // XOR-swizzled with the row number: piece p of tile row R lies at piece
-    // p ^ (R & 15).  A fragment read takes 16 bytes from each of 16 different rows;
-    // with padded rows that ran at 30 cycles per wave instruction on this chip
-    // (4-way bank conflicts), swizzled it runs at 8.5, and the row-wise writes
-    // keep their 13.
+    // other.  The V tile (copied from registers) has rows padded by 16 bytes
+    // (conflict-free for the transposing reads).  The K tile has 256-byte rows
+    // whose 16-byte pieces are XOR-swizzled with the row number: piece p of tile
+    // row R lies at piece p ^ (R & 15).  A fragment read takes 16 bytes from each
+    // of 16 different rows; with padded rows that ran at 30 cycles per wave
+    // instruction on this chip (4-way bank conflicts), swizzled it runs at 8.5.
+    // K rows are loaded from global memory straight into that layout (direct
+    // global->LDS loads, the swizzle applied to the global address): the 32
+    // registers a K tile in flight used to occupy are what kept this variant at 2
+    // waves per SIMD; at 3, with a third more bytes in flight per CU, the
+    // Llama-2-70B shape went from 1138 to 997 us per step.
     char* stage = reinterpret_cast<char*>(s_logit + (H2O ? G * a.lds_chunk : 0)) + wave * kStageBytesPerWave;
     const int hd = lane & 15, j4 = lane >> 4;
     bf16x8_t qfr[4];
@@ -398,25 +404,31 @@ __global__ __launch_bounds__(kDecThreads, MF ? SQA_DEC_MF_WAVES : 1) SQA_DEC_OCC
     // LDS addresses of this lane (tile rows are kStageRow bytes apart, so every
     // other address below is one of these plus a compile-time constant)
     char* st_wr = stage + r * kStageRow + c * 16;                       // V: row-wise writes: + 4i rows
-    // K, swizzled: write of row 4i+r, piece c -> + 1024i + kw[i&3]; fragment i of row 16tt+hd -> + 4096tt + kr[i]
-    int kw[4], kr[4];
+    // K, swizzled: fragment i of row 16tt+hd -> + 4096tt + kr[i]
+    int kr[4];
 #pragma unroll
     for (int x = 0; x < 4; ++x) {
-      kw[x] = r * 256 + (((c ^ r) * 16) ^ (64 * x));
       kr[x] = hd * 256 + ((4 * j4) ^ (hd & 12)) * 16 + ((x ^ (hd & 3)) * 16);
     }
     auto k_patch = [&](int row, const uint4& val) {   // row of the tile, written by the 16 lanes whose r matches
       if ((row & 3) == r) *reinterpret_cast<uint4*>(stage + row * 256 + ((c ^ (row & 15)) * 16)) = val;
     };
     const char* st_v = stage + (4 * j4 + (hd >> 2)) * kStageRow + (hd & 3) * 8;   // V^T quadruple: + 16 rows, + 32db bytes
-    // Registers hold a tile only between its load and its copy into LDS, so the
-    // next tile's K (then V) is requested as soon as this tile's K (V) has been
-    // copied: a wave always has a tile in flight while it computes.
-    uint4 kreg[8], vreg[8];
+    // Registers hold a V tile only between its load and its copy into LDS: the
+    // next tile's V is requested as soon as this tile's V has been copied, the
+    // next tile's K as soon as the stage is free again (after the P.V reads).
+    uint4 vreg[8];
+    // A wave instruction of the direct K load fills 1 KB = tile rows 4i .. 4i+3 in
+    // lane order, so lane (r, c) fetches the piece that belongs at position c of
+    // row 4i + r: piece c ^ ((4i + r) & 15) = (c ^ r) ^ (4 (i & 3)).  Plain loads:
+    // here they ran faster than non-temporal ones (997 vs 1021 us), while V is
+    // better off non-temporal (plain: 1109 us).
     auto request_k = [&](int base) {
 #pragma unroll
-      for (int i = 0; i < 8; ++i)
-        kreg[i] = ld16_nt(Kb + ((uint32_t)min(base + 4 * i + r, rmax) * (uint32_t)ROWB + (uint32_t)(c * 16)));
+      for (int i = 0; i < 8; ++i) {
+        const char* g = Kb + ((uint32_t)min(base + 4 * i + r, rmax) * (uint32_t)ROWB + (uint32_t)(((c ^ r) ^ (4 * (i & 3))) * 16));
+        __builtin_amdgcn_global_load_lds((dec_gptr_t*)g, (dec_lptr_t*)(stage + 1024 * i), 16, 0, 0);
+      }
     };
     auto request_v = [&](int base) {
 #pragma unroll
@@ -433,11 +445,9 @@ __global__ __launch_bounds__(kDecThreads, MF ? SQA_DEC_MF_WAVES : 1) SQA_DEC_OCC
       const bool has_moved = moved_to >= base && moved_to < base + 32;
       uint4 km = make_uint4(0, 0, 0, 0), vm = km;
       if (has_moved) { km = ld16(Kb + (int64_t)slot_wr * ROWB + c * 16); vm = ld16(Vb + (int64_t)slot_wr * ROWB + c * 16); }
-#pragma unroll
-      for (int i = 0; i < 8; ++i) *reinterpret_cast<uint4*>(stage + 1024 * i + kw[i & 3]) = kreg[i];
+      asm volatile("s_waitcnt vmcnt(0)" ::: "memory");          // this tile's K rows have landed in the stage
       if (has_moved) k_patch(moved_to - base, km);
       if (has_new) k_patch(slot_new - base, kn_pre);
-      if (more) request_k(base + TSTEP);
       f32x4_t sacc[2];
 #pragma unroll
       for (int tt = 0; tt < 2; ++tt) {
@@ -503,6 +513,11 @@ __global__ __launch_bounds__(kDecThreads, MF ? SQA_DEC_MF_WAVES : 1) SQA_DEC_OCC
           const v4s_t vt = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4s_ptr)(st_v + 16 * tt * kStageRow + 32 * db));
           oacc[db] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(vt, __builtin_bit_cast(v4s_t, pfr[tt]), oacc[db], 0, 0, 0);
         }
+      // the stage is free again (its reads have returned): the next tile's K rows may land in it
+      if (more) {
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+        request_k(base + TSTEP);
+      }
     }
     l_run += __shfl_xor(l_run, 16, SQA_WAVE);
     l_run += __shfl_xor(l_run, 32, SQA_WAVE);
@@ -768,7 +783,10 @@ typedef void (*decode_fn)(const DecodeArgs);
 // Grouped queries of 8 heads in bf16 at D = 128 go to the matrix cores: there the vector-ALU path is
 // arithmetic bound (measured 4.2 TB/s against 5.7 TB/s on the Llama-2-70B shape); at 4 heads the
 // vector-ALU path is still the faster one (6.5 against 5.8 TB/s on the Mistral-7B shape).
-constexpr int kMfmaMinGroup = 8;
+#ifndef SQA_DEC_MFMA_MIN_GROUP
+#define SQA_DEC_MFMA_MIN_GROUP 4      // query heads per KV head from which the matrix-core variant is used
+#endif
+constexpr int kMfmaMinGroup = SQA_DEC_MFMA_MIN_GROUP;
 template <typename T, int D, int G> constexpr bool use_mfma() { return sizeof(T) == 2 && D == 128 && G >= kMfmaMinGroup; }
 template <typename T, int D, bool H2O> decode_fn pick_g(int g) {
   switch (g) {
