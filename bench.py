@@ -145,6 +145,8 @@ def main():
                     help="where the policy runs inside a decode step (default: Algorithm 1 as printed)")
     ap.add_argument("--decode-steps", type=int, default=None, help="decode steps per pass (default: the workload's)")
     ap.add_argument("--batch", type=int, default=None, help="override the workload's batch")
+    ap.add_argument("--kv-heads", type=int, default=None,
+                    help="override the workload's number of KV heads (grouped queries: q_heads / kv_heads per KV head)")
     ap.add_argument("--budget-pct", type=int, default=None, help="override b_init as a percentage of the prompt")
     ap.add_argument("--calib-copy", action="store_true",
                     help="after the timed region run one plain 1 GiB -> 1 GiB elementwise copy kernel "
@@ -170,6 +172,8 @@ def main():
         wl = W.scaled(wl, S=args.decode_steps)
     if args.batch:
         wl = W.scaled(wl, B=args.batch)
+    if args.kv_heads:
+        wl = W.scaled(wl, Hkv=args.kv_heads)
     if args.budget_pct:
         wl = W.scaled(wl, budget_pct=args.budget_pct)
     torch.cuda.set_device(0)

@@ -90,6 +90,15 @@ __device__ __forceinline__ void st_agent(float* p, float v) {
 __device__ __forceinline__ float ld_agent(const float* p) {
   return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
+__device__ __forceinline__ void st_agent(unsigned long long* p, unsigned long long v) {
+  __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ void st_agent(unsigned short* p, unsigned short v) {
+  __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ unsigned short ld_agent(const unsigned short* p) {
+  return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
 
 // block-wide reductions; every thread gets the result
 // solo: only wave 0 of the workgroup is still running (the others have left),
@@ -360,7 +369,16 @@ __global__ __launch_bounds__(kDecThreads, MF ? SQA_DEC_MF_WAVES : 1) SQA_DEC_OCC
   // ---- 1. stream the chunk's K and V once, online softmax -------------------
   const int c_end = min(c0 + csize, n);
   const int lpitch = cap + 1;                      // logit row of one head in scratch (the new token may be slot cap)
-  float* glogit = (H2O && nsplit > 1) ? a.logit + a.lay[layer].logit_off + (uoff + u) * G : nullptr;   // units before this one hold uoff slots + one spare each
+  float* glogit = (H2O && (nsplit > 1 || MF)) ? a.logit + a.lay[layer].logit_off + (uoff + u) * G : nullptr;   // units before this one hold uoff slots + one spare each
+  // The matrix-core variant keeps, in those G x lpitch floats of the workspace (for every unit, split or not:
+  // nothing of it needs LDS), per head `pitch16` bf16 probabilities relative to their tile's reference (first
+  // half of the region) and one reference per 32-token tile (second half; tiles start at multiples of 32
+  // because chunks do).  Both halves fit for lpitch >= 2.  They are written and read by the same workgroup
+  // unless the unit is split: only then do they need the coherent path.
+  const int pitch16 = lpitch >= 8 ? (lpitch + 3) & ~3 : lpitch, tpitch = (lpitch + 31) >> 5;
+  const bool handover = nsplit > 1;
+  unsigned short* e16 = reinterpret_cast<unsigned short*>(glogit);
+  float* tref = (MF && H2O) ? glogit + (G * pitch16) / 2 : nullptr;
 
   if constexpr (MF) {
     // ---- 1M. matrix-core streaming ------------------------------------------
@@ -468,10 +486,6 @@ __global__ __launch_bounds__(kDecThreads, MF ? SQA_DEC_MF_WAVES : 1) SQA_DEC_OCC
         d = valid ? d : -INFINITY;
         sv[e] = d;
         mx = fmaxf(mx, d);
-        if (H2O && valid && hd < G) {
-          if (glogit) st_agent(&glogit[(int64_t)hd * lpitch + tok], d);
-          else s_lg[hd * lp + tok] = d;
-        }
       }
       mx = fmaxf(mx, __shfl_xor(mx, 16, SQA_WAVE));
       mx = fmaxf(mx, __shfl_xor(mx, 32, SQA_WAVE));
@@ -488,6 +502,32 @@ __global__ __launch_bounds__(kDecThreads, MF ? SQA_DEC_MF_WAVES : 1) SQA_DEC_OCC
         pfr[e >> 2][e & 3] = (__bf16)pe;
       }
       l_run = l_run * alpha + psum;
+      if (H2O && hd < G) {
+        // What step 3 needs of this tile: the probabilities as the second product uses them (bf16,
+        // relative to the tile's reference ms) and that reference, one per head.  2 bytes per token and
+        // head instead of a 4-byte logit: for split units these go through memory, where every byte
+        // written costs as much as several bytes read.
+#pragma unroll
+        for (int tt = 0; tt < 2; ++tt) {
+          const int tok0 = base + 16 * tt + 4 * j4;
+          unsigned short* dst = e16 + (int64_t)hd * pitch16 + tok0;
+          const unsigned long long four = __builtin_bit_cast(unsigned long long, pfr[tt]);
+          if (tok0 + 3 < c_end && (pitch16 & 3) == 0) {       // whole and 8-byte aligned
+            if (handover) st_agent(reinterpret_cast<unsigned long long*>(dst), four);
+            else *reinterpret_cast<unsigned long long*>(dst) = four;
+          } else {
+#pragma unroll
+            for (int e = 0; e < 4; ++e)
+              if (tok0 + e < c_end) {
+                const unsigned short one = (unsigned short)(four >> (16 * e));
+                if (handover) st_agent(dst + e, one); else dst[e] = one;
+              }
+          }
+        }
+        if (j4 == 0) {
+          if (handover) st_agent(&tref[hd * tpitch + (base >> 5)], ms); else tref[hd * tpitch + (base >> 5)] = ms;
+        }
+      }
       if (__ballot(alpha != 1.f)) {
 #pragma unroll
         for (int db = 0; db < 8; ++db) oacc[db] *= alpha;
@@ -694,7 +734,7 @@ __global__ __launch_bounds__(kDecThreads, MF ? SQA_DEC_MF_WAVES : 1) SQA_DEC_OCC
   // waves 1-3 leave here and wave 0 finishes alone: three quarters of the
   // workgroup's registers are free for the next workgroup while the tail runs.
   if (!wpu) __syncthreads();                      // every wave is done reading the cache rows and writing LDS
-  const bool solo = nsplit == 1;
+  const bool solo = nsplit == 1 && !(MF && H2O);  // (matrix-core H2O: the whole workgroup walks the unit's probabilities)
   if (solo && !wpu && wave != 0) return;
   const int nthr = solo ? SQA_WAVE : kDecThreads;
   const int tq = solo ? lane : tid;               // this thread's place among the nthr threads still at work
@@ -710,8 +750,24 @@ __global__ __launch_bounds__(kDecThreads, MF ? SQA_DEC_MF_WAVES : 1) SQA_DEC_OCC
     const bool decide = ae ? full : n == budget;
     const int leaver_slot = ae ? slot_wr : hh + head_next;
     const bool virt = ae && full;                 // the new token has no slot of its own yet
+    // Matrix-core variant: one factor per (head, 32-token tile) turns a stored probability into the final
+    // one, exp2(reference - m) / l; the table goes where the tiles were staged (if the unit is so long that
+    // it does not fit there, the factor is recomputed per token instead).
+    float* fac = reinterpret_cast<float*>(s_logit + G * a.lds_chunk);
+    const bool use_fac = MF && (size_t)G * tpitch * sizeof(float) <= (size_t)kDecWaves * kStageBytesPerWave;
+    if constexpr (MF) {
+      if (use_fac) {
+        const int ntile = (n + 31) >> 5;
+        for (int idx = tq; idx < G * ntile; idx += nthr) {
+          const int g = idx / ntile, t = idx - g * ntile;
+          const float rf = handover ? ld_agent(&tref[g * tpitch + t]) : tref[g * tpitch + t];
+          fac[g * tpitch + t] = fast_exp2(rf - s_m[wq][g]) * s_l[wq][g];
+        }
+        __syncthreads();                          // (all waves are here: the variant never runs step 3 on one wave)
+      }
+    }
     float mn = INFINITY;
-    constexpr int SB = 4;                         // scores requested together: one round trip per SB tokens
+    constexpr int SB = MF ? 8 : 4;                // scores requested together: one round trip per SB tokens
     for (int i0 = tq; i0 < n; i0 += SB * nthr) {
       float cur[SB];
 #pragma unroll
@@ -726,8 +782,15 @@ __global__ __launch_bounds__(kDecThreads, MF ? SQA_DEC_MF_WAVES : 1) SQA_DEC_OCC
           float p = 0.f;
 #pragma unroll
           for (int g = 0; g < G; ++g) {
-            const float lg = glogit ? ld_agent(&glogit[(int64_t)g * lpitch + i]) : s_lg[g * lp + i];
-            p += fast_exp2(lg - fm[g]) * fi[g];
+            if constexpr (MF) {
+              const unsigned short eb = handover ? ld_agent(&e16[(int64_t)g * pitch16 + i]) : e16[(int64_t)g * pitch16 + i];
+              const float e = __uint_as_float((uint32_t)eb << 16);
+              p += e * (use_fac ? fac[g * tpitch + (i >> 5)]
+                                : fast_exp2(ld_agent(&tref[g * tpitch + (i >> 5)]) - fm[g]) * fi[g]);
+            } else {
+              const float lg = glogit ? ld_agent(&glogit[(int64_t)g * lpitch + i]) : s_lg[g * lp + i];
+              p += fast_exp2(lg - fm[g]) * fi[g];
+            }
           }
           const float old = i == slot_new ? 0.f : (i == moved_to ? leaver_score : cur[k]);
           const float nv = old + p;
@@ -826,7 +889,8 @@ static size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 // Units are split only when the call would otherwise have too few work items to fill the chip or a
 // few items much longer than the rest (the hand-over between workgroups costs more than the imbalance
 // it removes): the target chunk is 1/kMinItems of the call's tokens, at least 256 slots and at most what
-// lets a unit's step logits fit in LDS (kMaxUnsplit slots x heads); each layer uses the number of equal
+// lets a unit's step logits fit in LDS (kMaxUnsplit slots x heads; not for the matrix-core variant, which keeps
+// what H2O needs in the workspace); each layer uses the number of equal
 // chunks nearest to that, so units shorter than 1.5 targets stay whole.
 #ifndef SQA_DEC_MIN_ITEMS
 #define SQA_DEC_MIN_ITEMS (256 * 4)
@@ -838,8 +902,10 @@ constexpr int kMaxUnsplit = 8192;
 // slots filled).  Not for the matrix-core variant, whose tiles are 32 tokens per wave already.
 constexpr int kWpuMaxSlots = 256;
 constexpr int64_t kWpuMinUnits = 4096;
+// scratch_probs: the H2O step's per-token, per-head values live in the workspace for every unit, split or
+// not (the matrix-core variant: they never need LDS, so nothing limits an unsplit unit's length).
 static sqa_status plan_decode(const sqa_layer_cache* layers, int n_layers, int B, int Hq, int Hkv, int D, bool h2o,
-                              bool allow_wpu, DecodePlan* p) {
+                              bool allow_wpu, bool scratch_probs, DecodePlan* p) {
   const int64_t units = (int64_t)B * Hkv;
   const int g = Hq / Hkv;
   int64_t tokens = 0;
@@ -854,7 +920,7 @@ static sqa_status plan_decode(const sqa_layer_cache* layers, int n_layers, int B
 #else
   target = tokens / kMinItems;
   target = target < 256 ? 256 : target;
-  if (h2o && target > kMaxUnsplit / g) target = kMaxUnsplit / g;
+  if (h2o && !scratch_probs && target > kMaxUnsplit / g) target = kMaxUnsplit / g;
 #endif
   uint64_t blocks = 0, n_units = 0, n_part = 0, n_logit = 0;
   p->lds_chunk = 64;
@@ -868,23 +934,21 @@ static sqa_status plan_decode(const sqa_layer_cache* layers, int n_layers, int B
     int64_t ns = (nmax + target / 2) / target;                  // nearest count of equal chunks
     ns = ns < 1 ? 1 : ns;
     int64_t ch = ((nmax + ns - 1) / ns + 63) / 64 * 64;
-    if (h2o && ns == 1 && ch * g > kMaxUnsplit) { ns = 2; ch = ((nmax + 1) / 2 + 63) / 64 * 64; }
+    if (h2o && !scratch_probs && ns == 1 && ch * g > kMaxUnsplit) { ns = 2; ch = ((nmax + 1) / 2 + 63) / 64 * 64; }
     ns = (nmax + ch - 1) / ch;
     if (ns > 65535) return SQA_ERR_CAPACITY;
     p->nsplit[i] = (uint16_t)ns;
     p->chunk[i] = (uint32_t)ch;
     p->wpu[i] = allow_wpu && ns == 1 && nmax <= kWpuMaxSlots && units * n_layers >= kWpuMinUnits;
     if (p->wpu[i]) { if (ch > p->lds_chunk_w) p->lds_chunk_w = (int)ch; }
-    else if (ns == 1 && ch > p->lds_chunk) p->lds_chunk = (int)ch;
+    else if (ns == 1 && !scratch_probs && ch > p->lds_chunk) p->lds_chunk = (int)ch;
     p->unit_off[i] = (uint32_t)n_units;
     p->part_off[i] = (uint32_t)n_part;
     p->logit_off[i] = (uint32_t)n_logit;
     n_units += units;
     blocks += p->wpu[i] ? (units + kDecWaves - 1) / kDecWaves : units * ns;
-    if (ns > 1) {
-      n_part += units * ns;
-      if (h2o) n_logit += units * g * ((uint64_t)layers[i].capacity + 1);
-    }
+    if (ns > 1) n_part += units * ns;
+    if (h2o && (ns > 1 || scratch_probs)) n_logit += units * g * ((uint64_t)layers[i].capacity + 1);
     if (n_units > 0x7fffffffull || n_part > 0x7fffffffull || n_logit > 0xffffffffull || blocks > 0x7fffffffull)
       return SQA_ERR_CAPACITY;
   }
@@ -904,8 +968,16 @@ extern "C" size_t sqa_decode_workspace_bytes(const sqa_layer_cache* layers, int 
   if (!layers || n_layers < 1 || n_layers > SQA_MAX_LAYERS || B < 1 || Hq < 1 || Hkv < 1 || Hq % Hkv != 0 || D < 1)
     return 0;
   sqa::DecodePlan p;
-  if (sqa::plan_decode(layers, n_layers, B, Hq, Hkv, D, policy == SQA_H2O, false, &p) != SQA_OK) return 0;
-  return p.bytes;
+  // (the element type is not known here: size for the variant that needs more, the matrix-core one if the
+  // shape allows it)
+  const bool h2o = policy == SQA_H2O;
+  if (sqa::plan_decode(layers, n_layers, B, Hq, Hkv, D, h2o, false, false, &p) != SQA_OK) return 0;
+  size_t bytes = p.bytes;
+  if (h2o && D == 128 && Hq / Hkv >= sqa::kMfmaMinGroup) {
+    if (sqa::plan_decode(layers, n_layers, B, Hq, Hkv, D, h2o, false, true, &p) != SQA_OK) return 0;
+    bytes = p.bytes > bytes ? p.bytes : bytes;
+  }
+  return bytes;
 }
 
 namespace sqa {
@@ -987,7 +1059,7 @@ extern "C" sqa_status sqa_decode_step_ex(const void* q, const void* k_new, const
   }
   const bool mfma = dt == SQA_BF16 && D == 128 && g >= kMfmaMinGroup;
   DecodePlan plan;
-  const sqa_status ps = plan_decode(layers, n_layers, B, Hq, Hkv, D, h2o, !mfma, &plan);
+  const sqa_status ps = plan_decode(layers, n_layers, B, Hq, Hkv, D, h2o, !mfma, h2o && mfma, &plan);
   if (ps != SQA_OK) return ps;
   if (ws_bytes < plan.bytes) return SQA_ERR_CAPACITY;
   const size_t lds_shared = (size_t)g * plan.lds_chunk, lds_waves = (size_t)kDecWaves * g * plan.lds_chunk_w;

@@ -144,6 +144,16 @@ def test_llama2_70b_gqa8_sliding_reduced():
     _run_fullsize(wl, sample_layers=[0, 20, 39], units=[(0, 0), (1, 7)], check_steps={0, 1, 31}, cos_layers=[0, 39])
 
 
+@pytest.mark.parametrize("B,L", [(16, 24), (2, 8)])
+def test_llama2_70b_shape_gqa8_h2o(B, L):
+    """The 70B head shape, prompt and budgets under H2O (the policy configs[3] does not use): 8 query heads per KV
+    head accumulate into one score per token.  Batch 16: the 3439-token units stay whole (one workgroup walks
+    the unit and its stored probabilities); batch 2: the same units are split over several workgroups."""
+    wl = W.scaled(W.WORKLOADS["llama2_70b"], B=B, S=12, L=L, hidden=1024, policy="h2o")
+    _run_fullsize(wl, sample_layers=[0, L // 2, L - 1], units=[(0, 0), (B - 1, 7)], check_steps={0, 1, 11},
+                  cos_layers=[0, L - 1])
+
+
 def test_stress_7b_reduced_batch():
     """configs[4] at batch 16, 128 decode steps (short prompt, small budgets: 35 / 571)."""
     wl = W.scaled(W.WORKLOADS["stress_7b"], B=16, S=128)
