@@ -265,8 +265,10 @@ sqa_status sqa_prefill_compress_layers_ex(const void* const* K, const void* cons
  *                  status word (see sqa_read_device_status).
  * Long units are cut into chunks that separate workgroups stream (split-K);
  * the workspace holds their partial results, the step's logits (H2O) and one
- * arrival counter per unit.  The merge order is fixed: results are identical
- * from run to run.
+ * arrival counter per unit; with 4 or more query heads per KV head (bf16,
+ * D = 128) it also holds, for every unit, the step's per-head probabilities
+ * that the H2O accumulation sums.  The merge order is fixed: results are
+ * identical from run to run.
  * A unit that on entry is longer than its budget, or has no free slot, is left
  * untouched, its out rows are zeroed and the status word is set to
  * SQA_ERR_STATE / SQA_ERR_CAPACITY. */
