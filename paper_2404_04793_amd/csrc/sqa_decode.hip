@@ -268,7 +268,7 @@ __global__ __launch_bounds__(kDecThreads, MF ? SQA_DEC_MF_WAVES : 1) SQA_DEC_OCC
   const unsigned local = blockIdx.x - (lo ? a.blk_end[lo - 1] : 0u);
   const int nsplit = (int)a.lay[layer].nsplit;
   // one wave per unit: the workgroup's waves own 4 consecutive units and never meet at a barrier
-  const bool wpu = !MF && a.lay[layer].wpu != 0;
+  const bool wpu = a.lay[layer].wpu != 0;
   const int u = wpu ? (int)local * kDecWaves + wave : (int)(local / (unsigned)nsplit);
   const int chunk = wpu ? 0 : (int)(local % (unsigned)nsplit);
   if (wpu && u >= a.B * a.Hkv) return;
@@ -453,9 +453,9 @@ __global__ __launch_bounds__(kDecThreads, MF ? SQA_DEC_MF_WAVES : 1) SQA_DEC_OCC
       for (int i = 0; i < 8; ++i)
         vreg[i] = ld16_nt(Vb + ((uint32_t)min(base + 4 * i + r, rmax) * (uint32_t)ROWB + (uint32_t)(c * 16)));
     };
-    constexpr int TSTEP = 32 * kDecWaves;
-    if (c0 + 32 * wave < c_end) { request_k(c0 + 32 * wave); request_v(c0 + 32 * wave); }
-    for (int base = c0 + 32 * wave; base < c_end; base += TSTEP) {
+    const int TSTEP = 32 * nw;                      // the unit's waves take its 32-token tiles in turn
+    if (c0 + 32 * wv < c_end) { request_k(c0 + 32 * wv); request_v(c0 + 32 * wv); }
+    for (int base = c0 + 32 * wv; base < c_end; base += TSTEP) {
       const bool more = base + TSTEP < c_end;
       // The two slots this step rewrites are still old in memory: their rows are
       // patched in the staged tile (wave-uniform tests, true for one tile per unit).
@@ -734,7 +734,8 @@ __global__ __launch_bounds__(kDecThreads, MF ? SQA_DEC_MF_WAVES : 1) SQA_DEC_OCC
   // waves 1-3 leave here and wave 0 finishes alone: three quarters of the
   // workgroup's registers are free for the next workgroup while the tail runs.
   if (!wpu) __syncthreads();                      // every wave is done reading the cache rows and writing LDS
-  const bool solo = nsplit == 1 && !(MF && H2O);  // (matrix-core H2O: the whole workgroup walks the unit's probabilities)
+  // (matrix-core H2O: the whole workgroup walks the unit's probabilities, unless each wave has a unit of its own)
+  const bool solo = nsplit == 1 && (wpu || !(MF && H2O));
   if (solo && !wpu && wave != 0) return;
   const int nthr = solo ? SQA_WAVE : kDecThreads;
   const int tq = solo ? lane : tid;               // this thread's place among the nthr threads still at work
@@ -742,9 +743,9 @@ __global__ __launch_bounds__(kDecThreads, MF ? SQA_DEC_MF_WAVES : 1) SQA_DEC_OCC
   const int head_next = full ? (head + 1 == rec ? 0 : head + 1) : head;
   int victim = -1;                                // attend-then-evict: heavy slot evicted in this step (-1: the leaver)
   if (H2O) {
-    float fm[G], fi[G];
+    float fm[G], fi[G];                           // (the matrix-core variant reads them from LDS where it needs them)
 #pragma unroll
-    for (int g = 0; g < G; ++g) { fm[g] = s_m[wq][g]; fi[g] = s_l[wq][g]; }
+    for (int g = 0; g < G; ++g) { fm[g] = MF ? 0.f : s_m[wq][g]; fi[g] = MF ? 0.f : s_l[wq][g]; }
     // the heavy region competes with: the NEXT ring leaver for the next step's decision (evict-then-attend),
     // or this step's ring leaver right now (attend-then-evict)
     const bool decide = ae ? full : n == budget;
@@ -753,8 +754,8 @@ __global__ __launch_bounds__(kDecThreads, MF ? SQA_DEC_MF_WAVES : 1) SQA_DEC_OCC
     // Matrix-core variant: one factor per (head, 32-token tile) turns a stored probability into the final
     // one, exp2(reference - m) / l; the table goes where the tiles were staged (if the unit is so long that
     // it does not fit there, the factor is recomputed per token instead).
-    float* fac = reinterpret_cast<float*>(s_logit + G * a.lds_chunk);
-    const bool use_fac = MF && (size_t)G * tpitch * sizeof(float) <= (size_t)kDecWaves * kStageBytesPerWave;
+    float* fac = reinterpret_cast<float*>(reinterpret_cast<char*>(s_logit + G * a.lds_chunk) + (wpu ? wave * kStageBytesPerWave : 0));
+    const bool use_fac = MF && (size_t)G * tpitch * sizeof(float) <= (size_t)nw * kStageBytesPerWave;
     if constexpr (MF) {
       if (use_fac) {
         const int ntile = (n + 31) >> 5;
@@ -763,11 +764,11 @@ __global__ __launch_bounds__(kDecThreads, MF ? SQA_DEC_MF_WAVES : 1) SQA_DEC_OCC
           const float rf = handover ? ld_agent(&tref[g * tpitch + t]) : tref[g * tpitch + t];
           fac[g * tpitch + t] = fast_exp2(rf - s_m[wq][g]) * s_l[wq][g];
         }
-        __syncthreads();                          // (all waves are here: the variant never runs step 3 on one wave)
+        if (!solo) __syncthreads();               // (a wave on its own reads back what it wrote itself: LDS keeps a wave's order)
       }
     }
     float mn = INFINITY;
-    constexpr int SB = MF ? 8 : 4;                // scores requested together: one round trip per SB tokens
+    constexpr int SB = 4;                         // scores requested together: one round trip per SB tokens
     for (int i0 = tq; i0 < n; i0 += SB * nthr) {
       float cur[SB];
 #pragma unroll
@@ -786,7 +787,7 @@ __global__ __launch_bounds__(kDecThreads, MF ? SQA_DEC_MF_WAVES : 1) SQA_DEC_OCC
               const unsigned short eb = handover ? ld_agent(&e16[(int64_t)g * pitch16 + i]) : e16[(int64_t)g * pitch16 + i];
               const float e = __uint_as_float((uint32_t)eb << 16);
               p += e * (use_fac ? fac[g * tpitch + (i >> 5)]
-                                : fast_exp2(ld_agent(&tref[g * tpitch + (i >> 5)]) - fm[g]) * fi[g]);
+                                : fast_exp2(ld_agent(&tref[g * tpitch + (i >> 5)]) - s_m[wq][g]) * s_l[wq][g]);
             } else {
               const float lg = glogit ? ld_agent(&glogit[(int64_t)g * lpitch + i]) : s_lg[g * lp + i];
               p += fast_exp2(lg - fm[g]) * fi[g];
@@ -899,7 +900,7 @@ constexpr int64_t kMinItems = SQA_DEC_MIN_ITEMS;
 constexpr int kMaxUnsplit = 8192;
 // One wave per unit: for units of at most kWpuMaxSlots slots, in calls that have at least kWpuMinUnits
 // units (one wave walks a unit 16 rows at a time, so the call needs many units to keep the chip's wave
-// slots filled).  Not for the matrix-core variant, whose tiles are 32 tokens per wave already.
+// slots filled; the matrix-core variant walks it one 32-token tile at a time).
 constexpr int kWpuMaxSlots = 256;
 constexpr int64_t kWpuMinUnits = 4096;
 // scratch_probs: the H2O step's per-token, per-head values live in the workspace for every unit, split or
@@ -923,8 +924,8 @@ static sqa_status plan_decode(const sqa_layer_cache* layers, int n_layers, int B
   if (h2o && !scratch_probs && target > kMaxUnsplit / g) target = kMaxUnsplit / g;
 #endif
   uint64_t blocks = 0, n_units = 0, n_part = 0, n_logit = 0;
-  p->lds_chunk = 64;
-  p->lds_chunk_w = 64;
+  p->lds_chunk = scratch_probs ? 0 : 64;           // (no LDS logits at all when they live in the workspace)
+  p->lds_chunk_w = scratch_probs ? 0 : 64;
 #ifdef SQA_DEC_NO_WPU
   allow_wpu = false;
 #endif
@@ -940,7 +941,7 @@ static sqa_status plan_decode(const sqa_layer_cache* layers, int n_layers, int B
     p->nsplit[i] = (uint16_t)ns;
     p->chunk[i] = (uint32_t)ch;
     p->wpu[i] = allow_wpu && ns == 1 && nmax <= kWpuMaxSlots && units * n_layers >= kWpuMinUnits;
-    if (p->wpu[i]) { if (ch > p->lds_chunk_w) p->lds_chunk_w = (int)ch; }
+    if (p->wpu[i]) { if (!scratch_probs && ch > p->lds_chunk_w) p->lds_chunk_w = (int)ch; }
     else if (ns == 1 && !scratch_probs && ch > p->lds_chunk) p->lds_chunk = (int)ch;
     p->unit_off[i] = (uint32_t)n_units;
     p->part_off[i] = (uint32_t)n_part;
@@ -1059,7 +1060,7 @@ extern "C" sqa_status sqa_decode_step_ex(const void* q, const void* k_new, const
   }
   const bool mfma = dt == SQA_BF16 && D == 128 && g >= kMfmaMinGroup;
   DecodePlan plan;
-  const sqa_status ps = plan_decode(layers, n_layers, B, Hq, Hkv, D, h2o, !mfma, h2o && mfma, &plan);
+  const sqa_status ps = plan_decode(layers, n_layers, B, Hq, Hkv, D, h2o, true, h2o && mfma, &plan);
   if (ps != SQA_OK) return ps;
   if (ws_bytes < plan.bytes) return SQA_ERR_CAPACITY;
   const size_t lds_shared = (size_t)g * plan.lds_chunk, lds_waves = (size_t)kDecWaves * g * plan.lds_chunk_w;
