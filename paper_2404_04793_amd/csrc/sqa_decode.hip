@@ -230,6 +230,9 @@ typedef __bf16 bf16x4_t __attribute__((ext_vector_type(4)));
 typedef short v4s_t __attribute__((ext_vector_type(4)));
 typedef short v8s_t __attribute__((ext_vector_type(8)));
 typedef __attribute__((address_space(3))) v4s_t* lds_v4s_ptr;
+constexpr int kLogitPad = 33;                     // a unit's H2O scratch region: G x (slots + kLogitPad) floats: the logit of the
+                                                  // new token as one more slot, or whole 32-token tiles of bf16 probabilities
+                                                  // plus a reference per tile and head
 constexpr int kStageRow = 256 + 16;               // LDS row pitch of a staged bf16 D=128 row (padded: no bank conflicts)
 constexpr int kStageBytesPerWave = 32 * kStageRow;   // one 32-token tile
 
@@ -369,16 +372,17 @@ __global__ __launch_bounds__(kDecThreads, MF ? SQA_DEC_MF_WAVES : 1) SQA_DEC_OCC
   // ---- 1. stream the chunk's K and V once, online softmax -------------------
   const int c_end = min(c0 + csize, n);
   const int lpitch = cap + 1;                      // logit row of one head in scratch (the new token may be slot cap)
-  float* glogit = (H2O && (nsplit > 1 || MF)) ? a.logit + a.lay[layer].logit_off + (uoff + u) * G : nullptr;   // units before this one hold uoff slots + one spare each
-  // The matrix-core variant keeps, in those G x lpitch floats of the workspace (for every unit, split or not:
-  // nothing of it needs LDS), per head `pitch16` bf16 probabilities relative to their tile's reference (first
-  // half of the region) and one reference per 32-token tile (second half; tiles start at multiples of 32
-  // because chunks do).  Both halves fit for lpitch >= 2.  They are written and read by the same workgroup
-  // unless the unit is split: only then do they need the coherent path.
-  const int pitch16 = lpitch >= 8 ? (lpitch + 3) & ~3 : lpitch, tpitch = (lpitch + 31) >> 5;
+  // (a unit's scratch region: G x (its slots + kLogitPad) floats, regions in unit order)
+  float* glogit = (H2O && (nsplit > 1 || MF)) ? a.logit + a.lay[layer].logit_off + (uoff + (int64_t)kLogitPad * u) * G : nullptr;
+  // The matrix-core variant keeps in that region (for every unit, split or not: nothing of it needs LDS), tile
+  // by tile of 32 tokens, the bf16 probabilities relative to the tile's reference, [tile][head][32] -- a wave
+  // writes a tile's G x 64 bytes in one go, whole cache lines -- and behind them the references, [tile][head]
+  // (tiles start at multiples of 32 because chunks do).  They are written and read by the same workgroup unless
+  // the unit is split: only then do they need the coherent path.
+  const int ntile_max = (lpitch + 31) >> 5;
   const bool handover = nsplit > 1;
   unsigned short* e16 = reinterpret_cast<unsigned short*>(glogit);
-  float* tref = (MF && H2O) ? glogit + (G * pitch16) / 2 : nullptr;
+  float* tref = (MF && H2O) ? glogit + (int64_t)ntile_max * G * 16 : nullptr;
 
   if constexpr (MF) {
     // ---- 1M. matrix-core streaming ------------------------------------------
@@ -508,24 +512,14 @@ __global__ __launch_bounds__(kDecThreads, MF ? SQA_DEC_MF_WAVES : 1) SQA_DEC_OCC
         // head instead of a 4-byte logit: for split units these go through memory, where every byte
         // written costs as much as several bytes read.
 #pragma unroll
-        for (int tt = 0; tt < 2; ++tt) {
-          const int tok0 = base + 16 * tt + 4 * j4;
-          unsigned short* dst = e16 + (int64_t)hd * pitch16 + tok0;
+        for (int tt = 0; tt < 2; ++tt) {            // (tokens beyond the unit's end get zeros: the region holds whole tiles)
+          unsigned long long* dst = reinterpret_cast<unsigned long long*>(e16 + ((int64_t)(base >> 5) * G + hd) * 32 + 16 * tt + 4 * j4);
           const unsigned long long four = __builtin_bit_cast(unsigned long long, pfr[tt]);
-          if (tok0 + 3 < c_end && (pitch16 & 3) == 0) {       // whole and 8-byte aligned
-            if (handover) st_agent(reinterpret_cast<unsigned long long*>(dst), four);
-            else *reinterpret_cast<unsigned long long*>(dst) = four;
-          } else {
-#pragma unroll
-            for (int e = 0; e < 4; ++e)
-              if (tok0 + e < c_end) {
-                const unsigned short one = (unsigned short)(four >> (16 * e));
-                if (handover) st_agent(dst + e, one); else dst[e] = one;
-              }
-          }
+          if (handover) st_agent(dst, four); else *dst = four;
         }
         if (j4 == 0) {
-          if (handover) st_agent(&tref[hd * tpitch + (base >> 5)], ms); else tref[hd * tpitch + (base >> 5)] = ms;
+          float* dst = &tref[(base >> 5) * G + hd];
+          if (handover) st_agent(dst, ms); else *dst = ms;
         }
       }
       if (__ballot(alpha != 1.f)) {
@@ -755,14 +749,14 @@ __global__ __launch_bounds__(kDecThreads, MF ? SQA_DEC_MF_WAVES : 1) SQA_DEC_OCC
     // one, exp2(reference - m) / l; the table goes where the tiles were staged (if the unit is so long that
     // it does not fit there, the factor is recomputed per token instead).
     float* fac = reinterpret_cast<float*>(reinterpret_cast<char*>(s_logit + G * a.lds_chunk) + (wpu ? wave * kStageBytesPerWave : 0));
-    const bool use_fac = MF && (size_t)G * tpitch * sizeof(float) <= (size_t)nw * kStageBytesPerWave;
+    const bool use_fac = MF && (size_t)G * ntile_max * sizeof(float) <= (size_t)nw * kStageBytesPerWave;
     if constexpr (MF) {
       if (use_fac) {
         const int ntile = (n + 31) >> 5;
         for (int idx = tq; idx < G * ntile; idx += nthr) {
-          const int g = idx / ntile, t = idx - g * ntile;
-          const float rf = handover ? ld_agent(&tref[g * tpitch + t]) : tref[g * tpitch + t];
-          fac[g * tpitch + t] = fast_exp2(rf - s_m[wq][g]) * s_l[wq][g];
+          const int g = idx % G;                  // idx = tile * G + head
+          const float rf = handover ? ld_agent(&tref[idx]) : tref[idx];
+          fac[idx] = fast_exp2(rf - s_m[wq][g]) * s_l[wq][g];
         }
         if (!solo) __syncthreads();               // (a wave on its own reads back what it wrote itself: LDS keeps a wave's order)
       }
@@ -784,10 +778,11 @@ __global__ __launch_bounds__(kDecThreads, MF ? SQA_DEC_MF_WAVES : 1) SQA_DEC_OCC
 #pragma unroll
           for (int g = 0; g < G; ++g) {
             if constexpr (MF) {
-              const unsigned short eb = handover ? ld_agent(&e16[(int64_t)g * pitch16 + i]) : e16[(int64_t)g * pitch16 + i];
+              const int64_t at = ((int64_t)(i >> 5) * G + g) * 32 + (i & 31);
+              const unsigned short eb = handover ? ld_agent(&e16[at]) : e16[at];
               const float e = __uint_as_float((uint32_t)eb << 16);
-              p += e * (use_fac ? fac[g * tpitch + (i >> 5)]
-                                : fast_exp2(ld_agent(&tref[g * tpitch + (i >> 5)]) - s_m[wq][g]) * s_l[wq][g]);
+              p += e * (use_fac ? fac[(i >> 5) * G + g]
+                                : fast_exp2(ld_agent(&tref[(i >> 5) * G + g]) - s_m[wq][g]) * s_l[wq][g]);
             } else {
               const float lg = glogit ? ld_agent(&glogit[(int64_t)g * lpitch + i]) : s_lg[g * lp + i];
               p += fast_exp2(lg - fm[g]) * fi[g];
@@ -949,7 +944,7 @@ static sqa_status plan_decode(const sqa_layer_cache* layers, int n_layers, int B
     n_units += units;
     blocks += p->wpu[i] ? (units + kDecWaves - 1) / kDecWaves : units * ns;
     if (ns > 1) n_part += units * ns;
-    if (h2o && (ns > 1 || scratch_probs)) n_logit += units * g * ((uint64_t)layers[i].capacity + 1);
+    if (h2o && (ns > 1 || scratch_probs)) n_logit += units * g * ((uint64_t)layers[i].capacity + kLogitPad);
     if (n_units > 0x7fffffffull || n_part > 0x7fffffffull || n_logit > 0xffffffffull || blocks > 0x7fffffffull)
       return SQA_ERR_CAPACITY;
   }
