@@ -10,6 +10,7 @@
 //   gather  the kept K and V rows are copied once (16 bytes per lane).
 // HBM traffic per unit: P scores (H2O) + read and write of the kept rows.
 #include "sqa_common.h"
+#include <algorithm>
 
 namespace sqa {
 
@@ -45,9 +46,10 @@ struct CompressBatch {
   const float* scores[kCmpBatch];
   // per-sequence variation (all NULL for a uniform batch)
   const int32_t* prompt_len;    // [B]
-  const int32_t* budget_seq;    // [n_layers][B], row of this launch's first layer = layer0
+  const int32_t* budget_seq;    // [n_layers][B]
   int32_t* status;
-  int B, Hkv, layer0;
+  int B, Hkv;
+  uint8_t layer[kCmpBatch];     // which layer of the call a slot of this launch holds (row of budget_seq)
 };
 
 template <typename T, int D>
@@ -73,7 +75,7 @@ __global__ __launch_bounds__(kCmpThreads) void prefill_compress_kernel(
   int b = L.budget;
   if (batch.prompt_len || batch.budget_seq) {
     if (batch.prompt_len) P = batch.prompt_len[bidx];
-    if (batch.budget_seq) b = batch.budget_seq[(int64_t)(batch.layer0 + blockIdx.y) * batch.B + bidx];
+    if (batch.budget_seq) b = batch.budget_seq[(int64_t)batch.layer[blockIdx.y] * batch.B + bidx];
     const int min_budget = policy == SQA_H2O ? 2 : (policy == SQA_STREAMING ? n_sink + 1 : 1);
     const bool bad_len = P < 0 || P > P_pad, bad_budget = b < min_budget || b > L.budget;
     if (bad_len || bad_budget) {                           // leave the unit empty and say why
@@ -295,16 +297,23 @@ extern "C" sqa_status sqa_prefill_compress_layers_ex(const void* const* K, const
     batch.prompt_len = opts ? opts->prompt_len : nullptr;
     batch.budget_seq = opts ? opts->budget_seq : nullptr;
     batch.status = opts ? opts->status : nullptr;
-    batch.B = B; batch.Hkv = Hkv; batch.layer0 = l0;
+    batch.B = B; batch.Hkv = Hkv;
+    // The layers that keep the most rows go first: their workgroups copy for the whole launch, and started last
+    // they would finish it alone with most of the chip idle (7B shape: 0.77 -> 0.72 ms for the 32 layers).
+    int order[kCmpBatch];
+    for (int i = 0; i < n; ++i) order[i] = l0 + i;
+    std::stable_sort(order, order + n, [&](int x, int y) { return layers[x].budget > layers[y].budget; });
     size_t lds = 0;
     for (int i = 0; i < n; ++i) {
-      batch.L[i] = layers[l0 + i];
-      batch.K[i] = K[l0 + i];
-      batch.V[i] = V[l0 + i];
-      batch.scores[i] = policy == SQA_H2O ? attn_scores[l0 + i] : nullptr;
-      lds = lds_layer[l0 + i] > lds ? lds_layer[l0 + i] : lds;
+      const int l = order[i];
+      batch.L[i] = layers[l];
+      batch.K[i] = K[l];
+      batch.V[i] = V[l];
+      batch.scores[i] = policy == SQA_H2O ? attn_scores[l] : nullptr;
+      batch.layer[i] = (uint8_t)l;
+      lds = lds_layer[l] > lds ? lds_layer[l] : lds;
     }
-    for (int i = n; i < kCmpBatch; ++i) { batch.L[i] = layers[l0]; batch.K[i] = nullptr; batch.V[i] = nullptr; batch.scores[i] = nullptr; }
+    for (int i = n; i < kCmpBatch; ++i) { batch.L[i] = layers[l0]; batch.K[i] = nullptr; batch.V[i] = nullptr; batch.scores[i] = nullptr; batch.layer[i] = 0; }
     hipError_t e;
     if (kv_dt == SQA_F32) {
       if (D == 64) e = launch_compress<float, 64>(batch, n, P, policy, n_sink, units, lds, st);
