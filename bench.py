@@ -28,7 +28,7 @@ HBM_PEAK_GBS = 8000.0
 # HBM bytes per decode launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, scaled by what the same
 # counters read for a plain 1 GiB copy kernel (x2.0 / x1.0); see profiles/decode_importance_compress__<workload>.txt.
 # Counters cannot be read from inside this process, so the figure is the one of the committed profile.
-MEASURED_TRAFFIC_BYTES = {("llama2_7b", "squeeze", "h2o", "all_layers"): 820869.1 * 1024 * 2.0 + 19392.9 * 1024}
+MEASURED_TRAFFIC_BYTES = {("llama2_7b", "squeeze", "h2o", "all_layers"): 820870.1 * 1024 * 2.0 + 19393.0 * 1024}
 
 
 def cpu_baseline(sess, units_per_layer: int, steps: int):
