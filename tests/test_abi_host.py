@@ -201,3 +201,12 @@ int main(void) {
     assert run.returncode == 0, (run.stdout, run.stderr)
     total, n3, low, high = [int(x) for x in run.stdout.split()]
     assert total == 32000 and n3 == 14 and low == 300 and high in (1544, 1545)   # 14 x 300 + 18 x 1544.4 = 32000
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """bench.py measures one GPU; asked for more it says so and exits before touching any device."""
+    import subprocess, sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True, text=True,
+                       timeout=120)
+    assert r.returncode == 2 and "ONE GPU" in r.stderr and r.stdout.strip() == ""
