@@ -51,6 +51,7 @@ struct CompressBatch {
   int B, Hkv;
   uint8_t layer[kCmpBatch];     // which layer of the call a slot of this launch holds (row of budget_seq)
 };
+static_assert(SQA_MAX_LAYERS <= 256, "CompressBatch::layer holds a layer index in 8 bits");
 
 template <typename T, int D>
 __global__ __launch_bounds__(kCmpThreads) void prefill_compress_kernel(
