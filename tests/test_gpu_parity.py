@@ -645,12 +645,14 @@ def test_decode_reports_bad_state_without_touching_the_cache(sqa):
     assert sqa.read_device_status(ws) == 6        # SQA_ERR_CAPACITY
 
 
-def test_decode_steps_replayed_from_a_hip_graph(sqa):
+@pytest.mark.parametrize("Hq", [4, 8])
+def test_decode_steps_replayed_from_a_hip_graph(sqa, Hq):
     """One launch per layer recorded once into a HIP graph (positions from a device array), replayed
     for every step with eager work and synchronisations between the replays: every replay must leave
-    the same bytes as the eager run of the same step."""
+    the same bytes as the eager run of the same step.  (8 query heads on 2 KV heads: the matrix-core
+    variant, with its direct loads into LDS and its scratch in the workspace.)"""
     from paper_2404_04793_amd.session import Session
-    wl = W.scaled(W.WORKLOADS["tiny"], L=4, B=2, P=96, S=10, dtype="bf16", D=128, Hq=4, Hkv=2, hidden=256)
+    wl = W.scaled(W.WORKLOADS["tiny"], L=4, B=2, P=96, S=10, dtype="bf16", D=128, Hq=Hq, Hkv=2, hidden=256)
     runs = []
     for use_graph in (False, True):
         sess = Session(wl, DEV)
