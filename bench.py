@@ -154,6 +154,7 @@ def main():
     ap.add_argument("--scores-only", action="store_true",
                     help="time only the H2O prompt-score producer (sqa_prefill_scores; set-up work of the pass, "
                          "matrix-core bound): a step = the scores of all layers of one prompt batch")
+    ap.add_argument("--progress", action="store_true", help="say on stderr when each phase of the run begins")
     ap.add_argument("--cpu-units", type=int, default=32)
     ap.add_argument("--cpu-steps", type=int, default=128)
     args = ap.parse_args()
@@ -180,8 +181,14 @@ def main():
     if args.scores_only:
         return scores_only(args, wl)
     plen = [wl.P - (b * wl.P) // (2 * wl.B) for b in range(wl.B)] if args.ragged else None
+    def say(what):
+        if args.progress:
+            print("bench.py: " + what, file=sys.stderr, flush=True)
+
+    say("generating inputs for %s" % wl.name)
     sess = Session(wl, "cuda:0", uniform_budget=args.uniform, full_cache=args.full_cache,
                    probe_tokens=args.probe_tokens, fused_probe=args.fused_probe, order=args.order, prompt_len=plen)
+    say("inputs ready")
 
     def do_decode():
         if args.graph:
@@ -221,9 +228,11 @@ def main():
             return cos
         one_pass.timed = 0.0
 
-    for _ in range(args.warmup):
+    for i in range(args.warmup):
+        say("warm-up pass %d" % (i + 1))
         one_pass()
     torch.cuda.synchronize()
+    say("timed passes")
     if args.decode_only:
         one_pass.timed = 0.0
     evs = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(args.steps)]
