@@ -339,11 +339,16 @@ __global__ __launch_bounds__(kScThreads) void score_rowstats_mfma_kernel(
         if (c0 > rb + 15) continue;                 // wave-uniform: all keys beyond all rows of the block
         const sc_f32x4_t s4 = block_product(afr, qfr[bb]);
         float v[4], mx = m_run[bb];
+        if (c0 + 15 <= rb && c0 + 16 <= P) {        // wave-uniform: the whole block is visible, only its neighbours are not
 #pragma unroll
-        for (int e = 0; e < 4; ++e) {
-          const int key = c0 + 4 * j4 + e;
-          v[e] = (key <= my_row && key < P) ? s4[e] * scale_log2 : -INFINITY;
-          mx = fmaxf(mx, v[e]);
+          for (int e = 0; e < 4; ++e) { v[e] = s4[e] * scale_log2; mx = fmaxf(mx, v[e]); }
+        } else {
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            const int key = c0 + 4 * j4 + e;
+            v[e] = (key <= my_row && key < P) ? s4[e] * scale_log2 : -INFINITY;
+            mx = fmaxf(mx, v[e]);
+          }
         }
         const float ms = mx == -INFINITY ? 0.f : mx;
         float sum = l_run[bb] * __builtin_amdgcn_exp2f(m_run[bb] - ms);
@@ -447,11 +452,16 @@ __global__ __launch_bounds__(kScThreads) void score_colsum_mfma_kernel(
         const int kb = k0 + 64 * bb, my_key = kb + n16;
         if (i0 + 15 < kb) continue;                 // wave-uniform: all rows above all keys of the block
         const sc_f32x4_t s4 = block_product(afr, kfr[bb]);
+        if (i0 >= kb + 15 && i0 + 16 <= Pq) {       // wave-uniform: every row of the block sees every key of it
 #pragma unroll
-        for (int e = 0; e < 4; ++e) {
-          const int row = i0 + 4 * j4 + e;
-          const float p = __builtin_amdgcn_exp2f(fmaf(s4[e], scale_log2, -crow[e]));
-          colsum[bb] += (row >= my_key && row < Pq) ? p : 0.f;
+          for (int e = 0; e < 4; ++e) colsum[bb] += __builtin_amdgcn_exp2f(fmaf(s4[e], scale_log2, -crow[e]));
+        } else {
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            const int row = i0 + 4 * j4 + e;
+            const float p = __builtin_amdgcn_exp2f(fmaf(s4[e], scale_log2, -crow[e]));
+            colsum[bb] += (row >= my_key && row < Pq) ? p : 0.f;
+          }
         }
       }
     }
