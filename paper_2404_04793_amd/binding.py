@@ -13,7 +13,7 @@ from typing import List, Optional, Sequence, Tuple
 import torch
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.environ.get("SQA_LIB", os.path.join(_HERE, "libsqa.so"))   # SQA_LIB: another build of the same ABI
+LIB_PATH = os.path.join(_HERE, "libsqa.so")
 
 if not os.path.exists(LIB_PATH):
     raise ImportError(

@@ -32,18 +32,9 @@
 
 namespace sqa {
 
-#ifndef SQA_DEC_THREADS
-#define SQA_DEC_THREADS 256
-#endif
-constexpr int kDecThreads = SQA_DEC_THREADS;
+constexpr int kDecThreads = 256;
 constexpr int kDecWaves = kDecThreads / SQA_WAVE;
-#ifndef SQA_DEC_UNROLL
-#define SQA_DEC_UNROLL 4
-#endif
-#ifndef SQA_DEC_PREFETCH
-#define SQA_DEC_PREFETCH 1
-#endif
-constexpr int kUnroll = SQA_DEC_UNROLL;     // rows per lane group in flight per loop trip
+constexpr int kUnroll = 4;                  // rows per lane group in flight per loop trip
 
 struct DecodeArgs {
   const void* q;
@@ -216,14 +207,7 @@ template <> struct RowMath<bf16_t> {
 
 typedef __attribute__((address_space(1))) const void dec_gptr_t;
 typedef __attribute__((address_space(3))) void dec_lptr_t;
-#ifndef SQA_DEC_MF_WAVES
-#define SQA_DEC_MF_WAVES 3      // waves per SIMD the matrix-core variant is compiled for
-#endif
-#ifdef SQA_DEC_WAVES_PER_EU
-#define SQA_DEC_OCC __attribute__((amdgpu_waves_per_eu(SQA_DEC_WAVES_PER_EU, SQA_DEC_WAVES_PER_EU)))
-#else
-#define SQA_DEC_OCC
-#endif
+constexpr int kMfWavesPerSimd = 3;                // waves per SIMD the matrix-core variant is compiled for
 typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
 typedef float f32x4_t __attribute__((ext_vector_type(4)));
 typedef __bf16 bf16x4_t __attribute__((ext_vector_type(4)));
@@ -239,7 +223,7 @@ constexpr int kStageBytesPerWave = 32 * kStageRow;   // one 32-token tile
 // MF = true (bf16, D = 128, grouped queries): the chunk is streamed in 32-token
 // tiles through LDS and q.K^T / P.V run on the matrix cores, see section 1M.
 template <typename T, int D, int G, bool H2O, bool MF>
-__global__ __launch_bounds__(kDecThreads, MF ? SQA_DEC_MF_WAVES : 1) SQA_DEC_OCC void decode_unit_kernel(const DecodeArgs a) {
+__global__ __launch_bounds__(kDecThreads, MF ? kMfWavesPerSimd : 1) void decode_unit_kernel(const DecodeArgs a) {
   static_assert(!MF || (sizeof(T) == 2 && D == 128 && G <= 16), "matrix-core path: bf16, D = 128");
   constexpr int ROWB = D * (int)sizeof(T);        // bytes per K or V row
   constexpr int LPR = ROWB / 16;                  // lanes per row
@@ -319,16 +303,21 @@ __global__ __launch_bounds__(kDecThreads, MF ? SQA_DEC_MF_WAVES : 1) SQA_DEC_OCC
   const uint4 kn_pre = ld16(knew + c * 16), vn_pre = ld16(vnew + c * 16);
   uint4 kf[kUnroll], vf[kUnroll];
   int slot[kUnroll];
+  // (a packed unit may own no slot at all -- it is reported below, once its length is known --: these
+  // early requests then read the new token's rows instead, which always exist)
+  const bool has_slots = cap > 0;
   if constexpr (!MF) {
+    const char* Kpre = has_slots ? Kb : knew;
+    const char* Vpre = has_slots ? Vb : vnew;
 #pragma unroll
     for (int uu = 0; uu < kUnroll; ++uu) {
       slot[uu] = c0 + uu * rows_it + wv * RPI + r;
-      const int sl = min(slot[uu], cap - 1);
-      kf[uu] = ld16_nt(Kb + (int64_t)sl * ROWB + c * 16);
-      vf[uu] = ld16_nt(Vb + (int64_t)sl * ROWB + c * 16);
+      const int sl = max(min(slot[uu], cap - 1), 0);
+      kf[uu] = ld16_nt(Kpre + (int64_t)sl * ROWB + c * 16);
+      vf[uu] = ld16_nt(Vpre + (int64_t)sl * ROWB + c * 16);
     }
   }
-  const float sc_pre = H2O ? sc[min(tix, cap - 1)] : 0.f;
+  const float sc_pre = (H2O && has_slots) ? sc[min(tix, cap - 1)] : 0.f;
 
   // ---- 0. where does the new token go, who leaves -------------------------
   if (sits_out) return;                           // the sequence takes no part in this step (every chunk agrees)
@@ -692,9 +681,13 @@ __global__ __launch_bounds__(kDecThreads, MF ? SQA_DEC_MF_WAVES : 1) SQA_DEC_OCC
   }
 
   if (nsplit > 1) {
-    // publish this chunk, find out whether it is the last one of the unit.  The
-    // barrier waits until every thread's stores above have completed (they are
-    // write-through), so whoever later sees the counter sees them too.
+    // Publish this chunk, find out whether it is the last one of the unit.  Every
+    // thread first waits until its own stores above (partials, logits, probabilities:
+    // agent-scope, written through to where every XCD sees them) have been
+    // acknowledged -- s_waitcnt vmcnt(0); a workgroup barrier alone orders LDS traffic,
+    // not outstanding global stores --, then the barrier collects the threads, and only
+    // then does thread 0 bump the counter: whoever sees the count sees the data.
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();
     int32_t* cnt = a.cnt + a.lay[layer].unit_off + u;
     if (tid == 0) s_ctl[0] = __hip_atomic_fetch_add(cnt, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -839,13 +832,10 @@ __global__ __launch_bounds__(kDecThreads, MF ? SQA_DEC_MF_WAVES : 1) SQA_DEC_OCC
 
 typedef void (*decode_fn)(const DecodeArgs);
 
-// Grouped queries of 8 heads in bf16 at D = 128 go to the matrix cores: there the vector-ALU path is
-// arithmetic bound (measured 4.2 TB/s against 5.7 TB/s on the Llama-2-70B shape); at 4 heads the
-// vector-ALU path is still the faster one (6.5 against 5.8 TB/s on the Mistral-7B shape).
-#ifndef SQA_DEC_MFMA_MIN_GROUP
-#define SQA_DEC_MFMA_MIN_GROUP 4      // query heads per KV head from which the matrix-core variant is used
-#endif
-constexpr int kMfmaMinGroup = SQA_DEC_MFMA_MIN_GROUP;
+// Grouped queries of 4 or more heads per KV head in bf16 at D = 128 go to the matrix cores: with 8 heads
+// the vector-ALU path is arithmetic bound (4.2 TB/s against 6.5 TB/s on the Llama-2-70B shape), with 4
+// heads the matrix-core variant is still slightly ahead (779 against 797 us per step on the Mistral-7B shape).
+constexpr int kMfmaMinGroup = 4;      // query heads per KV head from which the matrix-core variant is used
 template <typename T, int D, int G> constexpr bool use_mfma() { return sizeof(T) == 2 && D == 128 && G >= kMfmaMinGroup; }
 template <typename T, int D, bool H2O> decode_fn pick_g(int g) {
   switch (g) {
@@ -888,10 +878,7 @@ static size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 // lets a unit's step logits fit in LDS (kMaxUnsplit slots x heads; not for the matrix-core variant, which keeps
 // what H2O needs in the workspace); each layer uses the number of equal
 // chunks nearest to that, so units shorter than 1.5 targets stay whole.
-#ifndef SQA_DEC_MIN_ITEMS
-#define SQA_DEC_MIN_ITEMS (256 * 4)
-#endif
-constexpr int64_t kMinItems = SQA_DEC_MIN_ITEMS;
+constexpr int64_t kMinItems = 256 * 4;
 constexpr int kMaxUnsplit = 8192;
 // One wave per unit: for units of at most kWpuMaxSlots slots, in calls that have at least kWpuMinUnits
 // units (one wave walks a unit 16 rows at a time, so the call needs many units to keep the chip's wave
@@ -910,20 +897,12 @@ static sqa_status plan_decode(const sqa_layer_cache* layers, int n_layers, int B
     if (layers[i].budget < 1) return SQA_ERR_BUDGET;
     tokens += units * (layers[i].budget < layers[i].capacity ? layers[i].budget : layers[i].capacity);
   }
-  int64_t target;
-#ifdef SQA_DEC_FORCE_CHUNK
-  target = SQA_DEC_FORCE_CHUNK;
-#else
-  target = tokens / kMinItems;
+  int64_t target = tokens / kMinItems;
   target = target < 256 ? 256 : target;
   if (h2o && !scratch_probs && target > kMaxUnsplit / g) target = kMaxUnsplit / g;
-#endif
   uint64_t blocks = 0, n_units = 0, n_part = 0, n_logit = 0;
   p->lds_chunk = scratch_probs ? 0 : 64;           // (no LDS logits at all when they live in the workspace)
   p->lds_chunk_w = scratch_probs ? 0 : 64;
-#ifdef SQA_DEC_NO_WPU
-  allow_wpu = false;
-#endif
   for (int i = 0; i < n_layers; ++i) {
     // + 1: under attend-then-evict a full unit attends budget + 1 tokens
     const int nmax = (layers[i].budget < layers[i].capacity ? layers[i].budget : layers[i].capacity) + 1;

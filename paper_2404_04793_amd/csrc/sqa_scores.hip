@@ -15,9 +15,7 @@
 
 namespace sqa {
 
-#ifndef SQA_SC_NB
-#define SQA_SC_NB 2          // 16-row blocks a wave of the matrix-core kernels keeps in registers (4: no faster)
-#endif
+constexpr int kScBlocksPerWave = 2;   // 16-row blocks a wave of the matrix-core kernels keeps in registers (4: no faster)
 constexpr int kScThreads = 256;
 constexpr int kTile = 64;        // rows and columns of a logit tile
 constexpr int kDK = 32;          // slab of the head dimension staged per step
@@ -536,7 +534,7 @@ extern "C" sqa_status sqa_prefill_scores_ex(const void* Q, const void* K, sqa_dt
     else launch_scores<float, 128>(Q, K, B, Hq, Hkv, P, plen, scores_out, stats, st);
   } else {
     if (D == 64) launch_scores<bf16_t, 64>(Q, K, B, Hq, Hkv, P, plen, scores_out, stats, st);
-    else launch_scores_mfma<SQA_SC_NB>(Q, K, B, Hq, Hkv, P, plen, scores_out, reinterpret_cast<float*>(stats), st);
+    else launch_scores_mfma<kScBlocksPerWave>(Q, K, B, Hq, Hkv, P, plen, scores_out, reinterpret_cast<float*>(stats), st);
   }
   SQA_HIP_CHECK(hipGetLastError());
   return SQA_OK;

@@ -10,18 +10,26 @@ import torch
 
 from oracle import sqa_oracle as O
 from paper_2404_04793_amd import workloads as W
-from tests.harness import TOL, export_state, import_state, near_tie_swap, np64, rel_err, round_scores_f32
+from tests.harness import (TOL, carried_victim_pos, check_step_scores, clustering_margin, export_light, export_state,
+                           import_state, near_tie_swap, np64, oracle_next_victim_pos, oracle_view, rel_err,
+                           round_scores_f32, uses_matrix_cores)
 
 pytestmark = pytest.mark.gpu
 DEV = "cuda:0"
 
 
-def _run_fullsize(wl, sample_layers, units, check_steps, cos_layers, order="evict_then_attend"):
+def _run_fullsize(wl, sample_layers, units, check_steps, cos_layers, order="evict_then_attend", probe_tokens=None):
+    """check_steps are teacher-forced (the oracle's state is written into the sampled units first, which also
+    discards the eviction decision the unit carried: the kernel decides afresh); at every other step the test
+    only READS the sampled units' state before the step and lets the oracle take the same step from it, so the
+    state the GPU carries from step to step -- ring position, carried eviction decision -- is what is checked."""
     from paper_2404_04793_amd import binding as sqa
     from paper_2404_04793_amd.session import Session
-    sess = Session(wl, DEV, keep_prompt_q=True, order=order)
+    sess = Session(wl, DEV, keep_prompt_q=True, order=order, probe_tokens=probe_tokens)
     ae = order == "attend_then_evict"
     g, tol = wl.g, TOL[wl.dtype]
+    h2o = wl.policy == "h2o"
+    mc = uses_matrix_cores(wl.dtype, wl.D, g)
 
     # ---- probe + budgets --------------------------------------------------
     cos = np.array(sess.probe_and_allocate(), dtype=np.float32)
@@ -31,13 +39,15 @@ def _run_fullsize(wl, sample_layers, units, check_steps, cos_layers, order="evic
     want_b, want_g = O.allocate_budgets(cos, wl.total_budget, wl.p)
     assert sess.budgets == want_b and sess.groups == want_g and sum(want_b) == wl.total_budget
     budgets = sess.budgets
+    # budgets from GPU cosines may only be compared when fp32 noise cannot flip the clustering
+    assert clustering_margin(cos) > 1e-6, clustering_margin(cos)
 
     # ---- prompt scores + compression on sampled units -----------------------
     sample = [(l, b, h) for l in sample_layers for (b, h) in units]
     state = {}
     for (l, b, h) in sample:
         Kn, Vn = np64(sess.Kp[l][b, h]), np64(sess.Vp[l][b, h])
-        if wl.policy == "h2o":
+        if h2o:
             s_ref = O.prefill_scores(np64(sess.Qp[l][b, h * g:(h + 1) * g]), Kn)
             assert rel_err(np64(sess.scores[l][b, h])[None], s_ref[None]) < tol
             s32 = s_ref.astype(np.float32)
@@ -46,51 +56,69 @@ def _run_fullsize(wl, sample_layers, units, check_steps, cos_layers, order="evic
         else:
             s0 = np.zeros(wl.P)
         state[l, b, h] = O.prefill_compress(Kn, Vn, s0, budgets[l], wl.policy, wl.n_sink)
+    sess.Qp = None
     sess.compress_prompt()
     for key, c in state.items():
         got = export_state(sess.caches, *key)
         assert got["pos"].tolist() == c["pos"].tolist(), key
         assert np.array_equal(got["K"], c["K"]) and np.array_equal(got["V"], c["V"])
-        if wl.policy == "h2o":
+        if h2o:
             assert np.array_equal(got["score"], c["score"])
     for l in range(wl.L):
         assert bool((sess.caches.lens[l] == min(wl.P, budgets[l])).all())
 
-    # ---- decode: GPU runs every step for the whole batch; sampled units are
-    # teacher-forced at check_steps ------------------------------------------
+    # ---- decode: the GPU runs every step for the whole batch ---------------------
     qn = {k: np64(sess.q[:, k[0], k[1], k[2] * g:(k[2] + 1) * g]) for k in sample}
     kn = {k: np64(sess.k_new[:, k[0], k[1], k[2]]) for k in sample}
     vn = {k: np64(sess.v_new[:, k[0], k[1], k[2]]) for k in sample}
-    worst_out = 0.0
+    rows = {k: (np.concatenate([np64(sess.Kp[k[0]][k[1], k[2]]), kn[k]]),
+                np.concatenate([np64(sess.Vp[k[0]][k[1], k[2]]), vn[k]])) for k in sample}     # K, V rows by position
+    worst_out, worst_sc = 0.0, 0.0
+    seen = {"leaver_goes": 0, "heavy_goes": 0, "near_ties": 0}
+    first_divergence = None
     for t in range(wl.S):
-        if t in check_steps:
+        teacher = t in check_steps
+        if teacher:
             for key, c in state.items():
                 import_state(sess.caches, key[0], key[1], key[2], c)
+            before = dict(state)
+        else:
+            before = {key: export_light(sess.caches, *key, *rows[key]) for key in sample}
+            for key in sample:                  # information only: where the run on its own left the teacher's path
+                if first_divergence is None and before[key]["pos"].tolist() != state[key]["pos"].tolist():
+                    first_divergence = (t, key)
         sess.decode(steps=1, start=t)
         for key in sample:
-            before = state[key]
-            want_out, c2 = O.decode_step(before, qn[key][t], kn[key][t], vn[key][t], wl.P + t, budgets[key[0]],
-                                         wl.policy, wl.n_sink, order)
+            l, b, h = key
+            c = before[key]
+            args = (qn[key][t], kn[key][t], vn[key][t], wl.P + t)
+            want_out, c2 = O.decode_step(oracle_view(c), *args, budgets[l], wl.policy, wl.n_sink, order)
             state[key] = round_scores_f32(c2)
-            if t in check_steps:
-                l, b, h = key
-                got = export_state(sess.caches, l, b, h)
-                worst_out = max(worst_out, rel_err(np64(sess.out[t, l, b, h * g:(h + 1) * g]), want_out))
-                if ae and wl.policy == "h2o" and got["pos"].tolist() != c2["pos"].tolist():
-                    # decided on scores updated in this very step (fp32 there, fp64 here): a swap of two
-                    # candidates closer than the fp32 error is legitimate
-                    _, full = O.decode_step(before, qn[key][t], kn[key][t], vn[key][t], wl.P + t, 1 << 30,
-                                            wl.policy, wl.n_sink, order)
-                    upd = dict(zip(full["pos"].tolist(), full["score"].tolist()))
-                    bl = budgets[l]
-                    assert near_tie_swap(got["pos"].tolist(), c2["pos"].tolist(), before, upd, bl - bl // 2, 10 * tol)
-                    continue
-                assert got["pos"].tolist() == c2["pos"].tolist(), (key, t)
+            got = export_state(sess.caches, l, b, h) if teacher else export_light(sess.caches, l, b, h, *rows[key])
+            worst_out = max(worst_out, rel_err(np64(sess.out[t, l, b, h * g:(h + 1) * g]), want_out))
+            if ae and h2o and got["pos"].tolist() != c2["pos"].tolist():
+                # decided on scores updated in this very step (fp32 there, fp64 here): only two candidates the
+                # arithmetic cannot tell apart may be swapped
+                _, full = O.decode_step(oracle_view(c), *args, 1 << 30, wl.policy, wl.n_sink, order)
+                bl = budgets[l]
+                assert near_tie_swap(got["pos"].tolist(), c2["pos"].tolist(), c, full, bl - bl // 2, mc), (key, t)
+                seen["near_ties"] += 1
+                continue
+            assert got["pos"].tolist() == c2["pos"].tolist(), (key, t)
+            if teacher:
                 assert np.array_equal(got["K"], c2["K"]) and np.array_equal(got["V"], c2["V"]), (key, t)
-                if wl.policy == "h2o":
-                    assert rel_err(got["score"][None], c2["score"][None]) < tol, (key, t)
+            if h2o:
+                worst_sc = max(worst_sc, check_step_scores(got, c, c2, mc, (key, t)))
+                if not teacher and not ae and len(got["pos"]) == budgets[l]:
+                    carried = carried_victim_pos(got, budgets[l])
+                    assert carried is not None and carried == oracle_next_victim_pos(got, budgets[l]), (key, t, got["hint"])
+                    seen["leaver_goes" if got["hint"] == -1 else "heavy_goes"] += 1
+    print("%s %s: worst out %.2e (allowed %.0e), worst score error %.2f of its bound, %s, first step at which the "
+          "free-running units differ from the teacher-forced path: %s" % (wl.name, order, worst_out, tol, worst_sc, seen, first_divergence))
     assert worst_out < tol, worst_out
     assert sqa.read_device_status(sess.dec_ws) == 0
+    if h2o and not ae and len(check_steps) < wl.S:
+        assert seen["leaver_goes"] + seen["heavy_goes"] > 0
 
     # ---- properties of every unit -------------------------------------------
     end = wl.P + wl.S
@@ -110,8 +138,8 @@ def _run_fullsize(wl, sample_layers, units, check_steps, cos_layers, order="evic
                 rec = n - n // 2
             want = torch.arange(end - rec, end, device=DEV)
             assert bool((kept[:, :, n - rec:] == want).all()), l           # the recent window
-    assert bool(torch.isfinite(sess.out.float()).all())
-    if wl.policy == "h2o":
+    assert all(bool(torch.isfinite(sess.out[t]).all()) for t in range(wl.S))
+    if h2o:
         for l in range(wl.L):
             tot = sess.caches.score[l][:, :, :min(end, budgets[l])].double().sum(-1)
             assert bool((tot <= g * end * (1 + 1e-4)).all()) and bool((tot > 0).all())
@@ -130,6 +158,29 @@ def test_llama2_7b_full_size_attend_then_evict():
     wl = W.scaled(W.WORKLOADS["llama2_7b"], S=48)
     _run_fullsize(wl, sample_layers=[0, 5, 31], units=[(0, 0), (7, 31)], check_steps={0, 1, 2, 30, 47},
                   cos_layers=[16], order="attend_then_evict")
+
+
+def test_mistral_7b_full_size():
+    """configs[2] at its real batch (32) and layer count, in the launch bench.py times; 8 decode steps; the
+    probe sees 4096 token rows per layer so that the hidden states stay small."""
+    wl = W.scaled(W.WORKLOADS["mistral_7b"], S=8)
+    _run_fullsize(wl, sample_layers=[0, 9, 20, 31], units=[(0, 0), (31, 7)], check_steps={0, 7}, cos_layers=[1, 20],
+                  probe_tokens=4096)
+
+
+def test_llama2_70b_full_size():
+    """configs[3] at its real batch (16) and all 80 layers, in the launch bench.py times; 8 decode steps."""
+    wl = W.scaled(W.WORKLOADS["llama2_70b"], S=8)
+    _run_fullsize(wl, sample_layers=[0, 40, 79], units=[(0, 0), (15, 7)], check_steps={0, 7}, cos_layers=[0, 79],
+                  probe_tokens=2048)
+
+
+def test_stress_7b_full_size():
+    """configs[4] at its real batch (224), 70 decode steps: the 571-slot layers fill at step 59 and evict
+    from then on; the 35-slot layers (one wave per unit) evict from the first step."""
+    wl = W.scaled(W.WORKLOADS["stress_7b"], S=70)
+    _run_fullsize(wl, sample_layers=[0, 12, 31], units=[(0, 0), (223, 31)], check_steps={0, 1, 60, 69}, cos_layers=[0, 12],
+                  probe_tokens=4096)
 
 
 def test_mistral_7b_gqa_streaming_reduced_batch():
@@ -206,14 +257,15 @@ def test_llama2_7b_ragged_batch():
                 import_state(sess.caches, key[0], key[1], key[2], c)
         sess.decode(steps=1, start=t)
         for (l, b, h) in sample:
-            want_out, c2 = O.decode_step(state[l, b, h], np64(sess.q[t, l, b, h * g:(h + 1) * g]), np64(sess.k_new[t, l, b, h]),
+            state_before = state[l, b, h]
+            want_out, c2 = O.decode_step(state_before, np64(sess.q[t, l, b, h * g:(h + 1) * g]), np64(sess.k_new[t, l, b, h]),
                                          np64(sess.v_new[t, l, b, h]), plen[b] + t, sess.budget_seq[l][b], wl.policy, wl.n_sink)
             state[l, b, h] = round_scores_f32(c2)
             if t in check:
                 got = export_state(sess.caches, l, b, h)
                 assert got["pos"].tolist() == c2["pos"].tolist(), (l, b, h, t)
                 assert np.array_equal(got["K"], c2["K"]) and np.array_equal(got["V"], c2["V"])
-                assert rel_err(got["score"][None], c2["score"][None]) < tol
+                check_step_scores(got, state_before, c2, False, (l, b, h, t))
                 worst = max(worst, rel_err(np64(sess.out[t, l, b, h * g:(h + 1) * g]), want_out))
     assert worst < tol and sqa.read_device_status(sess.dec_ws) == 0
     for l in range(wl.L):                                    # every unit: its own length and newest position

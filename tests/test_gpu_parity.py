@@ -10,7 +10,8 @@ import torch
 from oracle import sqa_oracle as O
 from oracle import pipeline as OP
 from paper_2404_04793_amd import workloads as W
-from tests.harness import TOL, export_state, import_state, near_tie_swap, np64, rel_err, round_scores_f32
+from tests.harness import (TOL, check_scores_after_run, check_step_scores, clustering_margin, export_state, import_state,
+                           near_tie_swap, np64, rel_err, round_scores_f32, uses_matrix_cores)
 
 pytestmark = pytest.mark.gpu
 
@@ -309,7 +310,8 @@ def _teacher_forced(sqa, case, order):
     v_all = torch.stack([inp[l][5] for l in range(L)], 1).contiguous()
     qn, kn, vn = np64(q_all), np64(k_all), np64(v_all)
     out = torch.empty(L, B, Hq, D, dtype=wl.torch_dtype, device=DEV)
-    worst = 0.0
+    worst, worst_sc = 0.0, 0.0
+    mc = uses_matrix_cores(dtype, D, g)
     for t in range(S):
         for key, c in state.items():
             import_state(caches, key[0], key[1], key[2], c)
@@ -324,17 +326,17 @@ def _teacher_forced(sqa, case, order):
             if ae and policy == "h2o" and got["pos"].tolist() != c2["pos"].tolist():
                 _, full = O.decode_step(c, qn[t, l, b, h * g:(h + 1) * g], kn[t, l, b, h], vn[t, l, b, h],
                                         P + t, 1 << 30, policy, wl.n_sink, order)       # nothing evicted: all updated scores
-                upd = dict(zip(full["pos"].tolist(), full["score"].tolist()))
-                assert near_tie_swap(got["pos"].tolist(), c2["pos"].tolist(), c, upd, budgets[l] - budgets[l] // 2,
-                                      10 * TOL[dtype]), (name, t, l, b, h)
+                assert near_tie_swap(got["pos"].tolist(), c2["pos"].tolist(), c, full, budgets[l] - budgets[l] // 2,
+                                     mc), (name, t, l, b, h)
                 state[l, b, h] = round_scores_f32(c2)
                 continue
             assert got["pos"].tolist() == c2["pos"].tolist(), (name, t, l, b, h)
             assert np.array_equal(got["K"], c2["K"]) and np.array_equal(got["V"], c2["V"])
             if policy == "h2o":
-                assert rel_err(got["score"][None], c2["score"][None]) < TOL[dtype], (name, t, l, b, h)
+                worst_sc = max(worst_sc, check_step_scores(got, c, c2, mc, (name, t, l, b, h)))
             state[l, b, h] = round_scores_f32(c2)
     assert worst < TOL[dtype], (name, worst)
+    print("%s %s: worst out error %.2e of %.0e allowed, worst score error %.2f of its bound" % (name, order, worst, TOL[dtype], worst_sc))
 
 
 def test_decode_tie_breaking_and_leaver_cases(sqa):
@@ -356,7 +358,8 @@ def test_decode_tie_breaking_and_leaver_cases(sqa):
         want_out, c2 = O.decode_step(c, np64(q)[0, 0], np64(k)[0, 0, 0], np64(v)[0, 0, 0], 24, b, "h2o")
         got = export_state(caches, 0, 0, 0)
         assert got["pos"].tolist() == c2["pos"].tolist(), scores
-        assert rel_err(np64(out)[0, 0], want_out) < 1e-5 and rel_err(got["score"][None], c2["score"][None]) < 1e-5
+        assert rel_err(np64(out)[0, 0], want_out) < 1e-5
+        check_step_scores(got, c, c2, False, scores)
 
 
 def test_decode_free_running_tiny(sqa):
@@ -369,6 +372,9 @@ def test_decode_free_running_tiny(sqa):
     h_in = torch.stack([x[0] for x in hs]); h_out = torch.stack([x[1] for x in hs])
     cos = sqa.layer_importance(h_in, h_out).cpu().numpy()
     budgets, _ = sqa.allocate_budgets(cos, wl.total_budget, wl.p)
+    # budgets from the GPU's cosines against budgets from the oracle's: comparable because the best split is
+    # far ahead of the second best (fp32 noise in the cosines cannot flip it)
+    assert clustering_margin(cos) > 1e-6
     assert budgets == O.allocate_budgets(O.layer_importance(np64(h_in), np64(h_out)).astype(np.float32),
                                          wl.total_budget, wl.p)[0]
     caches = _mk_caches(sqa, budgets, budgets, wl.B, wl.Hkv, wl.D, wl.dtype)
@@ -400,7 +406,7 @@ def test_decode_free_running_tiny(sqa):
                 assert kept[t][l][0, h, :n].tolist() == states[t]["pos"].tolist(), (l, h, t)
                 assert rel_err(outs[t][l, 0, h * g:(h + 1) * g], o_ref[t]) < 1e-5
             got = export_state(caches, l, 0, h)
-            assert rel_err(got["score"][None], c["score"][None]) < 1e-5
+            check_scores_after_run(got["score"], c["score"], wl.S, False, (l, h))
 
 
 def test_decode_free_running_split_units(sqa):
@@ -439,7 +445,7 @@ def test_decode_free_running_split_units(sqa):
                     assert kept[t][l][b, h, :n].tolist() == states[t]["pos"].tolist(), (l, b, h, t)
                     assert rel_err(outs[t][l, b, h * g:(h + 1) * g], o_ref[t]) < 1e-5
                 got = export_state(caches, l, b, h)
-                assert rel_err(got["score"][None], c["score"][None]) < 1e-5
+                check_scores_after_run(got["score"], c["score"], wl.S, False, (l, b, h))
 
 
 @pytest.mark.parametrize("policy,dtype,D,g,order,B,Hkv,L", [
@@ -487,7 +493,7 @@ def test_many_short_units_one_wave_per_unit(sqa, policy, dtype, D, g, order, B, 
             assert rel_err(outs[t][l, b, h * g:(h + 1) * g], o_ref[t]) < TOL[dtype], (l, b, h, t)
         if policy == "h2o":
             got = export_state(caches, l, b, h)
-            assert rel_err(got["score"][None], c["score"][None]) < 1e-5
+            check_scores_after_run(got["score"], c["score"], S, uses_matrix_cores(dtype, D, g), (l, b, h))
 
 
 @pytest.mark.parametrize("g,order", [(4, "evict_then_attend"), (8, "evict_then_attend"), (8, "attend_then_evict")])
@@ -529,12 +535,11 @@ def test_many_short_units_grouped_queries_h2o(sqa, g, order):
             if got["pos"].tolist() != c2["pos"].tolist():           # only a near-tie under attend-then-evict may differ
                 assert ae
                 _, full = O.decode_step(c, *args, 1 << 30, policy, 4, order)
-                upd = dict(zip(full["pos"].tolist(), full["score"].tolist()))
-                assert near_tie_swap(got["pos"].tolist(), c2["pos"].tolist(), c, upd, budgets[l] - budgets[l] // 2,
-                                      10 * TOL[dtype]), (t, l, b, h)
+                assert near_tie_swap(got["pos"].tolist(), c2["pos"].tolist(), c, full, budgets[l] - budgets[l] // 2,
+                                     True), (t, l, b, h)
             else:
                 assert np.array_equal(got["K"], c2["K"]) and np.array_equal(got["V"], c2["V"])
-                assert rel_err(got["score"][None], c2["score"][None]) < TOL[dtype], (t, l, b, h)
+                check_step_scores(got, c, c2, True, (t, l, b, h))
             state[l, b, h] = round_scores_f32(c2)
 
 
@@ -575,18 +580,18 @@ def test_decode_one_very_long_unit(sqa):
     caches = _mk_caches(sqa, [b], [b], 1, 1, D, "bf16")
     sqa.prefill_compress(K, V, sc, "h2o", 4, caches, 0)
     ws = sqa.decode_workspace(caches, 1, "h2o")
-    c = O.new_cache(np64(K)[0, 0], np64(V)[0, 0], np64(sc)[0, 0])
     for t in range(2):
+        c = export_state(caches, 0, 0, 0)          # the oracle steps from what the GPU holds (same fp32 scores)
         q = torch.randn(1, 1, 1, D, device=DEV).to(torch.bfloat16)
         k = torch.randn(1, 1, 1, D, device=DEV).to(torch.bfloat16)
         v = torch.randn(1, 1, 1, D, device=DEV).to(torch.bfloat16)
         out = torch.empty_like(q)
         sqa.decode_step(q, k, v, P + t, "h2o", 4, caches, out, ws)
-        want, c = O.decode_step(c, np64(q)[0, 0], np64(k)[0, 0, 0], np64(v)[0, 0, 0], P + t, b, "h2o")
-        c = round_scores_f32(c)
+        want, c2 = O.decode_step(c, np64(q)[0, 0], np64(k)[0, 0, 0], np64(v)[0, 0, 0], P + t, b, "h2o")
         got = export_state(caches, 0, 0, 0)
-        assert got["pos"].tolist() == c["pos"].tolist(), t
-        assert rel_err(np64(out)[0, 0], want) < 2e-2 and rel_err(got["score"][None], c["score"][None]) < 1e-5
+        assert got["pos"].tolist() == c2["pos"].tolist(), t
+        assert rel_err(np64(out)[0, 0], want) < 2e-2
+        check_step_scores(got, c, c2, False, t)
     assert sqa.read_device_status(ws) == 0
 
 

@@ -8,7 +8,8 @@ import torch
 
 from oracle import sqa_oracle as O
 from paper_2404_04793_amd import workloads as W
-from tests.harness import TOL, export_state, import_state, np64, rel_err, round_scores_f32
+from tests.harness import (TOL, check_step_scores, export_state, import_state, np64, rel_err, round_scores_f32,
+                           uses_matrix_cores)
 
 pytestmark = pytest.mark.gpu
 DEV = "cuda:0"
@@ -136,7 +137,7 @@ def test_ragged_batch_end_to_end(sqa, policy, g, packed):
             assert np.array_equal(got["K"], c2["K"]) and np.array_equal(got["V"], c2["V"])
             worst = max(worst, rel_err(o[l, b, h * g:(h + 1) * g], want_out))
             if policy == "h2o":
-                assert rel_err(got["score"][None], c2["score"][None]) < TOL[dtype]
+                check_step_scores(got, c, c2, uses_matrix_cores(dtype, D, g), (t, l, b, h))
             state[l, b, h] = round_scores_f32(c2)
         for b in range(B):
             pos_now[b] += 1 if active[b] else 0
@@ -180,3 +181,29 @@ def test_out_of_range_per_sequence_values_are_reported(sqa):
     status.zero_()
     sqa.prefill_compress_layers([K], [V], None, "sliding", 4, small, opts=sqa.batch_opts(status=status))
     assert int(status.item()) == 6 and small.lens[0][:, 0].tolist() == [8, 0]
+
+
+def test_decode_with_an_empty_packed_unit(sqa):
+    """Packed units where one unit was given no slot at all: that unit is reported (no free slot) and its
+    out rows are zeroed; its neighbours, whose slot ranges touch it on both sides, step normally.  The
+    unit owns no memory, so nothing may be read through its (empty) range."""
+    B, Hkv, D, b = 3, 1, 64, 6
+    for empty in (0, 1, 2):                      # first, middle and last unit of the layer
+        caps = [b, b, b]
+        caps[empty] = 0
+        caches = sqa.LayerCaches([b], [b], B, Hkv, D, torch.float32, DEV, True, unit_capacities=[caps])
+        ws = sqa.decode_workspace(caches, Hkv, "h2o")
+        r = np.random.default_rng(empty)
+        state = {u: O.new_cache(np.zeros((0, D)), np.zeros((0, D))) for u in range(B) if u != empty}
+        for t in range(3):
+            q = torch.from_numpy(r.standard_normal((1, B, Hkv, D)).astype(np.float32)).to(DEV)
+            k = torch.from_numpy(r.standard_normal((1, B, Hkv, D)).astype(np.float32)).to(DEV)
+            v = torch.from_numpy(r.standard_normal((1, B, Hkv, D)).astype(np.float32)).to(DEV)
+            out = torch.full_like(q, 5.0)
+            sqa.decode_step(q, k, v, t, "h2o", 4, caches, out, ws)
+            assert sqa.read_device_status(ws) == 6           # SQA_ERR_CAPACITY, from the empty unit
+            assert bool((out[0, empty] == 0).all()) and int(caches.lens[0][empty, 0]) == 0
+            for u in state:
+                want, state[u] = O.decode_step(state[u], np64(q)[0, u], np64(k)[0, u, 0], np64(v)[0, u, 0], t, b, "h2o")
+                assert rel_err(np64(out)[0, u], want) < 1e-5
+                assert export_state(caches, 0, u, 0)["pos"].tolist() == state[u]["pos"].tolist()
