@@ -867,7 +867,8 @@ struct DecodePlan {
   uint32_t chunk[SQA_MAX_LAYERS];
   uint32_t unit_off[SQA_MAX_LAYERS], part_off[SQA_MAX_LAYERS], logit_off[SQA_MAX_LAYERS];
   uint64_t blocks;
-  size_t off_table, off_cnt, off_part, off_logit, bytes;
+  size_t cnt_bytes, part_bytes, logit_bytes;       // arrival counters, partial records, H2O logits / probabilities
+  size_t off_table, off_cnt, off_part, off_logit, bytes;   // where they lie in a caller's workspace
 };
 
 static size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
@@ -928,11 +929,14 @@ static sqa_status plan_decode(const sqa_layer_cache* layers, int n_layers, int B
       return SQA_ERR_CAPACITY;
   }
   p->blocks = blocks;
+  p->cnt_bytes = n_units * sizeof(int32_t);
+  p->part_bytes = n_part * g * (D + 2) * sizeof(float);
+  p->logit_bytes = n_logit * sizeof(float);
   p->off_table = kStatusBytes;
   p->off_cnt = align256(p->off_table + (size_t)n_layers * sizeof(sqa_layer_cache));
-  p->off_part = align256(p->off_cnt + n_units * sizeof(int32_t));
-  p->off_logit = align256(p->off_part + n_part * g * (D + 2) * sizeof(float));
-  p->bytes = align256(p->off_logit + n_logit * sizeof(float));
+  p->off_part = align256(p->off_cnt + p->cnt_bytes);
+  p->off_logit = align256(p->off_part + p->part_bytes);
+  p->bytes = align256(p->off_logit + p->logit_bytes);
   return SQA_OK;
 }
 
@@ -1001,14 +1005,23 @@ extern "C" sqa_status sqa_decode_step(const void* q, const void* k_new, const vo
                             out, workspace, ws_bytes, stream, nullptr);
 }
 
-extern "C" sqa_status sqa_decode_step_ex(const void* q, const void* k_new, const void* v_new, sqa_dtype dt,
-                                         int B, int Hq, int Hkv, int D, int32_t new_pos,
-                                         sqa_policy policy, int n_sink,
-                                         const sqa_layer_cache* layers, const sqa_layer_cache* layers_dev, int n_layers,
-                                         void* out, void* workspace, size_t ws_bytes, void* stream,
-                                         const sqa_batch_opts* opts) {
-  using namespace sqa;
-  if (!q || !k_new || !v_new || !layers || !out || !workspace) return SQA_ERR_NULL;
+namespace sqa {
+
+// Where one call's scratch lies: in a caller's workspace, or in the library's static array.
+struct DecodeScratch {
+  int32_t* status;     // device-side status word
+  char* table;         // room for the layer table when the caller gave no device copy
+  int32_t* cnt;        // arrival counters (zero on entry; the kernel leaves them zero)
+  float* part;         // partial records of split units
+  float* logit;        // H2O logits / probabilities
+};
+
+// Argument checks shared by the decode entry points; on success the kernel and the launch plan.
+static sqa_status decode_prepare(const void* q, const void* k_new, const void* v_new, sqa_dtype dt,
+                                 int B, int Hq, int Hkv, int D, int32_t new_pos, sqa_policy policy, int n_sink,
+                                 const sqa_layer_cache* layers, int n_layers, const void* out,
+                                 const sqa_batch_opts* opts, decode_fn* fn_out, DecodePlan* plan, size_t* lds_out) {
+  if (!q || !k_new || !v_new || !layers || !out) return SQA_ERR_NULL;
   if (opts && opts->order != SQA_EVICT_THEN_ATTEND && opts->order != SQA_ATTEND_THEN_EVICT) return SQA_ERR_POLICY;
   if (dt != SQA_F32 && dt != SQA_BF16) return SQA_ERR_DTYPE;
   if (policy != SQA_SLIDING && policy != SQA_STREAMING && policy != SQA_H2O) return SQA_ERR_POLICY;
@@ -1020,9 +1033,7 @@ extern "C" sqa_status sqa_decode_step_ex(const void* q, const void* k_new, const
   const bool h2o = policy == SQA_H2O;
   decode_fn fn = pick(dt, D, g, h2o);
   if (!fn) return SQA_ERR_SHAPE;
-  if (!aligned16(q) || !aligned16(k_new) || !aligned16(v_new) || !aligned16(out) ||
-      (reinterpret_cast<uintptr_t>(workspace) & 255u))
-    return SQA_ERR_SHAPE;
+  if (!aligned16(q) || !aligned16(k_new) || !aligned16(v_new) || !aligned16(out)) return SQA_ERR_SHAPE;
   const int min_budget = h2o ? 2 : (policy == SQA_STREAMING ? n_sink + 1 : 1);
   for (int i = 0; i < n_layers; ++i) {
     const sqa_layer_cache& c = layers[i];
@@ -1033,24 +1044,29 @@ extern "C" sqa_status sqa_decode_step_ex(const void* q, const void* k_new, const
     if (c.capacity < 1) return SQA_ERR_CAPACITY;
   }
   const bool mfma = dt == SQA_BF16 && D == 128 && g >= kMfmaMinGroup;
-  DecodePlan plan;
-  const sqa_status ps = plan_decode(layers, n_layers, B, Hq, Hkv, D, h2o, true, h2o && mfma, &plan);
+  const sqa_status ps = plan_decode(layers, n_layers, B, Hq, Hkv, D, h2o, true, h2o && mfma, plan);
   if (ps != SQA_OK) return ps;
-  if (ws_bytes < plan.bytes) return SQA_ERR_CAPACITY;
-  const size_t lds_shared = (size_t)g * plan.lds_chunk, lds_waves = (size_t)kDecWaves * g * plan.lds_chunk_w;
+  const size_t lds_shared = (size_t)g * plan->lds_chunk, lds_waves = (size_t)kDecWaves * g * plan->lds_chunk_w;
   const size_t lds = (h2o ? (lds_shared > lds_waves ? lds_shared : lds_waves) * sizeof(float) : 0) +
                      (mfma ? (size_t)kDecWaves * kStageBytesPerWave : 0);
   if (lds > 160 * 1024) return SQA_ERR_CAPACITY;
-  if (lds > 64 * 1024) SQA_HIP_CHECK(allow_dynamic_lds(reinterpret_cast<const void*>(fn), lds));
+  *fn_out = fn;
+  *lds_out = lds;
+  return SQA_OK;
+}
 
-  hipStream_t st = static_cast<hipStream_t>(stream);
-  char* ws = static_cast<char*>(workspace);
+static sqa_status decode_launch(decode_fn fn, const DecodePlan& plan, size_t lds, const DecodeScratch& sc,
+                                const void* q, const void* k_new, const void* v_new,
+                                int B, int Hq, int Hkv, int D, int32_t new_pos, sqa_policy policy, int n_sink,
+                                const sqa_layer_cache* layers, const sqa_layer_cache* layers_dev, int n_layers,
+                                void* out, hipStream_t st, const sqa_batch_opts* opts) {
+  if (lds > 64 * 1024) SQA_HIP_CHECK(allow_dynamic_lds(reinterpret_cast<const void*>(fn), lds));
   DecodeArgs a;
   a.q = q; a.k_new = k_new; a.v_new = v_new; a.out = out;
-  a.status = reinterpret_cast<int32_t*>(ws);
-  a.cnt = reinterpret_cast<int32_t*>(ws + plan.off_cnt);
-  a.part = reinterpret_cast<float*>(ws + plan.off_part);
-  a.logit = reinterpret_cast<float*>(ws + plan.off_logit);
+  a.status = sc.status;
+  a.cnt = sc.cnt;
+  a.part = sc.part;
+  a.logit = sc.logit;
   a.B = B; a.Hq = Hq; a.Hkv = Hkv; a.n_layers = n_layers;
   a.new_pos = new_pos; a.policy = (int)policy; a.n_sink = n_sink;
   a.new_pos_seq = opts ? opts->new_pos_seq : nullptr;
@@ -1082,11 +1098,39 @@ extern "C" sqa_status sqa_decode_step_ex(const void* q, const void* k_new, const
   if (layers_dev) {
     a.layers = layers_dev;
   } else {
-    char* tbl = ws + plan.off_table;
-    SQA_HIP_CHECK(hipMemcpyAsync(tbl, layers, (size_t)n_layers * sizeof(sqa_layer_cache), hipMemcpyHostToDevice, st));
-    a.layers = reinterpret_cast<const sqa_layer_cache*>(tbl);
+    SQA_HIP_CHECK(hipMemcpyAsync(sc.table, layers, (size_t)n_layers * sizeof(sqa_layer_cache), hipMemcpyHostToDevice, st));
+    a.layers = reinterpret_cast<const sqa_layer_cache*>(sc.table);
   }
   fn<<<(unsigned)plan.blocks, kDecThreads, lds, st>>>(a);
   SQA_HIP_CHECK(hipGetLastError());
   return SQA_OK;
+}
+
+}  // namespace sqa
+
+extern "C" sqa_status sqa_decode_step_ex(const void* q, const void* k_new, const void* v_new, sqa_dtype dt,
+                                         int B, int Hq, int Hkv, int D, int32_t new_pos,
+                                         sqa_policy policy, int n_sink,
+                                         const sqa_layer_cache* layers, const sqa_layer_cache* layers_dev, int n_layers,
+                                         void* out, void* workspace, size_t ws_bytes, void* stream,
+                                         const sqa_batch_opts* opts) {
+  using namespace sqa;
+  if (!workspace) return SQA_ERR_NULL;
+  decode_fn fn = nullptr;
+  DecodePlan plan;
+  size_t lds = 0;
+  const sqa_status ps = decode_prepare(q, k_new, v_new, dt, B, Hq, Hkv, D, new_pos, policy, n_sink, layers, n_layers, out,
+                                       opts, &fn, &plan, &lds);
+  if (ps != SQA_OK) return ps;
+  if (reinterpret_cast<uintptr_t>(workspace) & 255u) return SQA_ERR_SHAPE;
+  if (ws_bytes < plan.bytes) return SQA_ERR_CAPACITY;
+  char* ws = static_cast<char*>(workspace);
+  DecodeScratch sc;
+  sc.status = reinterpret_cast<int32_t*>(ws);
+  sc.table = ws + plan.off_table;
+  sc.cnt = reinterpret_cast<int32_t*>(ws + plan.off_cnt);
+  sc.part = reinterpret_cast<float*>(ws + plan.off_part);
+  sc.logit = reinterpret_cast<float*>(ws + plan.off_logit);
+  return decode_launch(fn, plan, lds, sc, q, k_new, v_new, B, Hq, Hkv, D, new_pos, policy, n_sink, layers, layers_dev,
+                       n_layers, out, static_cast<hipStream_t>(stream), opts);
 }
