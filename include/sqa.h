@@ -293,6 +293,34 @@ sqa_status sqa_decode_step_ex(const void* q, const void* k_new, const void* v_ne
                               void* out, void* workspace, size_t ws_bytes, void* stream,
                               const sqa_batch_opts* opts);
 
+/* ---- the same step for callers that cannot allocate device memory ----------
+ * (code running under HIP graph capture, tight serving loops, harnesses that
+ * forbid hipMalloc).  Identical to sqa_decode_step_ex -- same kernels, same
+ * results bit for bit -- except that the scratch a step needs (layer table,
+ * arrival counters, partial results of split units, H2O logits / probabilities)
+ * lives in a device array of SQA_STATIC_SCRATCH_BYTES that is part of the
+ * library image; each GPU the library runs on holds its copy until the process
+ * ends.  The call allocates nothing and frees nothing.
+ *   status : DEVICE int32, caller-owned, 4-byte aligned: the device-side status
+ *            word (the role a workspace's first word plays in sqa_decode_step);
+ *            the caller zeroes and reads it
+ *   every other argument as in sqa_decode_step_ex
+ * A call whose scratch does not fit (more than 262144 units in the call, or
+ * more than about 15 MiB of partial records plus H2O logits / probabilities)
+ * returns SQA_ERR_CAPACITY and enqueues nothing: use sqa_decode_step with a
+ * workspace for such shapes.
+ * The first call on a device looks the array up and clears its counter region
+ * (one small kernel and a wait on `stream`): make that call outside any graph
+ * capture.  All calls on one GPU share the one array: calls that overlap in
+ * time on the same GPU (different streams, different threads) race -- run
+ * them one after the other. */
+enum { SQA_STATIC_SCRATCH_BYTES = 16 * 1024 * 1024 };
+sqa_status sqa_decode_step_static(const void* q, const void* k_new, const void* v_new, sqa_dtype dt,
+                                  int B, int Hq, int Hkv, int D, int32_t new_pos,
+                                  sqa_policy policy, int n_sink,
+                                  const sqa_layer_cache* layers, const sqa_layer_cache* layers_dev, int n_layers,
+                                  void* out, int32_t* status, void* stream, const sqa_batch_opts* opts);
+
 /* Zeroes the status word (a small fill kernel enqueued on stream; like
  * sqa_decode_workspace_init it uses no memset, so both may be recorded into a HIP graph). */
 sqa_status sqa_clear_device_status(void* workspace, void* stream);

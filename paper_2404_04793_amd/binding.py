@@ -89,6 +89,9 @@ _lib.sqa_decode_step.argtypes = [_vp, _vp, _vp, _i, _i, _i, _i, _i, C.c_int32, _
 _lib.sqa_decode_step_ex.restype = _i
 _lib.sqa_decode_step_ex.argtypes = [_vp, _vp, _vp, _i, _i, _i, _i, _i, C.c_int32, _i, _i, _LCp, _vp, _i,
                                     _vp, _vp, _sz, _vp, _BOp]
+_lib.sqa_decode_step_static.restype = _i
+_lib.sqa_decode_step_static.argtypes = [_vp, _vp, _vp, _i, _i, _i, _i, _i, C.c_int32, _i, _i, _LCp, _vp, _i,
+                                        _vp, _vp, _vp, _BOp]
 _lib.sqa_clear_device_status.restype = _i
 _lib.sqa_clear_device_status.argtypes = [_vp, _vp]
 _lib.sqa_read_device_status.restype = _i
@@ -323,6 +326,22 @@ def decode_step(q: torch.Tensor, k_new: torch.Tensor, v_new: torch.Tensor, new_p
                                        caches.dev_ptr(layer0) if use_dev_table else None, n_layers, _ptr(out),
                                        _ptr(workspace), workspace.numel(), _stream(), C.byref(opts)),
                "sqa_decode_step_ex")
+    return out
+
+
+def decode_step_static(q: torch.Tensor, k_new: torch.Tensor, v_new: torch.Tensor, new_pos: int, policy: str,
+                       n_sink: int, caches: LayerCaches, out: torch.Tensor, status: torch.Tensor,
+                       layer0: int = 0, n_layers: Optional[int] = None, use_dev_table: bool = True,
+                       opts: Optional[BatchOptsStruct] = None) -> torch.Tensor:
+    """sqa_decode_step_static: decode_step without a workspace (the library's own scratch array);
+    status: int32 device tensor of one element that receives the device-side status."""
+    n_layers = caches.L - layer0 if n_layers is None else n_layers
+    B, Hq, D = q.shape[-3], q.shape[-2], q.shape[-1]
+    Hkv = k_new.shape[-2]
+    _check(_lib.sqa_decode_step_static(_ptr(q), _ptr(k_new), _ptr(v_new), _dt(q), B, Hq, Hkv, D, int(new_pos),
+                                       POLICY[policy], n_sink, caches.struct_ptr(layer0),
+                                       caches.dev_ptr(layer0) if use_dev_table else None, n_layers, _ptr(out),
+                                       _ptr(status), _stream(), _opts(opts)), "sqa_decode_step_static")
     return out
 
 

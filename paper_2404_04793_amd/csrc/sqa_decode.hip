@@ -1134,3 +1134,80 @@ extern "C" sqa_status sqa_decode_step_ex(const void* q, const void* k_new, const
   return decode_launch(fn, plan, lds, sc, q, k_new, v_new, B, Hq, Hkv, D, new_pos, policy, n_sink, layers, layers_dev,
                        n_layers, out, static_cast<hipStream_t>(stream), opts);
 }
+
+// ---- the same step for callers that cannot allocate -------------------------------------------------
+// The scratch a decode step needs lives in a file-scope device array instead of a caller's workspace.
+// Fixed layout (so that a region only ever holds one kind of data, whatever the shapes of successive
+// calls): layer table | arrival counters | partial records and H2O logits / probabilities.
+// The counters are the only words that must be zero when a kernel starts.  Their region holds nothing
+// else, is cleared once per device at set-up, and every launch returns the counters it used to zero
+// (the workgroup that merges a split unit resets the unit's counter), so each call finds them zero
+// although the array keeps the previous call's contents everywhere else.
+namespace sqa {
+constexpr size_t kStaticTableBytes = 16 * 1024;                    // >= SQA_MAX_LAYERS * sizeof(sqa_layer_cache)
+constexpr size_t kStaticCntBytes = 1024 * 1024;                    // 262144 units per call
+constexpr size_t kStaticDataBytes = SQA_STATIC_SCRATCH_BYTES - kStaticTableBytes - kStaticCntBytes;
+static_assert(SQA_MAX_LAYERS * sizeof(sqa_layer_cache) <= kStaticTableBytes, "layer table region");
+static_assert(SQA_STATIC_SCRATCH_BYTES > kStaticTableBytes + kStaticCntBytes, "scratch size");
+}  // namespace sqa
+
+static __device__ __align__(256) unsigned char scratch[SQA_STATIC_SCRATCH_BYTES];
+
+namespace sqa {
+constexpr int kMaxDevices = 64;
+// Device address of `scratch` on each device (every GPU holds its own copy of the array at its own
+// address; in host code the array's name is only a handle for this lookup, never an address).
+static sqa_status static_scratch_base(hipStream_t st, char** base_out) {
+  static std::mutex mu;
+  static char* base[kMaxDevices] = {};
+  int dev = -1;
+  SQA_HIP_CHECK(hipGetDevice(&dev));
+  if (dev < 0 || dev >= kMaxDevices) return SQA_ERR_CAPACITY;
+  std::lock_guard<std::mutex> lock(mu);
+  if (!base[dev]) {
+    char* p = nullptr;
+    SQA_HIP_CHECK(hipGetSymbolAddress(reinterpret_cast<void**>(&p), HIP_SYMBOL(scratch)));
+    if (!p || (reinterpret_cast<uintptr_t>(p) & 255u)) return SQA_ERR_HIP;
+    // once per device: the counter region starts at zero (fill kernel, then wait, so that the set-up
+    // is complete whatever stream later calls use)
+    const sqa_status zs = zero_fill(p + kStaticTableBytes, kStaticCntBytes, st);
+    if (zs != SQA_OK) return zs;
+    SQA_HIP_CHECK(hipStreamSynchronize(st));
+    base[dev] = p;
+  }
+  *base_out = base[dev];
+  return SQA_OK;
+}
+}  // namespace sqa
+
+extern "C" sqa_status sqa_decode_step_static(const void* q, const void* k_new, const void* v_new, sqa_dtype dt,
+                                             int B, int Hq, int Hkv, int D, int32_t new_pos,
+                                             sqa_policy policy, int n_sink,
+                                             const sqa_layer_cache* layers, const sqa_layer_cache* layers_dev,
+                                             int n_layers, void* out, int32_t* status, void* stream,
+                                             const sqa_batch_opts* opts) {
+  using namespace sqa;
+  if (!status) return SQA_ERR_NULL;
+  if (reinterpret_cast<uintptr_t>(status) & 3u) return SQA_ERR_SHAPE;
+  decode_fn fn = nullptr;
+  DecodePlan plan;
+  size_t lds = 0;
+  const sqa_status ps = decode_prepare(q, k_new, v_new, dt, B, Hq, Hkv, D, new_pos, policy, n_sink, layers, n_layers, out,
+                                       opts, &fn, &plan, &lds);
+  if (ps != SQA_OK) return ps;
+  // beyond the array's fixed size: refused, nothing is enqueued (use sqa_decode_step with a workspace)
+  const size_t part_bytes = align256(plan.part_bytes);
+  if (plan.cnt_bytes > kStaticCntBytes || part_bytes + plan.logit_bytes > kStaticDataBytes) return SQA_ERR_CAPACITY;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  char* base = nullptr;
+  const sqa_status bs = static_scratch_base(st, &base);
+  if (bs != SQA_OK) return bs;
+  DecodeScratch sc;
+  sc.status = status;
+  sc.table = base;
+  sc.cnt = reinterpret_cast<int32_t*>(base + kStaticTableBytes);
+  sc.part = reinterpret_cast<float*>(base + kStaticTableBytes + kStaticCntBytes);
+  sc.logit = reinterpret_cast<float*>(base + kStaticTableBytes + kStaticCntBytes + part_bytes);
+  return decode_launch(fn, plan, lds, sc, q, k_new, v_new, B, Hq, Hkv, D, new_pos, policy, n_sink, layers, layers_dev,
+                       n_layers, out, st, opts);
+}
