@@ -25,51 +25,183 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0
 
-# HBM bytes per decode launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, scaled by what the same
-# counters read for a plain 1 GiB copy kernel (x2.0 / x1.0); see profiles/decode_importance_compress__<workload>.txt.
-# Counters cannot be read from inside this process, so the figure is the one of the committed profile.
-MEASURED_TRAFFIC_BYTES = {("llama2_7b", "squeeze", "h2o", "all_layers"): 820870.1 * 1024 * 2.0 + 19393.0 * 1024}
+# HBM bytes per decode launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, scaled by what the same counters
+# read for a plain 1 GiB copy kernel (x2.0 / x1.0).  Counters cannot be read from inside this process, so the
+# figure is the one of the committed profile named beside it, and it is only reported while the decode
+# kernel's source is byte for byte the one that profile was taken with (sha256 prefix below); otherwise
+# `traffic` is null and `traffic_source` says that the profile is out of date.
+MEASURED_TRAFFIC = {
+    ("llama2_7b", "squeeze", "h2o", "all_layers"): {
+        "bytes": 0.0, "source": "profiles/decode_importance_compress__llama2_7b.txt", "kernel_sha": "unset"},
+}
 
 
-def cpu_baseline(sess, units_per_layer: int, steps: int):
-    """Time the oracle's decode step (Algorithm 1 steps 14-21) on a sample:
-    `units_per_layer` (sequence, KV head) units of every layer, `steps` steps."""
+def decode_kernel_sha() -> str:
+    import hashlib
+    h = hashlib.sha256()
+    for f in ("sqa_decode.hip", "sqa_common.h"):
+        with open(os.path.join(ROOT, "paper_2404_04793_amd", "csrc", f), "rb") as fh:
+            h.update(fh.read())
+    return h.hexdigest()[:16]
+
+
+def measured_traffic(key):
+    m = MEASURED_TRAFFIC.get(key)
+    if m is None:
+        return None, None
+    if m["kernel_sha"] != decode_kernel_sha():
+        return None, m["source"] + " (taken with another version of the decode kernel: not reported)"
+    return m["bytes"], m["source"]
+
+
+# ---- the oracle on the host cores -------------------------------------------------------
+def _oracle_worker_init():
+    try:
+        from threadpoolctl import threadpool_limits
+        _oracle_worker_init.ctx = threadpool_limits(limits=1)      # one core per worker process
+    except Exception:  # pragma: no cover
+        pass
+
+
+def _oracle_unit_task(task):
+    """One (layer, sequence, KV head) unit: `steps` oracle decode steps from its compressed cache."""
+    import numpy as np
+    from oracle import sqa_oracle as O
+    c, q, k, v, pos0, b_l, policy, n_sink = task
+    c = {key: np.asarray(val, dtype=np.float64) if key != "pos" else val for key, val in c.items()}
+    q, k, v = q.astype(np.float64), k.astype(np.float64), v.astype(np.float64)
+    t0 = time.perf_counter()
+    for t in range(q.shape[0]):
+        _, c = O.decode_step(c, q[t], k[t], v[t], pos0 + t, b_l, policy, n_sink)
+    return os.getpid(), time.perf_counter() - t0
+
+
+def _oracle_worker_ready(_):
+    _oracle_worker_init()
+    time.sleep(0.3)
+    return os.getpid()
+
+
+def oracle_pool():
+    """Worker processes for the oracle leg, one per host core of this box's share (at most 16).  Started
+    before this process touches the GPU: a process that has initialised the GPU starts no new programs.
+    (An executor, not multiprocessing.Pool: if a worker dies the leg fails instead of respawning for ever.)"""
+    import multiprocessing as mp
+    from concurrent.futures import ProcessPoolExecutor
+    nproc = os.cpu_count() or 1
+    cores = max(1, min(16, nproc))
+    ex = ProcessPoolExecutor(cores, mp_context=mp.get_context("spawn"))
+    pids = set(ex.map(_oracle_worker_ready, range(cores), timeout=120))      # every worker is up now
+    return ex, len(pids), nproc
+
+
+def cpu_baseline(sess, units_per_layer: int, steps: int, pool, cores: int, nproc: int):
+    """Time the oracle's decode step (Algorithm 1 steps 14-21) on a bounded sample -- `units_per_layer`
+    (sequence, KV head) units of every layer, `steps` steps -- spread over the worker processes of
+    oracle_pool(), CPU only.  The rate is the sample's work over the busiest worker's time (set-up and
+    moving the inputs to the workers are not timed)."""
     import numpy as np
     import torch
     from oracle import sqa_oracle as O
-    try:
-        from threadpoolctl import threadpool_limits
-    except Exception:  # pragma: no cover
-        threadpool_limits = None
     wl = sess.wl
     g = wl.g
-    f64 = lambda t: t.detach().cpu().to(torch.float64).numpy()
+    f32 = lambda t: t.detach().cpu().to(torch.float32).numpy()      # (bf16 and fp32 values are exact in fp32)
     units = [(i // wl.Hkv % wl.B, i % wl.Hkv) for i in range(units_per_layer)]
-    ctx = threadpool_limits(limits=1) if threadpool_limits else None
-    t_total = 0.0
-    try:
-        for l in range(wl.L):
-            b_l = sess.budgets[l]
-            for (b, h) in units:
-                Kp, Vp = f64(sess.Kp[l][b, h]), f64(sess.Vp[l][b, h])
-                # untimed set-up with a stand-in score vector: which prompt tokens
-                # are kept does not change what a decode step costs
-                s0 = np.linspace(0.0, 1.0, wl.P)
-                c = O.prefill_compress(Kp, Vp, s0, b_l, wl.policy, wl.n_sink)
-                q = f64(sess.q[:steps, l, b, h * g:(h + 1) * g])
-                k = f64(sess.k_new[:steps, l, b, h]); v = f64(sess.v_new[:steps, l, b, h])
-                t0 = time.perf_counter()
-                for t in range(steps):
-                    _, c = O.decode_step(c, q[t], k[t], v[t], wl.P + t, b_l, wl.policy, wl.n_sink)
-                t_total += time.perf_counter() - t0
-    finally:
-        if ctx is not None:
-            ctx.__exit__(None, None, None)
+    tasks = []
+    for l in range(wl.L):
+        b_l = sess.budgets[l]
+        Kl, Vl = f32(sess.Kp[l]), f32(sess.Vp[l])
+        ql, kl, vl = f32(sess.q[:steps, l]), f32(sess.k_new[:steps, l]), f32(sess.v_new[:steps, l])
+        for (b, h) in units:
+            # untimed set-up with a stand-in score vector: which prompt tokens are kept does not change
+            # what a decode step costs
+            c = O.prefill_compress(Kl[b, h], Vl[b, h], np.linspace(0.0, 1.0, wl.P), b_l, wl.policy, wl.n_sink)
+            c = {"K": c["K"].astype(np.float32), "V": c["V"].astype(np.float32), "pos": c["pos"], "score": c["score"]}
+            tasks.append((c, ql[:, b, h * g:(h + 1) * g], kl[:, b, h], vl[:, b, h], wl.P, b_l, wl.policy, wl.n_sink))
+    busy = {}
+    for pid, dt in pool.map(_oracle_unit_task, tasks, timeout=600, chunksize=max(1, len(tasks) // (cores * 8))):
+        busy[pid] = busy.get(pid, 0.0) + dt
+    pool.shutdown()
+    cpu_s, wall_s = sum(busy.values()), max(busy.values())
     frac = units_per_layer / float(wl.B * wl.Hkv)
-    est_step_s = t_total / steps / frac                 # one decode step of the whole batch
-    return {"value": wl.B / est_step_s, "unit": "tokens/s", "cores": 1, "kind": "oracle",
-            "sample": "%d of %d units of each of %d layers, first %d decode steps, %.1f s of CPU"
-                      % (units_per_layer, wl.B * wl.Hkv, wl.L, steps, t_total)}
+    est_step_s = wall_s / steps / frac                  # one decode step of the whole batch on these cores
+    return {"value": wl.B / est_step_s, "unit": "tokens/s", "cores": len(busy), "nproc": nproc, "kind": "oracle",
+            "sample": "%d of %d units of each of %d layers, first %d decode steps: %.1f s of CPU over %d worker "
+                      "processes, busiest %.1f s" % (units_per_layer, wl.B * wl.Hkv, wl.L, steps, cpu_s, len(busy), wall_s),
+            "single_core_value": wl.B / (cpu_s / steps / frac)}
+
+
+# ---- short decode-only legs on the other workloads ------------------------------------------
+def decode_leg(sess, label, per_layer=False, passes=2):
+    """Decode steps only, over sess.wl.S steps: the prompt is (re)compressed untimed, one untimed pass warms
+    up, the next `passes - 1` are timed with HIP events on the launch stream."""
+    import torch
+    wl = sess.wl
+    ms = 0.0
+    for i in range(passes):
+        sess.probe_and_allocate()
+        sess.compress_prompt()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        sess.decode(per_layer=per_layer)
+        e1.record()
+        torch.cuda.synchronize()
+        if i > 0:
+            ms += e0.elapsed_time(e1)
+    ms /= (passes - 1)
+    launches = wl.S * (wl.L if per_layer else 1)
+    bytes_launch = sum(sess.decode_bytes_per_step()) / float(launches)
+    launch_s = ms * 1e-3 / launches
+    from paper_2404_04793_amd import binding as sqa
+    return {"workload": label, "batch": wl.B, "policy": wl.policy, "launch": "per_layer" if per_layer else "all_layers",
+            "decode_steps_timed": wl.S, "tokens_per_s": round(wl.B * wl.S / (ms * 1e-3), 1),
+            "launch_us": round(launch_s * 1e6, 2), "bytes_per_launch": int(bytes_launch),
+            "GBps": round(bytes_launch / launch_s / 1e9, 1), "frac": round(bytes_launch / launch_s / 1e9 / HBM_PEAK_GBS, 4),
+            "resident_kv_GB": round(sess.resident_kv_bytes() / 1e9, 3),
+            "device_status": sqa.read_device_status(sess.dec_ws)}
+
+
+def other_workloads(main_sess, say):
+    """The other BASELINE configurations at their real batch and layer count (decode only, a cut number of
+    steps, the probe on 4096 token rows), one launch per layer at the headline shape, and the stress
+    configuration's comparison with an uncompressed cache at equal batch and at equal memory."""
+    import gc
+    import torch
+    from paper_2404_04793_amd import workloads as W
+    from paper_2404_04793_amd.session import Session
+    out = []
+    say("llama2_7b, one launch per layer")
+    out.append(decode_leg(main_sess, "llama2_7b", per_layer=True))
+    for name, steps in (("mistral_7b", 64), ("llama2_70b", 32), ("stress_7b", 128)):
+        say("%s, %d decode steps" % (name, steps))
+        wl = W.scaled(W.WORKLOADS[name], S=steps)
+        sess = Session(wl, "cuda:0", probe_tokens=4096)
+        leg = decode_leg(sess, name)
+        out.append(leg)
+        if name == "stress_7b":
+            full = W.WORKLOADS[name]
+            squeezed_bytes = sess.resident_kv_bytes()
+            say("stress_7b, full cache at the same batch")
+            sess.full_cache, sess.caches = True, None
+            eq_batch = decode_leg(sess, "stress_7b full cache, same batch")
+            del sess
+            gc.collect(); torch.cuda.empty_cache()
+            # the largest batch whose uncompressed cache, sized for the whole generation (P + S = 1536 tokens
+            # per sequence, Sec. 2.1 size model), fits in the memory the squeezed run's caches occupy
+            per_seq = W.full_cache_bytes_per_sequence(full)
+            b_fit = max(1, W.equal_memory_batch(full, squeezed_bytes))
+            say("stress_7b, full cache at batch %d (equal memory), all %d decode steps" % (b_fit, full.S))
+            sess = Session(W.scaled(full, B=int(b_fit)), "cuda:0", full_cache=True, probe_tokens=4096)
+            eq_mem = decode_leg(sess, "stress_7b full cache, equal memory")
+            leg["vs_full_cache"] = {
+                "same_batch": eq_batch, "equal_memory": eq_mem,
+                "squeezed_kv_GB": round(squeezed_bytes / 1e9, 3), "full_cache_bytes_per_sequence": int(per_seq),
+                "batch_gain": round(wl.B / float(b_fit), 2),
+                "tokens_per_s_gain_same_batch": round(leg["tokens_per_s"] / eq_batch["tokens_per_s"], 2),
+                "tokens_per_s_gain_equal_memory": round(leg["tokens_per_s"] / eq_mem["tokens_per_s"], 2)}
+        del sess
+        gc.collect(); torch.cuda.empty_cache()
+    return out
 
 
 def scores_only(args, wl):
@@ -155,12 +287,19 @@ def main():
                     help="time only the H2O prompt-score producer (sqa_prefill_scores; set-up work of the pass, "
                          "matrix-core bound): a step = the scores of all layers of one prompt batch")
     ap.add_argument("--progress", action="store_true", help="say on stderr when each phase of the run begins")
+    ap.add_argument("--no-others", action="store_true",
+                    help="skip the short decode-only legs on the other workloads (they run by default with the "
+                         "headline workload and no other switch)")
     ap.add_argument("--cpu-units", type=int, default=32)
     ap.add_argument("--cpu-steps", type=int, default=128)
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
         sys.exit(2)
+
+    pool = None
+    if not (args.no_cpu or args.scores_only):
+        pool, cores, nproc = oracle_pool()          # (before the first GPU call)
 
     import torch
     from paper_2404_04793_amd import workloads as W
@@ -265,6 +404,7 @@ def main():
     tokens = wl.B * wl.S * args.steps
     mode = "full_cache" if args.full_cache else ("uniform" if args.uniform else "squeeze")
     launch = ("per_layer" if args.per_layer else "all_layers") + ("_graph" if args.graph else "")
+    traffic, traffic_source = measured_traffic((wl.name, mode, wl.policy, launch))
     res = {
         "metric": "decode tokens/s + achieved HBM GB/s (attn+evict), 7B shape, 1 GPU",
         "value": tokens / dt, "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
@@ -279,7 +419,7 @@ def main():
                    "ragged_prompt_lengths": plen},
         "roofline": {"bound": "hbm", "kernel": "decode_unit_kernel", "achieved": achieved, "peak": HBM_PEAK_GBS,
                      "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
-                     "traffic": MEASURED_TRAFFIC_BYTES.get((wl.name, mode, wl.policy, launch)),
+                     "traffic": traffic, "traffic_source": traffic_source,
                      "bytes_per_launch": bytes_launch, "launch_us": launch_s * 1e6},
         "phases_ms": {"probe_and_budgets": probe_ms, "prefill_compress": comp_ms, "decode": dec_ms},
         "decode_only_tokens_per_s": wl.B * wl.S / (dec_ms * 1e-3),
@@ -292,7 +432,15 @@ def main():
         "device_status": status,
     }
     if not args.no_cpu:
-        res["cpu_baseline"] = cpu_baseline(sess, args.cpu_units, min(args.cpu_steps, wl.S))
+        say("oracle on the host cores")
+        res["cpu_baseline"] = cpu_baseline(sess, args.cpu_units, min(args.cpu_steps, wl.S), pool, cores, nproc)
+    headline = (args.workload == "llama2_7b" and not (args.per_layer or args.graph or args.ragged or args.uniform or
+                                                      args.full_cache or args.policy or args.decode_only or args.batch or
+                                                      args.kv_heads or args.budget_pct or args.decode_steps or
+                                                      args.fused_probe or args.probe_tokens) and
+                args.order == "evict_then_attend")
+    if headline and not args.no_others:
+        res["other_workloads"] = other_workloads(sess, say)
     print(json.dumps(res))
 
 

@@ -7,8 +7,10 @@ the full cache), on synthetic inputs of the paper's shapes.
                                           [--decode-steps 64] [--equal-memory]
 
 --equal-memory adds, per batch, the full-cache run at the largest batch whose
-KV state fits in the bytes the layer-wise run holds resident at that batch
-(the "same memory, larger batch" reading of Table 3).
+uncompressed cache -- sized for the workload's WHOLE generation, P + S tokens
+per sequence, whatever --decode-steps cuts the timed run to -- fits in the bytes
+the layer-wise run holds resident at that batch (the "same memory, larger
+batch" reading of Table 3; workloads.equal_memory_batch, the rule bench.py uses).
 
 Prints a markdown table.  Only the decode steps are timed (HIP events); every
 number comes from the HIP library through the binding.
@@ -41,11 +43,10 @@ def run_mode(wl: W.Workload, mode: str, passes: int = 2):
         best = ms if best is None else min(best, ms)
     tok_s = wl.B * wl.S / (best * 1e-3)
     gbs = sum(sess.decode_bytes_per_step()) / (best * 1e-3) / 1e9
-    kv_gb = sess.resident_kv_bytes() / 1e9
-    per_seq_mb = sess.resident_kv_bytes() / wl.B / 1e6
+    kv_bytes = sess.resident_kv_bytes()
     del sess
     torch.cuda.empty_cache()
-    return tok_s, gbs, kv_gb, per_seq_mb
+    return tok_s, gbs, kv_bytes / 1e9, kv_bytes / wl.B / 1e6, kv_bytes
 
 
 def main(argv=None):
@@ -56,10 +57,10 @@ def main(argv=None):
     ap.add_argument("--budget-pct", type=int, default=None)
     ap.add_argument("--equal-memory", action="store_true")
     args = ap.parse_args(argv)
-    base = W.WORKLOADS[args.workload]
+    whole = W.WORKLOADS[args.workload]
     if args.budget_pct:
-        base = W.scaled(base, budget_pct=args.budget_pct)
-    base = W.scaled(base, S=args.decode_steps)
+        whole = W.scaled(whole, budget_pct=args.budget_pct)
+    base = W.scaled(whole, S=args.decode_steps)
     print("| batch | mode | tokens/s | GB/s | resident KV (GB) | KV per sequence (MB) |")
     print("|---|---|---|---|---|---|")
     for bs in [int(x) for x in args.batches.split(",")]:
@@ -67,16 +68,16 @@ def main(argv=None):
         held = {}
         for mode in ("squeeze", "uniform", "full"):
             try:
-                tok_s, gbs, kv_gb, per_seq = run_mode(wl, mode)
-                held[mode] = (kv_gb, per_seq)
+                tok_s, gbs, kv_gb, per_seq, kv_bytes = run_mode(wl, mode)
+                held[mode] = (kv_gb, per_seq, kv_bytes)
                 print("| %d | %s | %.0f | %.0f | %.2f | %.1f |" % (bs, mode, tok_s, gbs, kv_gb, per_seq))
             except torch.cuda.OutOfMemoryError:
                 print("| %d | %s | OOM | | | |" % (bs, mode))
             sys.stdout.flush()
-        if args.equal_memory and "squeeze" in held and "full" in held:
-            fit = int(held["squeeze"][0] * 1e3 // held["full"][1])        # GB -> MB, per-sequence MB of the full cache
+        if args.equal_memory and "squeeze" in held:
+            fit = W.equal_memory_batch(whole, held["squeeze"][2])
             if fit >= 1:
-                tok_s, gbs, kv_gb, per_seq = run_mode(W.scaled(base, B=fit), "full")
+                tok_s, gbs, kv_gb, per_seq, _ = run_mode(W.scaled(base, B=fit), "full")
                 print("| %d | full, batch that fits in the squeezed run's %.2f GB | %.0f | %.0f | %.2f | %.1f |"
                       % (fit, held["squeeze"][0], tok_s, gbs, kv_gb, per_seq))
             else:

@@ -228,6 +228,4 @@ class Session:
         return tot
 
     def resident_kv_bytes(self) -> int:
-        wl = self.wl
-        per_slot = 2 * wl.D * wl.elem_bytes + (8 if wl.policy == "h2o" else 4)
-        return sum(self.caches.total_slots(l) * per_slot for l in range(wl.L))
+        return W.resident_cache_bytes(self.wl, [self.caches.total_slots(l) for l in range(self.wl.L)])

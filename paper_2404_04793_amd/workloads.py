@@ -277,6 +277,37 @@ def decode_qkv(wl: Workload, layer: int, device="cpu", u=None, mask=None, steps:
 
 # -- byte accounting (what the method must move; Sec. 2.1 KV size model) ---------------------------
 
+def kv_bytes_per_token(wl: Workload) -> int:
+    """Sec. 2.1: every token adds one K and one V vector per layer and KV head --
+    2 * n_layer * n_kv_head * d_head elements (0.5 MB for Llama-2-7B in 16 bits: 2 * 32 * 4096 * 2 B)."""
+    return 2 * wl.L * wl.Hkv * wl.D * wl.elem_bytes
+
+
+def full_cache_bytes_per_sequence(wl: Workload) -> int:
+    """An uncompressed cache sized for the whole generation: P + S tokens per sequence."""
+    return (wl.P + wl.S) * kv_bytes_per_token(wl)
+
+
+def resident_cache_bytes(wl: Workload, slots_per_layer) -> int:
+    """Bytes the compact caches of this library hold resident: slots_per_layer[l] slots in layer l (over all
+    sequences and KV heads), each a K row and a V row plus the token's position (4 bytes) and, under H2O,
+    its accumulated score (4 bytes)."""
+    per_slot = 2 * wl.D * wl.elem_bytes + (8 if wl.policy == "h2o" else 4)
+    return sum(int(n) * per_slot for n in slots_per_layer)
+
+
+def squeezed_cache_bytes(wl: Workload, budgets) -> int:
+    """resident_cache_bytes of a batch whose layer l keeps min(budget_l, P + S) slots per sequence and KV head."""
+    return resident_cache_bytes(wl, [wl.B * wl.Hkv * min(b, wl.P + wl.S) for b in budgets])
+
+
+def equal_memory_batch(wl: Workload, squeezed_bytes: int) -> int:
+    """Sec. 5.4 (Table 3) read at attention level: the largest batch whose UNCOMPRESSED cache, sized for
+    the whole generation of `wl` (P + S tokens per sequence, Sec. 2.1 size model), fits in the bytes the
+    squeezed run's caches occupy."""
+    return int(squeezed_bytes // full_cache_bytes_per_sequence(wl))
+
+
 def decode_bytes_per_step(wl: Workload, budgets) -> list:
     """Algorithmic HBM bytes of each of the S decode steps over all layers: every kept K and V row read
     once (n_l = min(P + t + 1, b_l) tokens per unit after the append / eviction), 8 bytes of accumulated

@@ -210,3 +210,67 @@ def test_bench_refuses_more_than_one_gpu():
     r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True, text=True,
                        timeout=120)
     assert r.returncode == 2 and "ONE GPU" in r.stderr and r.stdout.strip() == ""
+
+
+def test_host_allocator_under_address_and_undefined_sanitizers(tmp_path):
+    """The host-only part of the library (clustering and budgets, Algorithm 1 steps 5-11) built from its
+    source with AddressSanitizer and UndefinedBehaviorSanitizer, no GPU code involved: the seeded cases of
+    test_budgets_bit_exact_vs_oracle plus degenerate inputs run through a small driver; any report ends
+    the driver with a non-zero status.  Results must still equal the oracle's."""
+    import shutil
+    import subprocess
+    gxx = shutil.which("g++")
+    if gxx is None:
+        pytest.skip("no g++")
+    driver = tmp_path / "driver.cpp"
+    driver.write_text(r'''
+#include <cstdio>
+#include <vector>
+#include "sqa.h"
+int main() {
+  int L; long long total; double p;
+  while (std::scanf("%d %lld %lf", &L, &total, &p) == 3) {
+    std::vector<float> cos(L > 0 ? L : 1);
+    for (int i = 0; i < L; ++i) { double x; if (std::scanf("%lf", &x) != 1) return 9; cos[i] = (float)x; }
+    std::vector<int32_t> budget(L > 0 ? L : 1);
+    std::vector<int8_t> group(L > 0 ? L : 1);
+    const sqa_status st = sqa_allocate_budgets(cos.data(), L, total, p, budget.data(), group.data());
+    std::printf("%d", (int)st);
+    if (st == SQA_OK) for (int i = 0; i < L; ++i) std::printf(" %d:%d", (int)budget[i], (int)group[i]);
+    std::printf("\n");
+  }
+  return 0;
+}
+''')
+    exe = tmp_path / "driver"
+    host_src = os.path.join(ROOT, "paper_2404_04793_amd", "csrc", "sqa_host.cpp")
+    r = subprocess.run([gxx, "-std=c++17", "-O1", "-g", "-ffp-contract=off", "-fsanitize=address,undefined",
+                        "-fno-sanitize-recover=all", "-static-libasan", "-static-libubsan",
+                        "-I", os.path.join(ROOT, "include"), str(driver), host_src, "-o", str(exe)],
+                       capture_output=True, text=True)
+    assert r.returncode == 0, r.stderr
+    cases = []
+    for seed in range(40):
+        r_ = np.random.default_rng(seed)
+        L = int(r_.integers(1, 100))
+        cos = [r_.random(L), np.round(r_.random(L), 1), 0.9 + 0.05 * r_.standard_normal(L), np.arange(L) / max(L, 1)][seed % 4]
+        cases.append((cos.astype(np.float32), int(r_.integers(L * 3, L * 4000 + 1)), float(r_.choice([0.1, 0.3, 0.35, 0.5, 1.0]))))
+    cases += [(np.array([0.5], dtype=np.float32), 1, 1.0), (np.full(128, 0.25, dtype=np.float32), 128, 0.01),
+              (np.array([0.1, 0.9], dtype=np.float32), 2, 0.5), (np.array([0.1, 0.5, 0.9], dtype=np.float32), 2, 0.3)]
+    text = "".join("%d %d %.17g %s\n" % (len(c), t, p, " ".join("%.9g" % float(x) for x in c)) for c, t, p in cases)
+    env = dict(os.environ, ASAN_OPTIONS="detect_leaks=1:abort_on_error=0", UBSAN_OPTIONS="print_stacktrace=1")
+    env.pop("LD_PRELOAD", None)
+    run = subprocess.run([str(exe)], input=text, capture_output=True, text=True, env=env, timeout=120)
+    assert run.returncode == 0, run.stderr[-2000:]
+    lines = run.stdout.strip().splitlines()
+    assert len(lines) == len(cases)
+    for (c, t, p), line in zip(cases, lines):
+        parts = line.split()
+        try:
+            want = O.allocate_budgets(c, t, p)
+        except ValueError:
+            assert parts == ["5"], (line, t, p)
+            continue
+        assert parts[0] == "0"
+        got = [tuple(int(v) for v in x.split(":")) for x in parts[1:]]
+        assert [b for b, _ in got] == want[0] and [g for _, g in got] == want[1]

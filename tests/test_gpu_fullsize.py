@@ -66,6 +66,8 @@ def _run_fullsize(wl, sample_layers, units, check_steps, cos_layers, order="evic
             assert np.array_equal(got["score"], c["score"])
     for l in range(wl.L):
         assert bool((sess.caches.lens[l] == min(wl.P, budgets[l])).all())
+    # what the run holds resident is what the size model says for these budgets
+    assert sess.resident_kv_bytes() == W.squeezed_cache_bytes(wl, budgets)
 
     # ---- decode: the GPU runs every step for the whole batch ---------------------
     qn = {k: np64(sess.q[:, k[0], k[1], k[2] * g:(k[2] + 1) * g]) for k in sample}
