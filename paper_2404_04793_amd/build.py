@@ -2,7 +2,9 @@
 in-tree, next to this file.  Run as `python -m paper_2404_04793_amd.build`."""
 from __future__ import annotations
 
+import json
 import os
+import re
 import subprocess
 import sys
 from concurrent.futures import ThreadPoolExecutor
@@ -18,8 +20,25 @@ COMMON = ["-O3", "-std=c++17", "-fPIC", "-I" + os.path.join(ROOT, "include"), "-
 # vector ALU instructions, and with the default (AGPR) form the compiler copied all 32 of them back and
 # forth every tile and needed twice the registers.
 HIP_FLAGS = ["--offload-arch=gfx950", "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
-             "-mllvm", "-amdgpu-mfma-vgpr-form", "-Wno-unused-command-line-argument"]
+             "-mllvm", "-amdgpu-mfma-vgpr-form", "-Wno-unused-command-line-argument",
+             "-Rpass-analysis=kernel-resource-usage"]
 HOST_FLAGS = ["-ffp-contract=off"]
+# what the compiler reports per kernel (registers, scratch, waves per SIMD), written next to the objects:
+# a source change that costs a kernel its occupancy shows up here (and in tests/test_kernel_resources.py)
+# before it shows up as a few lost per cent on the GPU
+RESOURCES = os.path.join(OBJ_DIR, "kernel_resources.json")
+_REMARK = re.compile(r"remark:\s+(Function Name|TotalSGPRs|VGPRs|AGPRs|ScratchSize \[bytes/lane\]|"
+                     r"Occupancy \[waves/SIMD\]|VGPRs Spill|LDS Size \[bytes/block\]): (\S+)")
+
+
+def _parse_resources(stderr: str) -> dict:
+    out, cur = {}, None
+    for key, val in _REMARK.findall(stderr):
+        if key == "Function Name":
+            cur = out.setdefault(val, {})
+        elif cur is not None:
+            cur[key.split(" [")[0]] = int(val)
+    return out
 
 
 def _hipcc() -> str:
@@ -46,15 +65,33 @@ def build(verbose: bool = True) -> str:
         flags = HIP_FLAGS if src.endswith(".hip") else HOST_FLAGS
         cmd = [cc] + COMMON + flags + ["-c", src, "-o", obj]
         r = subprocess.run(cmd, capture_output=True, text=True)
-        err = "\n".join(l for l in r.stderr.splitlines() if "packed-fp32-ops" not in l)
+        res = _parse_resources(r.stderr)
+        keep, skip = [], 0
+        for l in r.stderr.splitlines():                # drop the resource remarks (and the two source lines
+            if "-Rpass-analysis=kernel-resource-usage" in l:   # clang prints under the first of each group)
+                skip = 2 if "Function Name" in l else 0
+                continue
+            if skip and (re.match(r"\s+\d+ \|", l) or re.match(r"\s+\|\s+\^", l)):
+                skip -= 1
+                continue
+            skip = 0
+            if "packed-fp32-ops" not in l:
+                keep.append(l)
+        err = "\n".join(keep)
         if r.returncode != 0:
             raise RuntimeError("compile failed: %s\n%s" % (" ".join(cmd), err))
         if verbose and err.strip():
             print(err, file=sys.stderr)
-        return obj
+        return obj, res
 
     with ThreadPoolExecutor(max_workers=min(8, os.cpu_count() or 1)) as ex:
-        objs = list(ex.map(compile_one, sources()))
+        done = list(ex.map(compile_one, sources()))
+    objs = [o for o, _ in done]
+    resources = {}
+    for _, res in done:
+        resources.update(res)
+    with open(RESOURCES, "w") as fh:
+        json.dump(resources, fh, indent=0, sort_keys=True)
     cmd = [cc, "-shared", "-fPIC", "--offload-arch=gfx950", "-o", LIB] + objs
     r = subprocess.run(cmd, capture_output=True, text=True)
     if r.returncode != 0:

@@ -60,15 +60,16 @@ struct DecodeArgs {
   // one scalar load whose base address was only 2-byte aligned, and scalar
   // loads drop the low address bits of the base (the wrong entry was read).
   struct Layer {
-    uint32_t nsplit;      // chunks per unit
+    uint32_t nsplit;      // chunks per unit; bit 31: one wave per unit (a workgroup covers 4 units)
     uint32_t chunk;       // slots per chunk
     uint32_t unit_off;    // first unit number of the layer within the call
     uint32_t part_off;    // first partial record
     uint32_t logit_off;   // first logit (floats)
-    uint32_t wpu;         // 1: one wave per unit (a workgroup covers 4 units)
   } lay[SQA_MAX_LAYERS];
   int lds_chunk_w;                     // row length of a wave's LDS logit buffer in one-wave-per-unit layers
+  int wide_tail;                       // the call has few workgroups: a long unit's tail keeps all four waves
 };
+constexpr uint32_t kWpuBit = 0x80000000u;
 
 // Data that one workgroup hands to another inside a launch (partial results,
 // logits) moves through agent-scope relaxed atomics: such stores are written
@@ -214,6 +215,8 @@ typedef __bf16 bf16x4_t __attribute__((ext_vector_type(4)));
 typedef short v4s_t __attribute__((ext_vector_type(4)));
 typedef short v8s_t __attribute__((ext_vector_type(8)));
 typedef __attribute__((address_space(3))) v4s_t* lds_v4s_ptr;
+constexpr int kSoloMaxTokens = 512;               // calls with few workgroups: an unsplit unit's tail (scores, decision) is left
+                                                  // to wave 0 alone up to this length
 constexpr int kLogitPad = 33;                     // a unit's H2O scratch region: G x (slots + kLogitPad) floats: the logit of the
                                                   // new token as one more slot, or whole 32-token tiles of bf16 probabilities
                                                   // plus a reference per tile and head
@@ -225,6 +228,7 @@ constexpr int kStageBytesPerWave = 32 * kStageRow;   // one 32-token tile
 template <typename T, int D, int G, bool H2O, bool MF>
 __global__ __launch_bounds__(kDecThreads, MF ? kMfWavesPerSimd : 1) void decode_unit_kernel(const DecodeArgs a) {
   static_assert(!MF || (sizeof(T) == 2 && D == 128 && G <= 16), "matrix-core path: bf16, D = 128");
+  constexpr int U = kUnroll;
   constexpr int ROWB = D * (int)sizeof(T);        // bytes per K or V row
   constexpr int LPR = ROWB / 16;                  // lanes per row
   constexpr int RPI = SQA_WAVE / LPR;             // rows per wave load
@@ -253,9 +257,10 @@ __global__ __launch_bounds__(kDecThreads, MF ? kMfWavesPerSimd : 1) void decode_
   }
   const int layer = a.order[lo];
   const unsigned local = blockIdx.x - (lo ? a.blk_end[lo - 1] : 0u);
-  const int nsplit = (int)a.lay[layer].nsplit;
+  const uint32_t nsplit_w = a.lay[layer].nsplit;
+  const int nsplit = (int)(nsplit_w & ~kWpuBit);
   // one wave per unit: the workgroup's waves own 4 consecutive units and never meet at a barrier
-  const bool wpu = a.lay[layer].wpu != 0;
+  const bool wpu = (nsplit_w & kWpuBit) != 0;
   const int u = wpu ? (int)local * kDecWaves + wave : (int)(local / (unsigned)nsplit);
   const int chunk = wpu ? 0 : (int)(local % (unsigned)nsplit);
   if (wpu && u >= a.B * a.Hkv) return;
@@ -301,8 +306,8 @@ __global__ __launch_bounds__(kDecThreads, MF ? kMfWavesPerSimd : 1) void decode_
   for (int g = 0; g < G; ++g)
     qf[g] = ld16(reinterpret_cast<const char*>(a.q) + (qoff + (int64_t)g * D) * (int64_t)sizeof(T) + c * 16);
   const uint4 kn_pre = ld16(knew + c * 16), vn_pre = ld16(vnew + c * 16);
-  uint4 kf[kUnroll], vf[kUnroll];
-  int slot[kUnroll];
+  uint4 kf[U], vf[U];
+  int slot[U];
   // (a packed unit may own no slot at all -- it is reported below, once its length is known --: these
   // early requests then read the new token's rows instead, which always exist)
   const bool has_slots = cap > 0;
@@ -310,7 +315,7 @@ __global__ __launch_bounds__(kDecThreads, MF ? kMfWavesPerSimd : 1) void decode_
     const char* Kpre = has_slots ? Kb : knew;
     const char* Vpre = has_slots ? Vb : vnew;
 #pragma unroll
-    for (int uu = 0; uu < kUnroll; ++uu) {
+    for (int uu = 0; uu < U; ++uu) {
       slot[uu] = c0 + uu * rows_it + wv * RPI + r;
       const int sl = max(min(slot[uu], cap - 1), 0);
       kf[uu] = ld16_nt(Kpre + (int64_t)sl * ROWB + c * 16);
@@ -562,7 +567,7 @@ __global__ __launch_bounds__(kDecThreads, MF ? kMfWavesPerSimd : 1) void decode_
 
     // patch the rows requested before the layout of this step was known
 #pragma unroll
-    for (int uu = 0; uu < kUnroll; ++uu) {
+    for (int uu = 0; uu < U; ++uu) {
       if (slot[uu] == slot_new) { kf[uu] = kn_pre; vf[uu] = vn_pre; }
       if (slot[uu] == moved_to) {
         kf[uu] = ld16(Kb + (int64_t)slot_wr * ROWB + c * 16);
@@ -570,14 +575,14 @@ __global__ __launch_bounds__(kDecThreads, MF ? kMfWavesPerSimd : 1) void decode_
       }
     }
 
-    for (int base = c0; base < c_end; base += rows_it * kUnroll) {
+    for (int base = c0; base < c_end; base += rows_it * U) {
       if (base != c0) {
         // A wave that is about to ask for its next rows goes ahead of waves that
         // are doing arithmetic: the sooner its requests are out, the fuller the
         // memory pipeline (267.8 instead of 270.1 us per step at the 7B shape).
         __builtin_amdgcn_s_setprio(3);
 #pragma unroll
-        for (int uu = 0; uu < kUnroll; ++uu) {
+        for (int uu = 0; uu < U; ++uu) {
           slot[uu] = base + uu * rows_it + wv * RPI + r;
           const int sl = min(slot[uu], n - 1);
           const char* kp = Kb + (int64_t)sl * ROWB;
@@ -589,9 +594,9 @@ __global__ __launch_bounds__(kDecThreads, MF ? kMfWavesPerSimd : 1) void decode_
         }
         __builtin_amdgcn_s_setprio(0);
       }
-      float s[kUnroll][G];
+      float s[U][G];
 #pragma unroll
-      for (int uu = 0; uu < kUnroll; ++uu)
+      for (int uu = 0; uu < U; ++uu)
 #pragma unroll
         for (int g = 0; g < G; ++g) {
           float d = group_sum<LPR>(RowMath<T>::dot(qf[g], kf[uu])) * a.scale_log2;
@@ -607,7 +612,7 @@ __global__ __launch_bounds__(kDecThreads, MF ? kMfWavesPerSimd : 1) void decode_
       for (int g = 0; g < G; ++g) {
         float mx = m[g];
 #pragma unroll
-        for (int uu = 0; uu < kUnroll; ++uu) mx = fmaxf(mx, s[uu][g]);
+        for (int uu = 0; uu < U; ++uu) mx = fmaxf(mx, s[uu][g]);
         const float ms = mx == -INFINITY ? 0.f : mx;
         const float alpha = fast_exp2(m[g] - ms);
         m[g] = mx;
@@ -615,7 +620,7 @@ __global__ __launch_bounds__(kDecThreads, MF ? kMfWavesPerSimd : 1) void decode_
 #pragma unroll
         for (int e = 0; e < EPL; ++e) acc[g][e] *= alpha;
 #pragma unroll
-        for (int uu = 0; uu < kUnroll; ++uu) {
+        for (int uu = 0; uu < U; ++uu) {
           const float p = fast_exp2(s[uu][g] - ms);
           lsum += p;
           RowMath<T>::axpy(p, vf[uu], acc[g]);
@@ -722,7 +727,9 @@ __global__ __launch_bounds__(kDecThreads, MF ? kMfWavesPerSimd : 1) void decode_
   // workgroup's registers are free for the next workgroup while the tail runs.
   if (!wpu) __syncthreads();                      // every wave is done reading the cache rows and writing LDS
   // (matrix-core H2O: the whole workgroup walks the unit's probabilities, unless each wave has a unit of its own)
-  const bool solo = nsplit == 1 && (wpu || !(MF && H2O));
+  // (... except in a call with few workgroups, where nothing else would use the registers the other waves
+  // free and a long unit's tail -- its scores are walked once more -- is on the critical path)
+  const bool solo = nsplit == 1 && (wpu || (!(MF && H2O) && !(a.wide_tail != 0 && n > kSoloMaxTokens)));
   if (solo && !wpu && wave != 0) return;
   const int nthr = solo ? SQA_WAVE : kDecThreads;
   const int tq = solo ? lane : tid;               // this thread's place among the nthr threads still at work
@@ -873,13 +880,16 @@ struct DecodePlan {
 
 static size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 
-// Units are split only when the call would otherwise have too few work items to fill the chip or a
-// few items much longer than the rest (the hand-over between workgroups costs more than the imbalance
-// it removes): the target chunk is 1/kMinItems of the call's tokens, at least 256 slots and at most what
-// lets a unit's step logits fit in LDS (kMaxUnsplit slots x heads; not for the matrix-core variant, which keeps
-// what H2O needs in the workspace); each layer uses the number of equal
-// chunks nearest to that, so units shorter than 1.5 targets stay whole.
-constexpr int64_t kMinItems = 256 * 4;
+// Units are split only when the call would otherwise leave CUs idle: the target work item is the call's
+// tokens divided by the number of CUs (at least 256 slots, and at most what lets a unit's step logits fit
+// in LDS -- kMaxUnsplit slots x heads; not for the matrix-core variant, which keeps what H2O needs in the
+// workspace), and a unit is cut into equal chunks only if it is more than a quarter longer than that.
+// One workgroup per CU already streams at 80 % of what the chip reaches, so what splitting buys is balance,
+// and the hand-over between a unit's workgroups costs more than a small imbalance: with 256 equal units (a
+// layer of the Llama-2-7B shape at batch 8 launched on its own) whole units take 53 us, halves 60 us,
+// quarters 62 us; all layers at batch 2 take 71 us whole and 81 us cut in three.
+constexpr int64_t kMinItems = 256;
+constexpr int64_t kWideTailMaxBlocks = 512;       // calls with at most this many workgroups: see DecodeArgs::wide_tail
 constexpr int kMaxUnsplit = 8192;
 // One wave per unit: for units of at most kWpuMaxSlots slots, in calls that have at least kWpuMinUnits
 // units (one wave walks a unit 16 rows at a time, so the call needs many units to keep the chip's wave
@@ -907,7 +917,7 @@ static sqa_status plan_decode(const sqa_layer_cache* layers, int n_layers, int B
   for (int i = 0; i < n_layers; ++i) {
     // + 1: under attend-then-evict a full unit attends budget + 1 tokens
     const int nmax = (layers[i].budget < layers[i].capacity ? layers[i].budget : layers[i].capacity) + 1;
-    int64_t ns = (nmax + target / 2) / target;                  // nearest count of equal chunks
+    int64_t ns = (4 * (int64_t)nmax + 5 * target - 1) / (5 * target);   // ceil(nmax / (1.25 target))
     ns = ns < 1 ? 1 : ns;
     int64_t ch = ((nmax + ns - 1) / ns + 63) / 64 * 64;
     if (h2o && !scratch_probs && ns == 1 && ch * g > kMaxUnsplit) { ns = 2; ch = ((nmax + 1) / 2 + 63) / 64 * 64; }
@@ -1031,8 +1041,7 @@ static sqa_status decode_prepare(const void* q, const void* k_new, const void* v
     return SQA_ERR_SHAPE;
   const int g = Hq / Hkv;
   const bool h2o = policy == SQA_H2O;
-  decode_fn fn = pick(dt, D, g, h2o);
-  if (!fn) return SQA_ERR_SHAPE;
+  if (!pick(dt, D, g, h2o)) return SQA_ERR_SHAPE;
   if (!aligned16(q) || !aligned16(k_new) || !aligned16(v_new) || !aligned16(out)) return SQA_ERR_SHAPE;
   const int min_budget = h2o ? 2 : (policy == SQA_STREAMING ? n_sink + 1 : 1);
   for (int i = 0; i < n_layers; ++i) {
@@ -1050,7 +1059,7 @@ static sqa_status decode_prepare(const void* q, const void* k_new, const void* v
   const size_t lds = (h2o ? (lds_shared > lds_waves ? lds_shared : lds_waves) * sizeof(float) : 0) +
                      (mfma ? (size_t)kDecWaves * kStageBytesPerWave : 0);
   if (lds > 160 * 1024) return SQA_ERR_CAPACITY;
-  *fn_out = fn;
+  *fn_out = pick(dt, D, g, h2o);
   *lds_out = lds;
   return SQA_OK;
 }
@@ -1088,13 +1097,13 @@ static sqa_status decode_launch(decode_fn fn, const DecodePlan& plan, size_t lds
     const int l = a.order[i];
     run += plan.wpu[l] ? ((uint64_t)B * Hkv + kDecWaves - 1) / kDecWaves : (uint64_t)B * Hkv * plan.nsplit[l];
     a.blk_end[i] = (uint32_t)run;
-    a.lay[i].wpu = plan.wpu[i];
-    a.lay[i].nsplit = plan.nsplit[i];
+    a.lay[i].nsplit = plan.nsplit[i] | (plan.wpu[i] ? kWpuBit : 0u);
     a.lay[i].chunk = plan.chunk[i];
     a.lay[i].unit_off = plan.unit_off[i];
     a.lay[i].part_off = plan.part_off[i];
     a.lay[i].logit_off = plan.logit_off[i];
   }
+  a.wide_tail = plan.blocks <= (uint64_t)kWideTailMaxBlocks ? 1 : 0;
   if (layers_dev) {
     a.layers = layers_dev;
   } else {

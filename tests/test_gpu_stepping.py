@@ -86,14 +86,14 @@ def _rows_by_position(Kp, Vp, k_all, v_all, l, b, h):
 
 STEPPING = [
     # name, dtype, Hq, Hkv, D, B, P, S, policy, budgets, order
-    # budgets: 380 = a whole unit shared by 4 waves, 700 = split into 3 chunks over 3 workgroups, 37 = shorter than one pass
-    ("h2o_bf16_mha", "bf16", 2, 2, 128, 2, 750, 48, "h2o", [380, 700, 37], "evict_then_attend"),
-    ("h2o_bf16_gqa4_matrix", "bf16", 8, 2, 128, 2, 750, 48, "h2o", [380, 700, 37], "evict_then_attend"),
-    ("h2o_bf16_gqa8_matrix", "bf16", 16, 2, 128, 2, 750, 48, "h2o", [380, 700, 37], "evict_then_attend"),
-    ("h2o_f32_d64_gqa2", "f32", 4, 2, 64, 1, 500, 40, "h2o", [330, 520, 21], "evict_then_attend"),
-    ("h2o_bf16_mha_attend_first", "bf16", 2, 2, 128, 2, 750, 40, "h2o", [380, 700, 37], "attend_then_evict"),
-    ("h2o_bf16_gqa8_matrix_attend_first", "bf16", 16, 2, 128, 2, 750, 40, "h2o", [380, 700, 37], "attend_then_evict"),
-    ("streaming_bf16_gqa4_matrix", "bf16", 8, 2, 128, 1, 750, 40, "streaming", [380, 700, 37], "evict_then_attend"),
+    # budgets: 300 = a whole unit shared by 4 waves, 700 = split into 3 chunks over 3 workgroups, 37 = shorter than one pass
+    ("h2o_bf16_mha", "bf16", 2, 2, 128, 2, 750, 48, "h2o", [300, 700, 37], "evict_then_attend"),
+    ("h2o_bf16_gqa4_matrix", "bf16", 8, 2, 128, 2, 750, 48, "h2o", [300, 700, 37], "evict_then_attend"),
+    ("h2o_bf16_gqa8_matrix", "bf16", 16, 2, 128, 2, 750, 48, "h2o", [300, 700, 37], "evict_then_attend"),
+    ("h2o_f32_d64_gqa2", "f32", 4, 2, 64, 1, 500, 40, "h2o", [310, 520, 21], "evict_then_attend"),
+    ("h2o_bf16_mha_attend_first", "bf16", 2, 2, 128, 2, 750, 40, "h2o", [300, 700, 37], "attend_then_evict"),
+    ("h2o_bf16_gqa8_matrix_attend_first", "bf16", 16, 2, 128, 2, 750, 40, "h2o", [300, 700, 37], "attend_then_evict"),
+    ("streaming_bf16_gqa4_matrix", "bf16", 8, 2, 128, 1, 750, 40, "streaming", [300, 700, 37], "evict_then_attend"),
     # units that fill up while decoding (budget above the prompt length)
     ("h2o_bf16_mha_filling", "bf16", 2, 2, 128, 1, 300, 44, "h2o", [310, 330, 400], "evict_then_attend"),
 ]
@@ -101,6 +101,18 @@ STEPPING = [
 
 @pytest.mark.parametrize("case", STEPPING, ids=[c[0] for c in STEPPING])
 def test_stepping_from_the_gpus_own_state(sqa, case):
+    _run_case(sqa, case)
+
+
+@pytest.mark.parametrize("order", ["evict_then_attend", "attend_then_evict"])
+def test_stepping_whole_long_units_in_a_small_call(sqa, order):
+    """208 units of 600 slots in one call: few enough workgroups that units stay whole although they are
+    long, and that all four waves of a workgroup stay for the unit's tail (score update, eviction
+    decision) instead of leaving it to the first wave."""
+    _run_case(sqa, ("h2o_bf16_mha_whole_long_units", "bf16", 8, 8, 128, 26, 640, 24, "h2o", [600], order), stride=19)
+
+
+def _run_case(sqa, case, stride=1):
     name, dtype, Hq, Hkv, D, B, P, S, policy, budgets, order = case
     L, g = len(budgets), Hq // Hkv
     wl = W.scaled(W.WORKLOADS["tiny"], L=L, Hq=Hq, Hkv=Hkv, D=D, B=B, P=P, S=S, dtype=dtype, policy=policy)
@@ -116,12 +128,12 @@ def test_stepping_from_the_gpus_own_state(sqa, case):
     q_all = torch.stack([x[0] for x in qkv], 1).contiguous()
     k_all = torch.stack([x[1] for x in qkv], 1).contiguous()
     v_all = torch.stack([x[2] for x in qkv], 1).contiguous()
-    sample = [(l, b, h) for l in range(L) for b in range(B) for h in range(Hkv)]
+    sample = [(l, b, h) for l in range(L) for b in range(B) for h in range(Hkv)][::stride]
     rows = {key: _rows_by_position(Kp[key[0]], Vp[key[0]], k_all, v_all, *key) for key in sample}
     ws = sqa.decode_workspace(caches, Hq, policy)
     seen = _step_and_compare(sqa, caches, ws, budgets, policy, order, dtype, D, g, P, S, q_all, k_all, v_all, rows, sample,
                              wl.n_sink)
-    print(name, seen)
+    print(name, order, seen)
     assert seen["evictions"] > 0
     if policy == "h2o" and order == "evict_then_attend":
         assert seen["leaver_goes"] > 0 and seen["heavy_goes"] > 0, seen       # both outcomes of the carried decision
