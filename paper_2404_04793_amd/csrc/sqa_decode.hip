@@ -60,7 +60,8 @@ struct DecodeArgs {
   // one scalar load whose base address was only 2-byte aligned, and scalar
   // loads drop the low address bits of the base (the wrong entry was read).
   struct Layer {
-    uint32_t nsplit;      // chunks per unit; bit 31: one wave per unit (a workgroup covers 4 units)
+    uint32_t nsplit;      // chunks per unit; bit 31: one wave per unit (a workgroup covers 4 units);
+                          // bit 30: the step's per-head probabilities (matrix-core variant under H2O) stay in LDS
     uint32_t chunk;       // slots per chunk
     uint32_t unit_off;    // first unit number of the layer within the call
     uint32_t part_off;    // first partial record
@@ -68,8 +69,9 @@ struct DecodeArgs {
   } lay[SQA_MAX_LAYERS];
   int lds_chunk_w;                     // row length of a wave's LDS logit buffer in one-wave-per-unit layers
   int wide_tail;                       // the call has few workgroups: a long unit's tail keeps all four waves
+  int lds_probs_w;                     // bytes of a wave's own LDS region for those probabilities in one-wave-per-unit layers
 };
-constexpr uint32_t kWpuBit = 0x80000000u;
+constexpr uint32_t kWpuBit = 0x80000000u, kLdsProbsBit = 0x40000000u;
 
 // Data that one workgroup hands to another inside a launch (partial results,
 // logits) moves through agent-scope relaxed atomics: such stores are written
@@ -235,14 +237,21 @@ __global__ __launch_bounds__(kDecThreads, MF ? kMfWavesPerSimd : 1) void decode_
   constexpr int EPL = RowMath<T>::EPL;            // elements per lane
   constexpr int PREC = D + 2;                     // floats per partial record: acc[D], m, l
 
-  extern __shared__ float s_logit[];              // H2O, unsplit units: [G][lds_chunk]
+  extern __shared__ __align__(256) float s_logit[];   // H2O, unsplit units: [G][lds_chunk]; matrix-core variant: stage buffers (16-byte LDS accesses)
   __shared__ float s_m[kDecWaves][G], s_l[kDecWaves][G];
-  __shared__ float s_acc[kDecWaves][G][D];
+  // per-wave output accumulators for the merge of a unit's waves; the matrix-core variant puts them where
+  // its tiles were staged (a wave's 8.5 KiB stage buffer is free once its last tile is consumed), which leaves
+  // the LDS of a CU to three workgroups AND a unit's probabilities (below)
+  __shared__ float s_acc_static[MF ? 1 : kDecWaves][MF ? 1 : G][D];
   __shared__ float s_red[kDecWaves];
   __shared__ unsigned long long s_red64[kDecWaves];
   __shared__ int s_ctl[2];
   __shared__ float s_ctlf[kDecWaves][2];
 
+  char* const stage_base = reinterpret_cast<char*>(s_logit + (H2O ? G * a.lds_chunk : 0));     // (matrix-core variant)
+  float* const acc_lds = MF ? reinterpret_cast<float*>(stage_base) : &s_acc_static[0][0][0];
+  constexpr int kAccWave = MF ? kStageBytesPerWave / 4 : G * D;                               // floats between waves
+  static_assert(!MF || G * D * 4 <= kStageBytesPerWave, "a wave's accumulators fit in its stage buffer");
   const int tid = threadIdx.x, lane = tid & (SQA_WAVE - 1);
   // (the wave number is the same in all lanes: say so, or everything derived from it -- the unit a wave
   // owns, its pointers, its length -- lands in vector registers and is loaded with vector loads)
@@ -258,7 +267,7 @@ __global__ __launch_bounds__(kDecThreads, MF ? kMfWavesPerSimd : 1) void decode_
   const int layer = a.order[lo];
   const unsigned local = blockIdx.x - (lo ? a.blk_end[lo - 1] : 0u);
   const uint32_t nsplit_w = a.lay[layer].nsplit;
-  const int nsplit = (int)(nsplit_w & ~kWpuBit);
+  const int nsplit = (int)(nsplit_w & ~(kWpuBit | kLdsProbsBit));
   // one wave per unit: the workgroup's waves own 4 consecutive units and never meet at a barrier
   const bool wpu = (nsplit_w & kWpuBit) != 0;
   const int u = wpu ? (int)local * kDecWaves + wave : (int)(local / (unsigned)nsplit);
@@ -373,10 +382,17 @@ __global__ __launch_bounds__(kDecThreads, MF ? kMfWavesPerSimd : 1) void decode_
   // writes a tile's G x 64 bytes in one go, whole cache lines -- and behind them the references, [tile][head]
   // (tiles start at multiples of 32 because chunks do).  They are written and read by the same workgroup unless
   // the unit is split: only then do they need the coherent path.
+  // Units short enough keep all of this in LDS instead (behind the stage buffers; a per-layer flag of the
+  // launch plan): what a step writes to memory costs several times what it reads, and these 2 bytes per token
+  // and head, written and read back by the same workgroup, are not part of what the method has to move.
   const int ntile_max = (lpitch + 31) >> 5;
   const bool handover = nsplit > 1;
+  const bool lds_probs = MF && H2O && (nsplit_w & kLdsProbsBit) != 0;
   unsigned short* e16 = reinterpret_cast<unsigned short*>(glogit);
   float* tref = (MF && H2O) ? glogit + (int64_t)ntile_max * G * 16 : nullptr;
+  char* const probs_lds = stage_base + kDecWaves * kStageBytesPerWave + (wpu ? wave * a.lds_probs_w : 0);
+  unsigned short* const e16_l = reinterpret_cast<unsigned short*>(probs_lds);                // [tile][head][32]
+  float* const tref_l = reinterpret_cast<float*>(probs_lds + ntile_max * G * 64);            // [tile][head]
 
   if constexpr (MF) {
     // ---- 1M. matrix-core streaming ------------------------------------------
@@ -404,7 +420,7 @@ __global__ __launch_bounds__(kDecThreads, MF ? kMfWavesPerSimd : 1) void decode_
     // registers a K tile in flight used to occupy are what kept this variant at 2
     // waves per SIMD; at 3, with a third more bytes in flight per CU, the
     // Llama-2-70B shape went from 1138 to 997 us per step.
-    char* stage = reinterpret_cast<char*>(s_logit + (H2O ? G * a.lds_chunk : 0)) + wave * kStageBytesPerWave;
+    char* stage = stage_base + wave * kStageBytesPerWave;
     const int hd = lane & 15, j4 = lane >> 4;
     bf16x8_t qfr[4];
 #pragma unroll
@@ -507,13 +523,21 @@ __global__ __launch_bounds__(kDecThreads, MF ? kMfWavesPerSimd : 1) void decode_
         // written costs as much as several bytes read.
 #pragma unroll
         for (int tt = 0; tt < 2; ++tt) {            // (tokens beyond the unit's end get zeros: the region holds whole tiles)
-          unsigned long long* dst = reinterpret_cast<unsigned long long*>(e16 + ((int64_t)(base >> 5) * G + hd) * 32 + 16 * tt + 4 * j4);
           const unsigned long long four = __builtin_bit_cast(unsigned long long, pfr[tt]);
-          if (handover) st_agent(dst, four); else *dst = four;
+          if (lds_probs) {
+            *reinterpret_cast<unsigned long long*>(e16_l + ((base >> 5) * G + hd) * 32 + 16 * tt + 4 * j4) = four;
+          } else {
+            unsigned long long* dst = reinterpret_cast<unsigned long long*>(e16 + ((int64_t)(base >> 5) * G + hd) * 32 + 16 * tt + 4 * j4);
+            if (handover) st_agent(dst, four); else *dst = four;
+          }
         }
         if (j4 == 0) {
-          float* dst = &tref[(base >> 5) * G + hd];
-          if (handover) st_agent(dst, ms); else *dst = ms;
+          if (lds_probs) {
+            tref_l[(base >> 5) * G + hd] = ms;
+          } else {
+            float* dst = &tref[(base >> 5) * G + hd];
+            if (handover) st_agent(dst, ms); else *dst = ms;
+          }
         }
       }
       if (__ballot(alpha != 1.f)) {
@@ -554,7 +578,7 @@ __global__ __launch_bounds__(kDecThreads, MF ? kMfWavesPerSimd : 1) void decode_
 #pragma unroll
       for (int db = 0; db < 8; ++db)
 #pragma unroll
-        for (int i = 0; i < 4; ++i) s_acc[wave][hd][16 * db + 4 * j4 + i] = oacc[db][i];
+        for (int i = 0; i < 4; ++i) acc_lds[wave * kAccWave + hd * D + 16 * db + 4 * j4 + i] = oacc[db][i];
     }
   } else {
     float m[G], l[G], acc[G][EPL];
@@ -650,7 +674,7 @@ __global__ __launch_bounds__(kDecThreads, MF ? kMfWavesPerSimd : 1) void decode_
       if (r == 0) {
         if (c == 0) { s_m[wave][g] = m[g]; s_l[wave][g] = l[g]; }
 #pragma unroll
-        for (int e = 0; e < EPL; ++e) s_acc[wave][g][c * EPL + e] = acc[g][e];
+        for (int e = 0; e < EPL; ++e) acc_lds[wave * kAccWave + g * D + c * EPL + e] = acc[g][e];
       }
     }
   }
@@ -669,7 +693,7 @@ __global__ __launch_bounds__(kDecThreads, MF ? kMfWavesPerSimd : 1) void decode_
       const float f = fast_exp2(s_m[w][g] - ms);
       lt += s_l[w][g] * f;
 #pragma unroll
-      for (int e = 0; e < EPL; ++e) o[e] += s_acc[w][g][c * EPL + e] * f;
+      for (int e = 0; e < EPL; ++e) o[e] += acc_lds[w * kAccWave + g * D + c * EPL + e] * f;
     }
     if (nsplit == 1) {
       const float inv = 1.f / lt;                 // n >= 1: lt > 0
@@ -748,14 +772,14 @@ __global__ __launch_bounds__(kDecThreads, MF ? kMfWavesPerSimd : 1) void decode_
     // Matrix-core variant: one factor per (head, 32-token tile) turns a stored probability into the final
     // one, exp2(reference - m) / l; the table goes where the tiles were staged (if the unit is so long that
     // it does not fit there, the factor is recomputed per token instead).
-    float* fac = reinterpret_cast<float*>(reinterpret_cast<char*>(s_logit + G * a.lds_chunk) + (wpu ? wave * kStageBytesPerWave : 0));
+    float* fac = reinterpret_cast<float*>(stage_base + (wpu ? wave * kStageBytesPerWave : 0));
     const bool use_fac = MF && (size_t)G * ntile_max * sizeof(float) <= (size_t)nw * kStageBytesPerWave;
     if constexpr (MF) {
       if (use_fac) {
         const int ntile = (n + 31) >> 5;
         for (int idx = tq; idx < G * ntile; idx += nthr) {
           const int g = idx % G;                  // idx = tile * G + head
-          const float rf = handover ? ld_agent(&tref[idx]) : tref[idx];
+          const float rf = lds_probs ? tref_l[idx] : (handover ? ld_agent(&tref[idx]) : tref[idx]);
           fac[idx] = fast_exp2(rf - s_m[wq][g]) * s_l[wq][g];
         }
         if (!solo) __syncthreads();               // (a wave on its own reads back what it wrote itself: LDS keeps a wave's order)
@@ -778,11 +802,11 @@ __global__ __launch_bounds__(kDecThreads, MF ? kMfWavesPerSimd : 1) void decode_
 #pragma unroll
           for (int g = 0; g < G; ++g) {
             if constexpr (MF) {
-              const int64_t at = ((int64_t)(i >> 5) * G + g) * 32 + (i & 31);
-              const unsigned short eb = handover ? ld_agent(&e16[at]) : e16[at];
+              const int at = ((i >> 5) * G + g) * 32 + (i & 31);
+              const unsigned short eb = lds_probs ? e16_l[at] : (handover ? ld_agent(&e16[at]) : e16[at]);
               const float e = __uint_as_float((uint32_t)eb << 16);
               p += e * (use_fac ? fac[(i >> 5) * G + g]
-                                : fast_exp2(ld_agent(&tref[(i >> 5) * G + g]) - s_m[wq][g]) * s_l[wq][g]);
+                                : fast_exp2((lds_probs ? tref_l[(i >> 5) * G + g] : ld_agent(&tref[(i >> 5) * G + g])) - s_m[wq][g]) * s_l[wq][g]);
             } else {
               const float lg = glogit ? ld_agent(&glogit[(int64_t)g * lpitch + i]) : s_lg[g * lp + i];
               p += fast_exp2(lg - fm[g]) * fi[g];
@@ -867,6 +891,8 @@ constexpr size_t kStatusBytes = 256;
 
 // How one call is cut into work items and where its scratch lives.
 struct DecodePlan {
+  int lds_probs, lds_probs_w;                      // LDS bytes for the probabilities of a workgroup / of one wave's unit
+  uint8_t probs_in_lds[SQA_MAX_LAYERS];            // matrix-core variant under H2O: this layer's units keep them in LDS
   int lds_chunk;                                   // longest unsplit unit shared by 4 waves (slots)
   int lds_chunk_w;                                 // longest one-wave unit (slots)
   uint8_t wpu[SQA_MAX_LAYERS];                     // one wave per unit in this layer
@@ -890,6 +916,9 @@ static size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 // quarters 62 us; all layers at batch 2 take 71 us whole and 81 us cut in three.
 constexpr int64_t kMinItems = 256;
 constexpr int64_t kWideTailMaxBlocks = 512;       // calls with at most this many workgroups: see DecodeArgs::wide_tail
+// Matrix-core variant under H2O: LDS a workgroup may use for a unit's per-head probabilities so that three
+// workgroups still fit a CU (160 KiB / 3, less the four stage buffers and the small static arrays).
+constexpr int kLdsProbsMax = 18 * 1024;
 constexpr int kMaxUnsplit = 8192;
 // One wave per unit: for units of at most kWpuMaxSlots slots, in calls that have at least kWpuMinUnits
 // units (one wave walks a unit 16 rows at a time, so the call needs many units to keep the chip's wave
@@ -912,6 +941,7 @@ static sqa_status plan_decode(const sqa_layer_cache* layers, int n_layers, int B
   target = target < 256 ? 256 : target;
   if (h2o && !scratch_probs && target > kMaxUnsplit / g) target = kMaxUnsplit / g;
   uint64_t blocks = 0, n_units = 0, n_part = 0, n_logit = 0;
+  p->lds_probs = p->lds_probs_w = 0;
   p->lds_chunk = scratch_probs ? 0 : 64;           // (no LDS logits at all when they live in the workspace)
   p->lds_chunk_w = scratch_probs ? 0 : 64;
   for (int i = 0; i < n_layers; ++i) {
@@ -926,6 +956,17 @@ static sqa_status plan_decode(const sqa_layer_cache* layers, int n_layers, int B
     p->nsplit[i] = (uint16_t)ns;
     p->chunk[i] = (uint32_t)ch;
     p->wpu[i] = allow_wpu && ns == 1 && nmax <= kWpuMaxSlots && units * n_layers >= kWpuMinUnits;
+    p->probs_in_lds[i] = 0;
+    if (h2o && scratch_probs && ns == 1) {
+      // per unit: whole 32-token tiles of bf16 values per head, plus one fp32 reference per tile and head
+      const int64_t ntile = ((int64_t)layers[i].capacity + 1 + 31) / 32;
+      const int64_t need = (int64_t)g * ntile * (64 + 4);
+      if (need * (p->wpu[i] ? kDecWaves : 1) <= kLdsProbsMax) {
+        p->probs_in_lds[i] = 1;
+        if (p->wpu[i] && need > p->lds_probs_w) p->lds_probs_w = (int)need;
+        if (need * (p->wpu[i] ? kDecWaves : 1) > p->lds_probs) p->lds_probs = (int)(need * (p->wpu[i] ? kDecWaves : 1));
+      }
+    }
     if (p->wpu[i]) { if (!scratch_probs && ch > p->lds_chunk_w) p->lds_chunk_w = (int)ch; }
     else if (ns == 1 && !scratch_probs && ch > p->lds_chunk) p->lds_chunk = (int)ch;
     p->unit_off[i] = (uint32_t)n_units;
@@ -934,10 +975,11 @@ static sqa_status plan_decode(const sqa_layer_cache* layers, int n_layers, int B
     n_units += units;
     blocks += p->wpu[i] ? (units + kDecWaves - 1) / kDecWaves : units * ns;
     if (ns > 1) n_part += units * ns;
-    if (h2o && (ns > 1 || scratch_probs)) n_logit += units * g * ((uint64_t)layers[i].capacity + kLogitPad);
+    if (h2o && (ns > 1 || scratch_probs) && !p->probs_in_lds[i]) n_logit += units * g * ((uint64_t)layers[i].capacity + kLogitPad);
     if (n_units > 0x7fffffffull || n_part > 0x7fffffffull || n_logit > 0xffffffffull || blocks > 0x7fffffffull)
       return SQA_ERR_CAPACITY;
   }
+  if (kDecWaves * p->lds_probs_w > p->lds_probs) p->lds_probs = kDecWaves * p->lds_probs_w;
   p->blocks = blocks;
   p->cnt_bytes = n_units * sizeof(int32_t);
   p->part_bytes = n_part * g * (D + 2) * sizeof(float);
@@ -1057,7 +1099,7 @@ static sqa_status decode_prepare(const void* q, const void* k_new, const void* v
   if (ps != SQA_OK) return ps;
   const size_t lds_shared = (size_t)g * plan->lds_chunk, lds_waves = (size_t)kDecWaves * g * plan->lds_chunk_w;
   const size_t lds = (h2o ? (lds_shared > lds_waves ? lds_shared : lds_waves) * sizeof(float) : 0) +
-                     (mfma ? (size_t)kDecWaves * kStageBytesPerWave : 0);
+                     (mfma ? (size_t)kDecWaves * kStageBytesPerWave : 0) + (size_t)plan->lds_probs;
   if (lds > 160 * 1024) return SQA_ERR_CAPACITY;
   *fn_out = pick(dt, D, g, h2o);
   *lds_out = lds;
@@ -1097,13 +1139,14 @@ static sqa_status decode_launch(decode_fn fn, const DecodePlan& plan, size_t lds
     const int l = a.order[i];
     run += plan.wpu[l] ? ((uint64_t)B * Hkv + kDecWaves - 1) / kDecWaves : (uint64_t)B * Hkv * plan.nsplit[l];
     a.blk_end[i] = (uint32_t)run;
-    a.lay[i].nsplit = plan.nsplit[i] | (plan.wpu[i] ? kWpuBit : 0u);
+    a.lay[i].nsplit = plan.nsplit[i] | (plan.wpu[i] ? kWpuBit : 0u) | (plan.probs_in_lds[i] ? kLdsProbsBit : 0u);
     a.lay[i].chunk = plan.chunk[i];
     a.lay[i].unit_off = plan.unit_off[i];
     a.lay[i].part_off = plan.part_off[i];
     a.lay[i].logit_off = plan.logit_off[i];
   }
   a.wide_tail = plan.blocks <= (uint64_t)kWideTailMaxBlocks ? 1 : 0;
+  a.lds_probs_w = plan.lds_probs_w;
   if (layers_dev) {
     a.layers = layers_dev;
   } else {

@@ -112,6 +112,14 @@ def test_stepping_whole_long_units_in_a_small_call(sqa, order):
     _run_case(sqa, ("h2o_bf16_mha_whole_long_units", "bf16", 8, 8, 128, 26, 640, 24, "h2o", [600], order), stride=19)
 
 
+def test_stepping_matrix_core_units_at_the_lds_limit(sqa):
+    """8 query heads per KV head, 208 whole units of 1050 slots: the largest units whose per-head
+    probabilities of a step (33 tiles x 8 heads x 68 bytes) still fit in LDS next to the stage buffers;
+    the second layer (1200 slots) is just beyond and keeps them in the workspace."""
+    _run_case(sqa, ("h2o_bf16_gqa8_matrix_lds_limit", "bf16", 64, 8, 128, 26, 1250, 10, "h2o", [1050, 1200],
+                    "evict_then_attend"), stride=37)
+
+
 def _run_case(sqa, case, stride=1):
     name, dtype, Hq, Hkv, D, B, P, S, policy, budgets, order = case
     L, g = len(budgets), Hq // Hkv
