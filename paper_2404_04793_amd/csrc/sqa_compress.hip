@@ -95,8 +95,6 @@ __global__ __launch_bounds__(kCmpThreads) void prefill_compress_kernel(
     }
     return;
   }
-  int* s_idx = reinterpret_cast<int*>(s_mem);              // [n_keep] kept positions, ascending
-  uint32_t* s_keys = s_mem + n_keep;                       // [M] when staged
   const float* sc = scores ? scores + (int64_t)u * P_pad : nullptr;
 
   // range rules
@@ -109,7 +107,13 @@ __global__ __launch_bounds__(kCmpThreads) void prefill_compress_kernel(
     else { hh = b / 2; hi_from = P - (b - hh); }
   }
   const int M = hi_from;  // H2O candidates are positions [0, M)
-  const bool keys_in_lds = hh > 0 && M <= kKeysInLdsMax && n_keep + M <= lds_words;
+  // The kept tokens in position order are: the positions below lo_keep, then the hh candidates chosen by
+  // score, then everything from hi_from on.  Only the middle part needs a list (in LDS); the other two
+  // are index arithmetic, so a unit's length is not limited by LDS (an uncompressed or sliding-window
+  // cache of any length; H2O budgets up to 65536).
+  int* s_idx = reinterpret_cast<int*>(s_mem);              // [hh] positions chosen by score, ascending
+  uint32_t* s_keys = s_mem + hh;                           // [M] when staged
+  const bool keys_in_lds = hh > 0 && M <= kKeysInLdsMax && hh + M <= lds_words;
 
   uint32_t thr = 0xffffffffu, take_eq = 0;
   if (hh > 0) {
@@ -143,27 +147,27 @@ __global__ __launch_bounds__(kCmpThreads) void prefill_compress_kernel(
     thr = prefix; take_eq = (uint32_t)k;
   }
 
-  // keep flags -> slots, in position order, 256 positions at a time
-  int eq_seen = 0, kept_seen = 0;
-  for (int base = 0; base < P; base += kCmpThreads) {
-    const int i = base + tid;
-    const bool in = i < P;
-    bool keep = in && (i < lo_keep || i >= hi_from);
-    if (hh > 0) {
-      const bool cand = in && i < M;
+  // keep flags of the candidates -> their order among the chosen, in position order, 256 positions at a time
+  if (hh > 0) {
+    int eq_seen = 0, kept_seen = 0;
+    for (int base = 0; base < M; base += kCmpThreads) {
+      const int i = base + tid;
+      const bool cand = i < M;
       const uint32_t key = cand ? score_key(sc[i]) : 0u;
       const bool eq = cand && key == thr;
       int eq_tot;
       const int eq_rank = eq_seen + block_excl_count(eq, s_wave_tot, eq_tot);
       eq_seen += eq_tot;
-      keep = keep || (cand && (key > thr || (eq && (uint32_t)eq_rank < take_eq)));
+      const bool keep = cand && (key > thr || (eq && (uint32_t)eq_rank < take_eq));
+      int kept_tot;
+      const int slot = kept_seen + block_excl_count(keep, s_wave_tot, kept_tot);
+      kept_seen += kept_tot;
+      if (keep) s_idx[slot] = i;
     }
-    int kept_tot;
-    const int slot = kept_seen + block_excl_count(keep, s_wave_tot, kept_tot);
-    kept_seen += kept_tot;
-    if (keep) s_idx[slot] = i;
+    __syncthreads();
   }
-  __syncthreads();
+  // position of the token that goes to slot j
+  auto source = [&](int j) { return j < lo_keep ? j : (j < lo_keep + hh ? s_idx[j - lo_keep] : hi_from + (j - lo_keep - hh)); };
 
   // gather rows, scores, positions
   const T* Ku = K + (int64_t)u * P_pad * D;
@@ -174,8 +178,8 @@ __global__ __launch_bounds__(kCmpThreads) void prefill_compress_kernel(
   constexpr int GROUPS = kCmpThreads / LPR;
   for (int j = grp; j < n_keep; j += 2 * GROUPS) {
     const int j2 = j + GROUPS;
-    const int src = s_idx[j];
-    const int src2 = j2 < n_keep ? s_idx[j2] : src;
+    const int src = source(j);
+    const int src2 = j2 < n_keep ? source(j2) : src;
     const uint4 k1 = ld16(reinterpret_cast<const char*>(Ku) + (int64_t)src * ROWB + c * 16);
     const uint4 v1 = ld16(reinterpret_cast<const char*>(Vu) + (int64_t)src * ROWB + c * 16);
     const uint4 k2 = ld16(reinterpret_cast<const char*>(Ku) + (int64_t)src2 * ROWB + c * 16);
@@ -189,7 +193,7 @@ __global__ __launch_bounds__(kCmpThreads) void prefill_compress_kernel(
   }
   int32_t* posu = L.pos + uoff;
   for (int j = tid; j < n_keep; j += kCmpThreads) {
-    const int src = s_idx[j];
+    const int src = source(j);
     posu[j] = src;
     if (L.score_acc) L.score_acc[uoff + j] = sc ? sc[src] : 0.f;
   }
@@ -197,7 +201,7 @@ __global__ __launch_bounds__(kCmpThreads) void prefill_compress_kernel(
 }
 
 // out[rank of pos[i]] = pos[i]; -1 beyond len.  Rank by counting (a test view, O(n^2)).
-__global__ __launch_bounds__(kCmpThreads) void kept_idx_sorted_kernel(sqa_layer_cache L, int32_t* __restrict__ out) {
+__global__ __launch_bounds__(kCmpThreads) void kept_idx_sorted_kernel(sqa_layer_cache L, int32_t* __restrict__ out, int use_lds) {
   extern __shared__ uint32_t s_mem[];
   int* s_pos = reinterpret_cast<int*>(s_mem);
   const int u = blockIdx.x;
@@ -207,13 +211,17 @@ __global__ __launch_bounds__(kCmpThreads) void kept_idx_sorted_kernel(sqa_layer_
   len = len < 0 ? 0 : (len > cap ? cap : len);
   const int32_t* posu = L.pos + uoff;
   int32_t* o = out + uoff;
-  for (int i = threadIdx.x; i < len; i += kCmpThreads) s_pos[i] = posu[i];
   for (int i = len + threadIdx.x; i < cap; i += kCmpThreads) o[i] = -1;
-  __syncthreads();
+  if (use_lds) {
+    for (int i = threadIdx.x; i < len; i += kCmpThreads) s_pos[i] = posu[i];
+    __syncthreads();
+  }
+  // (units too long for LDS are ranked from memory: the same count, slower)
+  const int32_t* src = use_lds ? s_pos : posu;
   for (int i = threadIdx.x; i < len; i += kCmpThreads) {
-    const int p = s_pos[i];
+    const int p = src[i];
     int rank = 0;
-    for (int j = 0; j < len; ++j) rank += (s_pos[j] < p) || (s_pos[j] == p && j < i);
+    for (int j = 0; j < len; ++j) rank += (src[j] < p) || (src[j] == p && j < i);
     o[rank] = p;
   }
 }
@@ -255,7 +263,9 @@ static sqa_status check_compress_layer(const void* K, const void* V, sqa_dtype k
   // per-sequence budget; their keys are staged in LDS when they fit
   const bool h2o_select = policy == SQA_H2O && (ragged ? P > 2 : P > L.budget);
   const int M = h2o_select ? (ragged ? P - 1 : P - (L.budget - L.budget / 2)) : 0;
-  *lds_out = ((size_t)n_keep + (M <= kKeysInLdsMax ? (size_t)M : 0)) * sizeof(uint32_t);
+  // (the list of positions chosen by score: at most floor(budget / 2) entries)
+  const size_t hh_max = policy == SQA_H2O ? (size_t)(L.budget / 2) : 0;
+  *lds_out = (hh_max + (M <= kKeysInLdsMax ? (size_t)M : 0)) * sizeof(uint32_t);
   return SQA_OK;
 }
 
@@ -344,11 +354,12 @@ extern "C" sqa_status sqa_kept_idx_sorted(const sqa_layer_cache* layer, int B, i
   if (!layer || !out || !layer->pos || !layer->unit_state) return SQA_ERR_NULL;
   if (B < 1 || Hkv < 1 || (int64_t)B * Hkv > INT32_MAX) return SQA_ERR_SHAPE;
   if (layer->capacity < 1) return SQA_ERR_CAPACITY;
-  const size_t lds = (size_t)layer->capacity * sizeof(int32_t);
-  if (lds > 128 * 1024) return SQA_ERR_CAPACITY;
+  size_t lds = (size_t)layer->capacity * sizeof(int32_t);
+  const int use_lds = lds <= 128 * 1024;
+  if (!use_lds) lds = 0;
   if (lds > 48 * 1024)
     SQA_HIP_CHECK(allow_dynamic_lds(reinterpret_cast<const void*>(kept_idx_sorted_kernel), lds));
-  kept_idx_sorted_kernel<<<(unsigned)(B * Hkv), kCmpThreads, lds, static_cast<hipStream_t>(stream)>>>(*layer, out);
+  kept_idx_sorted_kernel<<<(unsigned)(B * Hkv), kCmpThreads, lds, static_cast<hipStream_t>(stream)>>>(*layer, out, use_lds);
   SQA_HIP_CHECK(hipGetLastError());
   return SQA_OK;
 }

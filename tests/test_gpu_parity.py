@@ -595,6 +595,42 @@ def test_decode_one_very_long_unit(sqa):
     assert sqa.read_device_status(ws) == 0
 
 
+@pytest.mark.parametrize("policy,P,b", [("sliding", 70000, 70010), ("streaming", 70000, 66000), ("h2o", 50000, 40000)])
+def test_units_longer_than_any_lds_list(sqa, policy, P, b):
+    """Prompt compression and the sorted view for units beyond 32768 and 65536 kept tokens (an uncompressed
+    cache of a long context; an H2O budget of 40000): only the tokens chosen by score are listed in LDS,
+    the window and the sinks are index arithmetic, and the sorted view ranks from memory."""
+    D, S = 64, 2
+    gen = torch.Generator(device="cpu").manual_seed(5)
+    K = torch.randn(1, 1, P, D, generator=gen).to(DEV); V = torch.randn(1, 1, P, D, generator=gen).to(DEV)
+    sc = torch.rand(1, 1, P, generator=gen).to(DEV)
+    cap = min(b, P + S)
+    caches = _mk_caches(sqa, [b], [cap], 1, 1, D, "f32")
+    sqa.prefill_compress(K, V, sc if policy == "h2o" else None, policy, 4, caches, 0)
+    c = O.prefill_compress(np64(K)[0, 0], np64(V)[0, 0], np64(sc)[0, 0], b, policy, 4)
+    got = export_state(caches, 0, 0, 0)
+    assert got["pos"].tolist() == c["pos"].tolist()
+    assert np.array_equal(got["K"], c["K"]) and np.array_equal(got["V"], c["V"])
+    if policy == "h2o":
+        assert np.array_equal(got["score"], c["score"])
+    ws = sqa.decode_workspace(caches, 1, policy)
+    for t in range(S):
+        q = torch.randn(1, 1, 1, D, generator=gen).to(DEV); k = torch.randn(1, 1, 1, D, generator=gen).to(DEV)
+        v = torch.randn(1, 1, 1, D, generator=gen).to(DEV)
+        out = torch.empty_like(q)
+        before = export_state(caches, 0, 0, 0)
+        sqa.decode_step(q, k, v, P + t, policy, 4, caches, out, ws)
+        want, c2 = O.decode_step(before, np64(q)[0, 0], np64(k)[0, 0, 0], np64(v)[0, 0, 0], P + t, b, policy, 4)
+        got = export_state(caches, 0, 0, 0)
+        assert got["pos"].tolist() == c2["pos"].tolist(), t
+        assert rel_err(np64(out)[0, 0], want) < 1e-5
+        if policy == "h2o":
+            check_step_scores(got, before, c2, False, t)
+    assert sqa.read_device_status(ws) == 0
+    n = len(c2["pos"])
+    assert sqa.kept_idx_sorted(caches, 0)[0, 0, :n].cpu().tolist() == c2["pos"].tolist()
+
+
 def test_decode_is_deterministic_and_per_layer_calls_agree(sqa):
     """Same inputs twice -> identical bytes; one call over all layers == one call per layer
     (with and without the device copy of the layer table)."""
