@@ -32,7 +32,8 @@ HBM_PEAK_GBS = 8000.0
 # `traffic` is null and `traffic_source` says that the profile is out of date.
 MEASURED_TRAFFIC = {
     ("llama2_7b", "squeeze", "h2o", "all_layers"): {
-        "bytes": 0.0, "source": "profiles/decode_importance_compress__llama2_7b.txt", "kernel_sha": "unset"},
+        "bytes": 820861.1 * 1024 * 2.0 + 19392.9 * 1024,
+        "source": "profiles/decode_importance_compress__llama2_7b.txt", "kernel_sha": "9055d28474bc92d5"},
 }
 
 
