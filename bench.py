@@ -215,10 +215,23 @@ def scores_only(args, wl):
     n_gen = min(wl.L, 4)                                  # distinct layers' inputs, cycled
     u_dirs, mask = W.unit_dirs(wl), W.hh_mask(wl, dev)
     QK = [(W.prompt_q(wl, l, dev, u_dirs), W.prompt_kv(wl, l, dev, u_dirs, mask)[0]) for l in range(n_gen)]
+    LSE = None
+    if args.lse:
+        # the ln-normalisers of the prompt's causal attention, as a fused attention kernel would hand them over
+        # (input preparation with torch, untimed; one head at a time to keep the logit matrix small)
+        LSE = []
+        tri = torch.ones(wl.P, wl.P, dtype=torch.bool, device=dev).tril()
+        for Q, K in QK:
+            out = torch.empty(wl.B, wl.Hq, wl.P, dtype=torch.float32, device=dev)
+            for b in range(wl.B):
+                for h in range(wl.Hq):
+                    s_ = (Q[b, h].float() @ K[b, h // wl.g].float().T) / (wl.D ** 0.5)
+                    out[b, h] = torch.logsumexp(s_.masked_fill(~tri, float("-inf")), dim=-1)
+            LSE.append(out)
 
     def one_pass():
         for l in range(wl.L):
-            sqa.prefill_scores(QK[l % n_gen][0], QK[l % n_gen][1])
+            sqa.prefill_scores(QK[l % n_gen][0], QK[l % n_gen][1], row_lse=None if LSE is None else LSE[l % n_gen])
 
     for _ in range(args.warmup):
         one_pass()
@@ -232,7 +245,7 @@ def scores_only(args, wl):
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
     call_s = e0.elapsed_time(e1) * 1e-3 / (args.steps * wl.L)
-    flops = 2 * wl.B * wl.Hq * (wl.P * (wl.P + 1) // 2) * 2 * wl.D
+    flops = (1 if args.lse else 2) * wl.B * wl.Hq * (wl.P * (wl.P + 1) // 2) * 2 * wl.D
     peak = 2500.0 if (wl.dtype == "bf16" and wl.D == 128) else 157.3     # matrix cores (bf16, D = 128) or fp32 vector
     out = {
         "metric": "H2O prompt-score producer (causal softmax column sums), TFLOP/s", "value": flops / call_s / 1e12,
@@ -240,7 +253,8 @@ def scores_only(args, wl):
         "ms_per_step": dt / args.steps * 1e3, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": wl.dtype, "data": "synthetic",
         "config": {"workload": wl.name, "layers": wl.L, "q_heads": wl.Hq, "kv_heads": wl.Hkv, "head_dim": wl.D,
-                   "batch": wl.B, "prompt": wl.P, "phases": "scores_only"},
+                   "batch": wl.B, "prompt": wl.P, "phases": "scores_only",
+                   "passes": "column sums from given row normalisers" if args.lse else "row statistics + column sums"},
         "roofline": {"bound": "mfma" if peak == 2500.0 else "alu",
                      "kernel": "score_rowstats + score_colsum (one call = both)", "achieved": flops / call_s / 1e12,
                      "peak": peak, "unit": "TFLOP/s", "frac": flops / call_s / 1e12 / peak, "traffic": None,
@@ -287,6 +301,8 @@ def main():
     ap.add_argument("--scores-only", action="store_true",
                     help="time only the H2O prompt-score producer (sqa_prefill_scores; set-up work of the pass, "
                          "matrix-core bound): a step = the scores of all layers of one prompt batch")
+    ap.add_argument("--lse", action="store_true",
+                    help="with --scores-only: the row normalisers are given (sqa_prefill_scores_lse), one pass instead of two")
     ap.add_argument("--progress", action="store_true", help="say on stderr when each phase of the run begins")
     ap.add_argument("--no-others", action="store_true",
                     help="skip the short decode-only legs on the other workloads (they run by default with the "

@@ -205,6 +205,18 @@ sqa_status sqa_prefill_scores_ex(const void* Q, const void* K, sqa_dtype dt,
                                  float* scores_out, void* workspace, size_t ws_bytes, void* stream,
                                  const sqa_batch_opts* opts);
 
+/* The same scores when the softmax normalisers of the prompt's attention are already known: a fused
+ * attention kernel that runs the prompt returns, per query row, the logarithm of its normaliser, and with it
+ * the column sums need one pass over the logits instead of two (half the work of sqa_prefill_scores).
+ *   row_lse : DEVICE float [B][Hq][P], row_lse[b][h][i] = ln sum_{j<=i} exp(Q_i.K_j / sqrt(D))
+ *             (natural logarithm, logits already scaled by 1/sqrt(D), causal); rows of padding are not read
+ * Everything else, the workspace included, as for sqa_prefill_scores_ex.  The values are trusted: a wrong
+ * normaliser gives wrong scores, not an error. */
+sqa_status sqa_prefill_scores_lse(const void* Q, const void* K, const float* row_lse, sqa_dtype dt,
+                                  int B, int Hq, int Hkv, int P, int D,
+                                  float* scores_out, void* workspace, size_t ws_bytes, void* stream,
+                                  const sqa_batch_opts* opts);
+
 /* ---- Algorithm 1 steps 12 + 16-17: compress the prompt's KV to the budget --
  * Per unit keeps min(P, layer->budget) tokens chosen by the policy
  * (Sec. 2.2 / Sec. 5.1):

@@ -15,6 +15,8 @@ What each function follows:
                                      worked example (300 / 1544)
   prefill_scores                     Sec. 5.1 "Heavy-Hitter (H2O)": accumulated
                                      attention score of each token over the prompt
+  prefill_row_lse /                  the same from given softmax normalisers (Sec. 2.1
+  prefill_scores_from_lse            attention equation: the denominator of softmax)
   select_keep                        Sec. 2.2 / Sec. 5.1: sliding window, StreamingLLM
                                      (n sink tokens + recent), H2O (accumulated score)
   prefill_compress / decode_step     Algorithm 1 steps 12-21 with Eq. 2-3 (append)
@@ -197,6 +199,38 @@ def prefill_scores(Q, K) -> np.ndarray:
             row = S[i, : i + 1]
             e = np.exp(row - row.max())
             score[: i + 1] += e / e.sum()
+    return score
+
+
+def prefill_row_lse(Q, K) -> np.ndarray:
+    """Q [g, P, D], K [P, D] -> lse [g, P]: the natural logarithm of each prompt query's softmax normaliser,
+    lse[h, i] = ln sum_{j<=i} exp(Q[h,i].K[j] / sqrt(D)) (what a fused attention kernel returns beside its
+    output)."""
+    Q = np.asarray(Q, dtype=np.float64)
+    K = np.asarray(K, dtype=np.float64)
+    g, P, D = Q.shape
+    out = np.empty((g, P), dtype=np.float64)
+    for h in range(g):
+        S = (Q[h] @ K.T) / math.sqrt(D)
+        for i in range(P):
+            row = S[i, : i + 1]
+            m = row.max()
+            out[h, i] = m + math.log(np.exp(row - m).sum())
+    return out
+
+
+def prefill_scores_from_lse(Q, K, lse) -> np.ndarray:
+    """The same accumulated attention as prefill_scores, computed from given row normalisers:
+    score[j] = sum over heads h and queries i >= j of exp(Q[h,i].K[j] / sqrt(D) - lse[h, i])."""
+    Q = np.asarray(Q, dtype=np.float64)
+    K = np.asarray(K, dtype=np.float64)
+    lse = np.asarray(lse, dtype=np.float64)
+    g, P, D = Q.shape
+    score = np.zeros(P, dtype=np.float64)
+    for h in range(g):
+        S = (Q[h] @ K.T) / math.sqrt(D)
+        for i in range(P):
+            score[: i + 1] += np.exp(S[i, : i + 1] - lse[h, i])
     return score
 
 

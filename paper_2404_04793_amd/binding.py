@@ -71,6 +71,8 @@ _lib.sqa_prefill_scores.restype = _i
 _lib.sqa_prefill_scores.argtypes = [_vp, _vp, _i, _i, _i, _i, _i, _i, _vp, _vp, _sz, _vp]
 _lib.sqa_prefill_scores_ex.restype = _i
 _lib.sqa_prefill_scores_ex.argtypes = [_vp, _vp, _i, _i, _i, _i, _i, _i, _vp, _vp, _sz, _vp, _BOp]
+_lib.sqa_prefill_scores_lse.restype = _i
+_lib.sqa_prefill_scores_lse.argtypes = [_vp, _vp, _vp, _i, _i, _i, _i, _i, _i, _vp, _vp, _sz, _vp, _BOp]
 _lib.sqa_prefill_compress.restype = _i
 _lib.sqa_prefill_compress.argtypes = [_vp, _vp, _i, _vp, _i, _i, _i, _i, _i, _i, _LCp, _vp]
 _lib.sqa_prefill_compress_layers.restype = _i
@@ -192,16 +194,24 @@ def allocate_budgets(cos: Sequence[float], total_budget: int, p: float) -> Tuple
 
 
 def prefill_scores(Q: torch.Tensor, K: torch.Tensor, scores_out: Optional[torch.Tensor] = None,
-                   opts: Optional[BatchOptsStruct] = None) -> torch.Tensor:
-    """Q [B, Hq, P, D], K [B, Hkv, P, D] -> scores [B, Hkv, P] fp32."""
+                   opts: Optional[BatchOptsStruct] = None, row_lse: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """Q [B, Hq, P, D], K [B, Hkv, P, D] -> scores [B, Hkv, P] fp32.  row_lse [B, Hq, P] fp32 (optional): the
+    natural-log softmax normalisers of the prompt's causal attention, if the caller has them
+    (sqa_prefill_scores_lse: one pass instead of two)."""
     B, Hq, P, D = Q.shape
     Hkv = K.shape[1]
     if scores_out is None:
         scores_out = torch.empty(B, Hkv, P, dtype=torch.float32, device=Q.device)
     need = _lib.sqa_prefill_scores_workspace_bytes(B, Hq, Hkv, P, D)
     ws = torch.empty(max(need, 8), dtype=torch.uint8, device=Q.device)
-    _check(_lib.sqa_prefill_scores_ex(_ptr(Q), _ptr(K), _dt(Q), B, Hq, Hkv, P, D, _ptr(scores_out), _ptr(ws),
-                                      ws.numel(), _stream(), _opts(opts)), "sqa_prefill_scores")
+    if row_lse is None:
+        _check(_lib.sqa_prefill_scores_ex(_ptr(Q), _ptr(K), _dt(Q), B, Hq, Hkv, P, D, _ptr(scores_out), _ptr(ws),
+                                          ws.numel(), _stream(), _opts(opts)), "sqa_prefill_scores")
+    else:
+        if row_lse.dtype != torch.float32 or not row_lse.is_contiguous() or tuple(row_lse.shape) != (B, Hq, P):
+            raise TypeError("row_lse is a contiguous fp32 tensor [B, Hq, P]")
+        _check(_lib.sqa_prefill_scores_lse(_ptr(Q), _ptr(K), _ptr(row_lse), _dt(Q), B, Hq, Hkv, P, D, _ptr(scores_out),
+                                           _ptr(ws), ws.numel(), _stream(), _opts(opts)), "sqa_prefill_scores_lse")
     return scores_out
 
 

@@ -476,13 +476,15 @@ __global__ __launch_bounds__(kScThreads) void score_colsum_mfma_kernel(
 
 template <int NB>
 static void launch_scores_mfma(const void* Q, const void* K, int B, int Hq, int Hkv, int P,
-                                     const int32_t* prompt_len, float* scores, float* cstat, hipStream_t st) {
+                                     const int32_t* prompt_len, float* scores, float* cstat, hipStream_t st,
+                                     bool have_stats) {
   const float scale_log2 = (float)(1.4426950408889634 / sqrt(128.0));
   const int tiles = (P + kMT * NB - 1) / (kMT * NB);
   const size_t lds1 = 2 * (size_t)kMTileBytes, lds2 = 2 * ((size_t)kMTileBytes + kMT * sizeof(float));
   auto grid = [&](int heads, int per) { return (unsigned)(((heads / per + 7) / 8) * 8 * per * tiles); };
-  score_rowstats_mfma_kernel<NB><<<grid(B * Hq, Hq / Hkv), kScThreads, lds1, st>>>(
-      static_cast<const bf16_t*>(Q), static_cast<const bf16_t*>(K), Hq, Hkv, P, scale_log2, tiles, B * Hq, cstat);
+  if (!have_stats)
+    score_rowstats_mfma_kernel<NB><<<grid(B * Hq, Hq / Hkv), kScThreads, lds1, st>>>(
+        static_cast<const bf16_t*>(Q), static_cast<const bf16_t*>(K), Hq, Hkv, P, scale_log2, tiles, B * Hq, cstat);
   score_colsum_mfma_kernel<NB><<<grid(B * Hkv, 1), kScThreads, lds2, st>>>(
       static_cast<const bf16_t*>(Q), static_cast<const bf16_t*>(K), Hq, Hkv, P, scale_log2, cstat, prompt_len, tiles,
       B * Hkv, scores);
@@ -490,15 +492,27 @@ static void launch_scores_mfma(const void* Q, const void* K, int B, int Hq, int 
 
 template <typename T, int D>
 static void launch_scores(const void* Q, const void* K, int B, int Hq, int Hkv, int P, const int32_t* prompt_len,
-                          float* scores, float2* stats, hipStream_t st) {
+                          float* scores, float2* stats, hipStream_t st, bool have_stats) {
   const float scale_log2 = (float)(1.4426950408889634 / sqrt((double)D));
   const int tiles = (P + kTile - 1) / kTile;
   auto grid = [&](int heads, int per) { return (unsigned)(((heads / per + 7) / 8) * 8 * per * tiles); };
-  score_rowstats_kernel<T, D><<<grid(B * Hq, Hq / Hkv), kScThreads, 0, st>>>(
-      static_cast<const T*>(Q), static_cast<const T*>(K), Hq, Hkv, P, scale_log2, tiles, B * Hq, stats);
+  if (!have_stats)
+    score_rowstats_kernel<T, D><<<grid(B * Hq, Hq / Hkv), kScThreads, 0, st>>>(
+        static_cast<const T*>(Q), static_cast<const T*>(K), Hq, Hkv, P, scale_log2, tiles, B * Hq, stats);
   score_colsum_kernel<T, D><<<grid(B * Hkv, 1), kScThreads, 0, st>>>(
       static_cast<const T*>(Q), static_cast<const T*>(K), Hq, Hkv, P, scale_log2, stats, prompt_len, tiles, B * Hkv,
       scores);
+}
+
+// Row statistics supplied by the caller: lse[row] = ln sum_j<=i exp(q_i.k_j / sqrt(D)), as a fused attention
+// kernel returns it, rewritten into what the column-sum kernels read (the exp2 domain: c = lse * log2 e;
+// the vector-ALU kernels take (reference, 1/sum) = (c, 1)).
+__global__ __launch_bounds__(256) void lse_to_rowstats_kernel(const float* __restrict__ lse, int64_t n, int pairs,
+                                                              float* __restrict__ out) {
+  for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (int64_t)gridDim.x * 256) {
+    const float c = lse[i] * 1.4426950408889634f;
+    if (pairs) { out[2 * i] = c; out[2 * i + 1] = 1.f; } else out[i] = c;
+  }
 }
 
 }  // namespace sqa
@@ -515,27 +529,51 @@ extern "C" sqa_status sqa_prefill_scores(const void* Q, const void* K, sqa_dtype
   return sqa_prefill_scores_ex(Q, K, dt, B, Hq, Hkv, P, D, scores_out, workspace, ws_bytes, stream, nullptr);
 }
 
-extern "C" sqa_status sqa_prefill_scores_ex(const void* Q, const void* K, sqa_dtype dt,
-                                            int B, int Hq, int Hkv, int P, int D,
-                                            float* scores_out, void* workspace, size_t ws_bytes, void* stream,
-                                            const sqa_batch_opts* opts) {
-  using namespace sqa;
+namespace sqa {
+static sqa_status prefill_scores_impl(const void* Q, const void* K, const float* row_lse, sqa_dtype dt,
+                                      int B, int Hq, int Hkv, int P, int D,
+                                      float* scores_out, void* workspace, size_t ws_bytes, void* stream,
+                                      const sqa_batch_opts* opts) {
   const int32_t* plen = opts ? opts->prompt_len : nullptr;
   if (!Q || !K || !scores_out || !workspace) return SQA_ERR_NULL;
   if (dt != SQA_F32 && dt != SQA_BF16) return SQA_ERR_DTYPE;
   if (B < 1 || Hq < 1 || Hkv < 1 || P < 1 || Hq % Hkv != 0 || (D != 64 && D != 128)) return SQA_ERR_SHAPE;
   if (((int64_t)B * Hq + 8) * ((P + 63) / 64) > INT32_MAX) return SQA_ERR_SHAPE;   // workgroups of one launch
   if (!aligned16(Q) || !aligned16(K) || (reinterpret_cast<uintptr_t>(workspace) & 7u)) return SQA_ERR_SHAPE;
+  if (row_lse && (reinterpret_cast<uintptr_t>(row_lse) & 3u)) return SQA_ERR_SHAPE;
   if (ws_bytes < sqa_prefill_scores_workspace_bytes(B, Hq, Hkv, P, D)) return SQA_ERR_CAPACITY;
   hipStream_t st = static_cast<hipStream_t>(stream);
   float2* stats = static_cast<float2*>(workspace);
+  const bool mfma = dt == SQA_BF16 && D == 128;
+  const bool have = row_lse != nullptr;
+  if (have) {
+    const int64_t n = (int64_t)B * Hq * P;
+    const unsigned blocks = (unsigned)(n / 256 + 1 < 4096 ? n / 256 + 1 : 4096);
+    lse_to_rowstats_kernel<<<blocks, 256, 0, st>>>(row_lse, n, mfma ? 0 : 1, static_cast<float*>(workspace));
+  }
   if (dt == SQA_F32) {
-    if (D == 64) launch_scores<float, 64>(Q, K, B, Hq, Hkv, P, plen, scores_out, stats, st);
-    else launch_scores<float, 128>(Q, K, B, Hq, Hkv, P, plen, scores_out, stats, st);
+    if (D == 64) launch_scores<float, 64>(Q, K, B, Hq, Hkv, P, plen, scores_out, stats, st, have);
+    else launch_scores<float, 128>(Q, K, B, Hq, Hkv, P, plen, scores_out, stats, st, have);
   } else {
-    if (D == 64) launch_scores<bf16_t, 64>(Q, K, B, Hq, Hkv, P, plen, scores_out, stats, st);
-    else launch_scores_mfma<kScBlocksPerWave>(Q, K, B, Hq, Hkv, P, plen, scores_out, reinterpret_cast<float*>(stats), st);
+    if (D == 64) launch_scores<bf16_t, 64>(Q, K, B, Hq, Hkv, P, plen, scores_out, stats, st, have);
+    else launch_scores_mfma<kScBlocksPerWave>(Q, K, B, Hq, Hkv, P, plen, scores_out, reinterpret_cast<float*>(stats), st, have);
   }
   SQA_HIP_CHECK(hipGetLastError());
   return SQA_OK;
+}
+}  // namespace sqa
+
+extern "C" sqa_status sqa_prefill_scores_ex(const void* Q, const void* K, sqa_dtype dt,
+                                            int B, int Hq, int Hkv, int P, int D,
+                                            float* scores_out, void* workspace, size_t ws_bytes, void* stream,
+                                            const sqa_batch_opts* opts) {
+  return sqa::prefill_scores_impl(Q, K, nullptr, dt, B, Hq, Hkv, P, D, scores_out, workspace, ws_bytes, stream, opts);
+}
+
+extern "C" sqa_status sqa_prefill_scores_lse(const void* Q, const void* K, const float* row_lse, sqa_dtype dt,
+                                             int B, int Hq, int Hkv, int P, int D,
+                                             float* scores_out, void* workspace, size_t ws_bytes, void* stream,
+                                             const sqa_batch_opts* opts) {
+  if (!row_lse) return SQA_ERR_NULL;
+  return sqa::prefill_scores_impl(Q, K, row_lse, dt, B, Hq, Hkv, P, D, scores_out, workspace, ws_bytes, stream, opts);
 }

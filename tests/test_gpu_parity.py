@@ -213,6 +213,35 @@ def test_prefill_compress_large_prompt_h2o_global_keys(sqa):
     assert caches.pos[0][0, 0, :b].cpu().tolist() == keep.tolist()
 
 
+@pytest.mark.parametrize("dtype,D,g,P", [("bf16", 128, 1, 300), ("bf16", 128, 4, 257), ("f32", 64, 2, 130), ("bf16", 64, 1, 90),
+                                         ("f32", 128, 1, 64)])
+def test_prefill_scores_from_given_row_normalisers(sqa, dtype, D, g, P):
+    """sqa_prefill_scores_lse: one pass over the logits with the caller's ln-normalisers (as a fused attention
+    kernel returns them) against the oracle fed the same numbers, and against the two-pass call."""
+    B, Hkv = 2, 2
+    wl = W.scaled(W.WORKLOADS["tiny"], L=1, Hq=Hkv * g, Hkv=Hkv, D=D, B=B, P=P, dtype=dtype)
+    K, _ = W.prompt_kv(wl, 0, DEV)
+    Q = W.prompt_q(wl, 0, DEV)
+    Qn, Kn = np64(Q), np64(K)
+    lse = np.stack([np.concatenate([O.prefill_row_lse(Qn[b, h * g:(h + 1) * g], Kn[b, h]) for h in range(Hkv)]) for b in range(B)])
+    lse32 = torch.from_numpy(lse.astype(np.float32)).to(DEV).contiguous()                 # [B, Hq, P]
+    got = sqa.prefill_scores(Q, K, row_lse=lse32).cpu().numpy().astype(np.float64)
+    two_pass = sqa.prefill_scores(Q, K).cpu().numpy().astype(np.float64)
+    for b in range(B):
+        for h in range(Hkv):
+            ref = O.prefill_scores_from_lse(Qn[b, h * g:(h + 1) * g], Kn[b, h], np64(lse32)[b, h * g:(h + 1) * g])
+            assert rel_err(got[b, h], ref) < TOL[dtype], (b, h)
+            # element by element: every column is a sum of positive terms, each known to ~1e-5 relative
+            assert np.max(np.abs(got[b, h] - ref) / ref) < 1e-4, (b, h)
+            assert rel_err(got[b, h], two_pass[b, h]) < 1e-4
+    # ragged: queries beyond a sequence's own prompt are not counted
+    plen = torch.tensor([P, max(P // 3, 1)], dtype=torch.int32, device=DEV)
+    rag = sqa.prefill_scores(Q, K, row_lse=lse32, opts=sqa.batch_opts(prompt_len=plen)).cpu().numpy().astype(np.float64)
+    n = int(plen[1])
+    ref = O.prefill_scores_from_lse(Qn[1, :g, :n], Kn[1, 0, :n], np64(lse32)[1, :g, :n])
+    assert rel_err(rag[1, 0, :n], ref) < TOL[dtype] and np.all(rag[1, 0, n:] == 0.0)
+
+
 # ---------------------------------------------------------------- decode step, teacher forced
 
 def _unit_inputs(wl, layer, u_dirs, mask):

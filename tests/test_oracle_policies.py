@@ -54,6 +54,32 @@ def test_scores_bruteforce_loops():
     assert np.allclose(O.prefill_scores(Q, K), want, atol=1e-13)
 
 
+def test_row_lse_closed_forms_and_scores_from_it():
+    """The softmax normalisers a fused attention kernel returns, and the column sums taken with them."""
+    r = _rng(4)
+    g, P, D = 2, 9, 4
+    Q, K = r.standard_normal((g, P, D)), r.standard_normal((P, D))
+    lse = O.prefill_row_lse(Q, K)
+    # brute force: ln of the sum of exponentials, row by row, with plain loops
+    for h in range(g):
+        for i in range(P):
+            logit = [sum(Q[h, i, d] * K[j, d] for d in range(D)) / math.sqrt(D) for j in range(i + 1)]
+            assert abs(lse[h, i] - math.log(sum(math.exp(x) for x in logit))) < 1e-13
+    # the first row attends to one key: its normaliser is that logit
+    assert np.allclose(lse[:, 0], (Q[:, 0] * K[0]).sum(-1) / math.sqrt(D), atol=1e-14)
+    # all keys equal: every logit of row i is the same s_i, so lse_i = s_i + ln(i + 1)
+    Ke = np.tile(r.standard_normal(D), (P, 1))
+    s_i = (Q @ Ke[0]) / math.sqrt(D)
+    assert np.allclose(O.prefill_row_lse(Q, Ke), s_i + np.log(np.arange(1, P + 1)), atol=1e-13)
+    # column sums taken with the true normalisers are the H2O prompt scores (pinned above on their own)
+    assert np.allclose(O.prefill_scores_from_lse(Q, K, lse), O.prefill_scores(Q, K), atol=1e-12)
+    # a normaliser that is too large by ln 2 halves every probability of that row: one row, by hand
+    lse2 = lse.copy(); lse2[1, 5] += math.log(2.0)
+    diff = O.prefill_scores(Q, K) - O.prefill_scores_from_lse(Q, K, lse2)
+    row = np.exp((Q[1, 5] @ K[:6].T) / math.sqrt(D) - lse[1, 5])
+    assert np.allclose(diff[:6], row / 2, atol=1e-13) and np.allclose(diff[6:], 0.0, atol=1e-15)
+
+
 # ---------------- selection ----------------
 
 @pytest.mark.parametrize("policy", O.POLICIES)
