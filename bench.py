@@ -276,6 +276,8 @@ def main():
     ap.add_argument("--ragged", action="store_true",
                     help="a ragged batch: prompt lengths from P down to about P/2, each sequence probed, budgeted and "
                          "positioned on its own (per-sequence budgets and positions from device arrays)")
+    ap.add_argument("--blocked", action="store_true",
+                    help="K and V in pools of 16-row blocks scattered by a block table (sqa_layer_cache.block_table)")
     ap.add_argument("--uniform", action="store_true", help="sequence-only baseline: same budget in every layer")
     ap.add_argument("--full-cache", action="store_true", help="no compression (budget = P + S)")
     ap.add_argument("--policy", default=None, choices=["h2o", "streaming", "sliding"],
@@ -343,7 +345,8 @@ def main():
 
     say("generating inputs for %s" % wl.name)
     sess = Session(wl, "cuda:0", uniform_budget=args.uniform, full_cache=args.full_cache,
-                   probe_tokens=args.probe_tokens, fused_probe=args.fused_probe, order=args.order, prompt_len=plen)
+                   probe_tokens=args.probe_tokens, fused_probe=args.fused_probe, order=args.order, prompt_len=plen,
+                   blocked=args.blocked)
     say("inputs ready")
 
     def do_decode():
@@ -433,7 +436,7 @@ def main():
                    "mode": mode, "launch": launch,
                    "phases": "decode_only" if args.decode_only else "whole_pass",
                    "probe_tokens": sess.probe_tokens, "fused_probe": args.fused_probe, "order": args.order,
-                   "ragged_prompt_lengths": plen},
+                   "ragged_prompt_lengths": plen, "kv_allocation": "blocked" if args.blocked else "dense"},
         "roofline": {"bound": "hbm", "kernel": "decode_unit_kernel", "achieved": achieved, "peak": HBM_PEAK_GBS,
                      "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
                      "traffic": traffic, "traffic_source": traffic_source,
@@ -455,7 +458,7 @@ def main():
                                                       args.full_cache or args.policy or args.decode_only or args.batch or
                                                       args.kv_heads or args.budget_pct or args.decode_steps or
                                                       args.fused_probe or args.probe_tokens) and
-                args.order == "evict_then_attend")
+                args.order == "evict_then_attend" and not args.blocked)
     if headline and not args.no_others:
         res["other_workloads"] = other_workloads(sess, say)
     print(json.dumps(res))

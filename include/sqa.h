@@ -61,6 +61,7 @@ typedef enum { SQA_SLIDING = 0, SQA_STREAMING = 1, SQA_H2O = 2 } sqa_policy;
 typedef enum { SQA_EVICT_THEN_ATTEND = 0, SQA_ATTEND_THEN_EVICT = 1 } sqa_order;
 
 enum { SQA_MAX_LAYERS = 128 };
+enum { SQA_BLOCK_SLOTS = 16, SQA_MAX_BLOCKS_PER_UNIT = 1024 };   /* blocked K/V allocation (sqa_layer_cache.block_table) */
 enum { SQA_ST_LEN = 0, SQA_ST_RING_HEAD = 1, SQA_ST_EVICT_HINT = 2, SQA_ST_WORDS = 4 };
 
 /*
@@ -104,8 +105,22 @@ typedef struct sqa_layer_cache {
                           unit_offset[u+1]) -- as many as ITS budget needs, which is what
                           saves memory when budgets differ per sequence; `capacity` is
                           then the largest of them                                  */
+  const int32_t* block_table; /* NULL: K and V rows lie where unit_offset / capacity say (above).  Otherwise
+                          DEVICE int32 [B*Hkv][blocks_per_unit]: blocked allocation.  K and V are then
+                          POOLS of blocks of SQA_BLOCK_SLOTS rows, [n_blocks][SQA_BLOCK_SLOTS][D], shared by
+                          all units of the layer, and the rows of unit u's slots 16i .. 16i+15 are block
+                          block_table[u][i] of both pools (only the entries that the unit's own budget
+                          needs are read, i < ceil(min(capacity, its budget) / SQA_BLOCK_SLOTS): a sequence
+                          with a small budget holds few blocks).  A serving loop hands a leaving sequence's blocks to the next one,
+                          whatever their budgets, without moving anything.  score_acc, pos and unit_state
+                          stay dense ([B][Hkv][capacity]: 8 bytes per slot); unit_offset must be NULL.
+                          An entry outside [0, n_blocks) is reported through the device status
+                          (SQA_ERR_SHAPE) and the unit is left untouched                        */
   int32_t capacity;    /* slots per unit; >= min(budget, longest length reached)   */
   int32_t budget;      /* b^(i): most tokens this layer keeps                      */
+  int32_t blocks_per_unit; /* row length of block_table; >= ceil(capacity / SQA_BLOCK_SLOTS), at most
+                          SQA_MAX_BLOCKS_PER_UNIT                                    */
+  int32_t n_blocks;    /* blocks in each of the K and V pools                      */
 } sqa_layer_cache;
 
 /*

@@ -26,6 +26,7 @@ ERR = {1: "NULL", 2: "SHAPE", 3: "DTYPE", 4: "POLICY", 5: "BUDGET", 6: "CAPACITY
 SQA_F32, SQA_BF16 = 0, 1
 POLICY = {"sliding": 0, "streaming": 1, "h2o": 2}
 SQA_MAX_LAYERS = 128
+SQA_BLOCK_SLOTS = 16
 
 
 class SqaError(RuntimeError):
@@ -39,8 +40,8 @@ class SqaError(RuntimeError):
 class LayerCacheStruct(C.Structure):
     """Mirror of sqa_layer_cache."""
     _fields_ = [("K", C.c_void_p), ("V", C.c_void_p), ("score_acc", C.c_void_p), ("pos", C.c_void_p),
-                ("unit_state", C.c_void_p), ("unit_offset", C.c_void_p),
-                ("capacity", C.c_int32), ("budget", C.c_int32)]
+                ("unit_state", C.c_void_p), ("unit_offset", C.c_void_p), ("block_table", C.c_void_p),
+                ("capacity", C.c_int32), ("budget", C.c_int32), ("blocks_per_unit", C.c_int32), ("n_blocks", C.c_int32)]
 
 
 class BatchOptsStruct(C.Structure):
@@ -221,19 +222,39 @@ class LayerCaches:
 
     def __init__(self, budgets: Sequence[int], capacities: Sequence[int], B: int, Hkv: int, D: int,
                  dtype: torch.dtype, device, with_scores: bool = True,
-                 unit_capacities: Optional[Sequence[Sequence[int]]] = None):
+                 unit_capacities: Optional[Sequence[Sequence[int]]] = None, blocked: bool = False,
+                 block_seed: Optional[int] = 0, spare_blocks: int = 3):
         """unit_capacities[l][b*Hkv + h] (optional): packed units -- every unit gets exactly that many
         slots (sqa_layer_cache.unit_offset); K, V, score, pos of a layer are then flat over the slots and
-        `capacities[l]` must be the largest of them.  Use unit(l, b, h) to address a unit either way."""
+        `capacities[l]` must be the largest of them.
+        blocked: K and V of a layer are pools of 16-row blocks and every unit owns the blocks its table row
+        names (sqa_layer_cache.block_table); the blocks are dealt out in a seeded random order (block_seed;
+        None = in order), with a few spare blocks in between, so that no unit is contiguous.
+        Use unit(l, b, h) / unit_kv_rows(l, b, h) to address a unit whatever the layout."""
         self.L, self.B, self.Hkv, self.D, self.dtype = len(budgets), B, Hkv, D, dtype
         self.budgets, self.capacities = list(budgets), list(capacities)
+        self.blocked = blocked
+        assert not (blocked and unit_capacities is not None)
         self.K, self.V, self.score, self.pos, self.state = [], [], [], [], []
         self.lens, self.head, self.hint = [], [], []        # views of the [B, Hkv, 4] unit_state records
         self.offsets: List[Optional[torch.Tensor]] = []
         self.offsets_host: List[Optional[List[int]]] = []
+        self.block_table: List[Optional[torch.Tensor]] = []
         self.table = (LayerCacheStruct * self.L)()
         for i, (b, cap) in enumerate(zip(budgets, capacities)):
-            if unit_capacities is None:
+            bpu = n_blocks = 0
+            tbl = None
+            if blocked:
+                bpu = (cap + SQA_BLOCK_SLOTS - 1) // SQA_BLOCK_SLOTS
+                n_blocks = B * Hkv * bpu + spare_blocks
+                if block_seed is None:
+                    perm = torch.arange(n_blocks)
+                else:
+                    perm = torch.randperm(n_blocks, generator=torch.Generator().manual_seed(block_seed + 7919 * i))
+                tbl = perm[:B * Hkv * bpu].to(torch.int32).view(B * Hkv, bpu).contiguous().to(device)
+                shape_rows, shape_flat = (n_blocks, SQA_BLOCK_SLOTS, D), (B, Hkv, cap)
+                self.offsets.append(None); self.offsets_host.append(None)
+            elif unit_capacities is None:
                 shape_rows, shape_flat = (B, Hkv, cap, D), (B, Hkv, cap)
                 self.offsets.append(None); self.offsets_host.append(None)
             else:
@@ -245,6 +266,7 @@ class LayerCaches:
                 shape_rows, shape_flat = (off[-1], D), (off[-1],)
                 self.offsets_host.append(off)
                 self.offsets.append(torch.tensor(off, dtype=torch.int64, device=device))
+            self.block_table.append(tbl)
             self.K.append(torch.zeros(*shape_rows, dtype=dtype, device=device))
             self.V.append(torch.zeros(*shape_rows, dtype=dtype, device=device))
             self.score.append(torch.zeros(*shape_flat, dtype=torch.float32, device=device) if with_scores else None)
@@ -258,20 +280,61 @@ class LayerCaches:
             t.score_acc = self.score[i].data_ptr() if with_scores else None
             t.pos, t.unit_state = self.pos[i].data_ptr(), self.state[i].data_ptr()
             t.unit_offset = None if self.offsets[i] is None else self.offsets[i].data_ptr()
-            t.capacity, t.budget = int(cap), int(b)
+            t.block_table = None if tbl is None else tbl.data_ptr()
+            t.capacity, t.budget, t.blocks_per_unit, t.n_blocks = int(cap), int(b), int(bpu), int(n_blocks)
         raw = bytes(memoryview(self.table))
         self.table_dev = torch.frombuffer(bytearray(raw), dtype=torch.uint8).to(device)
 
     def unit(self, layer: int, b: int, h: int):
-        """(K, V, score or None, pos) views of unit (b, h): [slots, D], [slots, D], [slots], [slots]."""
+        """(K, V, score or None, pos) views of unit (b, h): [slots, D], [slots, D], [slots], [slots].
+        With blocked allocation K and V are None here: address their rows through unit_kv_rows."""
         sc = self.score[layer]
+        if self.blocked:
+            return None, None, None if sc is None else sc[b, h], self.pos[layer][b, h]
         if self.offsets_host[layer] is None:
             return self.K[layer][b, h], self.V[layer][b, h], None if sc is None else sc[b, h], self.pos[layer][b, h]
         u = b * self.Hkv + h
         lo, hi = self.offsets_host[layer][u], self.offsets_host[layer][u + 1]
         return self.K[layer][lo:hi], self.V[layer][lo:hi], None if sc is None else sc[lo:hi], self.pos[layer][lo:hi]
 
+    def unit_kv_rows(self, layer: int, b: int, h: int):
+        """(K rows [all rows of the layer, D], V rows likewise, index of the row of each of the unit's slots):
+        slot s of the unit is row idx[s] of both, whatever the layout."""
+        Kf, Vf = self.K[layer].view(-1, self.D), self.V[layer].view(-1, self.D)
+        dev = Kf.device
+        u = b * self.Hkv + h
+        cap = self.capacities[layer]
+        if self.blocked:
+            s = torch.arange(cap, device=dev)
+            blk = self.block_table[layer][u].to(torch.int64)
+            return Kf, Vf, blk[s // SQA_BLOCK_SLOTS] * SQA_BLOCK_SLOTS + s % SQA_BLOCK_SLOTS
+        if self.offsets_host[layer] is None:
+            return Kf, Vf, torch.arange(u * cap, (u + 1) * cap, device=dev)
+        lo, hi = self.offsets_host[layer][u], self.offsets_host[layer][u + 1]
+        return Kf, Vf, torch.arange(lo, hi, device=dev)
+
+    def sequence_table(self, b: int):
+        """sqa_layer_cache records (host) that describe sequence b alone as a batch of one: the same memory,
+        the per-unit arrays entered at the sequence's first unit.  For calls that concern one sequence of a
+        running batch -- compressing the prompt of a sequence that takes a finished one's place."""
+        assert all(o is None for o in self.offsets_host), "not for packed units"
+        t = (LayerCacheStruct * self.L)()
+        es = self.K[0].element_size()
+        for i in range(self.L):
+            u0, cap, src = b * self.Hkv, self.capacities[i], self.table[i]
+            t[i].K = src.K if self.blocked else src.K + u0 * cap * self.D * es
+            t[i].V = src.V if self.blocked else src.V + u0 * cap * self.D * es
+            t[i].score_acc = None if not src.score_acc else src.score_acc + u0 * cap * 4
+            t[i].pos, t[i].unit_state = src.pos + u0 * cap * 4, src.unit_state + u0 * 16
+            t[i].unit_offset = None
+            t[i].block_table = None if not self.blocked else src.block_table + u0 * src.blocks_per_unit * 4
+            t[i].capacity, t[i].budget = src.capacity, src.budget
+            t[i].blocks_per_unit, t[i].n_blocks = src.blocks_per_unit, src.n_blocks
+        return t
+
     def total_slots(self, layer: int) -> int:
+        if self.blocked:
+            return self.K[layer].shape[0] * SQA_BLOCK_SLOTS
         off = self.offsets_host[layer]
         return self.B * self.Hkv * self.capacities[layer] if off is None else off[-1]
 
@@ -292,15 +355,18 @@ def prefill_compress(K: torch.Tensor, V: torch.Tensor, attn_scores: Optional[tor
 
 def prefill_compress_layers(K: Sequence[torch.Tensor], V: Sequence[torch.Tensor],
                             attn_scores: Optional[Sequence[Optional[torch.Tensor]]], policy: str, n_sink: int,
-                            caches: LayerCaches, layer0: int = 0, opts: Optional[BatchOptsStruct] = None) -> None:
-    """K[i], V[i] [B, Hkv, P, D] of layer layer0 + i -> caches' layers layer0 .. layer0 + len(K) - 1."""
+                            caches: LayerCaches, layer0: int = 0, opts: Optional[BatchOptsStruct] = None,
+                            table=None) -> None:
+    """K[i], V[i] [B, Hkv, P, D] of layer layer0 + i -> caches' layers layer0 .. layer0 + len(K) - 1.
+    table: sqa_layer_cache records to use instead of the caches' own (LayerCaches.sequence_table)."""
     n = len(K)
     B, Hkv, P, D = K[0].shape
     Ks = (_vp * n)(*[t.data_ptr() for t in K])
     Vs = (_vp * n)(*[t.data_ptr() for t in V])
     Ss = None if attn_scores is None or attn_scores[0] is None else (_vp * n)(*[t.data_ptr() for t in attn_scores])
+    layers = caches.struct_ptr(layer0) if table is None else C.cast(C.byref(table, layer0 * C.sizeof(LayerCacheStruct)), _LCp)
     _check(_lib.sqa_prefill_compress_layers_ex(Ks, Vs, _dt(K[0]), Ss, B, Hkv, P, D, POLICY[policy], n_sink,
-                                               caches.struct_ptr(layer0), n, _stream(), _opts(opts)),
+                                               layers, n, _stream(), _opts(opts)),
            "sqa_prefill_compress_layers")
 
 

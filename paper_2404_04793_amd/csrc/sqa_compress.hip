@@ -88,6 +88,20 @@ __global__ __launch_bounds__(kCmpThreads) void prefill_compress_kernel(
     }
   }
   int n_keep = P < b ? P : b;
+  // blocked allocation: the unit's K and V rows lie in the 16-row blocks its table row names
+  const int32_t* tbl = L.block_table ? L.block_table + (int64_t)u * L.blocks_per_unit : nullptr;
+  if (tbl) {
+    int bad = 0;
+    const int nblk = (min(n_keep, cap) + SQA_BLOCK_SLOTS - 1) / SQA_BLOCK_SLOTS;
+    for (int i = tid; i < nblk; i += kCmpThreads) bad |= (unsigned)tbl[i] >= (unsigned)L.n_blocks;
+    if (__syncthreads_or(bad)) {                           // a block number outside the pools: touch nothing
+      if (tid == 0) {
+        *reinterpret_cast<int4*>(L.unit_state + (int64_t)u * SQA_ST_WORDS) = make_int4(0, 0, -2, 0);
+        if (batch.status) *batch.status = SQA_ERR_SHAPE;
+      }
+      return;
+    }
+  }
   if (n_keep > cap) {                                      // packed units: this one was given too few slots
     if (tid == 0) {
       *reinterpret_cast<int4*>(L.unit_state + (int64_t)u * SQA_ST_WORDS) = make_int4(0, 0, -2, 0);
@@ -172,8 +186,10 @@ __global__ __launch_bounds__(kCmpThreads) void prefill_compress_kernel(
   // gather rows, scores, positions
   const T* Ku = K + (int64_t)u * P_pad * D;
   const T* Vu = V + (int64_t)u * P_pad * D;
-  char* Kc = reinterpret_cast<char*>(L.K) + uoff * ROWB;
-  char* Vc = reinterpret_cast<char*>(L.V) + uoff * ROWB;
+  char* Kc = reinterpret_cast<char*>(L.K) + (tbl ? 0 : uoff * ROWB);
+  char* Vc = reinterpret_cast<char*>(L.V) + (tbl ? 0 : uoff * ROWB);
+  // row of the unit's slot j within Kc / Vc
+  auto row_of = [&](int j) -> int64_t { return tbl ? (int64_t)tbl[j / SQA_BLOCK_SLOTS] * SQA_BLOCK_SLOTS + j % SQA_BLOCK_SLOTS : (int64_t)j; };
   const int grp = tid / LPR, c = tid % LPR;
   constexpr int GROUPS = kCmpThreads / LPR;
   for (int j = grp; j < n_keep; j += 2 * GROUPS) {
@@ -184,11 +200,13 @@ __global__ __launch_bounds__(kCmpThreads) void prefill_compress_kernel(
     const uint4 v1 = ld16(reinterpret_cast<const char*>(Vu) + (int64_t)src * ROWB + c * 16);
     const uint4 k2 = ld16(reinterpret_cast<const char*>(Ku) + (int64_t)src2 * ROWB + c * 16);
     const uint4 v2 = ld16(reinterpret_cast<const char*>(Vu) + (int64_t)src2 * ROWB + c * 16);
-    st16(Kc + (int64_t)j * ROWB + c * 16, k1);
-    st16(Vc + (int64_t)j * ROWB + c * 16, v1);
+    const int64_t d1 = row_of(j);
+    st16(Kc + d1 * ROWB + c * 16, k1);
+    st16(Vc + d1 * ROWB + c * 16, v1);
     if (j2 < n_keep) {
-      st16(Kc + (int64_t)j2 * ROWB + c * 16, k2);
-      st16(Vc + (int64_t)j2 * ROWB + c * 16, v2);
+      const int64_t d2 = row_of(j2);
+      st16(Kc + d2 * ROWB + c * 16, k2);
+      st16(Vc + d2 * ROWB + c * 16, v2);
     }
   }
   int32_t* posu = L.pos + uoff;
@@ -250,9 +268,15 @@ static sqa_status check_compress_layer(const void* K, const void* V, sqa_dtype k
   if (L.budget < min_budget) return SQA_ERR_BUDGET;
   const int n_keep = P < L.budget ? P : L.budget;
   if (L.capacity < n_keep) return SQA_ERR_CAPACITY;
+  if (L.block_table) {                                     // blocked allocation of K and V
+    if (L.unit_offset || L.n_blocks < 1 || L.blocks_per_unit > SQA_MAX_BLOCKS_PER_UNIT ||
+        (int64_t)L.blocks_per_unit * SQA_BLOCK_SLOTS < L.capacity)
+      return SQA_ERR_SHAPE;
+  }
   // the prompt tensors must not overlap the cache they are gathered into
   const size_t eb = kv_dt == SQA_F32 ? 4 : 2;
-  const size_t in_bytes = (size_t)B * Hkv * P * D * eb, c_bytes = (size_t)B * Hkv * L.capacity * D * eb;
+  const size_t in_bytes = (size_t)B * Hkv * P * D * eb;
+  const size_t c_bytes = (L.block_table ? (size_t)L.n_blocks * SQA_BLOCK_SLOTS : (size_t)B * Hkv * L.capacity) * D * eb;
   auto overlaps = [](const void* a, size_t na, const void* b, size_t nb) {
     const uintptr_t x = reinterpret_cast<uintptr_t>(a), y = reinterpret_cast<uintptr_t>(b);
     return x < y + nb && y < x + na;

@@ -70,6 +70,7 @@ struct DecodeArgs {
   int lds_chunk_w;                     // row length of a wave's LDS logit buffer in one-wave-per-unit layers
   int wide_tail;                       // the call has few workgroups: a long unit's tail keeps all four waves
   int lds_probs_w;                     // bytes of a wave's own LDS region for those probabilities in one-wave-per-unit layers
+  int tbl_off;                         // blocked allocation: where in the dynamic LDS the unit's block numbers are staged (bytes)
 };
 constexpr uint32_t kWpuBit = 0x80000000u, kLdsProbsBit = 0x40000000u;
 
@@ -217,6 +218,7 @@ typedef __bf16 bf16x4_t __attribute__((ext_vector_type(4)));
 typedef short v4s_t __attribute__((ext_vector_type(4)));
 typedef short v8s_t __attribute__((ext_vector_type(8)));
 typedef __attribute__((address_space(3))) v4s_t* lds_v4s_ptr;
+constexpr int kWpuMaxSlots = 256;                 // one wave per unit: for units of at most this many slots
 constexpr int kSoloMaxTokens = 512;               // calls with few workgroups: an unsplit unit's tail (scores, decision) is left
                                                   // to wave 0 alone up to this length
 constexpr int kLogitPad = 33;                     // a unit's H2O scratch region: G x (slots + kLogitPad) floats: the logit of the
@@ -227,7 +229,9 @@ constexpr int kStageBytesPerWave = 32 * kStageRow;   // one 32-token tile
 
 // MF = true (bf16, D = 128, grouped queries): the chunk is streamed in 32-token
 // tiles through LDS and q.K^T / P.V run on the matrix cores, see section 1M.
-template <typename T, int D, int G, bool H2O, bool MF>
+// PG = true: blocked allocation -- the unit's K and V rows lie in 16-row blocks of the layer's pools, named by
+// its row of the block table (staged in LDS at the start); everything else is addressed as before.
+template <typename T, int D, int G, bool H2O, bool MF, bool PG>
 __global__ __launch_bounds__(kDecThreads, MF ? kMfWavesPerSimd : 1) void decode_unit_kernel(const DecodeArgs a) {
   static_assert(!MF || (sizeof(T) == 2 && D == 128 && G <= 16), "matrix-core path: bf16, D = 128");
   constexpr int U = kUnroll;
@@ -295,8 +299,34 @@ __global__ __launch_bounds__(kDecThreads, MF ? kMfWavesPerSimd : 1) void decode_
   const int64_t qoff = (((int64_t)layer * a.B + bidx) * a.Hq + (int64_t)kvh * G) * D;
   const int64_t kvoff = (((int64_t)layer * a.B + bidx) * a.Hkv + kvh) * D;
   char* outp = reinterpret_cast<char*>(a.out) + qoff * (int64_t)sizeof(T);
-  const char* Kb = reinterpret_cast<const char*>(L.K) + uoff * ROWB;
-  const char* Vb = reinterpret_cast<const char*>(L.V) + uoff * ROWB;
+  const char* Kb = reinterpret_cast<const char*>(L.K) + (PG ? 0 : uoff * ROWB);
+  const char* Vb = reinterpret_cast<const char*>(L.V) + (PG ? 0 : uoff * ROWB);
+  // row of the unit's slot s within Kb / Vb (block numbers staged at the end of the dynamic LDS: the whole
+  // row of the table, or a wave's own 16 entries with one wave per unit)
+  int* const s_tbl = reinterpret_cast<int*>(reinterpret_cast<char*>(s_logit) + (PG ? a.tbl_off : 0));
+  const int tb = wpu ? wave * (kWpuMaxSlots / SQA_BLOCK_SLOTS) : 0;
+  auto row_of = [&](int s_) -> int64_t {
+    if constexpr (PG) return (int64_t)s_tbl[tb + (s_ >> 4)] * SQA_BLOCK_SLOTS + (s_ & (SQA_BLOCK_SLOTS - 1));
+    else return (int64_t)s_;
+  };
+  // slots this step can touch: with blocks, a unit needs table entries only for its own budget's slots
+  // (a sequence with a small budget holds few blocks; the rest of its table row is never read)
+  const int span = PG ? min(cap, max(min(budget, L.budget), 0)) : cap;
+  bool bad_tbl = false;
+  if constexpr (PG) {
+    // (every workgroup of the unit stages the whole row: the tail touches any slot; a block number outside
+    // the pools is replaced by 0 here, so that the early requests below stay inside them, and reported)
+    const int32_t* tbl = L.block_table + (int64_t)u * L.blocks_per_unit;
+    const int nblk = (span + SQA_BLOCK_SLOTS - 1) / SQA_BLOCK_SLOTS;
+    int bad = 0;
+    for (int i = tix; i < nblk; i += nthr0) {
+      const int e = tbl[i];
+      const bool oob = (unsigned)e >= (unsigned)L.n_blocks;
+      bad |= oob;
+      s_tbl[tb + i] = oob ? 0 : e;
+    }
+    bad_tbl = wpu ? __ballot(bad) != 0ull : __syncthreads_or(bad) != 0;
+  }
   const char* knew = reinterpret_cast<const char*>(a.k_new) + kvoff * (int64_t)sizeof(T);
   const char* vnew = reinterpret_cast<const char*>(a.v_new) + kvoff * (int64_t)sizeof(T);
   float* sc = H2O ? L.score_acc + uoff : nullptr;
@@ -326,9 +356,10 @@ __global__ __launch_bounds__(kDecThreads, MF ? kMfWavesPerSimd : 1) void decode_
 #pragma unroll
     for (int uu = 0; uu < U; ++uu) {
       slot[uu] = c0 + uu * rows_it + wv * RPI + r;
-      const int sl = max(min(slot[uu], cap - 1), 0);
-      kf[uu] = ld16_nt(Kpre + (int64_t)sl * ROWB + c * 16);
-      vf[uu] = ld16_nt(Vpre + (int64_t)sl * ROWB + c * 16);
+      const int sl = max(min(slot[uu], span - 1), 0);
+      const int64_t rw = (has_slots && span > 0) ? row_of(sl) : 0;
+      kf[uu] = ld16_nt(Kpre + rw * ROWB + c * 16);
+      vf[uu] = ld16_nt(Vpre + rw * ROWB + c * 16);
     }
   }
   const float sc_pre = (H2O && has_slots) ? sc[min(tix, cap - 1)] : 0.f;
@@ -339,10 +370,11 @@ __global__ __launch_bounds__(kDecThreads, MF ? kMfWavesPerSimd : 1) void decode_
   const bool bad_budget = budget < min_budget || budget > L.budget;
   const bool bad_state = !bad_budget && (len > budget || len > cap || len < 0 || head < 0 || (len == budget && head >= rec));
   const bool bad_cap = !bad_budget && !bad_state && len < budget && len >= cap;
-  if (bad_budget || bad_state || bad_cap) {       // same verdict in every chunk of the unit
+  if (bad_budget || bad_state || bad_cap || bad_tbl) {       // same verdict in every chunk of the unit
     if (chunk == 0) {
       for (int i = tix; i < G * D; i += nthr0) reinterpret_cast<T*>(outp)[i] = T{};
-      if (tix == 0) *a.status = bad_budget ? SQA_ERR_BUDGET : (bad_state ? SQA_ERR_STATE : SQA_ERR_CAPACITY);
+      if (tix == 0)
+        *a.status = bad_tbl ? SQA_ERR_SHAPE : (bad_budget ? SQA_ERR_BUDGET : (bad_state ? SQA_ERR_STATE : SQA_ERR_CAPACITY));
     }
     return;
   }
@@ -458,14 +490,17 @@ __global__ __launch_bounds__(kDecThreads, MF ? kMfWavesPerSimd : 1) void decode_
     auto request_k = [&](int base) {
 #pragma unroll
       for (int i = 0; i < 8; ++i) {
-        const char* g = Kb + ((uint32_t)min(base + 4 * i + r, rmax) * (uint32_t)ROWB + (uint32_t)(((c ^ r) ^ (4 * (i & 3))) * 16));
+        const char* g;
+        if constexpr (PG) g = Kb + row_of(min(base + 4 * i + r, rmax)) * ROWB + (((c ^ r) ^ (4 * (i & 3))) * 16);
+        else g = Kb + ((uint32_t)min(base + 4 * i + r, rmax) * (uint32_t)ROWB + (uint32_t)(((c ^ r) ^ (4 * (i & 3))) * 16));
         __builtin_amdgcn_global_load_lds((dec_gptr_t*)g, (dec_lptr_t*)(stage + 1024 * i), 16, 0, 0);
       }
     };
     auto request_v = [&](int base) {
 #pragma unroll
       for (int i = 0; i < 8; ++i)
-        vreg[i] = ld16_nt(Vb + ((uint32_t)min(base + 4 * i + r, rmax) * (uint32_t)ROWB + (uint32_t)(c * 16)));
+        if constexpr (PG) vreg[i] = ld16_nt(Vb + row_of(min(base + 4 * i + r, rmax)) * ROWB + c * 16);
+        else vreg[i] = ld16_nt(Vb + ((uint32_t)min(base + 4 * i + r, rmax) * (uint32_t)ROWB + (uint32_t)(c * 16)));
     };
     const int TSTEP = 32 * nw;                      // the unit's waves take its 32-token tiles in turn
     if (c0 + 32 * wv < c_end) { request_k(c0 + 32 * wv); request_v(c0 + 32 * wv); }
@@ -476,7 +511,7 @@ __global__ __launch_bounds__(kDecThreads, MF ? kMfWavesPerSimd : 1) void decode_
       const bool has_new = slot_new >= base && slot_new < base + 32;
       const bool has_moved = moved_to >= base && moved_to < base + 32;
       uint4 km = make_uint4(0, 0, 0, 0), vm = km;
-      if (has_moved) { km = ld16(Kb + (int64_t)slot_wr * ROWB + c * 16); vm = ld16(Vb + (int64_t)slot_wr * ROWB + c * 16); }
+      if (has_moved) { km = ld16(Kb + row_of(slot_wr) * ROWB + c * 16); vm = ld16(Vb + row_of(slot_wr) * ROWB + c * 16); }
       asm volatile("s_waitcnt vmcnt(0)" ::: "memory");          // this tile's K rows have landed in the stage
       if (has_moved) k_patch(moved_to - base, km);
       if (has_new) k_patch(slot_new - base, kn_pre);
@@ -594,8 +629,8 @@ __global__ __launch_bounds__(kDecThreads, MF ? kMfWavesPerSimd : 1) void decode_
     for (int uu = 0; uu < U; ++uu) {
       if (slot[uu] == slot_new) { kf[uu] = kn_pre; vf[uu] = vn_pre; }
       if (slot[uu] == moved_to) {
-        kf[uu] = ld16(Kb + (int64_t)slot_wr * ROWB + c * 16);
-        vf[uu] = ld16(Vb + (int64_t)slot_wr * ROWB + c * 16);
+        kf[uu] = ld16(Kb + row_of(slot_wr) * ROWB + c * 16);
+        vf[uu] = ld16(Vb + row_of(slot_wr) * ROWB + c * 16);
       }
     }
 
@@ -609,9 +644,9 @@ __global__ __launch_bounds__(kDecThreads, MF ? kMfWavesPerSimd : 1) void decode_
         for (int uu = 0; uu < U; ++uu) {
           slot[uu] = base + uu * rows_it + wv * RPI + r;
           const int sl = min(slot[uu], n - 1);
-          const char* kp = Kb + (int64_t)sl * ROWB;
-          const char* vp = Vb + (int64_t)sl * ROWB;
-          if (sl == moved_to) { kp = Kb + (int64_t)slot_wr * ROWB; vp = Vb + (int64_t)slot_wr * ROWB; }
+          const int64_t rw = row_of(sl == moved_to ? slot_wr : sl);
+          const char* kp = Kb + rw * ROWB;
+          const char* vp = Vb + rw * ROWB;
           if (sl == slot_new) { kp = knew; vp = vnew; }
           kf[uu] = ld16_nt(kp + c * 16);
           vf[uu] = ld16_nt(vp + c * 16);
@@ -844,13 +879,13 @@ __global__ __launch_bounds__(kDecThreads, MF ? kMfWavesPerSimd : 1) void decode_
     char* Kw = const_cast<char*>(Kb);
     char* Vw = const_cast<char*>(Vb);
     if (dst >= 0) {
-      const uint4 kk = ld16(Kw + (int64_t)slot_wr * ROWB + c * 16);
-      const uint4 vv = ld16(Vw + (int64_t)slot_wr * ROWB + c * 16);
-      st16(Kw + (int64_t)dst * ROWB + c * 16, kk);
-      st16(Vw + (int64_t)dst * ROWB + c * 16, vv);
+      const uint4 kk = ld16(Kw + row_of(slot_wr) * ROWB + c * 16);
+      const uint4 vv = ld16(Vw + row_of(slot_wr) * ROWB + c * 16);
+      st16(Kw + row_of(dst) * ROWB + c * 16, kk);
+      st16(Vw + row_of(dst) * ROWB + c * 16, vv);
     }
-    st16(Kw + (int64_t)slot_wr * ROWB + c * 16, kn_pre);
-    st16(Vw + (int64_t)slot_wr * ROWB + c * 16, vn_pre);
+    st16(Kw + row_of(slot_wr) * ROWB + c * 16, kn_pre);
+    st16(Vw + row_of(slot_wr) * ROWB + c * 16, vn_pre);
     if (c == 0) {
       int32_t* posw = L.pos + uoff;
       if (dst >= 0) posw[dst] = posw[slot_wr];
@@ -868,29 +903,33 @@ typedef void (*decode_fn)(const DecodeArgs);
 // heads the matrix-core variant is still slightly ahead (779 against 797 us per step on the Mistral-7B shape).
 constexpr int kMfmaMinGroup = 4;      // query heads per KV head from which the matrix-core variant is used
 template <typename T, int D, int G> constexpr bool use_mfma() { return sizeof(T) == 2 && D == 128 && G >= kMfmaMinGroup; }
-template <typename T, int D, bool H2O> decode_fn pick_g(int g) {
+template <typename T, int D, bool H2O, bool PG> decode_fn pick_g(int g) {
   switch (g) {
-    case 1: return decode_unit_kernel<T, D, 1, H2O, false>;
-    case 2: return decode_unit_kernel<T, D, 2, H2O, false>;
-    case 4: return decode_unit_kernel<T, D, 4, H2O, use_mfma<T, D, 4>()>;
-    case 8: return decode_unit_kernel<T, D, 8, H2O, use_mfma<T, D, 8>()>;
+    case 1: return decode_unit_kernel<T, D, 1, H2O, false, PG>;
+    case 2: return decode_unit_kernel<T, D, 2, H2O, false, PG>;
+    case 4: return decode_unit_kernel<T, D, 4, H2O, use_mfma<T, D, 4>(), PG>;
+    case 8: return decode_unit_kernel<T, D, 8, H2O, use_mfma<T, D, 8>(), PG>;
   }
   return nullptr;
 }
-template <typename T, bool H2O> decode_fn pick_d(int d, int g) {
-  if (d == 64) return pick_g<T, 64, H2O>(g);
-  if (d == 128) return pick_g<T, 128, H2O>(g);
+template <typename T, bool H2O, bool PG> decode_fn pick_d(int d, int g) {
+  if (d == 64) return pick_g<T, 64, H2O, PG>(g);
+  if (d == 128) return pick_g<T, 128, H2O, PG>(g);
   return nullptr;
 }
-static decode_fn pick(sqa_dtype dt, int d, int g, bool h2o) {
-  if (dt == SQA_F32) return h2o ? pick_d<float, true>(d, g) : pick_d<float, false>(d, g);
-  return h2o ? pick_d<bf16_t, true>(d, g) : pick_d<bf16_t, false>(d, g);
+template <typename T, bool H2O> decode_fn pick_p(int d, int g, bool paged) {
+  return paged ? pick_d<T, H2O, true>(d, g) : pick_d<T, H2O, false>(d, g);
+}
+static decode_fn pick(sqa_dtype dt, int d, int g, bool h2o, bool paged) {
+  if (dt == SQA_F32) return h2o ? pick_p<float, true>(d, g, paged) : pick_p<float, false>(d, g, paged);
+  return h2o ? pick_p<bf16_t, true>(d, g, paged) : pick_p<bf16_t, false>(d, g, paged);
 }
 
 constexpr size_t kStatusBytes = 256;
 
 // How one call is cut into work items and where its scratch lives.
 struct DecodePlan {
+  int tbl_entries;                                 // blocked allocation: block numbers a workgroup stages in LDS
   int lds_probs, lds_probs_w;                      // LDS bytes for the probabilities of a workgroup / of one wave's unit
   uint8_t probs_in_lds[SQA_MAX_LAYERS];            // matrix-core variant under H2O: this layer's units keep them in LDS
   int lds_chunk;                                   // longest unsplit unit shared by 4 waves (slots)
@@ -923,7 +962,6 @@ constexpr int kMaxUnsplit = 8192;
 // One wave per unit: for units of at most kWpuMaxSlots slots, in calls that have at least kWpuMinUnits
 // units (one wave walks a unit 16 rows at a time, so the call needs many units to keep the chip's wave
 // slots filled; the matrix-core variant walks it one 32-token tile at a time).
-constexpr int kWpuMaxSlots = 256;
 constexpr int64_t kWpuMinUnits = 4096;
 // scratch_probs: the H2O step's per-token, per-head values live in the workspace for every unit, split or
 // not (the matrix-core variant: they never need LDS, so nothing limits an unsplit unit's length).
@@ -931,6 +969,7 @@ static sqa_status plan_decode(const sqa_layer_cache* layers, int n_layers, int B
                               bool allow_wpu, bool scratch_probs, DecodePlan* p) {
   const int64_t units = (int64_t)B * Hkv;
   const int g = Hq / Hkv;
+  const bool paged = layers[0].block_table != nullptr;
   int64_t tokens = 0;
   for (int i = 0; i < n_layers; ++i) {
     if (layers[i].capacity < 1) return SQA_ERR_CAPACITY;
@@ -941,6 +980,15 @@ static sqa_status plan_decode(const sqa_layer_cache* layers, int n_layers, int B
   target = target < 256 ? 256 : target;
   if (h2o && !scratch_probs && target > kMaxUnsplit / g) target = kMaxUnsplit / g;
   uint64_t blocks = 0, n_units = 0, n_part = 0, n_logit = 0;
+  p->tbl_entries = 0;
+  if (paged) {
+    p->tbl_entries = kDecWaves * (kWpuMaxSlots / SQA_BLOCK_SLOTS);
+    for (int i = 0; i < n_layers; ++i) {
+      const int used = layers[i].budget < layers[i].capacity ? layers[i].budget : layers[i].capacity;
+      const int e = (used + SQA_BLOCK_SLOTS - 1) / SQA_BLOCK_SLOTS;
+      p->tbl_entries = e > p->tbl_entries ? e : p->tbl_entries;
+    }
+  }
   p->lds_probs = p->lds_probs_w = 0;
   p->lds_chunk = scratch_probs ? 0 : 64;           // (no LDS logits at all when they live in the workspace)
   p->lds_chunk_w = scratch_probs ? 0 : 64;
@@ -961,7 +1009,7 @@ static sqa_status plan_decode(const sqa_layer_cache* layers, int n_layers, int B
       // per unit: whole 32-token tiles of bf16 values per head, plus one fp32 reference per tile and head
       const int64_t ntile = ((int64_t)layers[i].capacity + 1 + 31) / 32;
       const int64_t need = (int64_t)g * ntile * (64 + 4);
-      if (need * (p->wpu[i] ? kDecWaves : 1) <= kLdsProbsMax) {
+      if (need * (p->wpu[i] ? kDecWaves : 1) <= kLdsProbsMax - p->tbl_entries * (int)sizeof(int)) {
         p->probs_in_lds[i] = 1;
         if (p->wpu[i] && need > p->lds_probs_w) p->lds_probs_w = (int)need;
         if (need * (p->wpu[i] ? kDecWaves : 1) > p->lds_probs) p->lds_probs = (int)(need * (p->wpu[i] ? kDecWaves : 1));
@@ -1083,7 +1131,8 @@ static sqa_status decode_prepare(const void* q, const void* k_new, const void* v
     return SQA_ERR_SHAPE;
   const int g = Hq / Hkv;
   const bool h2o = policy == SQA_H2O;
-  if (!pick(dt, D, g, h2o)) return SQA_ERR_SHAPE;
+  const bool paged = layers[0].block_table != nullptr;        // blocked K/V allocation: all layers of a call or none
+  if (!pick(dt, D, g, h2o, paged)) return SQA_ERR_SHAPE;
   if (!aligned16(q) || !aligned16(k_new) || !aligned16(v_new) || !aligned16(out)) return SQA_ERR_SHAPE;
   const int min_budget = h2o ? 2 : (policy == SQA_STREAMING ? n_sink + 1 : 1);
   for (int i = 0; i < n_layers; ++i) {
@@ -1093,6 +1142,10 @@ static sqa_status decode_prepare(const void* q, const void* k_new, const void* v
     if (!aligned16(c.K) || !aligned16(c.V) || !aligned16(c.unit_state)) return SQA_ERR_SHAPE;
     if (c.budget < min_budget) return SQA_ERR_BUDGET;
     if (c.capacity < 1) return SQA_ERR_CAPACITY;
+    if ((c.block_table != nullptr) != paged) return SQA_ERR_SHAPE;
+    if (paged && (c.unit_offset || c.n_blocks < 1 || c.blocks_per_unit > SQA_MAX_BLOCKS_PER_UNIT ||
+                  (int64_t)c.blocks_per_unit * SQA_BLOCK_SLOTS < (c.budget < c.capacity ? c.budget : c.capacity)))
+      return SQA_ERR_SHAPE;
   }
   const bool mfma = dt == SQA_BF16 && D == 128 && g >= kMfmaMinGroup;
   const sqa_status ps = plan_decode(layers, n_layers, B, Hq, Hkv, D, h2o, true, h2o && mfma, plan);
@@ -1100,9 +1153,11 @@ static sqa_status decode_prepare(const void* q, const void* k_new, const void* v
   const size_t lds_shared = (size_t)g * plan->lds_chunk, lds_waves = (size_t)kDecWaves * g * plan->lds_chunk_w;
   const size_t lds = (h2o ? (lds_shared > lds_waves ? lds_shared : lds_waves) * sizeof(float) : 0) +
                      (mfma ? (size_t)kDecWaves * kStageBytesPerWave : 0) + (size_t)plan->lds_probs;
-  if (lds > 160 * 1024) return SQA_ERR_CAPACITY;
-  *fn_out = pick(dt, D, g, h2o);
-  *lds_out = lds;
+  // (blocked allocation: the staged block numbers come last; decode_launch passes their offset)
+  const size_t lds_all = ((lds + 15) & ~(size_t)15) + (size_t)plan->tbl_entries * sizeof(int);
+  if (lds_all > 160 * 1024) return SQA_ERR_CAPACITY;
+  *fn_out = pick(dt, D, g, h2o, paged);
+  *lds_out = lds_all;
   return SQA_OK;
 }
 
@@ -1147,6 +1202,7 @@ static sqa_status decode_launch(decode_fn fn, const DecodePlan& plan, size_t lds
   }
   a.wide_tail = plan.blocks <= (uint64_t)kWideTailMaxBlocks ? 1 : 0;
   a.lds_probs_w = plan.lds_probs_w;
+  a.tbl_off = (int)(lds - (size_t)plan.tbl_entries * sizeof(int));
   if (layers_dev) {
     a.layers = layers_dev;
   } else {

@@ -15,14 +15,18 @@ from . import workloads as W
 class Session:
     def __init__(self, wl: W.Workload, device="cuda:0", keep_prompt_q: bool = False, uniform_budget: bool = False,
                  full_cache: bool = False, probe_tokens: Optional[int] = None, fused_probe: bool = False,
-                 order: str = "evict_then_attend", prompt_len: Optional[List[int]] = None):
+                 order: str = "evict_then_attend", prompt_len: Optional[List[int]] = None, blocked: bool = False):
         """probe_tokens: hidden-state rows per layer given to the probe (default: all B*P prompt tokens;
         a smaller number keeps the hidden states of the largest workloads within HBM).
         fused_probe: the probe runs inside the residual add that writes h_out (Sec. 3).
         prompt_len: a ragged batch -- sequence b's prompt is its first prompt_len[b] <= P tokens (the
         tensors stay padded to P); each sequence is then probed and budgeted on its own
-        (sqa_layer_importance_seq, one sqa_allocate_budgets per sequence) and decodes at its own position."""
+        (sqa_layer_importance_seq, one sqa_allocate_budgets per sequence) and decodes at its own position.
+        blocked: K and V of every layer live in pools of 16-row blocks that a block table deals to the units
+        (in a seeded random order, so that no unit is contiguous)."""
         self.wl, self.dev = wl, device
+        self.blocked = blocked
+        assert not (blocked and prompt_len is not None)
         self.fused_probe = fused_probe
         self.order = order
         self.opts = None if order == "evict_then_attend" else sqa.batch_opts(order=order)
@@ -105,7 +109,7 @@ class Session:
         if self.caches is None or budgets != self.budgets:
             caps = [min(b, wl.P + wl.S) for b in budgets]
             self.caches = sqa.LayerCaches(budgets, caps, wl.B, wl.Hkv, wl.D, wl.torch_dtype, self.dev,
-                                          wl.policy == "h2o")
+                                          wl.policy == "h2o", blocked=self.blocked)
             self.dec_ws = sqa.decode_workspace(self.caches, wl.Hq, wl.policy)
             self.dec_ws_layer = [sqa.decode_workspace(self.caches, wl.Hq, wl.policy, l, 1) for l in range(wl.L)]
         self.budgets, self.groups = budgets, groups

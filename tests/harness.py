@@ -52,9 +52,10 @@ def import_state(caches, layer: int, b: int, h: int, c: dict) -> None:
     n = len(c["pos"])
     dev = caches.K[layer].device
     dt = caches.dtype
-    K, V, score, pos = caches.unit(layer, b, h)
-    K[:n] = torch.from_numpy(c["K"]).to(dt).to(dev)
-    V[:n] = torch.from_numpy(c["V"]).to(dt).to(dev)
+    _, _, score, pos = caches.unit(layer, b, h)
+    Kf, Vf, rows = caches.unit_kv_rows(layer, b, h)
+    Kf[rows[:n]] = torch.from_numpy(c["K"]).to(dt).to(dev)
+    Vf[rows[:n]] = torch.from_numpy(c["V"]).to(dt).to(dev)
     pos[:n] = torch.from_numpy(c["pos"].astype(np.int32)).to(dev)
     pos[n:] = -1
     if score is not None:
@@ -64,13 +65,20 @@ def import_state(caches, layer: int, b: int, h: int, c: dict) -> None:
     caches.hint[layer][b, h] = -2          # scores were edited: no eviction decision carried over
 
 
+def unit_kv(caches, layer: int, b: int, h: int, n: int):
+    """The K and V rows of the unit's first n slots, in slot order, widened to fp64."""
+    Kf, Vf, rows = caches.unit_kv_rows(layer, b, h)
+    return np64(Kf[rows[:n]]), np64(Vf[rows[:n]])
+
+
 def export_state(caches, layer: int, b: int, h: int) -> dict:
     """Unit (b, h) of a layer as an oracle-style cache sorted by position."""
     n = int(caches.lens[layer][b, h].item())
-    K, V, score, pos_t = caches.unit(layer, b, h)
+    _, _, score, pos_t = caches.unit(layer, b, h)
+    K, V = unit_kv(caches, layer, b, h, n)
     pos = pos_t[:n].cpu().numpy().astype(np.int64)
     order = np.argsort(pos, kind="stable")
-    out = {"pos": pos[order], "K": np64(K[:n])[order], "V": np64(V[:n])[order]}
+    out = {"pos": pos[order], "K": K[order], "V": V[order]}
     if score is not None:
         out["score"] = np64(score[:n])[order]
     else:

@@ -26,15 +26,16 @@ def test_every_declared_symbol_is_exported():
 
 
 def test_struct_layout_matches_header():
-    assert C.sizeof(sqa.LayerCacheStruct) == 56
-    assert sqa.LayerCacheStruct.capacity.offset == 48 and sqa.LayerCacheStruct.budget.offset == 52
+    assert C.sizeof(sqa.LayerCacheStruct) == 72
+    assert sqa.LayerCacheStruct.block_table.offset == 48 and sqa.LayerCacheStruct.capacity.offset == 56
+    assert sqa.LayerCacheStruct.budget.offset == 60 and sqa.LayerCacheStruct.n_blocks.offset == 68
 
 
 def test_batch_opts_layout_and_validation():
     assert C.sizeof(sqa.BatchOptsStruct) == 40 and sqa.BatchOptsStruct.order.offset == 32
     lib = sqa._lib
     p = C.c_void_p(0x1000)
-    lc = sqa.LayerCacheStruct(0x1000, 0x2000, 0x3000, 0x4000, 0x5000, None, 8, 4)
+    lc = sqa.LayerCacheStruct(0x1000, 0x2000, 0x3000, 0x4000, 0x5000, None, None, 8, 4, 0, 0)
     bad = sqa.BatchOptsStruct(None, None, None, None, 2)
     base = [p, p, p, 1, 1, 1, 1, 128, -1, 2, 4, C.byref(lc), None, 1, p, C.c_void_p(0x1000), 1 << 20, None]
     assert lib.sqa_decode_step_ex(*base, C.byref(bad)) == 4                       # unknown order
@@ -108,7 +109,7 @@ def test_device_entry_points_validate_before_any_gpu_call():
     assert lib.sqa_residual_add_importance(p, p, C.c_void_p(0x1008), 0, 1, 4, 64, p, p, 1 << 20, None) == 2
     assert lib.sqa_residual_add_importance(p, p, p, 2, 1, 4, 64, p, p, 1 << 20, None) == 3
     assert lib.sqa_residual_add_importance(p, p, p, 1, 1, 4, 64, p, p, 0, None) == 6
-    lc = sqa.LayerCacheStruct(0x1000, 0x2000, 0x3000, 0x4000, 0x5000, None, 8, 4)
+    lc = sqa.LayerCacheStruct(0x1000, 0x2000, 0x3000, 0x4000, 0x5000, None, None, 8, 4, 0, 0)
     args = lambda **kw: [kw.get("K", p), p, kw.get("dt", 1), kw.get("sc", p), 1, 1, kw.get("P", 16), kw.get("D", 128),
                          kw.get("pol", 2), kw.get("ns", 4), C.byref(kw.get("lc", lc)), None]
     assert lib.sqa_prefill_compress(*args(K=None)) == 1
@@ -117,9 +118,9 @@ def test_device_entry_points_validate_before_any_gpu_call():
     assert lib.sqa_prefill_compress(*args(D=96)) == 2
     assert lib.sqa_prefill_compress(*args(sc=None)) == 1                     # H2O needs scores
     assert lib.sqa_prefill_compress(*args(pol=1, ns=4)) == 5                 # streaming: budget 4 < n_sink+1
-    small = sqa.LayerCacheStruct(0x1000, 0x2000, 0x3000, 0x4000, 0x5000, None, 3, 4)
+    small = sqa.LayerCacheStruct(0x1000, 0x2000, 0x3000, 0x4000, 0x5000, None, None, 3, 4, 0, 0)
     assert lib.sqa_prefill_compress(*args(lc=small)) == 6                    # capacity 3 < min(P, budget)
-    one = sqa.LayerCacheStruct(0x1000, 0x2000, 0x3000, 0x4000, 0x5000, None, 8, 1)
+    one = sqa.LayerCacheStruct(0x1000, 0x2000, 0x3000, 0x4000, 0x5000, None, None, 8, 1, 0, 0)
     assert lib.sqa_prefill_compress(*args(lc=one)) == 5                      # H2O: budget 1 < 2
 
     def dec(**kw):
@@ -137,7 +138,7 @@ def test_device_entry_points_validate_before_any_gpu_call():
     assert dec(lc=one) == 5
     assert lib.sqa_decode_workspace_bytes(C.byref(lc), 0, 1, 4, 4, 128, 2) == 0
     assert lib.sqa_decode_workspace_bytes(C.byref(lc), 1, 1, 4, 4, 128, 2) >= 256 + 64
-    big = sqa.LayerCacheStruct(0x1000, 0x2000, 0x3000, 0x4000, 0x5000, None, 5000, 5000)
+    big = sqa.LayerCacheStruct(0x1000, 0x2000, 0x3000, 0x4000, 0x5000, None, None, 5000, 5000, 0, 0)
     # 5000 slots -> several chunks per unit: partial records, logits and counters
     assert lib.sqa_decode_workspace_bytes(C.byref(big), 1, 2, 4, 4, 128, 2) > 2 * 4 * 5000 * 4
     assert lib.sqa_decode_workspace_init(None, 16, None) == 1
@@ -159,7 +160,7 @@ def test_header_is_plain_c(tmp_path):
                    'int main(void) {\n'
                    '  sqa_batch_opts o = {0}; sqa_layer_cache c = {0};\n'
                    '  (void)o; (void)c;\n'
-                   '  return sizeof(sqa_layer_cache) == 56 && SQA_ST_WORDS == 4 ? 0 : 1;\n'
+                   '  return sizeof(sqa_layer_cache) == 72 && SQA_ST_WORDS == 4 && SQA_BLOCK_SLOTS == 16 ? 0 : 1;\n'
                    '}\n')
     r = subprocess.run([gcc, "-std=c99", "-Wall", "-Wextra", "-pedantic", "-Werror", "-I", os.path.join(ROOT, "include"),
                         str(src), "-o", str(tmp_path / "use_header")], capture_output=True, text=True)

@@ -18,14 +18,15 @@ pytestmark = pytest.mark.gpu
 DEV = "cuda:0"
 
 
-def _run_fullsize(wl, sample_layers, units, check_steps, cos_layers, order="evict_then_attend", probe_tokens=None):
+def _run_fullsize(wl, sample_layers, units, check_steps, cos_layers, order="evict_then_attend", probe_tokens=None,
+                  blocked=False):
     """check_steps are teacher-forced (the oracle's state is written into the sampled units first, which also
     discards the eviction decision the unit carried: the kernel decides afresh); at every other step the test
     only READS the sampled units' state before the step and lets the oracle take the same step from it, so the
     state the GPU carries from step to step -- ring position, carried eviction decision -- is what is checked."""
     from paper_2404_04793_amd import binding as sqa
     from paper_2404_04793_amd.session import Session
-    sess = Session(wl, DEV, keep_prompt_q=True, order=order, probe_tokens=probe_tokens)
+    sess = Session(wl, DEV, keep_prompt_q=True, order=order, probe_tokens=probe_tokens, blocked=blocked)
     ae = order == "attend_then_evict"
     g, tol = wl.g, TOL[wl.dtype]
     h2o = wl.policy == "h2o"
@@ -67,7 +68,8 @@ def _run_fullsize(wl, sample_layers, units, check_steps, cos_layers, order="evic
     for l in range(wl.L):
         assert bool((sess.caches.lens[l] == min(wl.P, budgets[l])).all())
     # what the run holds resident is what the size model says for these budgets
-    assert sess.resident_kv_bytes() == W.squeezed_cache_bytes(wl, budgets)
+    if not blocked:                                        # (pools hold whole 16-row blocks and a few spare ones)
+        assert sess.resident_kv_bytes() == W.squeezed_cache_bytes(wl, budgets)
 
     # ---- decode: the GPU runs every step for the whole batch ---------------------
     qn = {k: np64(sess.q[:, k[0], k[1], k[2] * g:(k[2] + 1) * g]) for k in sample}
@@ -152,6 +154,14 @@ def test_llama2_7b_full_size():
     wl = W.WORKLOADS["llama2_7b"]
     _run_fullsize(wl, sample_layers=[0, 5, 17, 31], units=[(0, 0), (7, 31)],
                   check_steps={0, 1, 2, 100, 222, 223, 224, 225, 255}, cos_layers=[0, 16, 31])
+
+
+def test_llama2_7b_full_size_blocked_allocation():
+    """configs[1] with K and V in pools of 16-row blocks scattered by a block table (the layout a serving loop
+    with sequences joining and leaving would use), 64 decode steps."""
+    wl = W.scaled(W.WORKLOADS["llama2_7b"], S=64)
+    _run_fullsize(wl, sample_layers=[0, 5, 31], units=[(0, 0), (7, 31)], check_steps={0, 1, 40, 63}, cos_layers=[16],
+                  blocked=True)
 
 
 def test_llama2_7b_full_size_attend_then_evict():

@@ -148,15 +148,18 @@ def test_prefill_scores_wide_logit_range(sqa, case):
 
 # ---------------------------------------------------------------- prefill compress
 
-def _mk_caches(sqa, budgets, caps, B, Hkv, D, dtype, h2o=True):
-    return sqa.LayerCaches(budgets, caps, B, Hkv, D, torch.float32 if dtype == "f32" else torch.bfloat16, DEV, h2o)
+def _mk_caches(sqa, budgets, caps, B, Hkv, D, dtype, h2o=True, blocked=False):
+    """blocked: K and V as pools of 16-row blocks dealt to the units in a seeded random order (block table)."""
+    return sqa.LayerCaches(budgets, caps, B, Hkv, D, torch.float32 if dtype == "f32" else torch.bfloat16, DEV, h2o,
+                           blocked=blocked, block_seed=sum(budgets))
 
 
+@pytest.mark.parametrize("blocked", [False, True], ids=["dense", "blocked"])
 @pytest.mark.parametrize("policy", ["sliding", "streaming", "h2o"])
 @pytest.mark.parametrize("dtype,B,Hkv,P,D,b", [("f32", 1, 2, 256, 64, 51), ("bf16", 2, 3, 700, 128, 143),
                                                 ("bf16", 1, 1, 64, 128, 64), ("f32", 1, 1, 40, 128, 100),
                                                 ("bf16", 1, 2, 1031, 64, 6), ("bf16", 1, 1, 513, 128, 512)])
-def test_prefill_compress(sqa, policy, dtype, B, Hkv, P, D, b):
+def test_prefill_compress(sqa, policy, dtype, B, Hkv, P, D, b, blocked):
     wl = W.scaled(W.WORKLOADS["tiny"], L=1, Hq=Hkv, Hkv=Hkv, D=D, B=B, P=P, dtype=dtype)
     K, V = W.prompt_kv(wl, 0, DEV)
     r = np.random.default_rng(P + b)
@@ -164,7 +167,7 @@ def test_prefill_compress(sqa, policy, dtype, B, Hkv, P, D, b):
     sc[:, :, r.integers(0, P, size=P // 3)] = 0.25          # many exact ties
     sc[:, :, r.integers(0, P, size=5)] = 0.0
     scores = torch.from_numpy(sc).to(DEV)
-    caches = _mk_caches(sqa, [b], [max(min(P, b), 1) + 1], B, Hkv, D, dtype)
+    caches = _mk_caches(sqa, [b], [max(min(P, b), 1) + 1], B, Hkv, D, dtype, blocked=blocked)
     sqa.prefill_compress(K, V, scores if policy == "h2o" else None, policy, 4, caches, 0)
     kept = sqa.kept_idx_sorted(caches, 0).cpu().numpy()
     Kn, Vn = np64(K), np64(V)
@@ -315,7 +318,41 @@ def test_decode_teacher_forced_attend_then_evict(sqa, case):
     _teacher_forced(sqa, case, "attend_then_evict")
 
 
-def _teacher_forced(sqa, case, order):
+BLOCKED_CASES = CASES + _random_cases(8, seed=4711)
+
+
+@pytest.mark.parametrize("order", ["evict_then_attend", "attend_then_evict"])
+@pytest.mark.parametrize("case", BLOCKED_CASES, ids=[c[0] for c in BLOCKED_CASES])
+def test_decode_teacher_forced_blocked_allocation(sqa, case, order):
+    """The same steps with K and V in pools of 16-row blocks that a per-unit table row names, dealt out in a
+    seeded random order: no unit is contiguous, neighbouring blocks belong to other units."""
+    _teacher_forced(sqa, case, order, blocked=True)
+
+
+def test_decode_reports_a_block_number_outside_the_pools(sqa):
+    """A table entry beyond the pools: the unit is left untouched, its out rows zeroed, SQA_ERR_SHAPE in the
+    status word; the other unit of the call steps normally.  Prompt compression reports the same."""
+    B, Hkv, D, b, P = 2, 1, 64, 40, 50
+    caches = _mk_caches(sqa, [b], [b], B, Hkv, D, "f32", blocked=True)
+    K = torch.randn(B, Hkv, P, D, device=DEV); V = torch.randn(B, Hkv, P, D, device=DEV); sc = torch.rand(B, Hkv, P, device=DEV)
+    sqa.prefill_compress(K, V, sc, "h2o", 4, caches, 0)
+    good = caches.block_table[0].clone()
+    before = caches.pos[0][1, 0, :b].sort().values.cpu().tolist()      # (positions are dense: no look-up through the table)
+    caches.block_table[0][1, 1] = caches.K[0].shape[0]                 # one past the last block, in unit 1
+    q = torch.randn(1, B, Hkv, D, device=DEV); out = torch.full_like(q, 3.0)
+    ws = sqa.decode_workspace(caches, Hkv, "h2o")
+    sqa.decode_step(q, q, q, P, "h2o", 4, caches, out, ws)
+    assert sqa.read_device_status(ws) == 2                             # SQA_ERR_SHAPE
+    assert bool((out[0, 1] == 0).all()) and not bool((out[0, 0] == 0).any())
+    assert int(caches.lens[0][1, 0]) == b and caches.pos[0][1, 0, :b].sort().values.cpu().tolist() == before
+    assert int(caches.pos[0][0, 0].max()) == P                         # unit 0 took the step
+    status = torch.zeros(1, dtype=torch.int32, device=DEV)
+    sqa.prefill_compress_layers([K], [V], [sc], "h2o", 4, caches, opts=sqa.batch_opts(status=status))
+    assert int(status.item()) == 2 and caches.lens[0][:, 0].tolist() == [b, 0]
+    caches.block_table[0].copy_(good)
+
+
+def _teacher_forced(sqa, case, order, blocked=False):
     name, dtype, L, Hq, Hkv, D, B, P, S, policy, budgets = case
     ae = order == "attend_then_evict"
     opts = sqa.batch_opts(order=order) if ae else None
@@ -324,7 +361,7 @@ def _teacher_forced(sqa, case, order):
     u_dirs, mask = W.unit_dirs(wl), W.hh_mask(wl, DEV)
     inp = [_unit_inputs(wl, l, u_dirs, mask) for l in range(L)]
     caps = [min(b, P + S) for b in budgets]
-    caches = _mk_caches(sqa, budgets, caps, B, Hkv, D, dtype)
+    caches = _mk_caches(sqa, budgets, caps, B, Hkv, D, dtype, blocked=blocked)
     ws = sqa.decode_workspace(caches, Hq, policy)
     # oracle trajectories (fp32-rounded score storage between steps)
     state = {}

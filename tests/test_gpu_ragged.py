@@ -207,3 +207,101 @@ def test_decode_with_an_empty_packed_unit(sqa):
                 want, state[u] = O.decode_step(state[u], np64(q)[0, u], np64(k)[0, u, 0], np64(v)[0, u, 0], t, b, "h2o")
                 assert rel_err(np64(out)[0, u], want) < 1e-5
                 assert export_state(caches, 0, u, 0)["pos"].tolist() == state[u]["pos"].tolist()
+
+
+@pytest.mark.parametrize("blocked", [True, False], ids=["blocked", "dense"])
+def test_a_new_sequence_takes_a_finished_ones_place(sqa, blocked):
+    """A running batch of three sequences: after some decode steps sequence 1 is finished and another prompt,
+    with its own length and its own per-layer budgets, takes its batch slot.  With blocked allocation the
+    leaving sequence's K/V blocks go back to a free list (host side, here a Python list) and the newcomer is
+    dealt blocks from it -- other blocks than before, in another order, more of them in one layer and fewer in
+    the other -- without anything of the other sequences moving.  Only the newcomer's prompt is compressed
+    (a batch-of-one call on the same memory); every sequence is checked against the oracle throughout."""
+    dtype, L, Hkv, g, D, B, P, S = "bf16", 2, 2, 2, 128, 3, 120, 14
+    Hq = Hkv * g
+    policy, join_at = "h2o", 6
+    budget_a = [[50, 50, 50], [90, 90, 90]]                     # [L][B] before the change
+    new_len, new_budget = 77, [64, 40]                          # the newcomer: prompt length and budgets per layer
+    layer_budget = [64, 90]
+    wl = W.scaled(W.WORKLOADS["tiny"], L=L, Hq=Hq, Hkv=Hkv, D=D, B=B, P=P, S=S, dtype=dtype, policy=policy)
+    wl2 = W.scaled(wl, B=1, P=new_len)
+    caps = [min(b, P + S) for b in layer_budget]
+    caches = sqa.LayerCaches(layer_budget, caps, B, Hkv, D, torch.bfloat16, DEV, True, blocked=blocked, block_seed=3,
+                             spare_blocks=12)
+    u_dirs, mask = W.unit_dirs(wl), W.hh_mask(wl, DEV)
+    bseq = _i32(budget_a)
+    Ks, Vs, Ss, qkv = [], [], [], []
+    for l in range(L):
+        K, V = W.prompt_kv(wl, l, DEV, u_dirs, mask)
+        Ks.append(K); Vs.append(V)
+        Ss.append(sqa.prefill_scores(W.prompt_q(wl, l, DEV, u_dirs), K))
+        qkv.append(W.decode_qkv(wl, l, DEV, u_dirs, mask))
+    status = torch.zeros(1, dtype=torch.int32, device=DEV)
+    sqa.prefill_compress_layers(Ks, Vs, Ss, policy, 4, caches, opts=sqa.batch_opts(budget_seq=bseq, status=status))
+    assert int(status.item()) == 0
+    state = {(l, b, h): O.prefill_compress(np64(Ks[l])[b, h], np64(Vs[l])[b, h], np64(Ss[l])[b, h], budget_a[l][b], policy, 4)
+             for l in range(L) for b in range(B) for h in range(Hkv)}
+    q_all = torch.stack([x[0] for x in qkv], 1).contiguous()
+    k_all = torch.stack([x[1] for x in qkv], 1).contiguous()
+    v_all = torch.stack([x[2] for x in qkv], 1).contiguous()
+    qn, kn, vn = np64(q_all), np64(k_all), np64(v_all)
+    ws = sqa.decode_workspace(caches, Hq, policy)
+    budget_now = [row[:] for row in budget_a]
+    pos_now = [P, P, P]
+    out = torch.empty(L, B, Hq, D, dtype=torch.bfloat16, device=DEV)
+    worst = 0.0
+    for t in range(S):
+        if t == join_at:
+            # ---- sequence 1 leaves, the newcomer takes batch slot 1 ---------------------------------------
+            Kn, Vn, Sn = [], [], []
+            for l in range(L):
+                K2, V2 = W.prompt_kv(wl2, l, DEV, u_dirs, W.hh_mask(wl2, DEV))
+                K2 = (K2.float() + 0.5).to(torch.bfloat16)              # (other values than the first prompts')
+                Kn.append(K2); Vn.append(V2)
+                Sn.append(sqa.prefill_scores(W.prompt_q(wl2, l, DEV, u_dirs), K2))
+            if blocked:
+                for l in range(L):
+                    tbl = caches.block_table[l]
+                    bpu, n_blocks = tbl.shape[1], caches.K[l].shape[0]
+                    in_use = set(tbl.flatten().tolist())
+                    free = sorted(set(range(n_blocks)) - in_use)                      # the pool's spare blocks
+                    free += tbl[1 * Hkv:2 * Hkv].flatten().tolist()                   # + what sequence 1 gives back
+                    need = (min(new_budget[l], new_len + S) + sqa.SQA_BLOCK_SLOTS - 1) // sqa.SQA_BLOCK_SLOTS
+                    for h in range(Hkv):
+                        mine = [free.pop(0) for _ in range(need)]                     # spare blocks first: other blocks than before
+                        tbl[1 * Hkv + h, :need] = torch.tensor(mine, dtype=torch.int32, device=DEV)
+                        tbl[1 * Hkv + h, need:] = -1                                   # (never read: beyond the unit's budget)
+            budget_now = [[budget_a[l][0], new_budget[l], budget_a[l][2]] for l in range(L)]
+            bseq = _i32(budget_now)
+            one = sqa.batch_opts(budget_seq=_i32([[new_budget[l]] for l in range(L)]), status=status)
+            sqa.prefill_compress_layers(Kn, Vn, Sn, policy, 4, caches, opts=one, table=caches.sequence_table(1))
+            assert int(status.item()) == 0
+            for l in range(L):
+                for h in range(Hkv):
+                    state[l, 1, h] = O.prefill_compress(np64(Kn[l])[0, h], np64(Vn[l])[0, h], np64(Sn[l])[0, h],
+                                                        new_budget[l], policy, 4)
+                    got = export_state(caches, l, 1, h)
+                    assert got["pos"].tolist() == state[l, 1, h]["pos"].tolist()
+                    assert np.array_equal(got["K"], state[l, 1, h]["K"]) and np.array_equal(got["score"], state[l, 1, h]["score"])
+            pos_now[1] = new_len
+        # every step: the GPU runs on its own state, the oracle steps from the exported state
+        before = {key: export_state(caches, *key) for key in state}
+        sqa.decode_step(q_all[t], k_all[t], v_all[t], 0, policy, 4, caches, out, ws,
+                        opts=sqa.batch_opts(budget_seq=bseq, new_pos_seq=_i32(pos_now)))
+        assert sqa.read_device_status(ws) == 0
+        o = np64(out)
+        for (l, b, h) in state:
+            want, c2 = O.decode_step(before[l, b, h], qn[t, l, b, h * g:(h + 1) * g], kn[t, l, b, h], vn[t, l, b, h],
+                                     pos_now[b], budget_now[l][b], policy, 4)
+            got = export_state(caches, l, b, h)
+            assert got["pos"].tolist() == c2["pos"].tolist(), (t, l, b, h)
+            assert np.array_equal(got["K"], c2["K"]) and np.array_equal(got["V"], c2["V"]), (t, l, b, h)
+            check_step_scores(got, before[l, b, h], c2, False, (t, l, b, h))
+            worst = max(worst, rel_err(o[l, b, h * g:(h + 1) * g], want))
+        pos_now = [p + 1 for p in pos_now]
+    assert worst < TOL[dtype]
+    if blocked:                                                  # no block belongs to two units
+        for l in range(L):
+            used = [x for x in caches.block_table[l].flatten().tolist() if x >= 0]
+            need1 = (min(new_budget[l], new_len + S) + 15) // 16
+            assert len(set(used)) == len(used) and len(used) == 2 * Hkv * caches.block_table[l].shape[1] + Hkv * need1

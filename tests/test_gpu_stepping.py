@@ -18,7 +18,7 @@ import torch
 from oracle import sqa_oracle as O
 from paper_2404_04793_amd import workloads as W
 from tests.harness import (TOL, carried_victim_pos, check_step_scores, export_light, near_tie_swap, np64,
-                           oracle_next_victim_pos, oracle_view, rel_err, uses_matrix_cores)
+                           oracle_next_victim_pos, oracle_view, rel_err, unit_kv, uses_matrix_cores)
 
 pytestmark = pytest.mark.gpu
 DEV = "cuda:0"
@@ -61,10 +61,10 @@ def _step_and_compare(sqa, caches, ws, budgets, policy, order, dtype, D, g, P, S
                 seen["near_ties"] += 1
                 continue
             # the rows the GPU holds are the rows of those positions
-            K, V, _, pos_t = caches.unit(l, b, h)
             n = len(got["pos"])
+            Kn, Vn = unit_kv(caches, l, b, h, n)
             order_idx = np.argsort(got["raw_pos"], kind="stable")
-            assert np.array_equal(np64(K[:n])[order_idx], c2["K"]) and np.array_equal(np64(V[:n])[order_idx], c2["V"]), (t, key)
+            assert np.array_equal(Kn[order_idx], c2["K"]) and np.array_equal(Vn[order_idx], c2["V"]), (t, key)
             if policy == "h2o":
                 seen["worst_score"] = max(seen["worst_score"], check_step_scores(got, c, c2, mc, (t, key)))
                 if not ae and len(got["pos"]) == budgets[l]:
@@ -120,13 +120,21 @@ def test_stepping_matrix_core_units_at_the_lds_limit(sqa):
                     "evict_then_attend"), stride=37)
 
 
-def _run_case(sqa, case, stride=1):
+@pytest.mark.parametrize("case", [STEPPING[0], STEPPING[2], STEPPING[3], STEPPING[5], STEPPING[7]],
+                         ids=[STEPPING[i][0] for i in (0, 2, 3, 5, 7)])
+def test_stepping_with_blocked_allocation(sqa, case):
+    """K and V rows in 16-row blocks of shared pools, the blocks of a unit scattered by a block table."""
+    _run_case(sqa, case, blocked=True)
+
+
+def _run_case(sqa, case, stride=1, blocked=False):
     name, dtype, Hq, Hkv, D, B, P, S, policy, budgets, order = case
     L, g = len(budgets), Hq // Hkv
     wl = W.scaled(W.WORKLOADS["tiny"], L=L, Hq=Hq, Hkv=Hkv, D=D, B=B, P=P, S=S, dtype=dtype, policy=policy)
     u_dirs, mask = W.unit_dirs(wl), W.hh_mask(wl, DEV)
     Kp, Vp, qkv = [], [], []
-    caches = sqa.LayerCaches(budgets, [min(b, P + S) for b in budgets], B, Hkv, D, wl.torch_dtype, DEV, True)
+    caches = sqa.LayerCaches(budgets, [min(b, P + S) for b in budgets], B, Hkv, D, wl.torch_dtype, DEV, True,
+                             blocked=blocked, block_seed=P + S)
     for l in range(L):
         K, V = W.prompt_kv(wl, l, DEV, u_dirs, mask)
         Kp.append(K); Vp.append(V)
@@ -147,10 +155,12 @@ def _run_case(sqa, case, stride=1):
         assert seen["leaver_goes"] > 0 and seen["heavy_goes"] > 0, seen       # both outcomes of the carried decision
 
 
-@pytest.mark.parametrize("dtype,D,g,order", [("bf16", 128, 1, "evict_then_attend"), ("bf16", 128, 4, "evict_then_attend"),
-                                              ("bf16", 128, 8, "evict_then_attend"), ("bf16", 128, 8, "attend_then_evict"),
-                                              ("f32", 64, 1, "evict_then_attend")])
-def test_stepping_one_wave_per_unit(sqa, dtype, D, g, order):
+@pytest.mark.parametrize("dtype,D,g,order,blocked", [
+    ("bf16", 128, 1, "evict_then_attend", False), ("bf16", 128, 4, "evict_then_attend", False),
+    ("bf16", 128, 8, "evict_then_attend", False), ("bf16", 128, 8, "attend_then_evict", False),
+    ("f32", 64, 1, "evict_then_attend", False), ("bf16", 128, 1, "evict_then_attend", True),
+    ("bf16", 128, 8, "evict_then_attend", True)])
+def test_stepping_one_wave_per_unit(sqa, dtype, D, g, order, blocked):
     """4096 short units in one call: every wave owns a unit and carries its eviction decision alone.
     40 steps on the GPU's own state, a sample of units against the oracle every step."""
     policy, B, Hkv, L, P, S = "h2o", 64, 8, 8, 40, 40
@@ -162,7 +172,7 @@ def test_stepping_one_wave_per_unit(sqa, dtype, D, g, order):
     Ks, Vs = [mk(B, Hkv, P, D) for _ in range(L)], [mk(B, Hkv, P, D) for _ in range(L)]
     Ss = [torch.rand(B, Hkv, P, generator=gen).to(DEV) for _ in range(L)]
     q_all, k_all, v_all = mk(S, L, B, Hq, D), mk(S, L, B, Hkv, D), mk(S, L, B, Hkv, D)
-    caches = sqa.LayerCaches(budgets, [min(b, P + S) for b in budgets], B, Hkv, D, tdt, DEV, True)
+    caches = sqa.LayerCaches(budgets, [min(b, P + S) for b in budgets], B, Hkv, D, tdt, DEV, True, blocked=blocked)
     sqa.prefill_compress_layers(Ks, Vs, Ss, policy, 4, caches)
     ws = sqa.decode_workspace(caches, Hq, policy)
     units = [(l, b, h) for l in range(L) for b in range(B) for h in range(Hkv)]

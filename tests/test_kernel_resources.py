@@ -28,22 +28,24 @@ def _one(res, *parts):
 
 def test_no_decode_kernel_spills(res):
     dec = {k: v for k, v in res.items() if "decode_unit_kernel" in k}
-    assert len(dec) == 32                              # 2 types x 2 head sizes x 4 group sizes x with/without H2O
+    assert len(dec) == 64                              # 2 types x 2 head sizes x 4 group sizes x with/without H2O x dense/blocked
     for k, v in dec.items():
         assert v["ScratchSize"] == 0 and v["VGPRs Spill"] == 0, k
 
 
 def test_decode_kernels_keep_their_waves(res):
     # bf16, D = 128, one query head per KV head: the headline kernel (H2O) and its policy-free sibling
-    h2o = _one(res, "decode_unit_kernel", "bf16_tELi128ELi1ELb1ELb0")
-    assert h2o["VGPRs"] <= 88 and h2o["Occupancy"] >= 5
-    plain = _one(res, "decode_unit_kernel", "bf16_tELi128ELi1ELb0ELb0")
-    assert plain["VGPRs"] <= 80 and plain["Occupancy"] >= 6
-    # matrix-core variant: compiled for 3 waves per SIMD (its LDS stage buffers allow exactly that)
-    for g in (4, 8):
-        for h in (0, 1):
-            mf = _one(res, "decode_unit_kernel", "bf16_tELi128ELi%dELb%dELb1" % (g, h))
-            assert mf["VGPRs"] <= 168 and mf["Occupancy"] >= 3 and mf["AGPRs"] == 0, (g, h, mf)
+    # (the last template argument: 0 = dense, 1 = K and V in blocks named by a block table)
+    for pg in (0, 1):
+        h2o = _one(res, "decode_unit_kernel", "bf16_tELi128ELi1ELb1ELb0ELb%dE" % pg)
+        assert h2o["VGPRs"] <= 88 and h2o["Occupancy"] >= 5
+        plain = _one(res, "decode_unit_kernel", "bf16_tELi128ELi1ELb0ELb0ELb%dE" % pg)
+        assert plain["VGPRs"] <= 80 and plain["Occupancy"] >= 6
+        # matrix-core variant: compiled for 3 waves per SIMD (its LDS stage buffers allow exactly that)
+        for g in (4, 8):
+            for h in (0, 1):
+                mf = _one(res, "decode_unit_kernel", "bf16_tELi128ELi%dELb%dELb1ELb%dE" % (g, h, pg))
+                assert mf["VGPRs"] <= 168 and mf["Occupancy"] >= 3 and mf["AGPRs"] == 0, (g, h, pg, mf)
 
 
 def test_other_hot_kernels(res):

@@ -32,7 +32,7 @@ def _inputs(wl):
     return Kp, Vp, Qp, q, k, v
 
 
-def _run_both(sqa, wl, budgets, order="evict_then_attend"):
+def _run_both(sqa, wl, budgets, order="evict_then_attend", blocked=False):
     """Runs wl.S steps through both entry points on separate copies of the caches and compares every byte
     after every step."""
     Kp, Vp, Qp, q_all, k_all, v_all = _inputs(wl)
@@ -41,7 +41,7 @@ def _run_both(sqa, wl, budgets, order="evict_then_attend"):
     opts = None if order == "evict_then_attend" else sqa.batch_opts(order=order)
     both = []
     for _ in range(2):
-        c = sqa.LayerCaches(budgets, caps, wl.B, wl.Hkv, wl.D, wl.torch_dtype, DEV, True)
+        c = sqa.LayerCaches(budgets, caps, wl.B, wl.Hkv, wl.D, wl.torch_dtype, DEV, True, blocked=blocked)
         for l in range(wl.L):
             sc = sqa.prefill_scores(Qp[l], Kp[l]) if h2o else None
             sqa.prefill_compress(Kp[l], Vp[l], sc, wl.policy, wl.n_sink, c, l)
@@ -82,6 +82,8 @@ def test_static_scratch_entry_point_matches_the_workspace_one(sqa):
     _run_both(sqa, mf, [650, 90], order="attend_then_evict")
     sl = W.scaled(W.WORKLOADS["tiny"], L=2, Hq=8, Hkv=2, D=128, B=1, P=900, S=4, dtype="bf16", policy="sliding")
     _run_both(sqa, sl, [777, 30])
+    # and with K / V in blocks named by a block table
+    _run_both(sqa, big, [700, 41, 520], blocked=True)
 
 
 def test_static_scratch_entry_point_limits_and_status(sqa):
