@@ -31,9 +31,12 @@ HBM_PEAK_GBS = 8000.0
 # kernel's source is byte for byte the one that profile was taken with (sha256 prefix below); otherwise
 # `traffic` is null and `traffic_source` says that the profile is out of date.
 MEASURED_TRAFFIC = {
-    ("llama2_7b", "squeeze", "h2o", "all_layers"): {
-        "bytes": 820861.1 * 1024 * 2.0 + 19392.9 * 1024,
-        "source": "profiles/decode_importance_compress__llama2_7b.txt", "kernel_sha": "9055d28474bc92d5"},
+    ("llama2_7b", "squeeze", "h2o", "all_layers", "dense"): {
+        "bytes": 820875.9 * 1024 * 2.0 + 19393.2 * 1024,
+        "source": "profiles/decode_importance_compress__llama2_7b.txt", "kernel_sha": "7242ed387a54383d"},
+    ("llama2_7b", "squeeze", "h2o", "all_layers", "blocked"): {
+        "bytes": 821456.2 * 1024 * 2.0 + 19390.4 * 1024,
+        "source": "profiles/decode_importance_compress__llama2_7b.txt", "kernel_sha": "7242ed387a54383d"},
 }
 
 
@@ -424,7 +427,7 @@ def main():
     tokens = wl.B * wl.S * args.steps
     mode = "full_cache" if args.full_cache else ("uniform" if args.uniform else "squeeze")
     launch = ("per_layer" if args.per_layer else "all_layers") + ("_graph" if args.graph else "")
-    traffic, traffic_source = measured_traffic((wl.name, mode, wl.policy, launch))
+    traffic, traffic_source = measured_traffic((wl.name, mode, wl.policy, launch, "blocked" if args.blocked else "dense"))
     res = {
         "metric": "decode tokens/s + achieved HBM GB/s (attn+evict), 7B shape, 1 GPU",
         "value": tokens / dt, "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
