@@ -176,6 +176,13 @@ def other_workloads(main_sess, say):
     out = []
     say("llama2_7b, one launch per layer")
     out.append(decode_leg(main_sess, "llama2_7b", per_layer=True))
+    if not main_sess.blocked and not main_sess.ragged:
+        say("llama2_7b, K and V in 16-row blocks behind a shuffled block table")
+        main_sess.blocked, main_sess.caches = True, None
+        leg = decode_leg(main_sess, "llama2_7b blocked allocation")
+        leg["kv_allocation"] = "blocked"
+        out.append(leg)
+        main_sess.blocked, main_sess.caches = False, None
     for name, steps in (("mistral_7b", 64), ("llama2_70b", 32), ("stress_7b", 128)):
         say("%s, %d decode steps" % (name, steps))
         wl = W.scaled(W.WORKLOADS[name], S=steps)

@@ -118,8 +118,8 @@ typedef struct sqa_layer_cache {
                           (SQA_ERR_SHAPE) and the unit is left untouched                        */
   int32_t capacity;    /* slots per unit; >= min(budget, longest length reached)   */
   int32_t budget;      /* b^(i): most tokens this layer keeps                      */
-  int32_t blocks_per_unit; /* row length of block_table; >= ceil(capacity / SQA_BLOCK_SLOTS), at most
-                          SQA_MAX_BLOCKS_PER_UNIT                                    */
+  int32_t blocks_per_unit; /* row length of block_table; >= ceil(min(capacity, budget) / SQA_BLOCK_SLOTS),
+                          at most SQA_MAX_BLOCKS_PER_UNIT (else SQA_ERR_SHAPE)        */
   int32_t n_blocks;    /* blocks in each of the K and V pools                      */
 } sqa_layer_cache;
 
@@ -246,7 +246,10 @@ sqa_status sqa_prefill_scores_lse(const void* Q, const void* K, const float* row
  *   attn_scores : DEVICE float [B][Hkv][P], values >= 0, required for SQA_H2O
  *   layer       : HOST struct with DEVICE pointers; budget and capacity preset,
  *                 capacity >= min(P, budget)
- * SQA_ERR_BUDGET if budget < 1 (sliding), < n_sink+1 (streaming), < 2 (H2O). */
+ * SQA_ERR_BUDGET if budget < 1 (sliding), < n_sink+1 (streaming), < 2 (H2O).
+ * SQA_ERR_CAPACITY if capacity < min(P, budget), or for SQA_H2O with budget > 65536 and P > budget (the
+ * floor(budget/2) positions chosen by score are listed in LDS; prompts and the other policies' budgets
+ * have no such limit). */
 sqa_status sqa_prefill_compress(const void* K, const void* V, sqa_dtype kv_dt, const float* attn_scores,
                                 int B, int Hkv, int P, int D, sqa_policy policy, int n_sink,
                                 const sqa_layer_cache* layer, void* stream);

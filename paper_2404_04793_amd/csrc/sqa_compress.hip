@@ -270,7 +270,7 @@ static sqa_status check_compress_layer(const void* K, const void* V, sqa_dtype k
   if (L.capacity < n_keep) return SQA_ERR_CAPACITY;
   if (L.block_table) {                                     // blocked allocation of K and V
     if (L.unit_offset || L.n_blocks < 1 || L.blocks_per_unit > SQA_MAX_BLOCKS_PER_UNIT ||
-        (int64_t)L.blocks_per_unit * SQA_BLOCK_SLOTS < L.capacity)
+        (int64_t)L.blocks_per_unit * SQA_BLOCK_SLOTS < (L.budget < L.capacity ? L.budget : L.capacity))
       return SQA_ERR_SHAPE;
   }
   // the prompt tensors must not overlap the cache they are gathered into

@@ -136,6 +136,17 @@ def test_device_entry_points_validate_before_any_gpu_call():
     assert dec(nl=1000) == 2
     assert dec(ws=8) == 6
     assert dec(lc=one) == 5
+    # blocked allocation: the table row must cover the unit's slots, packed units and blocks do not mix,
+    # the pools hold at least one block
+    tblp, offp = 0x6000, 0x7000
+    blk = lambda **kw: sqa.LayerCacheStruct(0x1000, 0x2000, 0x3000, 0x4000, 0x5000, kw.get("off"), tblp,
+                                            kw.get("cap", 40), kw.get("b", 40), kw.get("bpu", 3), kw.get("nb", 8))
+    for call in (lambda c: dec(lc=c), lambda c: lib.sqa_prefill_compress(*args(lc=c, P=64))):
+        assert call(blk(bpu=2)) == 2               # 2 x 16 rows < 40 slots
+        assert call(blk(off=offp)) == 2
+        assert call(blk(nb=0)) == 2
+        assert call(blk(bpu=1025, cap=20000, b=20000)) == 2
+    assert lib.sqa_prefill_compress(*args(lc=blk(cap=70000, b=70000, bpu=1024, nb=8), P=80000)) in (2, 6)
     assert lib.sqa_decode_workspace_bytes(C.byref(lc), 0, 1, 4, 4, 128, 2) == 0
     assert lib.sqa_decode_workspace_bytes(C.byref(lc), 1, 1, 4, 4, 128, 2) >= 256 + 64
     big = sqa.LayerCacheStruct(0x1000, 0x2000, 0x3000, 0x4000, 0x5000, None, None, 5000, 5000, 0, 0)
