@@ -363,6 +363,24 @@ sqa_status sqa_read_device_status(const void* workspace, void* stream, int32_t* 
  *         laid out like pos: unit u's entries start at out[unit_offset[u]] */
 sqa_status sqa_kept_idx_sorted(const sqa_layer_cache* layer, int B, int Hkv, int32_t* out, void* stream);
 
+/* ---- free list for blocked K/V allocation (host only) ----------------------
+ * Book-keeping for the block numbers of ONE pool pair (the K and V pools of one layer share numbers, see
+ * sqa_layer_cache.block_table): which of 0 .. n_blocks-1 are free.  The paper fixes a layer's budget once the
+ * prompt is seen (Algorithm 1 step 11), so a unit takes ceil(min(capacity, budget) / SQA_BLOCK_SLOTS) blocks
+ * when its sequence joins and gives them all back when it leaves; nothing is taken in between.  The pool
+ * knows nothing of device memory: the caller writes the numbers it takes into its DEVICE block table.
+ * HOST memory of the pool object belongs to the library (create / destroy); calls on one pool are serialised
+ * by a mutex inside it.
+ *   take: all n or nothing (SQA_ERR_CAPACITY, ids_out untouched); the lowest-numbered blocks that were
+ *         never used go first, blocks given back are reused last-in first-out
+ *   give: every id must be in range, in use and named once (else SQA_ERR_SHAPE and nothing changes)    */
+typedef struct sqa_block_pool sqa_block_pool;
+sqa_block_pool* sqa_block_pool_create(int32_t n_blocks);          /* NULL if n_blocks < 1 or out of memory */
+void sqa_block_pool_destroy(sqa_block_pool* pool);               /* NULL is allowed                       */
+int32_t sqa_block_pool_free_count(const sqa_block_pool* pool);   /* -1 for NULL                           */
+sqa_status sqa_block_pool_take(sqa_block_pool* pool, int32_t n, int32_t* ids_out /* HOST [n] */);
+sqa_status sqa_block_pool_give(sqa_block_pool* pool, const int32_t* ids /* HOST [n] */, int32_t n);
+
 #ifdef __cplusplus
 }
 #endif

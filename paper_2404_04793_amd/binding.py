@@ -101,6 +101,14 @@ _lib.sqa_read_device_status.restype = _i
 _lib.sqa_read_device_status.argtypes = [_vp, _vp, C.POINTER(C.c_int32)]
 _lib.sqa_kept_idx_sorted.restype = _i
 _lib.sqa_kept_idx_sorted.argtypes = [_LCp, _i, _i, _vp, _vp]
+_lib.sqa_block_pool_create.argtypes = [C.c_int32]
+_lib.sqa_block_pool_create.restype = _vp
+_lib.sqa_block_pool_destroy.argtypes = [_vp]
+_lib.sqa_block_pool_destroy.restype = None
+_lib.sqa_block_pool_free_count.argtypes = [_vp]
+_lib.sqa_block_pool_free_count.restype = C.c_int32
+_lib.sqa_block_pool_take.argtypes = [_vp, C.c_int32, C.POINTER(C.c_int32)]
+_lib.sqa_block_pool_give.argtypes = [_vp, C.POINTER(C.c_int32), C.c_int32]
 
 
 def _dt(t: torch.Tensor) -> int:
@@ -214,6 +222,35 @@ def prefill_scores(Q: torch.Tensor, K: torch.Tensor, scores_out: Optional[torch.
         _check(_lib.sqa_prefill_scores_lse(_ptr(Q), _ptr(K), _ptr(row_lse), _dt(Q), B, Hq, Hkv, P, D, _ptr(scores_out),
                                            _ptr(ws), ws.numel(), _stream(), _opts(opts)), "sqa_prefill_scores_lse")
     return scores_out
+
+
+class BlockPool:
+    """sqa_block_pool: the free list of one layer's K/V block numbers (host book-keeping)."""
+
+    def __init__(self, n_blocks: int):
+        self._p = _lib.sqa_block_pool_create(n_blocks)
+        if not self._p:
+            raise ValueError("sqa_block_pool_create(%d) failed" % n_blocks)
+
+    def free_count(self) -> int:
+        return int(_lib.sqa_block_pool_free_count(self._p))
+
+    def take(self, n: int) -> List[int]:
+        ids = (C.c_int32 * max(n, 1))()
+        _check(_lib.sqa_block_pool_take(self._p, n, ids), "sqa_block_pool_take")
+        return list(ids[:n])
+
+    def give(self, ids: Sequence[int]) -> None:
+        arr = (C.c_int32 * max(len(ids), 1))(*ids)
+        _check(_lib.sqa_block_pool_give(self._p, arr, len(ids)), "sqa_block_pool_give")
+
+    def close(self) -> None:
+        if self._p:
+            _lib.sqa_block_pool_destroy(self._p)
+            self._p = None
+
+    def __del__(self):
+        self.close()
 
 
 class LayerCaches:

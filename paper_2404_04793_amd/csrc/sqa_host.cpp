@@ -6,6 +6,8 @@
 #include <algorithm>
 #include <cmath>
 #include <cstdint>
+#include <mutex>
+#include <new>
 #include <vector>
 #include "sqa.h"
 
@@ -105,5 +107,75 @@ extern "C" sqa_status sqa_allocate_budgets(const float* cos, int n_layers, int64
   }
   for (int i = 0; i < L; ++i) budget_out[i] = budget[i];
   if (group_out) for (int i = 0; i < L; ++i) group_out[i] = group[i];
+  return SQA_OK;
+}
+
+// ---- free list of block numbers for blocked K/V allocation (host book-keeping only) ----
+struct sqa_block_pool {
+  std::mutex mu;
+  std::vector<int32_t> returned;     // blocks given back, reused last-in first-out
+  std::vector<uint8_t> in_use;       // [n_blocks]
+  int32_t next_fresh = 0;            // blocks next_fresh .. n_blocks-1 were never taken
+  int32_t n_blocks = 0;
+};
+
+extern "C" sqa_block_pool* sqa_block_pool_create(int32_t n_blocks) {
+  if (n_blocks < 1) return nullptr;
+  sqa_block_pool* p = new (std::nothrow) sqa_block_pool;
+  if (!p) return nullptr;
+  try {
+    p->in_use.assign(static_cast<size_t>(n_blocks), 0);
+    p->returned.reserve(static_cast<size_t>(n_blocks));
+  } catch (const std::bad_alloc&) {
+    delete p;
+    return nullptr;
+  }
+  p->n_blocks = n_blocks;
+  return p;
+}
+
+extern "C" void sqa_block_pool_destroy(sqa_block_pool* pool) { delete pool; }
+
+extern "C" int32_t sqa_block_pool_free_count(const sqa_block_pool* pool) {
+  if (!pool) return -1;
+  std::lock_guard<std::mutex> lock(const_cast<sqa_block_pool*>(pool)->mu);
+  return static_cast<int32_t>(pool->returned.size()) + (pool->n_blocks - pool->next_fresh);
+}
+
+extern "C" sqa_status sqa_block_pool_take(sqa_block_pool* pool, int32_t n, int32_t* ids_out) {
+  if (!pool || (n > 0 && !ids_out)) return SQA_ERR_NULL;
+  if (n < 0) return SQA_ERR_SHAPE;
+  std::lock_guard<std::mutex> lock(pool->mu);
+  const int64_t free_now = static_cast<int64_t>(pool->returned.size()) + (pool->n_blocks - pool->next_fresh);
+  if (n > free_now) return SQA_ERR_CAPACITY;
+  for (int32_t i = 0; i < n; ++i) {
+    int32_t id;
+    if (pool->next_fresh < pool->n_blocks) id = pool->next_fresh++;
+    else { id = pool->returned.back(); pool->returned.pop_back(); }
+    pool->in_use[static_cast<size_t>(id)] = 1;
+    ids_out[i] = id;
+  }
+  return SQA_OK;
+}
+
+extern "C" sqa_status sqa_block_pool_give(sqa_block_pool* pool, const int32_t* ids, int32_t n) {
+  if (!pool || (n > 0 && !ids)) return SQA_ERR_NULL;
+  if (n < 0) return SQA_ERR_SHAPE;
+  std::lock_guard<std::mutex> lock(pool->mu);
+  // check everything first (a block named twice in one call is caught by marking as we go and undoing)
+  int32_t ok = 0;
+  for (; ok < n; ++ok) {
+    const int32_t id = ids[ok];
+    if (id < 0 || id >= pool->n_blocks || pool->in_use[static_cast<size_t>(id)] != 1) break;
+    pool->in_use[static_cast<size_t>(id)] = 2;           // seen in this call
+  }
+  if (ok < n) {
+    for (int32_t i = 0; i < ok; ++i) pool->in_use[static_cast<size_t>(ids[i])] = 1;
+    return SQA_ERR_SHAPE;
+  }
+  for (int32_t i = 0; i < n; ++i) {
+    pool->in_use[static_cast<size_t>(ids[i])] = 0;
+    pool->returned.push_back(ids[i]);
+  }
   return SQA_OK;
 }

@@ -227,8 +227,9 @@ def test_bench_refuses_more_than_one_gpu():
 def test_host_allocator_under_address_and_undefined_sanitizers(tmp_path):
     """The host-only part of the library (clustering and budgets, Algorithm 1 steps 5-11) built from its
     source with AddressSanitizer and UndefinedBehaviorSanitizer, no GPU code involved: the seeded cases of
-    test_budgets_bit_exact_vs_oracle plus degenerate inputs run through a small driver; any report ends
-    the driver with a non-zero status.  Results must still equal the oracle's."""
+    test_budgets_bit_exact_vs_oracle plus degenerate inputs run through a small driver, then the block free
+    list under a random sequence of take / give calls; any report ends the driver with a non-zero status.
+    Results must still equal the oracle's."""
     import shutil
     import subprocess
     gxx = shutil.which("g++")
@@ -251,6 +252,36 @@ int main() {
     if (st == SQA_OK) for (int i = 0; i < L; ++i) std::printf(" %d:%d", (int)budget[i], (int)group[i]);
     std::printf("\n");
   }
+  // the block free list: sequences join and leave with different block counts; no block is ever held twice
+  sqa_block_pool* pool = sqa_block_pool_create(97);
+  if (!pool) return 8;
+  std::vector<std::vector<int32_t>> held;
+  std::vector<int> owner(97, -1);
+  unsigned long long x = 88172645463325252ull;
+  for (int step = 0; step < 5000; ++step) {
+    x ^= x << 13; x ^= x >> 7; x ^= x << 17;
+    if (!held.empty() && (x & 1)) {
+      const size_t k = (size_t)((x >> 8) % held.size());
+      if (sqa_block_pool_give(pool, held[k].data(), (int32_t)held[k].size()) != SQA_OK) return 7;
+      for (int32_t id : held[k]) owner[id] = -1;
+      if (sqa_block_pool_give(pool, held[k].data(), (int32_t)held[k].size()) != SQA_ERR_SHAPE && !held[k].empty()) return 6;   // twice
+      held.erase(held.begin() + (long)k);
+    } else {
+      const int32_t n = (int32_t)((x >> 8) % 40);
+      std::vector<int32_t> ids((size_t)n + 1, -7);
+      const int32_t before = sqa_block_pool_free_count(pool);
+      const sqa_status st = sqa_block_pool_take(pool, n, ids.data());
+      if (st == SQA_ERR_CAPACITY) { if (n <= before || ids[0] != -7) return 5; continue; }
+      if (st != SQA_OK || ids[(size_t)n] != -7) return 4;
+      ids.resize((size_t)n);
+      for (int32_t id : ids) { if (id < 0 || id >= 97 || owner[id] != -1) return 3; owner[id] = step; }
+      held.push_back(ids);
+    }
+  }
+  int32_t out_of_range[2] = {0, 97};
+  if (sqa_block_pool_give(pool, out_of_range, 2) != SQA_ERR_SHAPE) return 2;
+  sqa_block_pool_destroy(pool);
+  std::printf("pool ok\n");
   return 0;
 }
 ''')
@@ -271,10 +302,11 @@ int main() {
               (np.array([0.1, 0.9], dtype=np.float32), 2, 0.5), (np.array([0.1, 0.5, 0.9], dtype=np.float32), 2, 0.3)]
     text = "".join("%d %d %.17g %s\n" % (len(c), t, p, " ".join("%.9g" % float(x) for x in c)) for c, t, p in cases)
     env = dict(os.environ, ASAN_OPTIONS="detect_leaks=1:abort_on_error=0", UBSAN_OPTIONS="print_stacktrace=1")
-    env.pop("LD_PRELOAD", None)
     run = subprocess.run([str(exe)], input=text, capture_output=True, text=True, env=env, timeout=120)
     assert run.returncode == 0, run.stderr[-2000:]
     lines = run.stdout.strip().splitlines()
+    assert lines[-1] == "pool ok"
+    lines = lines[:-1]
     assert len(lines) == len(cases)
     for (c, t, p), line in zip(cases, lines):
         parts = line.split()

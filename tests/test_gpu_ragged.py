@@ -213,9 +213,9 @@ def test_decode_with_an_empty_packed_unit(sqa):
 def test_a_new_sequence_takes_a_finished_ones_place(sqa, blocked):
     """A running batch of three sequences: after some decode steps sequence 1 is finished and another prompt,
     with its own length and its own per-layer budgets, takes its batch slot.  With blocked allocation the
-    leaving sequence's K/V blocks go back to a free list (host side, here a Python list) and the newcomer is
-    dealt blocks from it -- other blocks than before, in another order, more of them in one layer and fewer in
-    the other -- without anything of the other sequences moving.  Only the newcomer's prompt is compressed
+    leaving sequence's K/V blocks go back to the layer's free list (sqa_block_pool) and the newcomer is dealt
+    blocks from it -- in another order, more of them in one layer and fewer in the other -- without anything
+    of the other sequences moving.  Only the newcomer's prompt is compressed
     (a batch-of-one call on the same memory); every sequence is checked against the oracle throughout."""
     dtype, L, Hkv, g, D, B, P, S = "bf16", 2, 2, 2, 128, 3, 120, 14
     Hq = Hkv * g
@@ -262,15 +262,22 @@ def test_a_new_sequence_takes_a_finished_ones_place(sqa, blocked):
             if blocked:
                 for l in range(L):
                     tbl = caches.block_table[l]
-                    bpu, n_blocks = tbl.shape[1], caches.K[l].shape[0]
+                    n_blocks = caches.K[l].shape[0]
+                    # the layer's free list (sqa_block_pool), brought to the state of the running batch: every
+                    # block taken, the spare ones (in no unit's table row) given back
+                    pool = sqa.BlockPool(n_blocks)
+                    pool.take(n_blocks)
                     in_use = set(tbl.flatten().tolist())
-                    free = sorted(set(range(n_blocks)) - in_use)                      # the pool's spare blocks
-                    free += tbl[1 * Hkv:2 * Hkv].flatten().tolist()                   # + what sequence 1 gives back
+                    pool.give(sorted(set(range(n_blocks)) - in_use))
+                    leaving = tbl[1 * Hkv:2 * Hkv].flatten().tolist()
+                    pool.give(leaving)                                                 # sequence 1 gives its blocks back
                     need = (min(new_budget[l], new_len + S) + sqa.SQA_BLOCK_SLOTS - 1) // sqa.SQA_BLOCK_SLOTS
                     for h in range(Hkv):
-                        mine = [free.pop(0) for _ in range(need)]                     # spare blocks first: other blocks than before
+                        mine = pool.take(need)                                         # last given back, first reused
                         tbl[1 * Hkv + h, :need] = torch.tensor(mine, dtype=torch.int32, device=DEV)
                         tbl[1 * Hkv + h, need:] = -1                                   # (never read: beyond the unit's budget)
+                    assert pool.free_count() == n_blocks - len(in_use) + len(leaving) - Hkv * need
+                    pool.close()
             budget_now = [[budget_a[l][0], new_budget[l], budget_a[l][2]] for l in range(L)]
             bseq = _i32(budget_now)
             one = sqa.batch_opts(budget_seq=_i32([[new_budget[l]] for l in range(L)]), status=status)
