@@ -101,5 +101,24 @@ def build(verbose: bool = True) -> str:
     return LIB
 
 
+def build_microbench(verbose: bool = True) -> str:
+    """microbench/store_cost.hip -> _build/store_cost (a standalone executable, not part of libsqa.so):
+    the measurement behind the statement that the decode step is bound by what it writes."""
+    os.makedirs(OBJ_DIR, exist_ok=True)
+    exe = os.path.join(OBJ_DIR, "store_cost")
+    cmd = [_hipcc(), "-O3", "-std=c++17", "--offload-arch=gfx950", "-Xclang", "-target-feature", "-Xclang",
+           "-packed-fp32-ops", "-Wno-unused-command-line-argument", "-Wno-unused-result",
+           os.path.join(HERE, "microbench", "store_cost.hip"), "-o", exe]
+    r = subprocess.run(cmd, capture_output=True, text=True)
+    if r.returncode != 0:
+        raise RuntimeError("compile failed: %s\n%s" % (" ".join(cmd), r.stderr))
+    if verbose:
+        print("built", exe)
+    return exe
+
+
 if __name__ == "__main__":
-    build()
+    if "--microbench" in sys.argv[1:]:
+        build_microbench()
+    else:
+        build()
