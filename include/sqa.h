@@ -351,6 +351,31 @@ sqa_status sqa_decode_step_static(const void* q, const void* k_new, const void* 
                                   const sqa_layer_cache* layers, const sqa_layer_cache* layers_dev, int n_layers,
                                   void* out, int32_t* status, void* stream, const sqa_batch_opts* opts);
 
+/* ---- the launch a decode call would make (host arithmetic only, no GPU call) ----
+ * How sqa_decode_step[_ex|_static] would lay the call out on the chip: for sizing, for logs, and so that the
+ * launch configuration of a workload can be checked without a GPU.  Of `layers` only budget, capacity and
+ * whether block_table is NULL are read.
+ *   info      : HOST, filled in
+ *   per_layer : HOST [n_layers] or NULL                                                                  */
+typedef struct sqa_decode_plan_info {
+  int64_t workgroups;       /* grid of the one launch, 256 threads each                                   */
+  int64_t workspace_bytes;  /* what the call uses of its workspace (<= sqa_decode_workspace_bytes)        */
+  int32_t lds_bytes;        /* dynamic LDS per workgroup                                                  */
+  int32_t matrix_cores;     /* 1: the MFMA variant runs (bf16, D = 128, 4 or 8 query heads per KV head)   */
+  int32_t wide_tail;        /* 1: so few workgroups that a long unit's score walk keeps all four waves    */
+  int32_t table_entries;    /* blocked allocation: block numbers a workgroup stages in LDS (else 0)       */
+} sqa_decode_plan_info;
+typedef struct sqa_decode_layer_plan {
+  int32_t workgroups_per_unit;  /* 1: a workgroup streams the whole unit; k > 1: the unit is cut into k work
+                                   items whose partial results the last one to finish merges; 0: see next  */
+  int32_t slots_per_workgroup;  /* length of such a work item in slots (a multiple of 64)                   */
+  int32_t wave_per_unit;        /* 1: short units, many of them: each of a workgroup's 4 waves owns a unit  */
+  int32_t probs_in_lds;         /* 1: MFMA variant under H2O keeps the step's probabilities in LDS          */
+} sqa_decode_layer_plan;
+sqa_status sqa_decode_plan(const sqa_layer_cache* layers, int n_layers, int B, int Hq, int Hkv, int D,
+                           sqa_dtype dt, sqa_policy policy, sqa_decode_plan_info* info,
+                           sqa_decode_layer_plan* per_layer);
+
 /* Zeroes the status word (a small fill kernel enqueued on stream; like
  * sqa_decode_workspace_init it uses no memset, so both may be recorded into a HIP graph). */
 sqa_status sqa_clear_device_status(void* workspace, void* stream);

@@ -44,6 +44,18 @@ class LayerCacheStruct(C.Structure):
                 ("capacity", C.c_int32), ("budget", C.c_int32), ("blocks_per_unit", C.c_int32), ("n_blocks", C.c_int32)]
 
 
+class DecodePlanInfo(C.Structure):
+    """Mirror of sqa_decode_plan_info."""
+    _fields_ = [("workgroups", C.c_int64), ("workspace_bytes", C.c_int64), ("lds_bytes", C.c_int32),
+                ("matrix_cores", C.c_int32), ("wide_tail", C.c_int32), ("table_entries", C.c_int32)]
+
+
+class DecodeLayerPlan(C.Structure):
+    """Mirror of sqa_decode_layer_plan."""
+    _fields_ = [("workgroups_per_unit", C.c_int32), ("slots_per_workgroup", C.c_int32),
+                ("wave_per_unit", C.c_int32), ("probs_in_lds", C.c_int32)]
+
+
 class BatchOptsStruct(C.Structure):
     """Mirror of sqa_batch_opts."""
     _fields_ = [("prompt_len", C.c_void_p), ("budget_seq", C.c_void_p), ("new_pos_seq", C.c_void_p),
@@ -101,6 +113,7 @@ _lib.sqa_read_device_status.restype = _i
 _lib.sqa_read_device_status.argtypes = [_vp, _vp, C.POINTER(C.c_int32)]
 _lib.sqa_kept_idx_sorted.restype = _i
 _lib.sqa_kept_idx_sorted.argtypes = [_LCp, _i, _i, _vp, _vp]
+_lib.sqa_decode_plan.argtypes = [_LCp, _i, _i, _i, _i, _i, _i, _i, C.POINTER(DecodePlanInfo), C.POINTER(DecodeLayerPlan)]
 _lib.sqa_block_pool_create.argtypes = [C.c_int32]
 _lib.sqa_block_pool_create.restype = _vp
 _lib.sqa_block_pool_destroy.argtypes = [_vp]
@@ -222,6 +235,26 @@ def prefill_scores(Q: torch.Tensor, K: torch.Tensor, scores_out: Optional[torch.
         _check(_lib.sqa_prefill_scores_lse(_ptr(Q), _ptr(K), _ptr(row_lse), _dt(Q), B, Hq, Hkv, P, D, _ptr(scores_out),
                                            _ptr(ws), ws.numel(), _stream(), _opts(opts)), "sqa_prefill_scores_lse")
     return scores_out
+
+
+def decode_plan(budgets: Sequence[int], capacities: Sequence[int], B: int, Hq: int, Hkv: int, D: int,
+                dtype: str, policy: str, blocked: bool = False) -> dict:
+    """sqa_decode_plan: the launch a decode call over these layers would make (host arithmetic, no GPU).
+    dtype: "bf16" or "f32"."""
+    n = len(budgets)
+    t = (LayerCacheStruct * n)()
+    for i in range(n):
+        t[i].capacity, t[i].budget = int(capacities[i]), int(budgets[i])
+        if blocked:
+            t[i].block_table = 0x1000                     # (only "is it NULL" is looked at)
+            t[i].blocks_per_unit = (min(int(capacities[i]), int(budgets[i])) + SQA_BLOCK_SLOTS - 1) // SQA_BLOCK_SLOTS
+            t[i].n_blocks = 1
+    info, per = DecodePlanInfo(), (DecodeLayerPlan * n)()
+    _check(_lib.sqa_decode_plan(t, n, B, Hq, Hkv, D, {"f32": 0, "bf16": 1}[dtype], POLICY[policy], C.byref(info), per),
+           "sqa_decode_plan")
+    out = {f: int(getattr(info, f)) for f, _ in DecodePlanInfo._fields_}
+    out["layers"] = [{f: int(getattr(per[i], f)) for f, _ in DecodeLayerPlan._fields_} for i in range(n)]
+    return out
 
 
 class BlockPool:

@@ -1117,6 +1117,24 @@ struct DecodeScratch {
 };
 
 // Argument checks shared by the decode entry points; on success the kernel and the launch plan.
+// The launch plan of a call and the dynamic LDS its workgroups need (host arithmetic only).
+static bool uses_mfma(sqa_dtype dt, int D, int g) { return dt == SQA_BF16 && D == 128 && g >= kMfmaMinGroup; }
+static sqa_status plan_call(sqa_dtype dt, int B, int Hq, int Hkv, int D, bool h2o, const sqa_layer_cache* layers,
+                            int n_layers, DecodePlan* plan, size_t* lds_out) {
+  const int g = Hq / Hkv;
+  const bool mfma = uses_mfma(dt, D, g);
+  const sqa_status ps = plan_decode(layers, n_layers, B, Hq, Hkv, D, h2o, true, h2o && mfma, plan);
+  if (ps != SQA_OK) return ps;
+  const size_t lds_shared = (size_t)g * plan->lds_chunk, lds_waves = (size_t)kDecWaves * g * plan->lds_chunk_w;
+  const size_t lds = (h2o ? (lds_shared > lds_waves ? lds_shared : lds_waves) * sizeof(float) : 0) +
+                     (mfma ? (size_t)kDecWaves * kStageBytesPerWave : 0) + (size_t)plan->lds_probs;
+  // (blocked allocation: the staged block numbers come last; decode_launch passes their offset)
+  const size_t lds_all = ((lds + 15) & ~(size_t)15) + (size_t)plan->tbl_entries * sizeof(int);
+  if (lds_all > 160 * 1024) return SQA_ERR_CAPACITY;
+  *lds_out = lds_all;
+  return SQA_OK;
+}
+
 static sqa_status decode_prepare(const void* q, const void* k_new, const void* v_new, sqa_dtype dt,
                                  int B, int Hq, int Hkv, int D, int32_t new_pos, sqa_policy policy, int n_sink,
                                  const sqa_layer_cache* layers, int n_layers, const void* out,
@@ -1147,17 +1165,9 @@ static sqa_status decode_prepare(const void* q, const void* k_new, const void* v
                   (int64_t)c.blocks_per_unit * SQA_BLOCK_SLOTS < (c.budget < c.capacity ? c.budget : c.capacity)))
       return SQA_ERR_SHAPE;
   }
-  const bool mfma = dt == SQA_BF16 && D == 128 && g >= kMfmaMinGroup;
-  const sqa_status ps = plan_decode(layers, n_layers, B, Hq, Hkv, D, h2o, true, h2o && mfma, plan);
+  const sqa_status ps = plan_call(dt, B, Hq, Hkv, D, h2o, layers, n_layers, plan, lds_out);
   if (ps != SQA_OK) return ps;
-  const size_t lds_shared = (size_t)g * plan->lds_chunk, lds_waves = (size_t)kDecWaves * g * plan->lds_chunk_w;
-  const size_t lds = (h2o ? (lds_shared > lds_waves ? lds_shared : lds_waves) * sizeof(float) : 0) +
-                     (mfma ? (size_t)kDecWaves * kStageBytesPerWave : 0) + (size_t)plan->lds_probs;
-  // (blocked allocation: the staged block numbers come last; decode_launch passes their offset)
-  const size_t lds_all = ((lds + 15) & ~(size_t)15) + (size_t)plan->tbl_entries * sizeof(int);
-  if (lds_all > 160 * 1024) return SQA_ERR_CAPACITY;
   *fn_out = pick(dt, D, g, h2o, paged);
-  *lds_out = lds_all;
   return SQA_OK;
 }
 
@@ -1215,6 +1225,36 @@ static sqa_status decode_launch(decode_fn fn, const DecodePlan& plan, size_t lds
 }
 
 }  // namespace sqa
+
+extern "C" sqa_status sqa_decode_plan(const sqa_layer_cache* layers, int n_layers, int B, int Hq, int Hkv, int D,
+                                      sqa_dtype dt, sqa_policy policy, sqa_decode_plan_info* info,
+                                      sqa_decode_layer_plan* per_layer) {
+  using namespace sqa;
+  if (!layers || !info) return SQA_ERR_NULL;
+  if (dt != SQA_F32 && dt != SQA_BF16) return SQA_ERR_DTYPE;
+  if (policy != SQA_SLIDING && policy != SQA_STREAMING && policy != SQA_H2O) return SQA_ERR_POLICY;
+  if (B < 1 || Hq < 1 || Hkv < 1 || n_layers < 1 || n_layers > SQA_MAX_LAYERS || Hq % Hkv != 0) return SQA_ERR_SHAPE;
+  const bool h2o = policy == SQA_H2O;
+  if (!pick(dt, D, Hq / Hkv, h2o, layers[0].block_table != nullptr)) return SQA_ERR_SHAPE;
+  DecodePlan plan;
+  size_t lds = 0;
+  const sqa_status ps = plan_call(dt, B, Hq, Hkv, D, h2o, layers, n_layers, &plan, &lds);
+  if (ps != SQA_OK) return ps;
+  info->workgroups = (int64_t)plan.blocks;
+  info->workspace_bytes = (int64_t)plan.bytes;
+  info->lds_bytes = (int32_t)lds;
+  info->matrix_cores = uses_mfma(dt, D, Hq / Hkv) ? 1 : 0;
+  info->wide_tail = plan.blocks <= (uint64_t)kWideTailMaxBlocks ? 1 : 0;
+  info->table_entries = plan.tbl_entries;
+  if (per_layer)
+    for (int i = 0; i < n_layers; ++i) {
+      per_layer[i].workgroups_per_unit = plan.wpu[i] ? 0 : plan.nsplit[i];
+      per_layer[i].slots_per_workgroup = (int32_t)plan.chunk[i];
+      per_layer[i].wave_per_unit = plan.wpu[i];
+      per_layer[i].probs_in_lds = plan.probs_in_lds[i];
+    }
+  return SQA_OK;
+}
 
 extern "C" sqa_status sqa_decode_step_ex(const void* q, const void* k_new, const void* v_new, sqa_dtype dt,
                                          int B, int Hq, int Hkv, int D, int32_t new_pos,
