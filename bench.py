@@ -435,6 +435,16 @@ def main():
     mode = "full_cache" if args.full_cache else ("uniform" if args.uniform else "squeeze")
     launch = ("per_layer" if args.per_layer else "all_layers") + ("_graph" if args.graph else "")
     traffic, traffic_source = measured_traffic((wl.name, mode, wl.policy, launch, "blocked" if args.blocked else "dense"))
+    launch_plan = None
+    if not args.per_layer and plen is None:
+        from paper_2404_04793_amd import binding as sqa_b
+        lp = sqa_b.decode_plan(sess.budgets, sess.caches.capacities, wl.B, wl.Hq, wl.Hkv, wl.D, wl.dtype, wl.policy,
+                               args.blocked)
+        launch_plan = {"workgroups": lp["workgroups"], "lds_bytes_per_workgroup": lp["lds_bytes"],
+                       "matrix_cores": bool(lp["matrix_cores"]),
+                       "layers_one_wave_per_unit": sum(l["wave_per_unit"] for l in lp["layers"]),
+                       "layers_whole_units": sum(l["workgroups_per_unit"] == 1 for l in lp["layers"]),
+                       "layers_split_units": sum(l["workgroups_per_unit"] > 1 for l in lp["layers"])}
     res = {
         "metric": "decode tokens/s + achieved HBM GB/s (attn+evict), 7B shape, 1 GPU",
         "value": tokens / dt, "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
@@ -450,7 +460,7 @@ def main():
         "roofline": {"bound": "hbm", "kernel": "decode_unit_kernel", "achieved": achieved, "peak": HBM_PEAK_GBS,
                      "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
                      "traffic": traffic, "traffic_source": traffic_source,
-                     "bytes_per_launch": bytes_launch, "launch_us": launch_s * 1e6},
+                     "bytes_per_launch": bytes_launch, "launch_us": launch_s * 1e6, "launch_plan": launch_plan},
         "phases_ms": {"probe_and_budgets": probe_ms, "prefill_compress": comp_ms, "decode": dec_ms},
         "decode_only_tokens_per_s": wl.B * wl.S / (dec_ms * 1e-3),
         "probe_GBps": None if args.decode_only else sess.probe_bytes() / (probe_ms * 1e-3) / 1e9,
