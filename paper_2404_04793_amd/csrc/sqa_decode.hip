@@ -388,7 +388,9 @@ __global__ __launch_bounds__(kDecThreads, MF ? kMfWavesPerSimd : 1) void decode_
   const int n = (full && !ae) ? budget : len + 1; // tokens attended this step
   const int slot_wr = full ? hh + head : len;     // physical slot the new token is written to
   const int slot_new = ae ? len : slot_wr;        // index of the new token while streaming
-  const int rmax = min(n, cap) - 1;               // last row that may be read from memory
+  // last row that may be read from memory (with blocks: the last one the staged table rows cover; under
+  // attend-then-evict a full unit's new token has index budget, which is never read from the cache)
+  const int rmax = min(n, span) - 1;
   int moved_to = -1;                              // heavy slot that receives the ring leaver
   if (H2O && full && !ae) {
     if (hint >= -1 && hint < hh) {
@@ -644,7 +646,9 @@ __global__ __launch_bounds__(kDecThreads, MF ? kMfWavesPerSimd : 1) void decode_
         for (int uu = 0; uu < U; ++uu) {
           slot[uu] = base + uu * rows_it + wv * RPI + r;
           const int sl = min(slot[uu], n - 1);
-          const int64_t rw = row_of(sl == moved_to ? slot_wr : sl);
+          // (with blocks: never a table entry beyond the staged ones -- a full unit's new token under
+          // attend-then-evict has index budget; its rows come from k_new / v_new just below)
+          const int64_t rw = row_of(PG ? min(sl == moved_to ? slot_wr : sl, rmax) : (sl == moved_to ? slot_wr : sl));
           const char* kp = Kb + rw * ROWB;
           const char* vp = Vb + rw * ROWB;
           if (sl == slot_new) { kp = knew; vp = vnew; }

@@ -329,6 +329,25 @@ def test_decode_teacher_forced_blocked_allocation(sqa, case, order):
     _teacher_forced(sqa, case, order, blocked=True)
 
 
+SPARE_CASES = [
+    # budgets that are multiples of the 16-row block, caches with more slots than the budget: a full unit's new
+    # token under attend-then-evict has index `budget`, the first slot of a block the unit never uses
+    ("h2o_bf16_gqa4_mfma_spare", "bf16", 2, 8, 2, 128, 2, 100, 6, "h2o", [64, 32]),
+    ("h2o_bf16_mha_spare", "bf16", 1, 2, 2, 128, 2, 100, 6, "h2o", [48]),
+    ("slide_bf16_gqa8_mfma_spare", "bf16", 1, 8, 1, 128, 2, 100, 6, "sliding", [80]),
+    ("stream_f32_spare", "f32", 1, 2, 2, 64, 1, 60, 6, "streaming", [16]),
+]
+
+
+@pytest.mark.parametrize("blocked", [True, False], ids=["blocked", "dense"])
+@pytest.mark.parametrize("order", ["evict_then_attend", "attend_then_evict"])
+@pytest.mark.parametrize("case", SPARE_CASES, ids=[c[0] for c in SPARE_CASES])
+def test_decode_capacity_above_budget(sqa, case, order, blocked):
+    """Caches allocated with 24 more slots per unit than the budget: nothing beyond the budget's slots (and,
+    with blocks, beyond the table entries they need) is ever touched."""
+    _teacher_forced(sqa, case, order, blocked=blocked, spare_slots=24)
+
+
 def test_decode_reports_a_block_number_outside_the_pools(sqa):
     """A table entry beyond the pools: the unit is left untouched, its out rows zeroed, SQA_ERR_SHAPE in the
     status word; the other unit of the call steps normally.  Prompt compression reports the same."""
@@ -352,7 +371,7 @@ def test_decode_reports_a_block_number_outside_the_pools(sqa):
     caches.block_table[0].copy_(good)
 
 
-def _teacher_forced(sqa, case, order, blocked=False):
+def _teacher_forced(sqa, case, order, blocked=False, spare_slots=0):
     name, dtype, L, Hq, Hkv, D, B, P, S, policy, budgets = case
     ae = order == "attend_then_evict"
     opts = sqa.batch_opts(order=order) if ae else None
@@ -360,7 +379,7 @@ def _teacher_forced(sqa, case, order, blocked=False):
     g = Hq // Hkv
     u_dirs, mask = W.unit_dirs(wl), W.hh_mask(wl, DEV)
     inp = [_unit_inputs(wl, l, u_dirs, mask) for l in range(L)]
-    caps = [min(b, P + S) for b in budgets]
+    caps = [min(b, P + S) + spare_slots for b in budgets]
     caches = _mk_caches(sqa, budgets, caps, B, Hkv, D, dtype, blocked=blocked)
     ws = sqa.decode_workspace(caches, Hq, policy)
     # oracle trajectories (fp32-rounded score storage between steps)
