@@ -273,6 +273,8 @@ CASES = [
     ("stream_bf16_gqa8_mfma_split", "bf16", 1, 8, 1, 128, 1, 900, 4, "streaming", [777]),
     ("h2o_bf16_gqa8_mfma_split", "bf16", 1, 8, 1, 128, 1, 700, 5, "h2o", [650]),
     ("slide_bf16_gqa8_mfma_tiny", "bf16", 1, 16, 2, 128, 1, 40, 6, "sliding", [3]),
+    # as many layers in one call as the library takes (SQA_MAX_LAYERS)
+    ("h2o_f32_128_layers", "f32", 128, 1, 1, 64, 1, 12, 3, "h2o", [5, 9, 14, 3] * 32),
 ]
 
 
