@@ -157,6 +157,8 @@ int main() {
     for (int wr : {0, 1}) {
       std::snprintf(nm, 160, "one workgroup per item, hardware dispatch%s", wr ? "" : " (nothing written)");
       timed(nm, bytes, [&] { per_item<PLAIN4><<<n, 256>>>(p, d, wb, sink, wr); });
+      std::snprintf(nm, 160, "two launches: the 1024 long items (resident at once), then the 1792 short ones%s", wr ? "" : " (nothing written)");
+      timed(nm, bytes, [&] { per_item<PLAIN4><<<1024, 256>>>(p, d, wb, sink, wr); per_item<PLAIN4><<<1792, 256>>>(p, d + 1024, wb, sink, wr); });
       std::snprintf(nm, 160, "persistent grid of 1024, stores after each item%s", wr ? "" : " (nothing written)");
       timed(nm, bytes, [&] { CK(hipMemsetAsync(queue, 0, 4)); persistent<false, 1><<<1024, 256>>>(p, d, n, queue, wb, sink, wr); });
       std::snprintf(nm, 160, "persistent grid of 1024, writes held in LDS until the queue is empty%s", wr ? "" : " (nothing written)");
