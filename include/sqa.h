@@ -370,7 +370,9 @@ typedef struct sqa_decode_layer_plan {
                                    items whose partial results the last one to finish merges; 0: see next  */
   int32_t slots_per_workgroup;  /* length of such a work item in slots (a multiple of 64)                   */
   int32_t wave_per_unit;        /* 1: short units, many of them: each of a workgroup's 4 waves owns a unit  */
-  int32_t probs_in_lds;         /* 1: MFMA variant under H2O keeps the step's probabilities in LDS          */
+  int32_t probs_in_lds;         /* MFMA variant under H2O, the step's per-head probabilities of a unit: 1 = all
+                                   stay in LDS, 2 = those of its leading tokens do (the rest passes through the
+                                   workspace), 0 = none                                                      */
 } sqa_decode_layer_plan;
 sqa_status sqa_decode_plan(const sqa_layer_cache* layers, int n_layers, int B, int Hq, int Hkv, int D,
                            sqa_dtype dt, sqa_policy policy, sqa_decode_plan_info* info,

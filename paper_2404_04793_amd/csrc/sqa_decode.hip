@@ -72,7 +72,11 @@ struct DecodeArgs {
   int lds_probs_w;                     // bytes of a wave's own LDS region for those probabilities in one-wave-per-unit layers
   int tbl_off;                         // blocked allocation: where in the dynamic LDS the unit's block numbers are staged (bytes)
 };
-constexpr uint32_t kWpuBit = 0x80000000u, kLdsProbsBit = 0x40000000u;
+// Layer::nsplit: bits 0-15 the number of work items per unit, bits 16-29 how many of a unit's leading 32-token
+// tiles keep their H2O probabilities in LDS (matrix-core variant), bit 31 one wave per unit
+constexpr uint32_t kWpuBit = 0x80000000u;
+constexpr int kLdsTilesShift = 16;
+constexpr uint32_t kLdsTilesMask = 0x3fffu;
 
 // Data that one workgroup hands to another inside a launch (partial results,
 // logits) moves through agent-scope relaxed atomics: such stores are written
@@ -271,7 +275,7 @@ __global__ __launch_bounds__(kDecThreads, MF ? kMfWavesPerSimd : 1) void decode_
   const int layer = a.order[lo];
   const unsigned local = blockIdx.x - (lo ? a.blk_end[lo - 1] : 0u);
   const uint32_t nsplit_w = a.lay[layer].nsplit;
-  const int nsplit = (int)(nsplit_w & ~(kWpuBit | kLdsProbsBit));
+  const int nsplit = (int)(nsplit_w & 0xffffu);
   // one wave per unit: the workgroup's waves own 4 consecutive units and never meet at a barrier
   const bool wpu = (nsplit_w & kWpuBit) != 0;
   const int u = wpu ? (int)local * kDecWaves + wave : (int)(local / (unsigned)nsplit);
@@ -421,12 +425,13 @@ __global__ __launch_bounds__(kDecThreads, MF ? kMfWavesPerSimd : 1) void decode_
   // and head, written and read back by the same workgroup, are not part of what the method has to move.
   const int ntile_max = (lpitch + 31) >> 5;
   const bool handover = nsplit > 1;
-  const bool lds_probs = MF && H2O && (nsplit_w & kLdsProbsBit) != 0;
+  // tiles below lds_tiles keep their probabilities and references in LDS, the others go through the workspace
+  const int lds_tiles = (MF && H2O) ? (int)((nsplit_w >> kLdsTilesShift) & kLdsTilesMask) : 0;
   unsigned short* e16 = reinterpret_cast<unsigned short*>(glogit);
   float* tref = (MF && H2O) ? glogit + (int64_t)ntile_max * G * 16 : nullptr;
   char* const probs_lds = stage_base + kDecWaves * kStageBytesPerWave + (wpu ? wave * a.lds_probs_w : 0);
   unsigned short* const e16_l = reinterpret_cast<unsigned short*>(probs_lds);                // [tile][head][32]
-  float* const tref_l = reinterpret_cast<float*>(probs_lds + ntile_max * G * 64);            // [tile][head]
+  float* const tref_l = reinterpret_cast<float*>(probs_lds + lds_tiles * G * 64);            // [tile][head]
 
   if constexpr (MF) {
     // ---- 1M. matrix-core streaming ------------------------------------------
@@ -561,7 +566,7 @@ __global__ __launch_bounds__(kDecThreads, MF ? kMfWavesPerSimd : 1) void decode_
 #pragma unroll
         for (int tt = 0; tt < 2; ++tt) {            // (tokens beyond the unit's end get zeros: the region holds whole tiles)
           const unsigned long long four = __builtin_bit_cast(unsigned long long, pfr[tt]);
-          if (lds_probs) {
+          if ((base >> 5) < lds_tiles) {
             *reinterpret_cast<unsigned long long*>(e16_l + ((base >> 5) * G + hd) * 32 + 16 * tt + 4 * j4) = four;
           } else {
             unsigned long long* dst = reinterpret_cast<unsigned long long*>(e16 + ((int64_t)(base >> 5) * G + hd) * 32 + 16 * tt + 4 * j4);
@@ -569,7 +574,7 @@ __global__ __launch_bounds__(kDecThreads, MF ? kMfWavesPerSimd : 1) void decode_
           }
         }
         if (j4 == 0) {
-          if (lds_probs) {
+          if ((base >> 5) < lds_tiles) {
             tref_l[(base >> 5) * G + hd] = ms;
           } else {
             float* dst = &tref[(base >> 5) * G + hd];
@@ -818,7 +823,7 @@ __global__ __launch_bounds__(kDecThreads, MF ? kMfWavesPerSimd : 1) void decode_
         const int ntile = (n + 31) >> 5;
         for (int idx = tq; idx < G * ntile; idx += nthr) {
           const int g = idx % G;                  // idx = tile * G + head
-          const float rf = lds_probs ? tref_l[idx] : (handover ? ld_agent(&tref[idx]) : tref[idx]);
+          const float rf = idx < lds_tiles * G ? tref_l[idx] : (handover ? ld_agent(&tref[idx]) : tref[idx]);
           fac[idx] = fast_exp2(rf - s_m[wq][g]) * s_l[wq][g];
         }
         if (!solo) __syncthreads();               // (a wave on its own reads back what it wrote itself: LDS keeps a wave's order)
@@ -842,10 +847,11 @@ __global__ __launch_bounds__(kDecThreads, MF ? kMfWavesPerSimd : 1) void decode_
           for (int g = 0; g < G; ++g) {
             if constexpr (MF) {
               const int at = ((i >> 5) * G + g) * 32 + (i & 31);
-              const unsigned short eb = lds_probs ? e16_l[at] : (handover ? ld_agent(&e16[at]) : e16[at]);
+              const bool in_lds = (i >> 5) < lds_tiles;
+              const unsigned short eb = in_lds ? e16_l[at] : (handover ? ld_agent(&e16[at]) : e16[at]);
               const float e = __uint_as_float((uint32_t)eb << 16);
               p += e * (use_fac ? fac[(i >> 5) * G + g]
-                                : fast_exp2((lds_probs ? tref_l[(i >> 5) * G + g] : ld_agent(&tref[(i >> 5) * G + g])) - s_m[wq][g]) * s_l[wq][g]);
+                                : fast_exp2((in_lds ? tref_l[(i >> 5) * G + g] : ld_agent(&tref[(i >> 5) * G + g])) - s_m[wq][g]) * s_l[wq][g]);
             } else {
               const float lg = glogit ? ld_agent(&glogit[(int64_t)g * lpitch + i]) : s_lg[g * lp + i];
               p += fast_exp2(lg - fm[g]) * fi[g];
@@ -935,7 +941,8 @@ constexpr size_t kStatusBytes = 256;
 struct DecodePlan {
   int tbl_entries;                                 // blocked allocation: block numbers a workgroup stages in LDS
   int lds_probs, lds_probs_w;                      // LDS bytes for the probabilities of a workgroup / of one wave's unit
-  uint8_t probs_in_lds[SQA_MAX_LAYERS];            // matrix-core variant under H2O: this layer's units keep them in LDS
+  uint16_t lds_tiles[SQA_MAX_LAYERS];              // matrix-core variant under H2O: leading tiles of a unit whose probabilities stay in LDS
+  uint8_t probs_in_lds[SQA_MAX_LAYERS];            // ... 1: all of them (nothing of it in the workspace), 2: the leading part
   int lds_chunk;                                   // longest unsplit unit shared by 4 waves (slots)
   int lds_chunk_w;                                 // longest one-wave unit (slots)
   uint8_t wpu[SQA_MAX_LAYERS];                     // one wave per unit in this layer
@@ -1009,12 +1016,21 @@ static sqa_status plan_decode(const sqa_layer_cache* layers, int n_layers, int B
     p->chunk[i] = (uint32_t)ch;
     p->wpu[i] = allow_wpu && ns == 1 && nmax <= kWpuMaxSlots && units * n_layers >= kWpuMinUnits;
     p->probs_in_lds[i] = 0;
+    p->lds_tiles[i] = 0;
     if (h2o && scratch_probs && ns == 1) {
-      // per unit: whole 32-token tiles of bf16 values per head, plus one fp32 reference per tile and head
+      // per unit: whole 32-token tiles of bf16 values per head, plus one fp32 reference per tile and head;
+      // a unit too long for the LDS a workgroup may use keeps its leading tiles there (a written byte costs
+      // many read bytes, so every tile that stays on the chip counts); one-wave units: all or nothing
       const int64_t ntile = ((int64_t)layers[i].capacity + 1 + 31) / 32;
-      const int64_t need = (int64_t)g * ntile * (64 + 4);
-      if (need * (p->wpu[i] ? kDecWaves : 1) <= kLdsProbsMax - p->tbl_entries * (int)sizeof(int)) {
-        p->probs_in_lds[i] = 1;
+      const int64_t per_tile = (int64_t)g * (64 + 4);
+      const int64_t avail = kLdsProbsMax - p->tbl_entries * (int)sizeof(int);
+      int64_t tiles = p->wpu[i] ? (ntile * per_tile * kDecWaves <= avail ? ntile : 0) : avail / per_tile;
+      tiles = tiles > ntile ? ntile : tiles;
+      tiles = tiles > (int64_t)kLdsTilesMask ? (int64_t)kLdsTilesMask : tiles;
+      if (tiles > 0) {
+        const int64_t need = tiles * per_tile;
+        p->lds_tiles[i] = (uint16_t)tiles;
+        p->probs_in_lds[i] = tiles == ntile ? 1 : 2;
         if (p->wpu[i] && need > p->lds_probs_w) p->lds_probs_w = (int)need;
         if (need * (p->wpu[i] ? kDecWaves : 1) > p->lds_probs) p->lds_probs = (int)(need * (p->wpu[i] ? kDecWaves : 1));
       }
@@ -1027,7 +1043,7 @@ static sqa_status plan_decode(const sqa_layer_cache* layers, int n_layers, int B
     n_units += units;
     blocks += p->wpu[i] ? (units + kDecWaves - 1) / kDecWaves : units * ns;
     if (ns > 1) n_part += units * ns;
-    if (h2o && (ns > 1 || scratch_probs) && !p->probs_in_lds[i]) n_logit += units * g * ((uint64_t)layers[i].capacity + kLogitPad);
+    if (h2o && (ns > 1 || scratch_probs) && p->probs_in_lds[i] != 1) n_logit += units * g * ((uint64_t)layers[i].capacity + kLogitPad);
     if (n_units > 0x7fffffffull || n_part > 0x7fffffffull || n_logit > 0xffffffffull || blocks > 0x7fffffffull)
       return SQA_ERR_CAPACITY;
   }
@@ -1054,11 +1070,14 @@ extern "C" size_t sqa_decode_workspace_bytes(const sqa_layer_cache* layers, int 
   // (the element type is not known here: size for the variant that needs more, the matrix-core one if the
   // shape allows it)
   const bool h2o = policy == SQA_H2O;
-  if (sqa::plan_decode(layers, n_layers, B, Hq, Hkv, D, h2o, false, false, &p) != SQA_OK) return 0;
-  size_t bytes = p.bytes;
-  if (h2o && D == 128 && Hq / Hkv >= sqa::kMfmaMinGroup) {
-    if (sqa::plan_decode(layers, n_layers, B, Hq, Hkv, D, h2o, false, true, &p) != SQA_OK) return 0;
+  size_t bytes = 0;
+  for (int wpu = 0; wpu < 2; ++wpu) {              // (a call may or may not give short units a wave each)
+    if (sqa::plan_decode(layers, n_layers, B, Hq, Hkv, D, h2o, wpu != 0, false, &p) != SQA_OK) return 0;
     bytes = p.bytes > bytes ? p.bytes : bytes;
+    if (h2o && D == 128 && Hq / Hkv >= sqa::kMfmaMinGroup) {
+      if (sqa::plan_decode(layers, n_layers, B, Hq, Hkv, D, h2o, wpu != 0, true, &p) != SQA_OK) return 0;
+      bytes = p.bytes > bytes ? p.bytes : bytes;
+    }
   }
   return bytes;
 }
@@ -1208,7 +1227,7 @@ static sqa_status decode_launch(decode_fn fn, const DecodePlan& plan, size_t lds
     const int l = a.order[i];
     run += plan.wpu[l] ? ((uint64_t)B * Hkv + kDecWaves - 1) / kDecWaves : (uint64_t)B * Hkv * plan.nsplit[l];
     a.blk_end[i] = (uint32_t)run;
-    a.lay[i].nsplit = plan.nsplit[i] | (plan.wpu[i] ? kWpuBit : 0u) | (plan.probs_in_lds[i] ? kLdsProbsBit : 0u);
+    a.lay[i].nsplit = plan.nsplit[i] | (plan.wpu[i] ? kWpuBit : 0u) | ((uint32_t)plan.lds_tiles[i] << kLdsTilesShift);
     a.lay[i].chunk = plan.chunk[i];
     a.lay[i].unit_off = plan.unit_off[i];
     a.lay[i].part_off = plan.part_off[i];

@@ -53,7 +53,8 @@ def test_stress_mistral_70b_launches():
     p, b, _ = _plan("mistral_7b", policy="h2o")
     assert all(l["probs_in_lds"] == 1 for l in p["layers"])
     p, b, _ = _plan("llama2_70b", policy="h2o")
-    assert [l["probs_in_lds"] for l in p["layers"]] == [1 if x == 491 else 0 for x in b]
+    # (a 3439-token unit keeps what fits -- its leading tiles -- and passes the rest through the workspace)
+    assert [l["probs_in_lds"] for l in p["layers"]] == [1 if x == 491 else 2 for x in b]
     assert p["lds_bytes"] <= 160 * 1024 // 3                                  # three workgroups per CU
 
 

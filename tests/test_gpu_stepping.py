@@ -113,11 +113,18 @@ def test_stepping_whole_long_units_in_a_small_call(sqa, order):
 
 
 def test_stepping_matrix_core_units_at_the_lds_limit(sqa):
-    """8 query heads per KV head, 208 whole units of 1050 slots: the largest units whose per-head
-    probabilities of a step (33 tiles x 8 heads x 68 bytes) still fit in LDS next to the stage buffers;
-    the second layer (1200 slots) is just beyond and keeps them in the workspace."""
-    _run_case(sqa, ("h2o_bf16_gqa8_matrix_lds_limit", "bf16", 64, 8, 128, 26, 1250, 10, "h2o", [1050, 1200],
+    """8 query heads per KV head, 208 whole units per layer.  1050 slots: the largest units whose per-head
+    probabilities of a step (33 tiles x 8 heads x 68 bytes) all fit in LDS next to the stage buffers; 1200 and
+    2300 slots: the leading 33 tiles stay in LDS, the other 5 / 39 pass through the workspace."""
+    _run_case(sqa, ("h2o_bf16_gqa8_matrix_lds_limit", "bf16", 64, 8, 128, 26, 2400, 10, "h2o", [1050, 1200, 2300],
                     "evict_then_attend"), stride=37)
+
+
+def test_stepping_matrix_core_long_units_attend_first_blocked(sqa):
+    """The same split of a unit's probabilities between LDS and workspace under attend-then-evict, with K and V
+    in 16-row blocks (the staged block numbers take their share of the LDS: 32 tiles stay)."""
+    _run_case(sqa, ("h2o_bf16_gqa8_matrix_lds_limit_ae", "bf16", 64, 8, 128, 26, 1500, 8, "h2o", [1100, 1400],
+                    "attend_then_evict"), stride=41, blocked=True)
 
 
 @pytest.mark.parametrize("case", [STEPPING[0], STEPPING[2], STEPPING[3], STEPPING[5], STEPPING[7]],
