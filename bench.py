@@ -212,6 +212,14 @@ def other_workloads(main_sess, say):
                 "tokens_per_s_gain_equal_memory": round(leg["tokens_per_s"] / eq_mem["tokens_per_s"], 2)}
         del sess
         gc.collect(); torch.cuda.empty_cache()
+    # H2O with grouped queries (the matrix-core variant that also accumulates scores): not a combination the
+    # paper's throughput table uses, measured because the kernel supports it
+    for name, steps in (("mistral_7b", 64), ("llama2_70b", 32)):
+        say("%s under H2O, %d decode steps" % (name, steps))
+        sess = Session(W.scaled(W.WORKLOADS[name], S=steps, policy="h2o"), "cuda:0", probe_tokens=4096)
+        out.append(decode_leg(sess, name + " --policy h2o"))
+        del sess
+        gc.collect(); torch.cuda.empty_cache()
     return out
 
 
