@@ -38,6 +38,24 @@ __device__ __forceinline__ int block_excl_count(bool flag, int* s_wave_tot, int&
   return before + within;
 }
 
+// inclusive prefix sum of v over the 256 threads
+__device__ __forceinline__ int block_incl_sum(int v, int* s_wave_tot) {
+  const int lane = threadIdx.x & (SQA_WAVE - 1), wave = threadIdx.x / SQA_WAVE;
+  int x = v;
+#pragma unroll
+  for (int o = 1; o < SQA_WAVE; o <<= 1) {
+    const int y = __shfl_up(x, o, SQA_WAVE);
+    x += lane >= o ? y : 0;
+  }
+  __syncthreads();                        // previous users of s_wave_tot are done
+  if (lane == SQA_WAVE - 1) s_wave_tot[wave] = x;
+  __syncthreads();
+  int before = 0;
+#pragma unroll
+  for (int w = 0; w < kCmpWaves; ++w) before += w < wave ? s_wave_tot[w] : 0;
+  return before + x;
+}
+
 constexpr int kCmpBatch = 32;             // layers per launch (their descriptors travel as kernel arguments)
 struct CompressBatch {
   sqa_layer_cache L[kCmpBatch];
@@ -149,11 +167,12 @@ __global__ __launch_bounds__(kCmpThreads) void prefill_compress_kernel(
         if ((key & mask) == prefix) atomicAdd(&s_hist[(key >> sh) & 255u], 1);
       }
       __syncthreads();
-      if (tid == 0) {
-        int cum = 0, v = 255;
-        for (; v > 0; --v) { if (cum + s_hist[v] >= k) break; cum += s_hist[v]; }
-        s_sel[0] = (uint32_t)v; s_sel[1] = (uint32_t)(k - cum);
-      }
+      // the digit of the k-th largest key: thread t looks at bin 255 - t; the sum over the bins above and
+      // including its own reaches k in exactly one non-empty bin (at least k keys carry the prefix)
+      static_assert(kCmpThreads == 256, "one thread per histogram bin");
+      const int h = s_hist[255 - tid];
+      const int incl = block_incl_sum(h, s_wave_tot);
+      if (incl >= k && incl - h < k) { s_sel[0] = (uint32_t)(255 - tid); s_sel[1] = (uint32_t)(k - (incl - h)); }
       __syncthreads();
       prefix |= s_sel[0] << sh; mask |= 255u << sh; k = (int)s_sel[1];
       __syncthreads();
@@ -167,7 +186,7 @@ __global__ __launch_bounds__(kCmpThreads) void prefill_compress_kernel(
     for (int base = 0; base < M; base += kCmpThreads) {
       const int i = base + tid;
       const bool cand = i < M;
-      const uint32_t key = cand ? score_key(sc[i]) : 0u;
+      const uint32_t key = cand ? (keys_in_lds ? s_keys[i] : score_key(sc[i])) : 0u;
       const bool eq = cand && key == thr;
       int eq_tot;
       const int eq_rank = eq_seen + block_excl_count(eq, s_wave_tot, eq_tot);
