@@ -3,6 +3,8 @@ the same seeded inputs.  Everything here goes through the C ABI (binding.py is
 argument marshalling only).  Tolerances: 1e-5 relative for fp32 inputs, 2e-2
 for bf16 (per output vector, max|x-ref|/max|ref|); kept indices, lengths and
 budgets bit-exact."""
+import os
+
 import numpy as np
 import pytest
 import torch
@@ -303,7 +305,8 @@ def _random_cases(n, seed=2024):
     return out
 
 
-RANDOM_CASES = _random_cases(28)
+# (SQA_RANDOM_CASES=1500 python -m pytest tests/test_gpu_parity.py -m gpu -k teacher_forced  runs a longer campaign)
+RANDOM_CASES = _random_cases(int(os.environ.get("SQA_RANDOM_CASES", "28")))
 
 
 @pytest.mark.parametrize("case", CASES + RANDOM_CASES, ids=[c[0] for c in CASES + RANDOM_CASES])
