@@ -117,8 +117,26 @@ def build_microbench(verbose: bool = True) -> str:
     return exe
 
 
+def build_demo(verbose: bool = True) -> str:
+    """tests/c_abi_demo.cpp -> _build/c_abi_demo: the library used from plain C++ through include/sqa.h
+    (needs libsqa.so built; tests/test_gpu_c_abi_demo.py runs it on the GPU)."""
+    os.makedirs(OBJ_DIR, exist_ok=True)
+    exe = os.path.join(OBJ_DIR, "c_abi_demo")
+    cmd = [_hipcc(), "-O2", "-std=c++17", "--offload-arch=gfx950", "-Wno-unused-command-line-argument", "-Wno-unused-result",
+           "-I" + os.path.join(ROOT, "include"), os.path.join(ROOT, "tests", "c_abi_demo.cpp"),
+           "-L" + HERE, "-lsqa", "-Wl,-rpath," + HERE, "-o", exe]
+    r = subprocess.run(cmd, capture_output=True, text=True)
+    if r.returncode != 0:
+        raise RuntimeError("compile failed: %s\n%s" % (" ".join(cmd), r.stderr))
+    if verbose:
+        print("built", exe)
+    return exe
+
+
 if __name__ == "__main__":
-    if "--microbench" in sys.argv[1:]:
+    if "--demo" in sys.argv[1:]:
+        build_demo()
+    elif "--microbench" in sys.argv[1:]:
         build_microbench()
     else:
         build()
