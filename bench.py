@@ -223,6 +223,49 @@ def other_workloads(main_sess, say):
     return out
 
 
+def launch_floor(args, wl):
+    """What a single-layer decode call costs on the GPU whatever it streams: four groups of 100 launches over the
+    units of ONE layer of the workload's shape (budget 143 tokens), each followed by a synchronisation so that a
+    kernel trace (rocprofv3 --kernel-trace) shows them one by one, in this order: the H2O step; the same launch
+    with every sequence sitting out (a workgroup returns after its first requests); the step with a sliding
+    window; a sitting-out launch over 8-token units.  Prints its own HIP-event medians, which include the gap
+    between two events (a few microseconds): the trace is the measurement."""
+    import torch
+    from paper_2404_04793_amd import binding as sqa
+    dev, n = "cuda:0", 100
+    B, H, D, P = wl.B, wl.Hkv, wl.D, wl.P
+    res = []
+    for label, budget, policy, sit in (("h2o_143", 143, "h2o", False), ("h2o_143_sitting_out", 143, "h2o", True),
+                                       ("sliding_143", 143, "sliding", False), ("h2o_8_sitting_out", 8, "h2o", True)):
+        caches = sqa.LayerCaches([budget], [min(budget, P + n + 40)], B, H, D, wl.torch_dtype, dev, True)
+        K = torch.randn(B, H, P, D, device=dev).to(wl.torch_dtype)
+        V = torch.randn(B, H, P, D, device=dev).to(wl.torch_dtype)
+        sc = torch.rand(B, H, P, device=dev)
+        sqa.prefill_compress(K, V, sc if policy == "h2o" else None, policy, wl.n_sink, caches, 0)
+        ws = sqa.decode_workspace(caches, wl.Hq, policy)
+        q = torch.randn(1, B, wl.Hq, D, device=dev).to(wl.torch_dtype)
+        kv = torch.randn(1, B, H, D, device=dev).to(wl.torch_dtype)
+        out = torch.empty_like(q)
+        pos = torch.full((B,), -1 if sit else P, dtype=torch.int32, device=dev)
+        opts = sqa.batch_opts(new_pos_seq=pos)
+        times = []
+        for i in range(n):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            sqa.decode_step(q, kv, kv, 0, policy, wl.n_sink, caches, out, ws, opts=opts)
+            e1.record()
+            torch.cuda.synchronize()
+            times.append(e0.elapsed_time(e1) * 1e3)
+            if not sit:
+                pos += 1
+        assert sqa.read_device_status(ws) == 0
+        times = sorted(times[10:])
+        res.append({"launches": label, "units": B * H, "median_us_between_events": round(times[len(times) // 2], 2)})
+    print(json.dumps({"metric": "single-layer decode launch, microseconds (see the kernel trace)", "config": {"workload": wl.name},
+                      "groups_in_launch_order": res}))
+    return 0
+
+
 def scores_only(args, wl):
     """The prompt-score producer alone: per layer one sqa_prefill_scores call (two kernels, row statistics then
     column sums) on generated prompt queries and keys; 2 passes x B*Hq*P(P+1)/2 logits x 2*D flops per layer."""
@@ -318,6 +361,8 @@ def main():
     ap.add_argument("--calib-copy", action="store_true",
                     help="after the timed region run one plain 1 GiB -> 1 GiB elementwise copy kernel "
                          "(reference point for scaling rocprofv3's FETCH_SIZE / WRITE_SIZE counters)")
+    ap.add_argument("--launch-floor", action="store_true",
+                    help="single-layer decode launches one by one, with and without work, for a kernel trace")
     ap.add_argument("--scores-only", action="store_true",
                     help="time only the H2O prompt-score producer (sqa_prefill_scores; set-up work of the pass, "
                          "matrix-core bound): a step = the scores of all layers of one prompt batch")
@@ -356,6 +401,8 @@ def main():
     torch.cuda.set_device(0)
     if args.scores_only:
         return scores_only(args, wl)
+    if args.launch_floor:
+        return launch_floor(args, wl)
     plen = [wl.P - (b * wl.P) // (2 * wl.B) for b in range(wl.B)] if args.ragged else None
     def say(what):
         if args.progress:
