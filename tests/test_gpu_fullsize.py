@@ -180,6 +180,14 @@ def test_mistral_7b_full_size():
                   probe_tokens=4096)
 
 
+def test_mistral_7b_full_size_under_h2o():
+    """The Mistral shape at its real batch and layer count under H2O (the policy configs[2] does not use; a leg
+    of bench.py): 4 query heads per KV head on the matrix cores, every unit's probabilities of a step in LDS."""
+    wl = W.scaled(W.WORKLOADS["mistral_7b"], S=6, policy="h2o")
+    _run_fullsize(wl, sample_layers=[0, 20], units=[(0, 0), (31, 7)], check_steps={0, 5}, cos_layers=[1],
+                  probe_tokens=4096)
+
+
 def test_llama2_70b_full_size():
     """configs[3] at its real batch (16) and all 80 layers, in the launch bench.py times; 8 decode steps."""
     wl = W.scaled(W.WORKLOADS["llama2_70b"], S=8)
