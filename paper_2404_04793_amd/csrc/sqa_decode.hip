@@ -60,8 +60,7 @@ struct DecodeArgs {
   // one scalar load whose base address was only 2-byte aligned, and scalar
   // loads drop the low address bits of the base (the wrong entry was read).
   struct Layer {
-    uint32_t nsplit;      // chunks per unit; bit 31: one wave per unit (a workgroup covers 4 units);
-                          // bit 30: the step's per-head probabilities (matrix-core variant under H2O) stay in LDS
+    uint32_t nsplit;      // chunks per unit, with the tile count and the flag described below the struct
     uint32_t chunk;       // slots per chunk
     uint32_t unit_off;    // first unit number of the layer within the call
     uint32_t part_off;    // first partial record
