@@ -97,6 +97,20 @@ __global__ __launch_bounds__(256) void persistent(const v4u* __restrict__ p, con
   }
 }
 
+// the same bytes per workgroup written as PIECES separate runs of `run` bytes each, `stride` bytes apart
+// (run * pieces = the bytes per workgroup; stride >= run): does a written byte cost the same whatever it lies next to?
+__global__ __launch_bounds__(256) void per_item_pieces(const v4u* __restrict__ p, unsigned rd_n, char* wbuf, int run, int pieces,
+                                                       size_t stride, size_t wg_pitch, uint4* sink) {
+  const v4u acc = read_region<4>(p + (size_t)blockIdx.x * rd_n, rd_n);
+  char* w = wbuf + (size_t)blockIdx.x * wg_pitch;
+  const int per_piece = run / 4;                              // floats
+  for (int i = threadIdx.x; i < per_piece * pieces; i += 256) {
+    const int pc = i / per_piece, k = i % per_piece;
+    reinterpret_cast<float*>(w + (size_t)pc * stride)[k] = __uint_as_float(acc.x) + i;
+  }
+  if ((acc.x ^ acc.y ^ acc.z ^ acc.w) == 0x12345678u) sink[blockIdx.x] = make_uint4(acc.x, acc.y, acc.z, acc.w);
+}
+
 int main() {
   hipEvent_t e0, e1; CK(hipEventCreate(&e0)); CK(hipEventCreate(&e1));
   uint4* sink; CK(hipMalloc(&sink, 1 << 20));
@@ -142,6 +156,23 @@ int main() {
           timed(nm, bytes, [&] { CK(hipMemsetAsync(queue, 0, 4)); persistent<true, 6912><<<1024, 256>>>(p, d, n, queue, wb, sink, wr); });
         }
       }
+    }
+  }
+  // ---- A2. 2304 bytes per workgroup in runs of different length ------------------------------------------------
+  {
+    const int n = 8192; const unsigned rd_n = 13600;
+    const size_t bytes = (size_t)n * rd_n * 16;
+    v4u* p; CK(hipMalloc(&p, bytes)); CK(hipMemset(p, 1, bytes));
+    const size_t pitch = 144 * 4096;                                    // room for 144 pieces 4 KB apart
+    char* wb; CK(hipMalloc(&wb, (size_t)n * pitch));
+    std::printf("A2. %d items of %.1f KB read; 2304 bytes written per item as separate runs\n", n, rd_n * 16 / 1024.0);
+    struct { int run, pieces; size_t stride; const char* what; } cases[] = {
+      {2304, 1, 2304, "1 run of 2304 B"}, {256, 9, 4096, "9 runs of 256 B, 4 KB apart"}, {256, 9, 256, "9 runs of 256 B, adjacent"},
+      {128, 18, 4096, "18 runs of 128 B, 4 KB apart"}, {64, 36, 4096, "36 runs of 64 B, 4 KB apart"}, {64, 36, 128, "36 runs of 64 B, one per 128-byte line"},
+      {16, 144, 4096, "144 runs of 16 B, 4 KB apart"}, {16, 144, 128, "144 runs of 16 B, one per 128-byte line"}};
+    for (auto& cs : cases) {
+      std::snprintf(nm, 160, "%s", cs.what);
+      timed(nm, bytes, [&] { per_item_pieces<<<n, 256>>>(p, rd_n, wb, cs.run, cs.pieces, cs.stride, pitch, sink); });
     }
   }
   // ---- B. the items of the decode launch at the Llama-2-7B shape --------------------------------------------
