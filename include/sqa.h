@@ -12,6 +12,10 @@
  *                                     C_seq applied with the layer's own budget)
  *   decode:   sqa_decode_step        (steps 14-21 with Eq. 2-3: append, evict if
  *                                     over budget, attention, H2O accumulation)
+ *   Around them: *_ex forms for batches whose sequences differ (sqa_batch_opts),
+ *   sqa_prefill_scores_lse, sqa_residual_add_importance, sqa_decode_plan (what a
+ *   decode call would launch), sqa_kept_idx_sorted, and for K/V kept in 16-row
+ *   blocks (sqa_layer_cache.block_table) the host free list sqa_block_pool_*.
  *
  * Conventions
  *   - "DEVICE" pointers are HIP device memory owned by the caller and borrowed
@@ -22,7 +26,10 @@
  *     (apart from remembering which kernels it has already allowed to use
  *     more than 64 KiB of on-chip memory on a device); scratch
  *     space comes in through `workspace` (DEVICE, 256-byte aligned), whose
- *     minimum size the matching *_workspace_bytes call returns.
+ *     minimum size the matching *_workspace_bytes call returns.  Two exceptions,
+ *     both stated where they are declared: sqa_decode_step_static keeps its
+ *     scratch in a device array of the library image, and a sqa_block_pool is a
+ *     host object that the caller creates and destroys.
  *   - Arguments are validated on the host before any HIP call is made; on an
  *     error nothing is enqueued and no output is touched.  Kernels are
  *     enqueued asynchronously; nothing synchronises the stream except
