@@ -270,7 +270,10 @@ sqa_status sqa_prefill_compress_layers(const void* const* K, const void* const* 
                                        sqa_policy policy, int n_sink, const sqa_layer_cache* layers, int n_layers,
                                        void* stream);
 /* With opts->prompt_len / opts->budget_seq: unit (b, h) of layer l compresses
- * the first prompt_len[b] tokens to budget_seq[l][b].  opts may be NULL. */
+ * the first prompt_len[b] tokens to budget_seq[l][b] and needs min(prompt_len[b],
+ * budget_seq[l][b]) slots (of layers[l].capacity, or of its own range with
+ * unit_offset).  The host cannot see these values: a unit with too few slots is
+ * left empty and SQA_ERR_CAPACITY is written to opts->status.  opts may be NULL. */
 sqa_status sqa_prefill_compress_layers_ex(const void* const* K, const void* const* V, sqa_dtype kv_dt,
                                           const float* const* attn_scores, int B, int Hkv, int P, int D,
                                           sqa_policy policy, int n_sink, const sqa_layer_cache* layers, int n_layers,

@@ -285,14 +285,17 @@ static sqa_status check_compress_layer(const void* K, const void* V, sqa_dtype k
   if (!aligned16(K) || !aligned16(V) || !aligned16(L.K) || !aligned16(L.V) || !aligned16(L.unit_state)) return SQA_ERR_SHAPE;
   const int min_budget = policy == SQA_H2O ? 2 : (policy == SQA_STREAMING ? n_sink + 1 : 1);
   if (L.budget < min_budget) return SQA_ERR_BUDGET;
+  // (with per-sequence lengths or budgets a unit needs min(its prompt length, its budget) slots, which only
+  // the kernel can see: it leaves a unit that has too few empty and reports SQA_ERR_CAPACITY through opts->status)
   const int n_keep = P < L.budget ? P : L.budget;
-  if (L.capacity < n_keep) return SQA_ERR_CAPACITY;
+  if (ragged ? L.capacity < 1 : L.capacity < n_keep) return SQA_ERR_CAPACITY;
   if (L.block_table) {                                     // blocked allocation of K and V
     if (L.unit_offset || L.n_blocks < 1 || L.blocks_per_unit > SQA_MAX_BLOCKS_PER_UNIT ||
         (int64_t)L.blocks_per_unit * SQA_BLOCK_SLOTS < (L.budget < L.capacity ? L.budget : L.capacity))
       return SQA_ERR_SHAPE;
   }
-  // the prompt tensors must not overlap the cache they are gathered into
+  // the prompt tensors must not overlap the cache they are gathered into (checked where the host knows the
+  // cache's extent: packed units end at unit_offset[B*Hkv], which lies in device memory)
   const size_t eb = kv_dt == SQA_F32 ? 4 : 2;
   const size_t in_bytes = (size_t)B * Hkv * P * D * eb;
   const size_t c_bytes = (L.block_table ? (size_t)L.n_blocks * SQA_BLOCK_SLOTS : (size_t)B * Hkv * L.capacity) * D * eb;
@@ -300,8 +303,8 @@ static sqa_status check_compress_layer(const void* K, const void* V, sqa_dtype k
     const uintptr_t x = reinterpret_cast<uintptr_t>(a), y = reinterpret_cast<uintptr_t>(b);
     return x < y + nb && y < x + na;
   };
-  if (overlaps(K, in_bytes, L.K, c_bytes) || overlaps(K, in_bytes, L.V, c_bytes) ||
-      overlaps(V, in_bytes, L.K, c_bytes) || overlaps(V, in_bytes, L.V, c_bytes)) return SQA_ERR_SHAPE;
+  if (!L.unit_offset && (overlaps(K, in_bytes, L.K, c_bytes) || overlaps(K, in_bytes, L.V, c_bytes) ||
+                         overlaps(V, in_bytes, L.K, c_bytes) || overlaps(V, in_bytes, L.V, c_bytes))) return SQA_ERR_SHAPE;
   // H2O candidates of a unit: at most P - (b - b/2) with the layer's budget, up to P - 1 with a smaller
   // per-sequence budget; their keys are staged in LDS when they fit
   const bool h2o_select = policy == SQA_H2O && (ragged ? P > 2 : P > L.budget);

@@ -312,3 +312,37 @@ def test_a_new_sequence_takes_a_finished_ones_place(sqa, blocked):
             used = [x for x in caches.block_table[l].flatten().tolist() if x >= 0]
             need1 = (min(new_budget[l], new_len + S) + 15) // 16
             assert len(set(used)) == len(used) and len(used) == 2 * Hkv * caches.block_table[l].shape[1] + Hkv * need1
+
+
+def test_packed_units_smaller_than_the_layer_budget_and_next_to_the_prompt(sqa):
+    """Two things the host cannot know with packed units and per-sequence values, and must therefore not
+    refuse: (1) the largest unit of a layer may have fewer slots than min(P, the layer's budget) -- a long
+    prompt with a small budget beside a short prompt with a large one; (2) the packed cache ends at
+    unit_offset[B*Hkv], far before B*Hkv*capacity rows, so a prompt tensor that follows it directly in memory
+    does not overlap it.  (Both were rejected with SQA_ERR_CAPACITY / SQA_ERR_SHAPE before.)"""
+    dtype, Hkv, D, B, P, S, policy = "bf16", 1, 128, 2, 40, 4, "sliding"
+    plen, budget_seq = [40, 6], [[5, 30]]
+    unit_caps = [[min(budget_seq[0][b], plen[b] + S) for b in range(B)]]          # [5, 10]: capacity 10 < min(40, 30)
+    caches = sqa.LayerCaches([30], [max(unit_caps[0])], B, Hkv, D, torch.bfloat16, DEV, True, unit_capacities=unit_caps)
+    total = caches.total_slots(0)
+    assert total == 15 and B * Hkv * caches.capacities[0] > total
+    wl = W.scaled(W.WORKLOADS["tiny"], L=1, Hq=Hkv, Hkv=Hkv, D=D, B=B, P=P, S=S, dtype=dtype, policy=policy)
+    u_dirs, mask = W.unit_dirs(wl), W.hh_mask(wl, DEV)
+    K0, V0 = W.prompt_kv(wl, 0, DEV, u_dirs, mask)
+    # one buffer: the 15 rows of the packed K cache, then the prompt's K rows right behind them
+    big = torch.zeros(total + B * Hkv * P, D, dtype=torch.bfloat16, device=DEV)
+    Kp = big[total:].view(B, Hkv, P, D)
+    Kp.copy_(K0)
+    caches.K[0] = big[:total]
+    caches.table[0].K = caches.K[0].data_ptr()
+    status = torch.zeros(1, dtype=torch.int32, device=DEV)
+    opts = sqa.batch_opts(prompt_len=_i32(plen), budget_seq=_i32(budget_seq), status=status)
+    sqa.prefill_compress_layers([Kp], [V0], None, policy, wl.n_sink, caches, opts=opts)
+    assert int(status.item()) == 0
+    assert torch.equal(Kp, K0)                                                   # the prompt behind the cache is untouched
+    Kn, Vn = np64(K0), np64(V0)
+    for b in range(B):
+        want = O.prefill_compress(Kn[b, 0, :plen[b]], Vn[b, 0, :plen[b]], None, budget_seq[0][b], policy, wl.n_sink)
+        got = export_state(caches, 0, b, 0)
+        assert got["pos"].tolist() == want["pos"].tolist()
+        assert np.array_equal(got["K"], want["K"]) and np.array_equal(got["V"], want["V"])
