@@ -111,6 +111,54 @@ def test_prefill_scores(sqa, dtype, B, Hq, Hkv, P, D):
             assert abs(got[b, h].sum() - g * P) < 1e-3 * g * P
 
 
+def _random_score_cases(n, seed=606):
+    r = np.random.default_rng(seed)
+    out = []
+    for k in range(n):
+        dtype = ["bf16", "f32"][int(r.integers(2))]
+        D, g = [64, 128][int(r.integers(2))], [1, 2, 4, 8][int(r.integers(4))]
+        Hkv, B = int(r.integers(1, 4)), int(r.integers(1, 4))
+        P = int(r.choice([1, 2, 15, 16, 17, 31, 33, 63, 64, 65, 127, 128, 129, 200, 255, 257, 384, 500, 777]))
+        ragged = bool(r.integers(2))
+        plen = [int(r.integers(0, P + 1)) if ragged else P for _ in range(B)]
+        out.append(("sc%02d_%s_D%d_g%d_P%d%s" % (k, dtype, D, g, P, "_ragged" if ragged else ""), dtype, D, g, Hkv, B, P, plen,
+                    ragged, int(r.integers(3)) == 0))
+    return out
+
+
+# (SQA_RANDOM_CASES=1500 python -m pytest tests/test_gpu_parity.py -m gpu -k random_shapes  runs a longer campaign)
+RANDOM_SCORES = _random_score_cases(max(1, int(os.environ.get("SQA_RANDOM_CASES", "28")) // 2))
+
+
+@pytest.mark.parametrize("case", RANDOM_SCORES, ids=[c[0] for c in RANDOM_SCORES])
+def test_prefill_scores_random_shapes(sqa, case):
+    """The score producer on seeded random shapes (prompt lengths around its tile sizes, per-sequence lengths down
+    to zero, a wider logit range in a third of the cases): two passes, and one pass from the oracle's normalisers."""
+    _, dtype, D, g, Hkv, B, P, plen, ragged, wide = case
+    wl = W.scaled(W.WORKLOADS["tiny"], L=1, Hq=Hkv * g, Hkv=Hkv, D=D, B=B, P=P, dtype=dtype)
+    K, _ = W.prompt_kv(wl, 0, DEV)
+    Q = W.prompt_q(wl, 0, DEV)
+    if wide:
+        K, Q = (K.float() * 3).to(K.dtype), (Q.float() * 2).to(Q.dtype)
+    opts = sqa.batch_opts(prompt_len=torch.tensor(plen, dtype=torch.int32, device=DEV)) if ragged else None
+    got = sqa.prefill_scores(Q, K, opts=opts).cpu().numpy().astype(np.float64)
+    Qn, Kn = np64(Q), np64(K)
+    for b in range(B):
+        for h in range(Hkv):
+            m = plen[b]
+            if m:
+                ref = O.prefill_scores(Qn[b, h * g:(h + 1) * g, :m], Kn[b, h, :m])
+                assert rel_err(got[b, h, :m], ref) < TOL[dtype]
+                assert abs(got[b, h, :m].sum() - g * m) < 2e-3 * g * m
+            assert np.all(got[b, h, m:] == 0.0)
+    if not ragged:
+        lse = np.stack([np.stack([O.prefill_row_lse(Qn[b, hq:hq + 1], Kn[b, hq // g])[0] for hq in range(Hkv * g)]) for b in range(B)])
+        got2 = sqa.prefill_scores(Q, K, row_lse=torch.tensor(lse, dtype=torch.float32, device=DEV)).cpu().numpy().astype(np.float64)
+        for b in range(B):
+            for h in range(Hkv):
+                assert rel_err(got2[b, h], O.prefill_scores(Qn[b, h * g:(h + 1) * g], Kn[b, h])) < TOL[dtype]
+
+
 def _wide_range_qk(case, P, Hq, Hkv, D):
     """Queries and keys that share one direction u; the keys' component along u sets the logit level."""
     r = torch.Generator().manual_seed({"steps_up": 11, "late_peak": 12, "steps_down": 13}[case])

@@ -2,6 +2,8 @@
 budgets per sequence, sequences that sit a step out, per-sequence cosines.
 The oracle works one (layer, sequence, KV head) unit at a time, so it needs no
 notion of a ragged batch: each unit is simply given its own lengths."""
+import os
+
 import numpy as np
 import pytest
 import torch
@@ -72,17 +74,54 @@ def test_ragged_batch_end_to_end(sqa, policy, g, packed):
     compress -> decode (teacher forced), one of them sitting out some steps.  g = 8 takes the
     matrix-core variant of the decode kernel; packed: every unit owns exactly the slots its own
     budget needs (unit_offset) instead of the layer's maximum."""
-    dtype, L, Hkv, D, B, P, S = "bf16", 2, 2, 128, 3, 150, 7
-    Hq = Hkv * g
-    plen = [150, 61, 9]
     lo = {"sliding": 1, "streaming": 5, "h2o": 2}[policy]
-    budget_seq = [[40, 13, max(lo, 6)], [153, 70, 12]]            # [L][B]
+    _ragged_case(sqa, policy, g, packed, False, "bf16", 128, 2, 2, 3, 150, 7, [150, 61, 9],
+                 [[40, 13, max(lo, 6)], [153, 70, 12]], lambda b, t: [True, t % 3 != 1, t < 5][b])
+
+
+def _random_ragged_cases(n, seed=515):
+    r = np.random.default_rng(seed)
+    out = []
+    for k in range(n):
+        dtype = ["bf16", "f32"][int(r.integers(2))]
+        D = [64, 128][int(r.integers(2))]
+        g = [1, 2, 4, 8][int(r.integers(4))]
+        Hkv, B, L = int(r.integers(1, 4)), int(r.integers(2, 6)), int(r.integers(1, 4))
+        P, S = int(r.choice([40, 97, 150, 260, 420])), int(r.integers(3, 8))
+        policy = ["sliding", "streaming", "h2o"][int(r.integers(3))]
+        lo = {"sliding": 1, "streaming": 5, "h2o": 2}[policy]
+        plen = [P] + [int(r.integers(1, P + 1)) for _ in range(B - 1)]
+        budget_seq = [[int(max(lo, r.choice([r.integers(lo, lo + 8), r.integers(lo, P), plen[b], plen[b] + 3])))
+                       for b in range(B)] for _ in range(L)]
+        layout = int(r.integers(3))
+        out.append(("rag%02d_%s_%s_D%d_g%d_%s" % (k, policy, dtype, D, g, ["dense", "packed", "blocked"][layout]),
+                    policy, g, layout == 1, layout == 2, dtype, D, L, Hkv, B, P, S, plen, budget_seq, int(r.integers(2, 5))))
+    return out
+
+
+# (SQA_RANDOM_CASES=1500 python -m pytest tests/test_gpu_ragged.py -m gpu -k random  runs a longer campaign)
+RANDOM_RAGGED = _random_ragged_cases(max(1, int(os.environ.get("SQA_RANDOM_CASES", "28")) // 2))
+
+
+@pytest.mark.parametrize("case", RANDOM_RAGGED, ids=[c[0] for c in RANDOM_RAGGED])
+def test_ragged_random_batches(sqa, case):
+    """Seeded random batches: 2-5 sequences with their own prompt lengths and per-layer budgets (below, at
+    and above their lengths), sitting out every 2nd-4th step in turn, in the dense, packed or blocked layout."""
+    _, policy, g, packed, blocked, dtype, D, L, Hkv, B, P, S, plen, budget_seq, sit_mod = case
+    _ragged_case(sqa, policy, g, packed, blocked, dtype, D, L, Hkv, B, P, S, plen, budget_seq,
+                 lambda b, t: (b + t) % sit_mod != sit_mod - 1 or b == 0)
+
+
+def _ragged_case(sqa, policy, g, packed, blocked, dtype, D, L, Hkv, B, P, S, plen, budget_seq, is_active):
+    tdt = torch.float32 if dtype == "f32" else torch.bfloat16
+    Hq = Hkv * g
     layer_budget = [max(r) for r in budget_seq]
     wl = W.scaled(W.WORKLOADS["tiny"], L=L, Hq=Hq, Hkv=Hkv, D=D, B=B, P=P, S=S, dtype=dtype, policy=policy)
     u_dirs, mask = W.unit_dirs(wl), W.hh_mask(wl, DEV)
     unit_caps = [[min(budget_seq[l][b], plen[b] + S) for b in range(B) for _ in range(Hkv)] for l in range(L)]
     caches = sqa.LayerCaches(layer_budget, [max(c) for c in unit_caps] if packed else [min(b, P + S) for b in layer_budget],
-                             B, Hkv, D, torch.bfloat16, DEV, True, unit_capacities=unit_caps if packed else None)
+                             B, Hkv, D, tdt, DEV, True, unit_capacities=unit_caps if packed else None,
+                             blocked=blocked, block_seed=P)
     status = torch.zeros(1, dtype=torch.int32, device=DEV)
     plen_d, bseq_d = _i32(plen), _i32(budget_seq)
     opts_pre = sqa.batch_opts(prompt_len=plen_d, budget_seq=bseq_d, status=status)
@@ -116,11 +155,11 @@ def test_ragged_batch_end_to_end(sqa, policy, g, packed):
     pos_now = list(plen)
     worst = 0.0
     for t in range(S):
-        active = [True, t % 3 != 1, t < 5]
+        active = [is_active(b, t) for b in range(B)]
         new_pos = [pos_now[b] if active[b] else -1 for b in range(B)]
         for key, c in state.items():
             import_state(caches, key[0], key[1], key[2], c)
-        out = torch.full((L, B, Hq, D), 7.0, dtype=torch.bfloat16, device=DEV)
+        out = torch.full((L, B, Hq, D), 7.0, dtype=tdt, device=DEV)
         sqa.decode_step(q_all[t], k_all[t], v_all[t], 0, policy, wl.n_sink, caches, out, ws,
                         opts=sqa.batch_opts(budget_seq=bseq_d, new_pos_seq=_i32(new_pos)))
         assert sqa.read_device_status(ws) == 0

@@ -11,6 +11,8 @@ says will go next must be the token the oracle's selection drops when the next t
 Covered: the vector-ALU kernel with 4 waves per unit (whole and split units) and one wave per unit, the
 matrix-core kernel (4 and 8 query heads per KV head; whole, split, one wave per unit), both orders of a
 step, fp32 and bf16."""
+import os
+
 import numpy as np
 import pytest
 import torch
@@ -134,7 +136,9 @@ def test_stepping_with_blocked_allocation(sqa, case):
     _run_case(sqa, case, blocked=True)
 
 
-def _run_case(sqa, case, stride=1, blocked=False):
+def _run_case(sqa, case, stride=1, blocked=False, need_both_outcomes=True):
+    """need_both_outcomes: the case is built so that units evict and, under H2O, both results of the carried
+    decision occur (the random shapes make no such promise: a budget above everything never evicts)."""
     name, dtype, Hq, Hkv, D, B, P, S, policy, budgets, order = case
     L, g = len(budgets), Hq // Hkv
     wl = W.scaled(W.WORKLOADS["tiny"], L=L, Hq=Hq, Hkv=Hkv, D=D, B=B, P=P, S=S, dtype=dtype, policy=policy)
@@ -157,6 +161,8 @@ def _run_case(sqa, case, stride=1, blocked=False):
     seen = _step_and_compare(sqa, caches, ws, budgets, policy, order, dtype, D, g, P, S, q_all, k_all, v_all, rows, sample,
                              wl.n_sink)
     print(name, order, seen)
+    if not need_both_outcomes:
+        return
     assert seen["evictions"] > 0
     if policy == "h2o" and order == "evict_then_attend":
         assert seen["leaver_goes"] > 0 and seen["heavy_goes"] > 0, seen       # both outcomes of the carried decision
@@ -190,3 +196,34 @@ def test_stepping_one_wave_per_unit(sqa, dtype, D, g, order, blocked):
     assert seen["evictions"] > 0
     if order == "evict_then_attend":
         assert seen["leaver_goes"] > 0 and seen["heavy_goes"] > 0, seen
+
+
+def _random_stepping_cases(n, seed=808):
+    """Seeded random larger shapes: prompts to 2100 tokens, 1-3 layers, 1-208 units, every group size and policy,
+    both orders, dense or blocked rows; about six units of each are followed."""
+    r = np.random.default_rng(seed)
+    out = []
+    for k in range(n):
+        dtype = ["bf16", "bf16", "f32"][int(r.integers(3))]
+        D = 128 if dtype == "bf16" and r.integers(4) else [64, 128][int(r.integers(2))]
+        g = [1, 2, 4, 8][int(r.integers(4))]
+        Hkv, B = int(r.choice([1, 2, 4, 8])), int(r.choice([1, 2, 4, 13, 26]))
+        P, S = int(r.choice([200, 330, 700, 1250, 2100])), int(r.integers(6, 14))
+        policy = ["h2o", "h2o", "sliding", "streaming"][int(r.integers(4))]
+        lo = {"sliding": 1, "streaming": 5, "h2o": 2}[policy]
+        budgets = [int(max(lo, r.choice([r.integers(lo, 70), r.integers(100, min(400, P)), r.integers(min(400, P - 1), P),
+                                         P - 3, P + 2]))) for _ in range(int(r.integers(1, 4)))]
+        order = ["evict_then_attend", "attend_then_evict"][int(r.integers(2))]
+        blocked = bool(r.integers(2))
+        out.append((("step%02d_%s_%s_D%d_g%d" % (k, policy, dtype, D, g), dtype, Hkv * g, Hkv, D, B, P, S, policy, budgets, order),
+                    max(1, B * Hkv * len(budgets) // 6), blocked))
+    return out
+
+
+# (SQA_RANDOM_CASES=1500 python -m pytest tests/test_gpu_stepping.py -m gpu -k random  runs a longer campaign)
+RANDOM_STEPPING = _random_stepping_cases(max(1, int(os.environ.get("SQA_RANDOM_CASES", "28")) // 4))
+
+
+@pytest.mark.parametrize("case,stride,blocked", RANDOM_STEPPING, ids=[c[0][0] for c in RANDOM_STEPPING])
+def test_stepping_random_shapes(sqa, case, stride, blocked):
+    _run_case(sqa, case, stride=stride, blocked=blocked, need_both_outcomes=False)
